@@ -1,0 +1,189 @@
+"""ctypes loader for the SentenceKV CPU oracle -- TEST INFRASTRUCTURE ONLY.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import this package.
+The product path (paper_2504_00970_amd) never does.
+
+Two builds of the same C source exist: `f32` (REAL = float, the reference precision of the
+parity gates) and `f64` (REAL = double, used by the pins to bound the f32 build's own rounding).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sentencekv_oracle.c")
+_BUILD = os.path.join(_HERE, "_build")
+
+F32, BF16 = 0, 1
+
+
+def lib_path(real: str) -> str:
+    return os.path.join(_BUILD, f"libskv_oracle_{real}.so")
+
+
+def build(force: bool = False) -> None:
+    """Compile both precision builds with gcc (no fast-math, no FMA contraction)."""
+    os.makedirs(_BUILD, exist_ok=True)
+    for real, ctype in (("f32", "float"), ("f64", "double")):
+        out = lib_path(real)
+        if not force and os.path.exists(out) and os.path.getmtime(out) >= os.path.getmtime(_SRC):
+            continue
+        cmd = ["gcc", "-std=c99", "-O2", "-ffp-contract=off", "-fno-fast-math", "-Wall", "-Wextra",
+               f"-DSKVO_REAL={ctype}", "-shared", "-fPIC", _SRC, "-o", out, "-lm"]
+        subprocess.run(cmd, check=True)
+
+
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_u32p = ctypes.POINTER(ctypes.c_uint32)
+_f32p = ctypes.POINTER(ctypes.c_float)
+_vp = ctypes.c_void_p
+_i = ctypes.c_int32
+_ci = ctypes.c_int
+
+
+def _ptr(a: np.ndarray, typ):
+    assert a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(typ)
+
+
+def _dtype_of(a: np.ndarray) -> int:
+    if a.dtype == np.float32:
+        return F32
+    if a.dtype == np.uint16:
+        return BF16
+    raise TypeError(f"oracle inputs are float32 or bf16-as-uint16, got {a.dtype}")
+
+
+class Oracle:
+    """numpy front end of one precision build of the oracle."""
+
+    def __init__(self, real: str = "f32"):
+        build()
+        self.real = real
+        self.lib = ctypes.CDLL(lib_path(real))
+        L = self.lib
+        L.skvo_segment.argtypes = [_i32p, _i, _u32p, _i, _i32p, _i32p, _i32p, _i, _i32p]
+        L.skvo_segment.restype = _ci
+        L.skvo_semvec.argtypes = [_vp, _ci, _i, _i, _i, _i, _i32p, _i, _f32p]
+        L.skvo_semvec.restype = None
+        L.skvo_score.argtypes = [_vp, _ci, _i, _i, _i, _f32p, _i, _f32p]
+        L.skvo_score.restype = None
+        L.skvo_select.argtypes = [_f32p, _i32p, _i32p, _i, _i, _i, _i32p, _i, _i32p, _i32p, _i, _i32p]
+        L.skvo_select.restype = None
+        L.skvo_gather.argtypes = [_vp, _ci, _i, _i, _i, _i32p, _i, _i32p, _vp]
+        L.skvo_gather.restype = None
+        L.skvo_attend.argtypes = [_vp, _vp, _vp, _ci, _i, _i, _i, _i32p, _i, _f32p, _f32p]
+        L.skvo_attend.restype = None
+        L.skvo_real_bytes.restype = _ci
+        assert L.skvo_real_bytes() == (4 if real == "f32" else 8)
+
+    # -- prefill ---------------------------------------------------------------------------
+    def segment(self, tok: np.ndarray, bitmap: np.ndarray, vocab: int, cap_sent: Optional[int] = None):
+        """-> (seg_id[T], sent_off[S+1], sent_len[S], S).  Raises if S exceeds cap_sent."""
+        tok = np.ascontiguousarray(tok, dtype=np.int32)
+        bitmap = np.ascontiguousarray(bitmap, dtype=np.uint32)
+        T = tok.shape[0]
+        cap = T if cap_sent is None else cap_sent
+        seg_id = np.zeros(T, dtype=np.int32)
+        off = np.zeros(cap + 1, dtype=np.int32)
+        ln = np.zeros(max(cap, 1), dtype=np.int32)
+        n = np.zeros(1, dtype=np.int32)
+        rc = self.lib.skvo_segment(_ptr(tok, _i32p), T, _ptr(bitmap, _u32p), vocab, _ptr(seg_id, _i32p),
+                                   _ptr(off, _i32p), _ptr(ln, _i32p), cap, _ptr(n, _i32p))
+        S = int(n[0])
+        if rc != 0:
+            raise OverflowError(f"{S} sentences exceed capacity {cap}")
+        return seg_id, off[: S + 1].copy(), ln[:S].copy(), S
+
+    def semvec(self, K: np.ndarray, sent_off: np.ndarray) -> np.ndarray:
+        """K [L][Hkv][T][D] (float32 or bf16 bits) -> semvec float32 [L][Hkv][S][D]."""
+        K = np.ascontiguousarray(K)
+        L, H, T, D = K.shape
+        sent_off = np.ascontiguousarray(sent_off, dtype=np.int32)
+        S = sent_off.shape[0] - 1
+        out = np.zeros((L, H, S, D), dtype=np.float32)
+        self.lib.skvo_semvec(K.ctypes.data_as(_vp), _dtype_of(K), L, H, T, D, _ptr(sent_off, _i32p), S,
+                             _ptr(out, _f32p))
+        return out
+
+    # -- decode ----------------------------------------------------------------------------
+    def score(self, q: np.ndarray, semvec: np.ndarray) -> np.ndarray:
+        """q [Hq][D], semvec [Hkv][S][D] float32 -> score float32 [Hkv][S]."""
+        q = np.ascontiguousarray(q)
+        semvec = np.ascontiguousarray(semvec, dtype=np.float32)
+        Hq, D = q.shape
+        H, S, D2 = semvec.shape
+        assert D == D2 and Hq % H == 0
+        out = np.zeros((H, S), dtype=np.float32)
+        self.lib.skvo_score(q.ctypes.data_as(_vp), _dtype_of(q), Hq, H, D, _ptr(semvec, _f32p), S, _ptr(out, _f32p))
+        return out
+
+    def select(self, score: np.ndarray, sent_off: np.ndarray, sent_len: np.ndarray, budget: int,
+               budget_stride: Optional[int] = None, max_sel: Optional[int] = None):
+        """-> (sel_sent[Hkv][max_sel], n_sel[Hkv], tok_idx[Hkv][stride], n_tok[Hkv]); unused slots are -1."""
+        score = np.ascontiguousarray(score, dtype=np.float32)
+        H, S = score.shape
+        sent_off = np.ascontiguousarray(sent_off, dtype=np.int32)
+        sent_len = np.ascontiguousarray(sent_len, dtype=np.int32)
+        stride = max(budget, 1) if budget_stride is None else budget_stride
+        assert stride >= budget
+        msel = max(min(S, max(budget, 0)), 1) if max_sel is None else max_sel
+        sel = np.full((H, msel), -1, dtype=np.int32)
+        n_sel = np.zeros(H, dtype=np.int32)
+        tok_idx = np.full((H, stride), -1, dtype=np.int32)
+        n_tok = np.zeros(H, dtype=np.int32)
+        self.lib.skvo_select(_ptr(score, _f32p), _ptr(sent_off, _i32p), _ptr(sent_len, _i32p), S, H, budget,
+                             _ptr(sel, _i32p), msel, _ptr(n_sel, _i32p), _ptr(tok_idx, _i32p), stride,
+                             _ptr(n_tok, _i32p))
+        return sel, n_sel, tok_idx, n_tok
+
+    def gather(self, pool: np.ndarray, tok_idx: np.ndarray, n_tok: np.ndarray) -> np.ndarray:
+        """pool [Hkv][T][D] -> [Hkv][stride][D]; rows past n_tok[h] stay zero."""
+        pool = np.ascontiguousarray(pool)
+        H, T, D = pool.shape
+        tok_idx = np.ascontiguousarray(tok_idx, dtype=np.int32)
+        n_tok = np.ascontiguousarray(n_tok, dtype=np.int32)
+        stride = tok_idx.shape[1]
+        out = np.zeros((H, stride, D), dtype=pool.dtype)
+        self.lib.skvo_gather(pool.ctypes.data_as(_vp), _dtype_of(pool), H, T, D, _ptr(tok_idx, _i32p), stride,
+                             _ptr(n_tok, _i32p), out.ctypes.data_as(_vp))
+        return out
+
+    def attend(self, q: np.ndarray, K_sel: np.ndarray, V_sel: np.ndarray, n_tok: np.ndarray):
+        """q [Hq][D], K_sel/V_sel [Hkv][stride][D] -> (out float32 [Hq][D], lse float32 [Hq])."""
+        q = np.ascontiguousarray(q)
+        K_sel = np.ascontiguousarray(K_sel)
+        V_sel = np.ascontiguousarray(V_sel)
+        n_tok = np.ascontiguousarray(n_tok, dtype=np.int32)
+        Hq, D = q.shape
+        H, stride, _ = K_sel.shape
+        assert _dtype_of(q) == _dtype_of(K_sel) == _dtype_of(V_sel)
+        out = np.zeros((Hq, D), dtype=np.float32)
+        lse = np.zeros(Hq, dtype=np.float32)
+        self.lib.skvo_attend(q.ctypes.data_as(_vp), K_sel.ctypes.data_as(_vp), V_sel.ctypes.data_as(_vp),
+                             _dtype_of(q), Hq, H, D, _ptr(n_tok, _i32p), stride, _ptr(out, _f32p), _ptr(lse, _f32p))
+        return out, lse
+
+    def decode_step(self, q_score, q_attn, K_layer, V_layer, semvec_layer, sent_off, sent_len, budget):
+        """The whole decode chain for one layer, one sequence (score -> select -> gather -> attend)."""
+        sc = self.score(q_score, semvec_layer)
+        sel, n_sel, tok_idx, n_tok = self.select(sc, sent_off, sent_len, budget)
+        Ks = self.gather(K_layer, tok_idx, n_tok)
+        Vs = self.gather(V_layer, tok_idx, n_tok)
+        out, lse = self.attend(q_attn, Ks, Vs, n_tok)
+        return dict(score=sc, sel_sent=sel, n_sel=n_sel, tok_idx=tok_idx, n_tok=n_tok, K_sel=Ks, V_sel=Vs,
+                    out=out, lse=lse)
+
+
+_cache = {}
+
+
+def get(real: str = "f32") -> Oracle:
+    if real not in _cache:
+        _cache[real] = Oracle(real)
+    return _cache[real]

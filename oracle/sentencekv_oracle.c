@@ -1,0 +1,252 @@
+/*
+ * SentenceKV CPU oracle -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+ *
+ * A plain, slow, single-threaded implementation of what the SentenceKV hot path computes,
+ * written from the paper's definitions (arxiv 2504.00970).  It exists only so that the HIP
+ * kernels can be checked against it; nothing in the product path may call it.  It shares no
+ * source, header, table or helper with the HIP library.
+ *
+ * Arithmetic: REAL (float unless built with -DSKVO_REAL=double), one operation at a time in the
+ * order written (build with -ffp-contract=off, no -ffast-math).  bf16 inputs are widened exactly.
+ * Semantic vectors and scores are stored as float in both builds.
+ *
+ * Steps (names follow the paper's notation):
+ *   skvo_segment  sentence buckets from a token stream          (Sec. 4.1 "split ... into sentences
+ *                                                                according to punctuation"; Alg. 1 prefill)
+ *   skvo_semvec   mean key vector k-bar_{s,h} per bucket, head  (Eq. 1)
+ *   skvo_score    S(q-bar, k-bar_{s,h}) = q-bar^T k-bar_{s,h}   (Sec. 4.2 "Semantic similarity and token retrieval")
+ *   skvo_select   rank buckets by score, take whole buckets in descending order until the token
+ *                 budget tau is reached                        (Sec. 4.2; App. "Effect of Sentence Length")
+ *   skvo_gather   K_tau, V_tau = rows of the selected tokens    (Sec. 4.2 "loaded ... back to the GPU"; Alg. 1)
+ *   skvo_attend   O = softmax(q K_tau^T / sqrt(d)) V_tau        (Eq. 3)
+ *
+ * Readings taken where the paper is silent (each is a documented constant of this oracle):
+ *   - the terminator set is input data (a bitmap over the vocabulary);
+ *   - a sentence ends WITH its terminator; trailing tokens after the last terminator form a
+ *     final sentence; a terminator at the last position opens no empty sentence; every
+ *     terminator closes a sentence (runs of terminators give length-1 sentences);
+ *   - S_s of Eq. 1 is the whole sentence (the KV pool is the full context);
+ *   - with grouped-query attention one selection is made per KV head and the bucket score is
+ *     the sum over the G query heads of the group of q-bar_j^T k-bar_{s,h}; query head j uses
+ *     KV head floor(j / G);
+ *   - no scaling or normalisation of the score;
+ *   - buckets are taken in (score descending, id ascending) order and the walk stops at the
+ *     first bucket that does not fit the remaining budget (no skipping ahead, no partial
+ *     bucket); NaN scores rank lowest; -0 == +0;
+ *   - gathered tokens are in ascending position order;
+ *   - an empty selection gives O = 0 and lse = -inf.
+ *
+ * Parity pins: every function here is pinned by tests/test_oracle_*.py (hand-built streams,
+ * float64 brute force from raw keys, an independent O(S^2) characterisation of the selection,
+ * dense softmax attention in float64 when tau >= T).  The readings listed above are fixed by
+ * this file and its documentation only: the paper prints no worked numerical example.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifndef SKVO_REAL
+#define SKVO_REAL float
+#endif
+typedef SKVO_REAL real;
+
+enum { SKVO_F32 = 0, SKVO_BF16 = 1 };
+
+/* exact widening of one stored element to REAL */
+static real load_elt(const void* base, int dtype, int64_t i) {
+    if (dtype == SKVO_F32) return (real)((const float*)base)[i];
+    uint32_t bits = ((uint32_t)((const uint16_t*)base)[i]) << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (real)f;
+}
+
+static size_t elt_size(int dtype) { return dtype == SKVO_F32 ? 4u : 2u; }
+
+static int is_terminator(const uint32_t* bitmap, int32_t vocab, int32_t id) {
+    if (id < 0 || id >= vocab) return 0;
+    return (int)((bitmap[id >> 5] >> (id & 31)) & 1u);
+}
+
+/* Sec. 4.1 / Alg. 1 prefill: sentence buckets.  seg_id[i] = number of terminators strictly before i.
+ * sent_off has room for cap_sent + 1 entries, sent_len for cap_sent.  *n_sent receives S even if
+ * S > cap_sent (then only the first cap_sent buckets are written and -1 is returned). */
+int skvo_segment(const int32_t* tok, int32_t T, const uint32_t* bitmap, int32_t vocab,
+                 int32_t* seg_id, int32_t* sent_off, int32_t* sent_len, int32_t cap_sent, int32_t* n_sent) {
+    int32_t seg = 0, start = 0;
+    for (int32_t i = 0; i < T; ++i) {
+        seg_id[i] = seg;
+        int closes = is_terminator(bitmap, vocab, tok[i]) || i == T - 1;
+        if (closes) {
+            if (seg < cap_sent) {
+                sent_off[seg] = start;
+                sent_len[seg] = i + 1 - start;
+            }
+            start = i + 1;
+            seg++;
+        }
+    }
+    *n_sent = seg;
+    if (seg <= cap_sent) sent_off[seg] = T;
+    return seg <= cap_sent ? 0 : -1;
+}
+
+/* Eq. 1: semvec[l][h][s][:] = (1/|S_s|) sum_{x in S_s} k_{x,h}, S_s = all tokens of sentence s. */
+void skvo_semvec(const void* K, int dtype, int32_t L, int32_t Hkv, int32_t T, int32_t D,
+                 const int32_t* sent_off, int32_t S, float* semvec) {
+    real* acc = (real*)malloc(sizeof(real) * (size_t)D);
+    for (int32_t l = 0; l < L; ++l)
+        for (int32_t h = 0; h < Hkv; ++h)
+            for (int32_t s = 0; s < S; ++s) {
+                int32_t b = sent_off[s], e = sent_off[s + 1];
+                for (int32_t d = 0; d < D; ++d) acc[d] = 0;
+                for (int32_t x = b; x < e; ++x) {
+                    int64_t row = (((int64_t)l * Hkv + h) * T + x) * D;
+                    for (int32_t d = 0; d < D; ++d) acc[d] = acc[d] + load_elt(K, dtype, row + d);
+                }
+                real n = (real)(e - b);
+                float* out = semvec + (((int64_t)l * Hkv + h) * S + s) * D;
+                for (int32_t d = 0; d < D; ++d) out[d] = (float)(acc[d] / n);
+            }
+    free(acc);
+}
+
+/* Sec. 4.2: score[h][s] = sum_{g<G} q[hG+g]^T semvec[h][s]  (one layer; semvec is [Hkv][S][D]). */
+void skvo_score(const void* q, int dtype, int32_t Hq, int32_t Hkv, int32_t D,
+                const float* semvec, int32_t S, float* score) {
+    int32_t G = Hq / Hkv;
+    for (int32_t h = 0; h < Hkv; ++h)
+        for (int32_t s = 0; s < S; ++s) {
+            const float* kbar = semvec + ((int64_t)h * S + s) * D;
+            real acc = 0;
+            for (int32_t g = 0; g < G; ++g)
+                for (int32_t d = 0; d < D; ++d) {
+                    real prod = load_elt(q, dtype, (int64_t)(h * G + g) * D + d) * (real)kbar[d];
+                    acc = acc + prod;
+                }
+            score[(int64_t)h * S + s] = (float)acc;
+        }
+}
+
+/* ranking order of the buckets: higher score first, NaN last, equal scores by lower id */
+typedef struct { float score; int32_t id; } ranked;
+
+static int rank_before(const void* pa, const void* pb) {
+    const ranked* a = (const ranked*)pa;
+    const ranked* b = (const ranked*)pb;
+    int an = isnan(a->score), bn = isnan(b->score);
+    if (an != bn) return an ? 1 : -1;
+    if (!an) {
+        if (a->score > b->score) return -1;
+        if (a->score < b->score) return 1;
+    }
+    return (a->id > b->id) - (a->id < b->id);
+}
+
+static int by_id(const void* pa, const void* pb) {
+    int32_t a = *(const int32_t*)pa, b = *(const int32_t*)pb;
+    return (a > b) - (a < b);
+}
+
+/* Sec. 4.2 ranking + budgeted retrieval, per KV head.  score is [Hkv][S].  Outputs per head h:
+ * sel_sent[h][0..n_sel[h]) selected bucket ids ascending (row stride max_sel), tok_idx[h][0..n_tok[h])
+ * their token positions ascending (row stride budget_stride). */
+void skvo_select(const float* score, const int32_t* sent_off, const int32_t* sent_len, int32_t S,
+                 int32_t Hkv, int32_t budget, int32_t* sel_sent, int32_t max_sel, int32_t* n_sel,
+                 int32_t* tok_idx, int32_t budget_stride, int32_t* n_tok) {
+    ranked* order = (ranked*)malloc(sizeof(ranked) * (size_t)(S > 0 ? S : 1));
+    int32_t* chosen = (int32_t*)malloc(sizeof(int32_t) * (size_t)(S > 0 ? S : 1));
+    for (int32_t h = 0; h < Hkv; ++h) {
+        for (int32_t s = 0; s < S; ++s) {
+            order[s].score = score[(int64_t)h * S + s];
+            order[s].id = s;
+        }
+        qsort(order, (size_t)S, sizeof(ranked), rank_before);
+        int32_t used = 0, cnt = 0;
+        for (int32_t r = 0; r < S; ++r) {
+            int32_t len = sent_len[order[r].id];
+            if (used + len > budget) break;          /* first bucket that does not fit ends the walk */
+            used += len;
+            chosen[cnt++] = order[r].id;
+        }
+        qsort(chosen, (size_t)cnt, sizeof(int32_t), by_id);
+        int32_t w = 0;
+        for (int32_t c = 0; c < cnt; ++c) {
+            int32_t s = chosen[c];
+            if (c < max_sel) sel_sent[(int64_t)h * max_sel + c] = s;
+            for (int32_t x = sent_off[s]; x < sent_off[s] + sent_len[s]; ++x)
+                tok_idx[(int64_t)h * budget_stride + w++] = x;
+        }
+        n_sel[h] = cnt;
+        n_tok[h] = w;
+    }
+    free(order);
+    free(chosen);
+}
+
+/* Alg. 1 decode "load keys and values of the corresponding tokens": row copy.
+ * pool is one layer [Hkv][T][D]; dst is [Hkv][budget_stride][D]; rows >= n_tok[h] are left untouched. */
+void skvo_gather(const void* pool, int dtype, int32_t Hkv, int32_t T, int32_t D,
+                 const int32_t* tok_idx, int32_t budget_stride, const int32_t* n_tok, void* dst) {
+    size_t row = (size_t)D * elt_size(dtype);
+    for (int32_t h = 0; h < Hkv; ++h)
+        for (int32_t j = 0; j < n_tok[h]; ++j) {
+            int32_t x = tok_idx[(int64_t)h * budget_stride + j];
+            memcpy((char*)dst + ((size_t)h * budget_stride + j) * row,
+                   (const char*)pool + ((size_t)h * T + x) * row, row);
+        }
+}
+
+/* Eq. 3 for every query head j (KV head floor(j/G)): two-pass softmax over the gathered tokens.
+ * K_sel, V_sel are [Hkv][budget_stride][D]; out is [Hq][D]; lse (nullable) is [Hq]. */
+void skvo_attend(const void* q, const void* K_sel, const void* V_sel, int dtype,
+                 int32_t Hq, int32_t Hkv, int32_t D, const int32_t* n_tok, int32_t budget_stride,
+                 float* out, float* lse) {
+    int32_t G = Hq / Hkv;
+    int32_t max_n = 0;
+    for (int32_t h = 0; h < Hkv; ++h) if (n_tok[h] > max_n) max_n = n_tok[h];
+    real* logit = (real*)malloc(sizeof(real) * (size_t)(max_n > 0 ? max_n : 1));
+    real* acc = (real*)malloc(sizeof(real) * (size_t)D);
+    real scale = sizeof(real) == sizeof(float) ? (real)(1.0f / sqrtf((float)D)) : (real)(1.0 / sqrt((double)D));
+    for (int32_t j = 0; j < Hq; ++j) {
+        int32_t h = j / G, n = n_tok[h];
+        if (n <= 0) {
+            for (int32_t d = 0; d < D; ++d) out[(int64_t)j * D + d] = 0.0f;
+            if (lse) lse[j] = -INFINITY;
+            continue;
+        }
+        real m = -INFINITY;
+        for (int32_t i = 0; i < n; ++i) {
+            int64_t row = ((int64_t)h * budget_stride + i) * D;
+            real dot = 0;
+            for (int32_t d = 0; d < D; ++d) {
+                real prod = load_elt(q, dtype, (int64_t)j * D + d) * load_elt(K_sel, dtype, row + d);
+                dot = dot + prod;
+            }
+            logit[i] = dot * scale;
+            if (logit[i] > m) m = logit[i];
+        }
+        real denom = 0;
+        for (int32_t d = 0; d < D; ++d) acc[d] = 0;
+        for (int32_t i = 0; i < n; ++i) {
+            int64_t row = ((int64_t)h * budget_stride + i) * D;
+            real p = sizeof(real) == sizeof(float) ? (real)expf((float)(logit[i] - m))
+                                                   : (real)exp((double)(logit[i] - m));
+            denom = denom + p;
+            for (int32_t d = 0; d < D; ++d) {
+                real prod = p * load_elt(V_sel, dtype, row + d);
+                acc[d] = acc[d] + prod;
+            }
+        }
+        for (int32_t d = 0; d < D; ++d) out[(int64_t)j * D + d] = (float)(acc[d] / denom);
+        if (lse)
+            lse[j] = sizeof(real) == sizeof(float) ? (float)m + logf((float)denom)
+                                                   : (float)((double)m + log((double)denom));
+    }
+    free(logit);
+    free(acc);
+}
+
+/* size of REAL in this build (4 = float, 8 = double), so a loader can tell the two libraries apart */
+int skvo_real_bytes(void) { return (int)sizeof(real); }

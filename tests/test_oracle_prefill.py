@@ -1,0 +1,147 @@
+"""Pins for the oracle's prefill steps: sentence segmentation (Sec. 4.1) and mean key vectors (Eq. 1).
+
+None of these checks re-uses the oracle's own loop: they compare against hand-built streams with
+written-out answers, numpy's prefix sum, the lengths the generator drew before it built the token
+stream, and float64 brute force from the raw keys.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from workload import gen
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+VOCAB, TERM = 64, 7          # tiny vocabulary for hand-built streams: id 7 is the only terminator
+
+
+def _bitmap(vocab, terms):
+    w = np.zeros((vocab + 31) // 32, dtype=np.uint32)
+    for t in terms:
+        w[t // 32] |= np.uint32(1) << np.uint32(t % 32)
+    return w
+
+
+def _stream(text):
+    return np.array([TERM if c == "." else 3 for c in text], dtype=np.int32)
+
+
+def _cases():
+    out = []
+    for line in open(os.path.join(GOLDEN, "segment_cases.txt")):
+        if line.startswith("#") or "|" not in line:
+            continue
+        text, lens = line.rstrip("\n").split("|")
+        out.append((text, [int(x) for x in lens.split(",")] if lens else []))
+    return out
+
+
+@pytest.mark.parametrize("text,lens", _cases())
+def test_segment_hand_built_streams(oracle32, text, lens):
+    seg_id, off, ln, S = oracle32.segment(_stream(text), _bitmap(VOCAB, [TERM]), VOCAB)
+    assert S == len(lens)
+    assert ln.tolist() == lens
+    starts = [sum(lens[:i]) for i in range(len(lens) + 1)]
+    assert off.tolist() == starts
+    expect_ids = [s for s, n in enumerate(lens) for _ in range(n)]
+    assert seg_id.tolist() == expect_ids
+
+
+def test_segment_matches_exclusive_prefix_sum_and_invariants(oracle32):
+    rng = np.random.default_rng(5)
+    bitmap = gen.terminator_bitmap(1000, 20)
+    for T in (1, 2, 63, 64, 65, 1000, 4097):
+        tok = rng.integers(0, 1000, size=T).astype(np.int32)
+        flag = (tok % 20 == 0).astype(np.int64)
+        seg_id, off, ln, S = oracle32.segment(tok, bitmap, 1000)
+        excl = np.concatenate([[0], np.cumsum(flag)[:-1]])        # textbook exclusive scan
+        assert np.array_equal(seg_id, excl)
+        assert S == seg_id[-1] + 1
+        assert ln.sum() == T and ln.min() >= 1
+        assert np.all(np.diff(off) > 0) and off[0] == 0 and off[-1] == T
+        assert np.array_equal(np.diff(seg_id), flag[:-1])
+        assert np.array_equal(off[1:] - off[:-1], ln)
+        # every sentence but possibly the last ends with a terminator and has none inside
+        for s in range(S):
+            inner = flag[off[s]: off[s + 1] - 1]
+            assert inner.sum() == 0
+            if s < S - 1:
+                assert flag[off[s + 1] - 1] == 1
+
+
+def test_segment_ignores_ids_outside_vocabulary(oracle32):
+    tok = np.array([3, -1, 7, 64, 9999, 7, 2], dtype=np.int32)
+    _, off, ln, S = oracle32.segment(tok, _bitmap(VOCAB, [TERM]), VOCAB)
+    assert ln.tolist() == [3, 3, 1]
+
+
+def test_segment_recovers_generator_lengths(oracle32):
+    """The generator draws lengths first and only then plants terminators: the segmenter must return them."""
+    wl = gen.CFG3.scaled(n_tokens=32768)
+    p = gen.prefill_inputs(wl, seed=3, with_keys=False)
+    seg_id, off, ln, S = oracle32.segment(p.tok, p.bitmap, wl.vocab)
+    assert S == len(p.lengths)
+    assert np.array_equal(ln, p.lengths)
+    # about 5% of positions are terminators (the contract's probability)
+    assert 0.04 < S / wl.n_tokens < 0.06
+
+
+def test_segment_capacity_overflow_reported(oracle32):
+    with pytest.raises(OverflowError):
+        oracle32.segment(_stream("a.a.a.a."), _bitmap(VOCAB, [TERM]), VOCAB, cap_sent=3)
+    _, off, ln, S = oracle32.segment(_stream("a.a.a.a."), _bitmap(VOCAB, [TERM]), VOCAB, cap_sent=4)
+    assert S == 4
+
+
+# ----------------------------------------------------------------------------- Eq. 1
+
+def _keys(L, H, T, D, dtype, seed):
+    g = torch.Generator().manual_seed(seed)
+    return torch.randn(L, H, T, D, generator=g).to(dtype)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_semvec_equals_float64_brute_force(oracle32, oracle64, dtype):
+    lens = np.array([1, 5, 17, 1, 64, 3, 130, 2], dtype=np.int32)
+    off = gen.offsets_of(lens)
+    K = _keys(2, 3, int(lens.sum()), 128, dtype, 11)
+    got = oracle32.semvec(gen.to_numpy(K), off)
+    got64 = oracle64.semvec(gen.to_numpy(K), off)
+    Kd = K.to(torch.float64).numpy()
+    for s in range(len(lens)):
+        want = Kd[:, :, off[s]:off[s + 1], :].mean(axis=2)
+        assert np.allclose(got[:, :, s, :], want, rtol=1e-6, atol=1e-6)
+        assert np.allclose(got64[:, :, s, :], want.astype(np.float32), rtol=0, atol=1e-7)
+
+
+def test_semvec_special_cases(oracle32):
+    D = 128
+    # length-1 sentences: the vector is the key itself, bit for bit
+    K = _keys(1, 2, 9, D, torch.bfloat16, 2)
+    off = np.arange(10, dtype=np.int32)
+    sv = oracle32.semvec(gen.to_numpy(K), off)
+    assert np.array_equal(sv[0], K[0].to(torch.float32).numpy())
+    # constant keys inside a sentence: the mean is that key exactly (sums of n equal floats of
+    # few mantissa bits are exact, and x*n/n == x)
+    row = torch.randn(D, generator=torch.Generator().manual_seed(4)).to(torch.bfloat16)
+    K = row.expand(1, 1, 12, D).contiguous()
+    sv = oracle32.semvec(gen.to_numpy(K), np.array([0, 4, 12], dtype=np.int32))
+    assert np.array_equal(sv[0, 0, 0], row.to(torch.float32).numpy())
+    assert np.array_equal(sv[0, 0, 1], row.to(torch.float32).numpy())
+    # a wrong divisor or an off-by-one range would break this: keys 1..n -> mean (n+1)/2
+    K = torch.arange(1, 8, dtype=torch.float32).view(1, 1, 7, 1).expand(1, 1, 7, D).contiguous()
+    sv = oracle32.semvec(K.numpy(), np.array([0, 3, 7], dtype=np.int32))
+    assert np.all(sv[0, 0, 0] == 2.0) and np.all(sv[0, 0, 1] == 5.5)
+
+
+def test_semvec_tracks_sentence_centres_of_the_synthetic_keys(oracle32):
+    """Structure of the workload: key = centre + 0.5*noise, so the mean is within ~4*0.5/sqrt(len) of the centre."""
+    lens = gen.sentence_lengths(("uniform", 8, 40), 1024, seed=1)
+    K, _ = gen.kv_layer(lens, 2, 128, torch.float32, seed=1, layer=0)
+    # regenerate the centres exactly as the generator does (first draw of the layer's stream)
+    g = gen._tgen(1, 1000, "cpu")
+    centres = torch.randn(2, len(lens), 128, generator=g).numpy()
+    sv = oracle32.semvec(K.unsqueeze(0).numpy(), gen.offsets_of(lens))[0]
+    bound = 5.0 * 0.5 / np.sqrt(lens.astype(np.float64))
+    assert np.all(np.abs(sv - centres).max(axis=2) <= bound[None, :])
