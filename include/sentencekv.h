@@ -1,0 +1,161 @@
+/*
+ * sentencekv.h -- C ABI of the MI355X (gfx950) SentenceKV hot path (arxiv 2504.00970).
+ *
+ * The library implements, as hand-written HIP kernels, the data-parallel work SentenceKV does
+ *   - once per prompt (prefill):  sentence buckets and their mean key vectors (Sec. 4.1, Eq. 1);
+ *   - at every decode step, per layer: similarity scores of every bucket against the (mean) query,
+ *     ranking and budgeted retrieval of whole buckets, loading the retrieved tokens' K/V, and
+ *     attention over them (Sec. 4.2, Eq. 3, Alg. 1 decoding phase).
+ *
+ * Conventions
+ *   - Every function returns an int: SKV_OK (0) or a negative skv_status.  Nothing aborts, throws
+ *     or prints.  Argument checks are done on the host before anything is launched.
+ *   - "dev" pointers are device memory (HBM) unless stated otherwise, "host" pointers host memory.
+ *     All are caller-owned, 16-byte aligned, and must stay valid until the work queued on the
+ *     context's stream has finished.  The library owns only the context and its workspace, which
+ *     is sized from skv_desc at skv_create; no call after skv_create allocates.
+ *   - All tensors are dense, row-major, innermost dimension last.  head_dim D is 128.
+ *     K/V/q element type is skv_desc.kv_dtype (fp32 or bf16); semantic vectors, scores, attention
+ *     outputs and log-sum-exps are fp32; every index, length and count is int32.
+ *   - Grouped-query attention: query head j reads KV head j / G, G = n_q_heads / n_kv_heads.
+ *     One bucket selection is made per KV head (and per layer, per sequence); the score of a bucket
+ *     is the sum over the group's G query heads of q_j^T k-bar (the paper states the score per
+ *     attention head and is silent on GQA).
+ *   - Decode calls are asynchronous on the context's stream and never block the host.  Calls on one
+ *     context must come from one host thread at a time and execute in stream order; they share the
+ *     context's workspace, so two contexts are needed for concurrent streams.
+ */
+#ifndef SENTENCEKV_H
+#define SENTENCEKV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SKV_OK = 0,
+    SKV_EINVAL = -1,     /* null / misaligned pointer, negative size, shape not matching the descriptor */
+    SKV_ECAPACITY = -2,  /* tokens, sentences, budget or batch exceed the maxima given at skv_create */
+    SKV_EHIP = -3,       /* a HIP runtime call or kernel launch failed (no usable GPU included) */
+    SKV_ENOMEM = -4      /* workspace allocation failed */
+} skv_status;
+
+typedef enum { SKV_F32 = 0, SKV_BF16 = 1 } skv_dtype;
+
+typedef struct {
+    int32_t n_layers;       /* L: leading dimension of the K/V pools and of the semantic-vector table */
+    int32_t n_q_heads;      /* Hq, a multiple of n_kv_heads; G = Hq / Hkv must be 1, 2, 4 or 8 */
+    int32_t n_kv_heads;     /* Hkv */
+    int32_t head_dim;       /* D, must be 128 */
+    int32_t kv_dtype;       /* skv_dtype of K, V and the queries */
+    int32_t max_tokens;     /* largest T (T_total for a ragged batch) any call will pass */
+    int32_t max_sentences;  /* largest S (S_total for a ragged batch) any call will pass */
+    int32_t max_budget;     /* largest per-sequence token budget tau any call will pass */
+    int32_t max_batch;      /* largest number of sequences in one skv_decode_step (>= 1) */
+} skv_desc;
+
+typedef struct skv_ctx skv_ctx;   /* opaque */
+
+/* Creates a context on the current HIP device.  `hip_stream` (a hipStream_t, may be NULL for the
+ * default stream) is borrowed, not owned.  Fails with SKV_EINVAL on a bad descriptor (checked before
+ * the GPU is touched), SKV_EHIP / SKV_ENOMEM if the device or its memory is unavailable. */
+int skv_create(skv_ctx** out, const skv_desc* desc, void* hip_stream);
+void skv_destroy(skv_ctx* ctx);
+int skv_set_stream(skv_ctx* ctx, void* hip_stream);
+const char* skv_strerror(int status);
+/* Bytes of device workspace the context holds (0 for a NULL context). */
+int64_t skv_workspace_bytes(const skv_ctx* ctx);
+
+/* ---------------------------------------------------------------------------------------------
+ * (1) Prefill.  Sec. 4.1 first paragraph and Alg. 1 prefilling phase: the prompt is split into
+ * sentence buckets at punctuation.  Which token ids are punctuation is data: bit (id % 32) of word
+ * (id / 32) of `term_bitmap` is set for a terminator; ids outside [0, vocab) are never terminators.
+ *
+ * A bucket ends WITH its terminator; tokens after the last terminator form a final bucket; every
+ * terminator of a run closes a (length-1) bucket.  Hence
+ *     seg_id[i]   = number of terminators among tok[0..i)         (exclusive prefix sum)
+ *     S           = seg_id[T-1] + 1  (0 when T == 0)
+ *     sent_off[s] = first position of bucket s, sent_off[S] = T;  sent_len[s] = sent_off[s+1] - sent_off[s]
+ *
+ * tok          dev  [T]                      seg_id      dev [T]
+ * term_bitmap  dev  [ceil(vocab / 32)]       sent_off    dev [max_sentences + 1]
+ * n_sent_dev   dev  [1], receives S          sent_len    dev [max_sentences]
+ * n_sent_host  host [1] or NULL.  Non-NULL: the call waits for the stream, stores S there and returns
+ *              SKV_ECAPACITY if S > max_sentences.  Buckets beyond max_sentences are never written
+ *              (n_sent_dev still receives the true S).  NULL: fully asynchronous.
+ * Errors: SKV_EINVAL (null pointers, T < 0, vocab <= 0), SKV_ECAPACITY (T > max_tokens). */
+int skv_segment(skv_ctx* ctx, const int32_t* tok, int32_t T, const uint32_t* term_bitmap, int32_t vocab,
+                int32_t* seg_id, int32_t* sent_off, int32_t* sent_len, int32_t* n_sent_dev,
+                int32_t* n_sent_host);
+
+/* Eq. 1: semvec[l][h][s][:] = mean over the tokens x of bucket s of K_pool[l][h][x][:], accumulated
+ * in fp32.  The pool holds the full context, so the set S_s of Eq. 1 is the whole bucket.
+ * K_pool  dev [L][Hkv][T][D] kv_dtype          sent_off  dev [S + 1] (as produced by skv_segment)
+ * semvec  dev [L][Hkv][S][D] fp32
+ * Errors: SKV_EINVAL, SKV_ECAPACITY (T > max_tokens or S > max_sentences).  S == 0 is a no-op. */
+int skv_build_semvec(skv_ctx* ctx, const void* K_pool, int32_t T, const int32_t* sent_off, int32_t S,
+                     float* semvec);
+
+/* ---------------------------------------------------------------------------------------------
+ * (2) Sec. 4.2 "Semantic similarity and token retrieval": score[h][s] = sum over the G query heads j
+ * of KV head h of q_score[j]^T semvec[layer][h][s].  No scaling, no normalisation.  q_score is the
+ * mean query q-bar of Eq. 2 (or the current query: the choice is the caller's).
+ * q_score dev [Hq][D] kv_dtype;  semvec dev [L][Hkv][S][D] fp32 (whole table; `layer` selects the slice);
+ * score   dev [Hkv][S] fp32. */
+int skv_score(skv_ctx* ctx, int32_t layer, const void* q_score, const float* semvec, int32_t S, float* score);
+
+/* (3) Sec. 4.2 ranking and budgeted retrieval, App. "Effect of Sentence Length": per KV head, buckets
+ * are ranked by score (descending; equal scores by ascending id; NaN last; -0 == +0) and whole buckets
+ * are taken along the ranking until the first one that does not fit the remaining budget.
+ * score    dev [Hkv][S]         sent_off dev [S+1]      sent_len dev [S]
+ * sel_sent dev [Hkv][max_sel]   selected bucket ids, ascending; max_sel = min(max_sentences, max_budget)
+ * n_sel    dev [Hkv]            tok_idx  dev [Hkv][budget] token positions of the selected buckets, ascending
+ * n_tok    dev [Hkv]            (n_tok[h] <= budget).  Entries past n_sel[h] / n_tok[h] are not written.
+ * Errors: SKV_EINVAL (budget < 0 ...), SKV_ECAPACITY (S > max_sentences, budget > max_budget). */
+int skv_select(skv_ctx* ctx, const float* score, const int32_t* sent_off, const int32_t* sent_len, int32_t S,
+               int32_t budget, int32_t* sel_sent, int32_t* n_sel, int32_t* tok_idx, int32_t* n_tok);
+
+/* (4) Alg. 1 decode "load keys and values of the corresponding tokens": K_sel[h][j][:] =
+ * K_pool[layer][h][tok_idx[h][j]][:] for j < n_tok[h], same for V.  Rows j >= n_tok[h] are not written.
+ * K_pool, V_pool  [L][Hkv][T][D] kv_dtype, in HBM (pool_in_host == 0) or in pinned, device-mapped host
+ *                 memory (pool_in_host == 1: the paper's CPU-offloaded store; the kernel reads it over
+ *                 PCIe and the pointer passed is the host pointer).
+ * tok_idx dev [Hkv][budget], n_tok dev [Hkv];  K_sel, V_sel dev [Hkv][budget][D] kv_dtype.
+ * A tok_idx entry outside [0, T) is skipped, never dereferenced. */
+int skv_gather(skv_ctx* ctx, int32_t layer, const void* K_pool, const void* V_pool, int32_t T, int pool_in_host,
+               const int32_t* tok_idx, const int32_t* n_tok, int32_t budget, void* K_sel, void* V_sel);
+
+/* (5) Eq. 3: out[j] = softmax(q_attn[j] K_sel[h]^T / sqrt(D)) V_sel[h] over the first n_tok[h] rows,
+ * h = j / G; fp32 softmax and accumulation; lse[j] = log sum_i exp(logit_i) (natural log).
+ * n_tok[h] == 0 gives out = 0 and lse = -inf.
+ * q_attn dev [Hq][D] kv_dtype;  K_sel, V_sel dev [Hkv][budget][D];  out dev [Hq][D] fp32;
+ * lse dev [Hq] fp32 or NULL. */
+int skv_attend(skv_ctx* ctx, const void* q_attn, const void* K_sel, const void* V_sel, const int32_t* n_tok,
+               int32_t budget, float* out, float* lse);
+
+/* ---------------------------------------------------------------------------------------------
+ * One call per layer for the whole decode chain of Alg. 1 (score -> rank/retrieve -> attend), for a
+ * batch of B sequences concatenated along the token axis and the bucket axis.  The retrieved tokens
+ * are read straight from the HBM pool (no K_sel/V_sel copy).  Results equal skv_score + skv_select +
+ * skv_gather + skv_attend run per sequence.
+ * q_score, q_attn  dev [B][Hq][D] kv_dtype (may alias)
+ * K_pool, V_pool   dev [L][Hkv][T_total][D]        semvec dev [L][Hkv][S_total][D]
+ * cu_tok   dev [B+1]  token offset of each sequence in the pool (cu_tok[B] == T_total)
+ * cu_sent  dev [B+1]  bucket offset of each sequence (cu_sent[B] == S_total)
+ * sent_off dev [S_total + B]  per sequence b, S_b + 1 positions local to the sequence, stored at
+ *                             sent_off + cu_sent[b] + b;   sent_len dev [S_total]
+ * budget   dev [B]   per-sequence token budget, each <= max_budget
+ * out dev [B][Hq][D] fp32;  lse dev [B][Hq] or NULL
+ * tok_idx_out dev [B][Hkv][max_budget] or NULL: positions (local to the sequence) of the retrieved
+ *             tokens;  n_tok_out dev [B][Hkv] or NULL. */
+int skv_decode_step(skv_ctx* ctx, int32_t layer, int32_t B, const void* q_score, const void* q_attn,
+                    const void* K_pool, const void* V_pool, int32_t T_total, const float* semvec, int32_t S_total,
+                    const int32_t* cu_tok, const int32_t* cu_sent, const int32_t* sent_off, const int32_t* sent_len,
+                    const int32_t* budget, float* out, float* lse, int32_t* tok_idx_out, int32_t* n_tok_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SENTENCEKV_H */

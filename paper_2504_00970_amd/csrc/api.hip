@@ -1,0 +1,266 @@
+// C ABI of libsentencekv: context management, host-side argument checks, and the launch sequence of
+// every entry point declared in sentencekv.h.  All checks run before anything touches the GPU.
+#include <new>
+
+#include "skv_internal.h"
+
+using skv::Ctx;
+using skv::SeqView;
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool bad_ptr(const void* p) { return p == nullptr || !aligned16(p); }
+inline size_t round256(size_t n) { return (n + 255) & ~size_t(255); }
+
+int check_desc(const skv_desc* d) {
+    if (!d) return SKV_EINVAL;
+    if (d->n_layers < 1 || d->n_q_heads < 1 || d->n_kv_heads < 1) return SKV_EINVAL;
+    if (d->head_dim != skv::kHeadDim) return SKV_EINVAL;
+    if (d->kv_dtype != SKV_F32 && d->kv_dtype != SKV_BF16) return SKV_EINVAL;
+    if (d->n_q_heads % d->n_kv_heads != 0) return SKV_EINVAL;
+    const int G = d->n_q_heads / d->n_kv_heads;
+    if (G != 1 && G != 2 && G != 4 && G != 8) return SKV_EINVAL;
+    if (d->max_tokens < 1 || d->max_sentences < 1 || d->max_budget < 1 || d->max_batch < 1) return SKV_EINVAL;
+    if (d->max_batch > 4096) return SKV_EINVAL;
+    return SKV_OK;
+}
+
+inline int hip_status(hipError_t e) {
+    if (e == hipSuccess) return SKV_OK;
+    return e == hipErrorOutOfMemory ? SKV_ENOMEM : SKV_EHIP;
+}
+
+// The context belongs to one device; refuse calls made with another device current.
+int check_ctx(const skv_ctx* ctx) {
+    if (!ctx) return SKV_EINVAL;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return SKV_EHIP;
+    return dev == ctx->c.device ? SKV_OK : SKV_EINVAL;
+}
+
+inline int64_t layer_elems(const Ctx& c, int64_t rows) { return (int64_t)c.d.n_kv_heads * rows * skv::kHeadDim; }
+inline int elt_bytes(const Ctx& c) { return c.d.kv_dtype == SKV_BF16 ? 2 : 4; }
+
+}  // namespace
+
+extern "C" {
+
+const char* skv_strerror(int status) {
+    switch (status) {
+        case SKV_OK: return "ok";
+        case SKV_EINVAL: return "invalid argument";
+        case SKV_ECAPACITY: return "size exceeds the capacity given at skv_create";
+        case SKV_EHIP: return "HIP runtime error";
+        case SKV_ENOMEM: return "out of device memory";
+        default: return "unknown status";
+    }
+}
+
+int skv_create(skv_ctx** out, const skv_desc* desc, void* hip_stream) {
+    if (!out) return SKV_EINVAL;
+    *out = nullptr;
+    const int rc = check_desc(desc);
+    if (rc != SKV_OK) return rc;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return SKV_EHIP;
+
+    skv_ctx* ctx = new (std::nothrow) skv_ctx();
+    if (!ctx) return SKV_ENOMEM;
+    Ctx& c = ctx->c;
+    c.d = *desc;
+    c.stream = static_cast<hipStream_t>(hip_stream);
+    c.device = dev;
+    c.G = desc->n_q_heads / desc->n_kv_heads;
+    c.max_sel = desc->max_sentences < desc->max_budget ? desc->max_sentences : desc->max_budget;
+    c.max_splits = (desc->max_budget + skv::kAttChunk - 1) / skv::kAttChunk;
+
+    const size_t BH = (size_t)desc->max_batch * desc->n_kv_heads, BQ = (size_t)desc->max_batch * desc->n_q_heads;
+    const size_t n_seg = (size_t)(desc->max_tokens + skv::kSegTokPerBlock - 1) / skv::kSegTokPerBlock;
+    const size_t sz[] = {
+        round256(n_seg * sizeof(unsigned long long)),                        // seg_part
+        round256(BQ * c.max_splits * skv::kHeadDim * sizeof(float)),         // att_part
+        round256(BQ * c.max_splits * 2 * sizeof(float)),                     // att_ml
+        round256(BH * sizeof(unsigned int)),                                 // att_counter
+        round256((size_t)desc->n_kv_heads * desc->max_sentences * sizeof(float)),  // f_score
+        round256(BH * c.max_sel * sizeof(int32_t)),                          // sel_tokpos
+        round256(BH * c.max_sel * sizeof(int32_t)),                          // f_sel_sent
+        round256(BH * sizeof(int32_t)),                                      // f_n_sel
+        round256(BH * sizeof(int32_t)),                                      // f_n_tok
+        round256(BH * desc->max_budget * sizeof(int32_t)),                   // f_tok_idx
+    };
+    size_t total = 0;
+    for (size_t s : sz) total += s;
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&c.ws), total);
+    if (e != hipSuccess) { delete ctx; return hip_status(e); }
+    e = hipMemset(c.ws, 0, total);
+    if (e != hipSuccess) { (void)hipFree(c.ws); delete ctx; return hip_status(e); }
+    c.ws_bytes = total;
+    char* p = c.ws;
+    c.seg_part = reinterpret_cast<unsigned long long*>(p); p += sz[0];
+    c.att_part = reinterpret_cast<float*>(p); p += sz[1];
+    c.att_ml = reinterpret_cast<float*>(p); p += sz[2];
+    c.att_counter = reinterpret_cast<unsigned int*>(p); p += sz[3];
+    c.f_score = reinterpret_cast<float*>(p); p += sz[4];
+    c.sel_tokpos = reinterpret_cast<int32_t*>(p); p += sz[5];
+    c.f_sel_sent = reinterpret_cast<int32_t*>(p); p += sz[6];
+    c.f_n_sel = reinterpret_cast<int32_t*>(p); p += sz[7];
+    c.f_n_tok = reinterpret_cast<int32_t*>(p); p += sz[8];
+    c.f_tok_idx = reinterpret_cast<int32_t*>(p); p += sz[9];
+    *out = ctx;
+    return SKV_OK;
+}
+
+void skv_destroy(skv_ctx* ctx) {
+    if (!ctx) return;
+    if (ctx->c.ws) {
+        (void)hipStreamSynchronize(ctx->c.stream);
+        (void)hipFree(ctx->c.ws);
+    }
+    delete ctx;
+}
+
+int skv_set_stream(skv_ctx* ctx, void* hip_stream) {
+    if (!ctx) return SKV_EINVAL;
+    ctx->c.stream = static_cast<hipStream_t>(hip_stream);
+    return SKV_OK;
+}
+
+int64_t skv_workspace_bytes(const skv_ctx* ctx) { return ctx ? (int64_t)ctx->c.ws_bytes : 0; }
+
+int skv_segment(skv_ctx* ctx, const int32_t* tok, int32_t T, const uint32_t* term_bitmap, int32_t vocab,
+                int32_t* seg_id, int32_t* sent_off, int32_t* sent_len, int32_t* n_sent_dev, int32_t* n_sent_host) {
+    if (!ctx) return SKV_EINVAL;
+    if (T < 0 || vocab <= 0) return SKV_EINVAL;
+    if (bad_ptr(tok) || bad_ptr(term_bitmap) || bad_ptr(seg_id) || bad_ptr(sent_off) || bad_ptr(sent_len) ||
+        bad_ptr(n_sent_dev))
+        return SKV_EINVAL;
+    if (T > ctx->c.d.max_tokens) return SKV_ECAPACITY;
+    int rc = check_ctx(ctx);
+    if (rc != SKV_OK) return rc;
+    rc = hip_status(skv::launch_segment(&ctx->c, tok, T, term_bitmap, vocab, seg_id, sent_off, sent_len, n_sent_dev));
+    if (rc != SKV_OK || !n_sent_host) return rc;
+    hipError_t e = hipMemcpyAsync(n_sent_host, n_sent_dev, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->c.stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->c.stream);
+    if (e != hipSuccess) return SKV_EHIP;
+    return *n_sent_host > ctx->c.d.max_sentences ? SKV_ECAPACITY : SKV_OK;
+}
+
+int skv_build_semvec(skv_ctx* ctx, const void* K_pool, int32_t T, const int32_t* sent_off, int32_t S, float* semvec) {
+    if (!ctx) return SKV_EINVAL;
+    if (T < 0 || S < 0) return SKV_EINVAL;
+    if (S > 0 && (bad_ptr(K_pool) || bad_ptr(sent_off) || bad_ptr(semvec))) return SKV_EINVAL;
+    if (S > T) return SKV_EINVAL;                       // every bucket holds at least one token
+    if (T > ctx->c.d.max_tokens || S > ctx->c.d.max_sentences) return SKV_ECAPACITY;
+    const int rc = check_ctx(ctx);
+    if (rc != SKV_OK) return rc;
+    return hip_status(skv::launch_semvec(&ctx->c, K_pool, T, sent_off, S, semvec));
+}
+
+int skv_score(skv_ctx* ctx, int32_t layer, const void* q_score, const float* semvec, int32_t S, float* score) {
+    if (!ctx) return SKV_EINVAL;
+    if (layer < 0 || layer >= ctx->c.d.n_layers || S < 0) return SKV_EINVAL;
+    if (S > 0 && (bad_ptr(q_score) || bad_ptr(semvec) || bad_ptr(score))) return SKV_EINVAL;
+    if (S > ctx->c.d.max_sentences) return SKV_ECAPACITY;
+    const int rc = check_ctx(ctx);
+    if (rc != SKV_OK) return rc;
+    const SeqView v{nullptr, nullptr, nullptr, 0, S, 0, 1};
+    const float* sv = semvec + (int64_t)layer * layer_elems(ctx->c, S);
+    return hip_status(skv::launch_score(&ctx->c, q_score, sv, v, score));
+}
+
+int skv_select(skv_ctx* ctx, const float* score, const int32_t* sent_off, const int32_t* sent_len, int32_t S,
+               int32_t budget, int32_t* sel_sent, int32_t* n_sel, int32_t* tok_idx, int32_t* n_tok) {
+    if (!ctx) return SKV_EINVAL;
+    if (S < 0 || budget < 0) return SKV_EINVAL;
+    if (bad_ptr(n_sel) || bad_ptr(n_tok)) return SKV_EINVAL;
+    if (S > 0 && budget > 0 &&
+        (bad_ptr(score) || bad_ptr(sent_off) || bad_ptr(sent_len) || bad_ptr(sel_sent) || bad_ptr(tok_idx)))
+        return SKV_EINVAL;
+    if (S > ctx->c.d.max_sentences || budget > ctx->c.d.max_budget) return SKV_ECAPACITY;
+    const int rc = check_ctx(ctx);
+    if (rc != SKV_OK) return rc;
+    const SeqView v{nullptr, nullptr, nullptr, 0, S, budget, 1};
+    return hip_status(skv::launch_select(&ctx->c, score, sent_off, sent_len, v, sel_sent, ctx->c.sel_tokpos, n_sel,
+                                         tok_idx, budget, n_tok));
+}
+
+int skv_gather(skv_ctx* ctx, int32_t layer, const void* K_pool, const void* V_pool, int32_t T, int pool_in_host,
+               const int32_t* tok_idx, const int32_t* n_tok, int32_t budget, void* K_sel, void* V_sel) {
+    if (!ctx) return SKV_EINVAL;
+    if (layer < 0 || layer >= ctx->c.d.n_layers || T < 0 || budget < 0) return SKV_EINVAL;
+    if (pool_in_host != 0 && pool_in_host != 1) return SKV_EINVAL;
+    if (budget > 0 && (bad_ptr(K_pool) || bad_ptr(V_pool) || bad_ptr(tok_idx) || bad_ptr(n_tok) || bad_ptr(K_sel) ||
+                       bad_ptr(V_sel)))
+        return SKV_EINVAL;
+    if (T > ctx->c.d.max_tokens || budget > ctx->c.d.max_budget) return SKV_ECAPACITY;
+    const int rc = check_ctx(ctx);
+    if (rc != SKV_OK) return rc;
+    if (budget == 0) return SKV_OK;
+    const void* Kd = K_pool;
+    const void* Vd = V_pool;
+    if (pool_in_host) {      // device-visible address of the pinned host allocation
+        void *kd = nullptr, *vd = nullptr;
+        if (hipHostGetDevicePointer(&kd, const_cast<void*>(K_pool), 0) != hipSuccess ||
+            hipHostGetDevicePointer(&vd, const_cast<void*>(V_pool), 0) != hipSuccess) {
+            (void)hipGetLastError();
+            return SKV_EINVAL;
+        }
+        Kd = kd;
+        Vd = vd;
+    }
+    const int64_t off = (int64_t)layer * layer_elems(ctx->c, T) * elt_bytes(ctx->c);
+    return hip_status(skv::launch_gather(&ctx->c, (const char*)Kd + off, (const char*)Vd + off, T, tok_idx, n_tok, budget,
+                                         K_sel, V_sel));
+}
+
+int skv_attend(skv_ctx* ctx, const void* q_attn, const void* K_sel, const void* V_sel, const int32_t* n_tok,
+               int32_t budget, float* out, float* lse) {
+    if (!ctx) return SKV_EINVAL;
+    if (budget < 0) return SKV_EINVAL;
+    if (bad_ptr(q_attn) || bad_ptr(n_tok) || bad_ptr(out)) return SKV_EINVAL;
+    if (lse && !aligned16(lse)) return SKV_EINVAL;
+    if (budget > 0 && (bad_ptr(K_sel) || bad_ptr(V_sel))) return SKV_EINVAL;
+    if (budget > ctx->c.d.max_budget) return SKV_ECAPACITY;
+    const int rc = check_ctx(ctx);
+    if (rc != SKV_OK) return rc;
+    const SeqView v{nullptr, nullptr, nullptr, 0, 0, budget, 1};
+    const int n_splits = (budget + skv::kAttChunk - 1) / skv::kAttChunk;
+    return hip_status(skv::launch_attend(&ctx->c, q_attn, K_sel, V_sel, nullptr, 0, budget, n_tok, n_splits, v, out, lse));
+}
+
+int skv_decode_step(skv_ctx* ctx, int32_t layer, int32_t B, const void* q_score, const void* q_attn,
+                    const void* K_pool, const void* V_pool, int32_t T_total, const float* semvec, int32_t S_total,
+                    const int32_t* cu_tok, const int32_t* cu_sent, const int32_t* sent_off, const int32_t* sent_len,
+                    const int32_t* budget, float* out, float* lse, int32_t* tok_idx_out, int32_t* n_tok_out) {
+    if (!ctx) return SKV_EINVAL;
+    Ctx& c = ctx->c;
+    if (layer < 0 || layer >= c.d.n_layers || B < 1 || T_total < 0 || S_total < 0) return SKV_EINVAL;
+    if (bad_ptr(q_score) || bad_ptr(q_attn) || bad_ptr(cu_tok) || bad_ptr(cu_sent) || bad_ptr(sent_off) ||
+        bad_ptr(budget) || bad_ptr(out))
+        return SKV_EINVAL;
+    if (S_total > 0 && (bad_ptr(semvec) || bad_ptr(sent_len))) return SKV_EINVAL;
+    if (T_total > 0 && (bad_ptr(K_pool) || bad_ptr(V_pool))) return SKV_EINVAL;
+    if ((lse && !aligned16(lse)) || (tok_idx_out && !aligned16(tok_idx_out)) || (n_tok_out && !aligned16(n_tok_out)))
+        return SKV_EINVAL;
+    if (B > c.d.max_batch || T_total > c.d.max_tokens || S_total > c.d.max_sentences) return SKV_ECAPACITY;
+    const int rc = check_ctx(ctx);
+    if (rc != SKV_OK) return rc;
+
+    const SeqView v{cu_tok, cu_sent, budget, T_total, S_total, 0, B};
+    const float* sv = semvec + (int64_t)layer * layer_elems(c, S_total);
+    const int64_t pool_off = (int64_t)layer * layer_elems(c, T_total) * elt_bytes(c);
+    int32_t* tok_idx = tok_idx_out ? tok_idx_out : c.f_tok_idx;
+    int32_t* n_tok = n_tok_out ? n_tok_out : c.f_n_tok;
+
+    hipError_t e = skv::launch_score(&c, q_score, sv, v, c.f_score);
+    if (e != hipSuccess) return hip_status(e);
+    e = skv::launch_select(&c, c.f_score, sent_off, sent_len, v, c.f_sel_sent, c.sel_tokpos, c.f_n_sel, tok_idx,
+                           c.d.max_budget, n_tok);
+    if (e != hipSuccess) return hip_status(e);
+    e = skv::launch_attend(&c, q_attn, (const char*)K_pool + pool_off, (const char*)V_pool + pool_off, tok_idx,
+                           c.d.max_budget, 0, n_tok, c.max_splits, v, out, lse);
+    return hip_status(e);
+}
+
+}  // extern "C"

@@ -1,0 +1,222 @@
+// Prefill kernels: sentence segmentation (Sec. 4.1, Alg. 1 prefilling phase) and per-bucket mean key
+// vectors (Eq. 1).  gfx950, wave64.
+#include "skv_internal.h"
+
+namespace skv {
+
+// ------------------------------------------------------------------------------------------------
+// Segmentation.  A token closes a bucket iff it is a terminator; seg_id is the exclusive prefix sum
+// of the terminator flags.  Two launches over blocks of kSegTokPerBlock tokens:
+//   seg_count : per block (number of terminators, 1 + position of the last terminator or 0)
+//   seg_scan  : block prefix from the preceding blocks' partials, wave-level scan inside the block,
+//               then each thread walks its 4 tokens and emits seg_id and, at every bucket end,
+//               the bucket's start and length.
+// The scan operator on (count, last_end) pairs is (a.count + b.count, max(a.last_end, b.last_end)).
+// ------------------------------------------------------------------------------------------------
+
+__device__ __forceinline__ bool is_terminator(const uint32_t* __restrict__ bitmap, int32_t vocab, int32_t id) {
+    if (id < 0 || id >= vocab) return false;
+    return (bitmap[id >> 5] >> (id & 31)) & 1u;
+}
+
+struct SegLocal {
+    int flags;   // bit k set: token i0 + k is a terminator
+    int cnt;
+    int last;    // 1 + position of the thread's last terminator, 0 if none
+};
+
+__device__ __forceinline__ SegLocal seg_load(const int32_t* __restrict__ tok, int32_t T,
+                                             const uint32_t* __restrict__ bitmap, int32_t vocab, int32_t i0) {
+    int32_t t[kSegTokPerThread];
+    if (i0 + kSegTokPerThread <= T) {
+        const int4 v = *reinterpret_cast<const int4*>(tok + i0);
+        t[0] = v.x; t[1] = v.y; t[2] = v.z; t[3] = v.w;
+    } else {
+#pragma unroll
+        for (int k = 0; k < kSegTokPerThread; ++k) t[k] = (i0 + k < T) ? tok[i0 + k] : -1;
+    }
+    SegLocal r{0, 0, 0};
+#pragma unroll
+    for (int k = 0; k < kSegTokPerThread; ++k) {
+        if (i0 + k < T && is_terminator(bitmap, vocab, t[k])) {
+            r.flags |= 1 << k;
+            r.cnt += 1;
+            r.last = i0 + k + 1;
+        }
+    }
+    return r;
+}
+
+__device__ __forceinline__ void wave_reduce_sum_max(int& s, int& m) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        s += __shfl_xor(s, off);
+        m = max(m, __shfl_xor(m, off));
+    }
+}
+
+// Block-wide (sum, max) over kSegThreads threads; result valid in every thread.
+__device__ __forceinline__ void block_reduce_sum_max(int& s, int& m, int* sh /*[2 * waves]*/) {
+    constexpr int kWaves = kSegThreads / kWave;
+    wave_reduce_sum_max(s, m);
+    const int w = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) { sh[w] = s; sh[kWaves + w] = m; }
+    __syncthreads();
+    s = 0; m = 0;
+#pragma unroll
+    for (int i = 0; i < kWaves; ++i) { s += sh[i]; m = max(m, sh[kWaves + i]); }
+}
+
+__global__ __launch_bounds__(kSegThreads) void seg_count_kernel(const int32_t* __restrict__ tok, int32_t T,
+                                                                const uint32_t* __restrict__ bitmap, int32_t vocab,
+                                                                unsigned long long* __restrict__ part) {
+    __shared__ int sh[2 * (kSegThreads / kWave)];
+    const int32_t i0 = (blockIdx.x * kSegThreads + threadIdx.x) * kSegTokPerThread;
+    SegLocal loc = seg_load(tok, T, bitmap, vocab, i0);
+    int s = loc.cnt, m = loc.last;
+    block_reduce_sum_max(s, m, sh);
+    if (threadIdx.x == 0) part[blockIdx.x] = ((unsigned long long)(unsigned)s << 32) | (unsigned)m;
+}
+
+__global__ __launch_bounds__(kSegThreads) void seg_scan_kernel(const int32_t* __restrict__ tok, int32_t T,
+                                                               const uint32_t* __restrict__ bitmap, int32_t vocab,
+                                                               const unsigned long long* __restrict__ part,
+                                                               int32_t* __restrict__ seg_id, int32_t* __restrict__ sent_off,
+                                                               int32_t* __restrict__ sent_len, int32_t cap_sent,
+                                                               int32_t* __restrict__ n_sent) {
+    constexpr int kWaves = kSegThreads / kWave;
+    __shared__ int sh[2 * kWaves];
+    __shared__ int sh_scan[2 * kWaves];
+    if (T == 0) {                       // launched with one block
+        if (threadIdx.x == 0) { *n_sent = 0; sent_off[0] = 0; }
+        return;
+    }
+    // prefix of the blocks before this one
+    int base_cnt = 0, base_last = 0;
+    for (int j = threadIdx.x; j < (int)blockIdx.x; j += kSegThreads) {
+        const unsigned long long p = part[j];
+        base_cnt += (int)(p >> 32);
+        base_last = max(base_last, (int)(p & 0xffffffffu));
+    }
+    block_reduce_sum_max(base_cnt, base_last, sh);
+
+    const int32_t i0 = (blockIdx.x * kSegThreads + threadIdx.x) * kSegTokPerThread;
+    const SegLocal loc = seg_load(tok, T, bitmap, vocab, i0);
+
+    // inclusive wave scan of (cnt, last)
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int c = loc.cnt, l = loc.last;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int tc = __shfl_up(c, off), tl = __shfl_up(l, off);
+        if (lane >= off) { c += tc; l = max(l, tl); }
+    }
+    if (lane == 63) { sh_scan[w] = c; sh_scan[kWaves + w] = l; }
+    __syncthreads();
+    int ec = __shfl_up(c, 1), el = __shfl_up(l, 1);       // exclusive within the wave
+    if (lane == 0) { ec = 0; el = 0; }
+    for (int i = 0; i < w; ++i) { ec += sh_scan[i]; el = max(el, sh_scan[kWaves + i]); }
+
+    int seg = base_cnt + ec;
+    int start = max(base_last, el);
+#pragma unroll
+    for (int k = 0; k < kSegTokPerThread; ++k) {
+        const int32_t i = i0 + k;
+        if (i >= T) break;
+        seg_id[i] = seg;
+        const bool term = (loc.flags >> k) & 1;
+        const bool closes = term || i == T - 1;
+        if (closes) {
+            if (seg < cap_sent) { sent_off[seg] = start; sent_len[seg] = i + 1 - start; }
+            if (i == T - 1) {
+                *n_sent = seg + 1;
+                if (seg + 1 <= cap_sent) sent_off[seg + 1] = T;
+            }
+            start = i + 1;
+            seg += 1;
+        }
+    }
+}
+
+hipError_t launch_segment(Ctx* c, const int32_t* tok, int32_t T, const uint32_t* bitmap, int32_t vocab,
+                          int32_t* seg_id, int32_t* sent_off, int32_t* sent_len, int32_t* n_sent_dev) {
+    const int nb = (T + kSegTokPerBlock - 1) / kSegTokPerBlock;
+    if (nb > 0) {
+        hipLaunchKernelGGL(seg_count_kernel, dim3(nb), dim3(kSegThreads), 0, c->stream, tok, T, bitmap, vocab,
+                           c->seg_part);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(seg_scan_kernel, dim3(nb > 0 ? nb : 1), dim3(kSegThreads), 0, c->stream, tok, T, bitmap, vocab,
+                       c->seg_part, seg_id, sent_off, sent_len, c->d.max_sentences, n_sent_dev);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Eq. 1: one wave per (layer * head, bucket).  A bucket's rows are contiguous in the pool, a row is
+// D * EB bytes = LPR lanes of 16 bytes, so one wave-wide load instruction covers RPW = 64 / LPR
+// consecutive rows fully coalesced.  Four such loads are kept in flight per lane.
+// ------------------------------------------------------------------------------------------------
+
+template <int EB>
+__global__ __launch_bounds__(kSemvecWavesPerBlock * kWave) void semvec_kernel(const char* __restrict__ K, int32_t T,
+                                                                              const int32_t* __restrict__ sent_off,
+                                                                              int32_t S, float* __restrict__ semvec) {
+    using R = Row<EB>;
+    constexpr int kUnroll = 4;
+    const int lane = threadIdx.x & 63;
+    const int32_t s = blockIdx.x * kSemvecWavesPerBlock + (threadIdx.x >> 6);
+    if (s >= S) return;                                   // wave-uniform
+    const int64_t lh = blockIdx.y;
+    const int32_t b = max(sent_off[s], 0), e = min(sent_off[s + 1], T);   // never read outside the pool
+    const int r = lane / R::LPR, cc = lane % R::LPR;
+    const char* base = K + (lh * T) * (int64_t)(kHeadDim * EB) + (int64_t)cc * 16;
+
+    float acc[R::EPL];
+#pragma unroll
+    for (int i = 0; i < R::EPL; ++i) acc[i] = 0.f;
+
+    for (int32_t x0 = b + r; x0 < e; x0 += R::RPW * kUnroll) {
+        uint4 v[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int32_t x = x0 + u * R::RPW;
+            v[u] = (x < e) ? *reinterpret_cast<const uint4*>(base + (int64_t)x * (kHeadDim * EB)) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            float f[R::EPL];
+            R::unpack(v[u], f);
+#pragma unroll
+            for (int i = 0; i < R::EPL; ++i) acc[i] += f[i];
+        }
+    }
+#pragma unroll
+    for (int off = R::LPR; off < 64; off <<= 1) {
+#pragma unroll
+        for (int i = 0; i < R::EPL; ++i) acc[i] += __shfl_xor(acc[i], off);
+    }
+    if (r == 0) {
+        const float n = (e > b) ? (float)(e - b) : 1.f;      // an (invalid) empty bucket yields zeros
+        float* out = semvec + (lh * S + s) * (int64_t)kHeadDim + cc * R::EPL;
+#pragma unroll
+        for (int i = 0; i < R::EPL; i += 4) {
+            float4 o = make_float4(acc[i] / n, acc[i + 1] / n, acc[i + 2] / n, acc[i + 3] / n);
+            *reinterpret_cast<float4*>(out + i) = o;
+        }
+    }
+}
+
+hipError_t launch_semvec(Ctx* c, const void* K_pool, int32_t T, const int32_t* sent_off, int32_t S, float* semvec) {
+    if (S == 0) return hipSuccess;
+    const dim3 grid((S + kSemvecWavesPerBlock - 1) / kSemvecWavesPerBlock, c->d.n_layers * c->d.n_kv_heads);
+    const dim3 block(kSemvecWavesPerBlock * kWave);
+    if (c->d.kv_dtype == SKV_BF16)
+        hipLaunchKernelGGL(semvec_kernel<2>, grid, block, 0, c->stream, (const char*)K_pool, T, sent_off, S, semvec);
+    else
+        hipLaunchKernelGGL(semvec_kernel<4>, grid, block, 0, c->stream, (const char*)K_pool, T, sent_off, S, semvec);
+    return hipGetLastError();
+}
+
+}  // namespace skv

@@ -1,0 +1,106 @@
+// Internal declarations shared by the translation units of libsentencekv (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sentencekv.h"
+
+namespace skv {
+
+constexpr int kHeadDim = 128;
+constexpr int kWave = 64;
+
+// ---- launch geometry (host and device must agree; the host checks shapes against these) ----------
+constexpr int kSegThreads = 256;
+constexpr int kSegTokPerThread = 4;
+constexpr int kSegTokPerBlock = kSegThreads * kSegTokPerThread;      // 1024 tokens per block
+
+constexpr int kSemvecWavesPerBlock = 4;                               // one wave per (layer*head, bucket)
+
+constexpr int kScoreRowsPerWave = 8;
+constexpr int kScoreWavesPerBlock = 4;
+constexpr int kScoreRowsPerBlock = kScoreRowsPerWave * kScoreWavesPerBlock;   // 32 buckets per block
+
+constexpr int kSelectThreads = 1024;
+
+constexpr int kGatherRowsPerBlock = 64;
+constexpr int kGatherThreads = 256;
+
+constexpr int kAttChunk = 64;         // tokens per split-K block (one wave-width of logits)
+constexpr int kAttThreads = 256;
+
+struct Ctx {
+    skv_desc d;
+    hipStream_t stream;
+    int device;
+    int G;
+    int max_sel;            // min(max_sentences, max_budget)
+    int max_splits;         // ceil(max_budget / kAttChunk)
+    char* ws;               // one device allocation, carved below
+    size_t ws_bytes;
+    unsigned long long* seg_part;  // [ceil(max_tokens / kSegTokPerBlock)] packed (count << 32 | last_end)
+    float* att_part;        // [max_batch * Hq][max_splits][D] un-normalised partial outputs
+    float* att_ml;          // [max_batch * Hq][max_splits][2] (running max in log2 units, sum)
+    unsigned int* att_counter;  // [max_batch * Hkv] arrivals per (sequence, KV head); zero between calls
+    float* f_score;         // [Hkv][max_sentences] scores of the fused path
+    int32_t* sel_tokpos;    // [max_batch * Hkv][max_sel] first output slot of each selected bucket
+    int32_t* f_sel_sent;    // [max_batch * Hkv][max_sel]
+    int32_t* f_n_sel;       // [max_batch * Hkv]
+    int32_t* f_n_tok;       // [max_batch * Hkv]
+    int32_t* f_tok_idx;     // [max_batch * Hkv][max_budget]
+};
+
+// Ragged-batch view handed to the decode kernels.  For single-sequence calls cu_tok / cu_sent /
+// budget_arr are null and the scalar fields apply.
+struct SeqView {
+    const int32_t* cu_tok;      // [B+1] or null
+    const int32_t* cu_sent;     // [B+1] or null
+    const int32_t* budget_arr;  // [B] or null
+    int32_t T_total;
+    int32_t S_total;
+    int32_t budget;             // scalar budget when budget_arr is null
+    int32_t B;
+};
+
+// ---- launchers (defined in prefill.hip / decode.hip); each returns the hipError_t of its launch -----
+hipError_t launch_segment(Ctx* c, const int32_t* tok, int32_t T, const uint32_t* bitmap, int32_t vocab,
+                          int32_t* seg_id, int32_t* sent_off, int32_t* sent_len, int32_t* n_sent_dev);
+hipError_t launch_semvec(Ctx* c, const void* K_pool, int32_t T, const int32_t* sent_off, int32_t S, float* semvec);
+hipError_t launch_score(Ctx* c, const void* q, const float* semvec_layer, const SeqView& v, float* score);
+hipError_t launch_select(Ctx* c, const float* score, const int32_t* sent_off, const int32_t* sent_len,
+                         const SeqView& v, int32_t* sel_sent, int32_t* tokpos, int32_t* n_sel,
+                         int32_t* tok_idx, int32_t idx_stride, int32_t* n_tok);
+hipError_t launch_gather(Ctx* c, const void* K_layer, const void* V_layer, int32_t T, const int32_t* tok_idx,
+                         const int32_t* n_tok, int32_t budget, void* K_sel, void* V_sel);
+// K/V rows come either from K_sel/V_sel [B*Hkv][row_stride][D] (tok_idx == null) or from the layer's
+// pool [Hkv][T_total][D] through tok_idx [B*Hkv][idx_stride] (positions local to the sequence).
+hipError_t launch_attend(Ctx* c, const void* q, const void* Kbase, const void* Vbase, const int32_t* tok_idx,
+                         int32_t idx_stride, int32_t row_stride, const int32_t* n_tok, int32_t n_splits,
+                         const SeqView& v, float* out, float* lse);
+
+// A K/V row is D * EB bytes = LPR lanes of 16 bytes, so one wave-wide 128-bit load covers RPW
+// consecutive rows; each lane holds EPL elements of its row.
+template <int EB> struct Row;
+template <> struct Row<2> {          // bf16: 8 elements per 16-byte lane chunk
+    static constexpr int LPR = 16, RPW = 4, EPL = 8;
+    __device__ static __forceinline__ void unpack(const uint4& v, float* f) {
+        f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
+        f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
+        f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xffff0000u);
+        f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
+    }
+};
+template <> struct Row<4> {          // fp32: 4 elements per 16-byte lane chunk
+    static constexpr int LPR = 32, RPW = 2, EPL = 4;
+    __device__ static __forceinline__ void unpack(const uint4& v, float* f) {
+        f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
+        f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+    }
+};
+
+}  // namespace skv
+
+struct skv_ctx {
+    skv::Ctx c;
+};

@@ -1,0 +1,99 @@
+"""Helpers for the GPU parity tests: allocate device buffers, call the C ABI through the binding,
+bring results back as numpy.  No arithmetic of the method lives here."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import paper_2504_00970_amd as skv
+from workload import gen
+
+DEV = "cuda:0"
+
+
+def i32(a, device=DEV):
+    return torch.as_tensor(np.ascontiguousarray(a, dtype=np.int32)).to(device)
+
+
+def empty_i32(*shape, fill=None):
+    t = torch.empty(*shape, dtype=torch.int32, device=DEV)
+    if fill is not None:
+        t.fill_(fill)
+    return t
+
+
+def make_ctx(wl: gen.Workload, T, S, budget, batch=1):
+    return skv.Context(skv.Desc(n_layers=wl.n_layers, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
+                                kv_dtype=skv.dtype_code(wl.torch_dtype), max_tokens=max(T, 1),
+                                max_sentences=max(S, 1), max_budget=max(budget, 1), max_batch=batch))
+
+
+def np_of(t: torch.Tensor) -> np.ndarray:
+    return gen.to_numpy(t.detach().cpu())
+
+
+def gpu_segment(ctx, tok: np.ndarray, bitmap: np.ndarray, vocab: int, cap: int):
+    T = len(tok)
+    d_tok = i32(tok) if T else empty_i32(4)
+    d_bm = torch.as_tensor(bitmap.view(np.int32)).to(DEV)
+    seg_id = empty_i32(max(T, 4), fill=-7)
+    off = empty_i32(cap + 1 + 4, fill=-7)
+    ln = empty_i32(cap + 4, fill=-7)
+    n = empty_i32(4, fill=-7)
+    d_tok_view = d_tok[:T] if T else d_tok[:0]
+    S = ctx.segment(d_tok_view, d_bm, vocab, seg_id, off, ln, n)
+    torch.cuda.synchronize()
+    return seg_id.cpu().numpy()[:T], off.cpu().numpy(), ln.cpu().numpy(), S, int(n.cpu()[0])
+
+
+def gpu_decode_chain(ctx, wl, layer, q_dev, K_dev, V_dev, semvec_dev, sent_off, sent_len, budget, pool_in_host=False):
+    """score -> select -> gather -> attend through the four C entry points.  Returns numpy results."""
+    H, Hq, D = wl.n_kv_heads, wl.n_q_heads, wl.head_dim
+    T = K_dev.shape[2]
+    S = len(sent_len)
+    max_sel = ctx.desc.max_sel
+    d_off, d_len = i32(sent_off), i32(sent_len) if S else empty_i32(4)
+    score = torch.full((H, max(S, 1)), -777.0, dtype=torch.float32, device=DEV)
+    sel = empty_i32(H, max_sel, fill=-1)
+    n_sel, n_tok = empty_i32(max(H, 4), fill=-5), empty_i32(max(H, 4), fill=-5)
+    tok_idx = empty_i32(H, max(budget, 1), fill=-1)
+    K_sel = torch.zeros(H, max(budget, 1), D, dtype=wl.torch_dtype, device=DEV)
+    V_sel = torch.zeros_like(K_sel)
+    out = torch.full((Hq, D), 555.0, dtype=torch.float32, device=DEV)
+    lse = torch.full((max(Hq, 4),), 555.0, dtype=torch.float32, device=DEV)
+    ctx.score(layer, q_dev, semvec_dev, S, score)
+    ctx.select(score, d_off, d_len, S, budget, sel, n_sel, tok_idx, n_tok)
+    ctx.gather(layer, K_dev, V_dev, T, tok_idx, n_tok, budget, K_sel, V_sel, pool_in_host=pool_in_host)
+    ctx.attend(q_dev, K_sel, V_sel, n_tok, budget, out, lse)
+    torch.cuda.synchronize()
+    return dict(score=score.cpu().numpy()[:, :S], sel_sent=sel.cpu().numpy(), n_sel=n_sel.cpu().numpy()[:H],
+                tok_idx=tok_idx.cpu().numpy(), n_tok=n_tok.cpu().numpy()[:H], K_sel=np_of(K_sel), V_sel=np_of(V_sel),
+                out=out.cpu().numpy(), lse=lse.cpu().numpy()[:Hq])
+
+
+def score_tolerance(score_ref: np.ndarray) -> np.ndarray:
+    """Allowed |gpu - oracle| per score: 1e-5 relative to the larger of |score| and the head's rms score.
+    Both sides sum the same G*D = 512..1024 fp32 products in different orders; the rounding error of
+    such a sum scales with the magnitude of its partial sums (the rms score), not with a score that
+    happens to cancel to near zero."""
+    rms = np.sqrt((score_ref.astype(np.float64) ** 2).mean(axis=1, keepdims=True)) if score_ref.size else 0.0
+    return 1e-5 * np.maximum(np.abs(score_ref), rms)
+
+
+def ranking(score: np.ndarray) -> np.ndarray:
+    """Bucket ids by (score descending, id ascending); NaN last."""
+    key = np.where(np.isnan(score), -np.inf, score.astype(np.float64))
+    return np.lexsort((np.arange(len(score)), np.isnan(score), -key))
+
+
+def documented_tie(score_cpu: np.ndarray, score_gpu: np.ndarray, upto: int, rel=1e-5):
+    """Among the first `upto` ranks (the part of the ranking that decides the selection) the two
+    rankings first diverge at a pair of buckets; returns (is_tie, a, b, relative gap of the oracle's
+    scores of that pair).  A selection difference is acceptable only when that gap is < rel."""
+    oc, og = ranking(score_cpu)[:upto], ranking(score_gpu)[:upto]
+    neq = np.nonzero(oc != og)[0]
+    if len(neq) == 0:
+        return True, -1, -1, 0.0
+    a, b = int(oc[neq[0]]), int(og[neq[0]])
+    gap = abs(float(score_cpu[a]) - float(score_cpu[b])) / max(abs(float(score_cpu[a])), abs(float(score_cpu[b])), 1e-30)
+    return gap < rel, a, b, gap
