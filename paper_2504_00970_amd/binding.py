@@ -138,9 +138,11 @@ class Context:
         return int(_lib().skv_workspace_bytes(self._h))
 
     # ---- (1) prefill ----------------------------------------------------------------------------
-    def segment(self, tok, term_bitmap, vocab: int, seg_id, sent_off, sent_len, n_sent_dev, sync: bool = True) -> Optional[int]:
+    def segment(self, tok, term_bitmap, vocab: int, seg_id, sent_off, sent_len, n_sent_dev, sync: bool = True,
+                T: Optional[int] = None) -> Optional[int]:
         host = ctypes.c_int32(-1)
-        rc = _lib().skv_segment(self._h, _p(tok), tok.shape[0], _p(term_bitmap), vocab, _p(seg_id), _p(sent_off),
+        T = tok.shape[0] if T is None else T
+        rc = _lib().skv_segment(self._h, _p(tok), T, _p(term_bitmap), vocab, _p(seg_id), _p(sent_off),
                                 _p(sent_len), _p(n_sent_dev), ctypes.addressof(host) if sync else None)
         _check(rc, "skv_segment")
         return int(host.value) if sync else None

@@ -40,8 +40,7 @@ def gpu_segment(ctx, tok: np.ndarray, bitmap: np.ndarray, vocab: int, cap: int):
     off = empty_i32(cap + 1 + 4, fill=-7)
     ln = empty_i32(cap + 4, fill=-7)
     n = empty_i32(4, fill=-7)
-    d_tok_view = d_tok[:T] if T else d_tok[:0]
-    S = ctx.segment(d_tok_view, d_bm, vocab, seg_id, off, ln, n)
+    S = ctx.segment(d_tok, d_bm, vocab, seg_id, off, ln, n, T=T)
     torch.cuda.synchronize()
     return seg_id.cpu().numpy()[:T], off.cpu().numpy(), ln.cpu().numpy(), S, int(n.cpu()[0])
 

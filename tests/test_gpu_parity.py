@@ -50,7 +50,12 @@ def test_segment_bit_exact(U, oracle32, T):
     assert np.all(off[S_ref + 1:] == -7) and np.all(ln[S_ref:] == -7)      # nothing written past S
 
 
-@pytest.mark.parametrize("text", ["aaaa", "....", "aaa.", ".aaa", "a", ".", "a.a.a.a.", "aa..a", "." * 2050, "a" * 3000 + "."])
+_STREAMS = {"no_term": "aaaa", "all_term": "....", "term_last": "aaa.", "term_first": ".aaa", "one_tok": "a",
+            "one_term": ".", "alternating": "a.a.a.a.", "run_of_terms": "aa..a", "2050_terms": "." * 2050,
+            "3000_then_term": "a" * 3000 + "."}
+
+
+@pytest.mark.parametrize("text", list(_STREAMS.values()), ids=list(_STREAMS.keys()))
 def test_segment_hand_built_streams(U, oracle32, text):
     tok = np.array([7 if c == "." else 3 for c in text], dtype=np.int32)
     bitmap = np.zeros(2, dtype=np.uint32)
@@ -80,7 +85,7 @@ def test_segment_reports_capacity_overflow(U, oracle32):
 @pytest.mark.parametrize("dist", [("geometric", 0.05), ("uniform", 8, 40), ("fixed", 1), ("fixed", 257)])
 def test_semvec_matches_oracle(U, oracle32, dtype, dist):
     _say("semvec", dtype, dist)
-    wl = gen.CFG3.scaled(n_layers=3, n_kv_heads=2, n_tokens=3001, dtype=dtype, len_dist=dist)
+    wl = gen.CFG3.scaled(n_layers=3, n_kv_heads=2, n_q_heads=8, n_tokens=3001, dtype=dtype, len_dist=dist)
     lens = gen.sentence_lengths(wl.len_dist, wl.n_tokens, seed=5)
     off = gen.offsets_of(lens)
     S = len(lens)
@@ -157,7 +162,7 @@ def _chain_case(U, oracle32, wl, seed, budget, pool_in_host=False, layers=None):
         assert err <= ATT_TOL[wl.dtype], err
         fin = np.isfinite(lse_ref)
         assert np.array_equal(np.isfinite(g["lse"]), fin)
-        assert np.abs(g["lse"][fin] - lse_ref[fin]).max() <= ATT_TOL[wl.dtype]
+        assert not fin.any() or np.abs(g["lse"][fin] - lse_ref[fin]).max() <= ATT_TOL[wl.dtype]
     return n_ties
 
 
@@ -331,7 +336,7 @@ def _fused_case(U, oracle32, wl, seed, layers):
             o_ref, l_ref = oracle32.attend(q, Ks, Vs, n_ref)
             assert np.abs(o[b] - o_ref).max() <= ATT_TOL[wl.dtype]
             fin = np.isfinite(l_ref)
-            assert np.abs(ls[b][fin] - l_ref[fin]).max() <= ATT_TOL[wl.dtype]
+            assert not fin.any() or np.abs(ls[b][fin] - l_ref[fin]).max() <= ATT_TOL[wl.dtype]
         # without the optional outputs the result is the same
         out2 = torch.zeros_like(out)
         ctx.decode_step(li, B, qd[li], qd[li], Kd, Vd, T_total, sv, S_total, d["cu_tok"], d["cu_sent"], d["sent_off"],
