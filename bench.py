@@ -1,0 +1,287 @@
+#!/usr/bin/env python3
+"""Benchmark of the SentenceKV decode hot path on one MI355X.
+
+A "step" is one decode step of the whole model: for every layer, one skv_decode_step call
+(scores of all buckets -> budgeted selection -> attention over the retrieved tokens read straight
+from the HBM pool).  The prefill side (segmentation + mean key vectors) runs once before the timed
+region and is timed separately.  Inputs are synthetic and resident in HBM before timing starts.
+
+Prints ONE JSON line:  metric / value = achieved HBM GB/s of the decode step (algorithmic bytes of
+the fused path over wall time), us_per_layer, per-kernel live timings, the roofline of the
+attention kernel, and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import paper_2504_00970_amd as skv          # noqa: E402
+from workload import gen                    # noqa: E402
+
+HBM_PEAK_GBPS = 8000.0                      # MI355X datasheet HBM3E bandwidth
+N_QUERY_SETS = 16                           # distinct query sets rotated across steps
+
+
+def i32(a, dev):
+    return torch.as_tensor(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
+
+
+class Timer:
+    """HIP events on the stream the kernels are launched on (torch's current stream)."""
+
+    def __init__(self):
+        self.a = torch.cuda.Event(enable_timing=True)
+        self.b = torch.cuda.Event(enable_timing=True)
+
+    def __enter__(self):
+        self.a.record()
+        return self
+
+    def __exit__(self, *exc):
+        self.b.record()
+        self.b.synchronize()
+        self.ms = self.a.elapsed_time(self.b)
+
+
+def capture(ctx, fn):
+    """Record fn()'s launches into a HIP graph (the library launches on the capturing stream)."""
+    g = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g):
+        ctx.set_stream(torch.cuda.current_stream().cuda_stream)
+        fn()
+    ctx.set_stream(torch.cuda.current_stream().cuda_stream)
+    return g
+
+
+def decode_bytes(wl, S, n_tok_sum, n_sel_sum, fused=True):
+    """Algorithmic bytes of one layer's decode step (what the method itself has to move)."""
+    H, D, e = wl.n_kv_heads, wl.head_dim, wl.elt_bytes
+    q_bytes = wl.n_q_heads * D * e
+    score = S * H * D * 4 + S * H * 4 + q_bytes
+    select = S * H * 4 + S * 8 + (n_tok_sum + 2 * n_sel_sum) * 4
+    kv = 2 * n_tok_sum * D * e
+    attend = kv + n_tok_sum * 4 + q_bytes + wl.n_q_heads * D * 4
+    gather = 2 * kv + n_tok_sum * 4
+    total = score + select + attend + (0 if fused else gather)
+    return dict(score=score, select=select, gather=gather, attend=attend, total=total)
+
+
+def run_single_sequence(args, wl, budget):
+    dev = "cuda:0"
+    L, H, Hq, D, T = wl.n_layers, wl.n_kv_heads, wl.n_q_heads, wl.head_dim, wl.n_tokens
+    t0 = time.time()
+    lengths = gen.sentence_lengths(wl.len_dist, T, args.seed)
+    tok = gen.token_stream(lengths, wl.vocab, wl.term_mod, args.seed)
+    bitmap = gen.terminator_bitmap(wl.vocab, wl.term_mod)
+    inp = gen.decode_inputs(wl, seed=args.seed, device=dev)
+    qsets = gen.queries(N_QUERY_SETS * L, Hq, D, wl.torch_dtype, args.seed + 1, dev).view(N_QUERY_SETS, L, Hq, D)
+    torch.cuda.synchronize()
+    gen_s = time.time() - t0
+
+    S_cap = len(lengths) + 8
+    ctx = skv.Context(skv.Desc(n_layers=L, n_q_heads=Hq, n_kv_heads=H, kv_dtype=skv.dtype_code(wl.torch_dtype),
+                               max_tokens=T, max_sentences=S_cap, max_budget=budget, max_batch=1))
+
+    # ---- prefill: segmentation + semantic vectors (HIP path), timed once -----------------------------
+    d_tok, d_bm = i32(tok, dev), torch.as_tensor(bitmap.view(np.int32)).to(dev)
+    seg_id = torch.empty(T, dtype=torch.int32, device=dev)
+    sent_off = torch.empty(S_cap + 1, dtype=torch.int32, device=dev)
+    sent_len = torch.empty(S_cap, dtype=torch.int32, device=dev)
+    n_sent = torch.empty(4, dtype=torch.int32, device=dev)
+    S = ctx.segment(d_tok, d_bm, wl.vocab, seg_id, sent_off, sent_len, n_sent)
+    assert S == len(lengths), (S, len(lengths))
+    semvec = torch.empty(L, H, S, D, dtype=torch.float32, device=dev)
+    ctx.build_semvec(inp.K, sent_off, S, semvec)
+    torch.cuda.synchronize()
+    with Timer() as t_seg:
+        ctx.segment(d_tok, d_bm, wl.vocab, seg_id, sent_off, sent_len, n_sent, sync=False)
+    with Timer() as t_sv:
+        ctx.build_semvec(inp.K, sent_off, S, semvec)
+    semvec_bytes = L * H * T * D * wl.elt_bytes + L * H * S * D * 4
+
+    # ---- decode ---------------------------------------------------------------------------------------
+    cu_tok, cu_sent = i32([0, T], dev), i32([0, S], dev)
+    d_budget = i32([budget], dev)
+    out = torch.empty(L, Hq, D, dtype=torch.float32, device=dev)
+    n_tok_rec = torch.zeros(N_QUERY_SETS, L, H, dtype=torch.int32, device=dev)
+
+    q_cur = torch.empty(L, Hq, D, dtype=wl.torch_dtype, device=dev)     # the step's queries (graph input)
+
+    def layers(record_into=None):
+        for l in range(L):
+            ctx.decode_step(l, 1, q_cur[l], q_cur[l], inp.K, inp.V, T, semvec, S, cu_tok, cu_sent, sent_off, sent_len,
+                            d_budget, out[l], None, None, None if record_into is None else record_into[l])
+
+    for i in range(N_QUERY_SETS):            # records n_tok of every (query set, layer)
+        q_cur.copy_(qsets[i])
+        layers(record_into=n_tok_rec[i])
+    torch.cuda.synchronize()
+
+    def timed(run_step):
+        for i in range(args.warmup):
+            q_cur.copy_(qsets[i % N_QUERY_SETS])
+            run_step()
+        torch.cuda.synchronize()
+        wall0 = time.perf_counter()
+        with Timer() as t:
+            for i in range(args.steps):
+                q_cur.copy_(qsets[i % N_QUERY_SETS])
+                run_step()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - wall0
+        return max(t.ms, wall * 1e3) / max(args.steps, 1)
+
+    ms_direct = timed(layers)                # one host call per layer
+    graph = capture(ctx, layers)             # the same launches replayed as one HIP graph per decode step
+    ms_graph = timed(graph.replay)
+    ms_per_step = ms_graph if args.launch == "graph" else ms_direct
+
+    n_tok_all = n_tok_rec.cpu().numpy().astype(np.int64)
+    used = [i % N_QUERY_SETS for i in range(args.steps)]
+    n_tok_layer = float(n_tok_all[used].sum(axis=2).mean()) if used else 0.0     # sum over heads, mean over layer-steps
+    n_sel_layer = n_tok_layer / float(lengths.mean())
+    bytes_layer = decode_bytes(wl, S, n_tok_layer, n_sel_layer, fused=True)
+    us_per_layer = ms_per_step * 1e3 / L
+    gbps = bytes_layer["total"] / (us_per_layer * 1e-6) / 1e9
+
+    # ---- per-kernel live timing: each stage launched back-to-back over all layers ------------------------
+    score = torch.empty(L, H, S, dtype=torch.float32, device=dev)
+    sel = torch.empty(L, H, ctx.desc.max_sel, dtype=torch.int32, device=dev)
+    n_sel = torch.empty(L, 8 if H < 8 else H, dtype=torch.int32, device=dev)
+    n_tok = torch.empty(L, 8 if H < 8 else H, dtype=torch.int32, device=dev)
+    tok_idx = torch.empty(L, H, budget, dtype=torch.int32, device=dev)
+    K_sel = torch.empty(L, H, budget, D, dtype=wl.torch_dtype, device=dev)
+    V_sel = torch.empty_like(K_sel)
+    lse = torch.empty(L, Hq, dtype=torch.float32, device=dev)
+    qs = qsets[0]
+    stages = {
+        "score": lambda l: ctx.score(l, qs[l], semvec, S, score[l]),
+        "select": lambda l: ctx.select(score[l], sent_off, sent_len, S, budget, sel[l], n_sel[l], tok_idx[l], n_tok[l]),
+        "gather": lambda l: ctx.gather(l, inp.K, inp.V, T, tok_idx[l], n_tok[l], budget, K_sel[l], V_sel[l]),
+        "attend": lambda l: ctx.attend(qs[l], K_sel[l], V_sel[l], n_tok[l], budget, out[l], lse[l]),
+    }
+    kern = {}
+    reps = max(2, min(20, args.steps))
+    for name, fn in stages.items():
+        def all_layers(fn=fn):
+            for l in range(L):
+                fn(l)
+        all_layers()
+        g = capture(ctx, all_layers)
+        g.replay()
+        torch.cuda.synchronize()
+        with Timer() as t:
+            for _ in range(reps):
+                g.replay()
+        kern[name] = t.ms * 1e3 / (reps * L)
+    nt_chain = float(n_tok[:, :H].sum().item()) / L
+    b_unf = decode_bytes(wl, S, nt_chain, nt_chain / float(lengths.mean()), fused=False)
+    kernels = {k: dict(us=round(v, 3), bytes=int(b_unf[k]), GBps=round(b_unf[k] / (v * 1e-6) / 1e9, 1))
+               for k, v in kern.items()}
+    att = kernels["attend"]
+    roofline = dict(bound="hbm", kernel="attend_kernel", achieved=att["GBps"], peak=HBM_PEAK_GBPS, unit="GB/s",
+                    frac=round(att["GBps"] / HBM_PEAK_GBPS, 4), traffic=None,
+                    bytes_per_launch=att["bytes"], us_per_launch=att["us"])
+
+    cpu = cpu_baseline(args, wl, inp, semvec, lengths, qsets, budget) if not args.no_cpu_baseline else None
+
+    return {
+        "metric": "decode-step achieved HBM GB/s (score+select+gather+attn) at %s ctx" % _ctx_name(T),
+        "value": round(gbps, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "layers": L, "q_heads": Hq, "kv_heads": H, "head_dim": D, "context": T,
+                   "sentences": S, "budget": budget, "batch": 1, "path": "skv_decode_step (score+select+attend from pool)",
+                   "kv_pool": "hbm", "launch": args.launch},
+        "us_per_layer": round(us_per_layer, 3),
+        "us_per_layer_direct_launch": round(ms_direct * 1e3 / L, 3),
+        "us_per_layer_hip_graph": round(ms_graph * 1e3 / L, 3),
+        "bytes_per_layer": int(bytes_layer["total"]),
+        "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4),
+        "mean_tokens_selected_per_head": round(n_tok_layer / H, 1),
+        "kernels_unfused": kernels,
+        "unfused_us_per_layer": round(sum(kern.values()), 3),
+        "unfused_GBps": round(b_unf["total"] / (sum(kern.values()) * 1e-6) / 1e9, 1),
+        "prefill": {"segment_us": round(t_seg.ms * 1e3, 1), "semvec_ms": round(t_sv.ms, 3),
+                    "semvec_GBps": round(semvec_bytes / (t_sv.ms * 1e-3) / 1e9, 1)},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "input_gen_s": round(gen_s, 1),
+    }
+
+
+def _ctx_name(T):
+    return "%dk" % (T // 1024) if T % 1024 == 0 else str(T)
+
+
+def cpu_baseline(args, wl, inp, semvec, lengths, qsets, budget):
+    """The CPU oracle, as it stands, on the same inputs: whole decode steps (all layers) until ~10 s."""
+    import oracle
+    orc = oracle.get("f32")
+    L, H = wl.n_layers, wl.n_kv_heads
+    off = gen.offsets_of(lengths)
+    n_layers = min(L, args.cpu_layers)
+    Kh = [gen.to_numpy(inp.K[l]) for l in range(n_layers)]
+    Vh = [gen.to_numpy(inp.V[l]) for l in range(n_layers)]
+    svh = [semvec[l].cpu().numpy() for l in range(n_layers)]
+    qh = [gen.to_numpy(qsets[0, l]) for l in range(n_layers)]
+    done, t_total, n_tok_sum = 0, 0.0, 0
+    t_end = time.perf_counter() + args.cpu_seconds
+    while True:
+        for l in range(n_layers):
+            t0 = time.perf_counter()
+            r = orc.decode_step(qh[l], qh[l], Kh[l], Vh[l], svh[l], off, lengths, budget)
+            t_total += time.perf_counter() - t0
+            n_tok_sum += int(r["n_tok"].sum())
+            done += 1
+        if time.perf_counter() > t_end:
+            break
+    us_layer = t_total / done * 1e6
+    b = decode_bytes(wl, len(lengths), n_tok_sum / done, n_tok_sum / done / float(lengths.mean()), fused=True)
+    return {"value": round(b["total"] / (us_layer * 1e-6) / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "us_per_layer": round(us_layer, 1),
+            "sample": "%d layer-steps of the same workload (layers 0..%d, query set 0), score+select+gather+attend, "
+                      "single thread, fp32" % (done, n_layers - 1)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2"])
+    ap.add_argument("--budget", type=int, default=0, help="token budget (default: the workload's largest)")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--launch", default="graph", choices=["graph", "direct"],
+                    help="graph: the step's launches replayed as one HIP graph; direct: one host call per layer")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--cpu-layers", type=int, default=32)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the path has no multi-GPU form in this build (run with --gpus 1)",
+              file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    wl = gen.CONFIGS[args.workload]
+    budget = args.budget or max(wl.budgets)
+    res = run_single_sequence(args, wl, budget)
+    res["host"] = {"nproc": os.cpu_count()}
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

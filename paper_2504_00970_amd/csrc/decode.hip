@@ -71,12 +71,13 @@ __global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_kernel(cons
     constexpr int kIter = kScoreRowsPerWave / 2;
     const int32_t row0 = blk * kScoreRowsPerBlock + w * kScoreRowsPerWave + half;
     const float* base = semvec + ((int64_t)h * v.S_total + sq.sent_base) * kHeadDim + c * 4;
+    // Addresses are clamped into the sequence instead of predicating the loads, so that all of a
+    // lane's loads are issued back to back; rows past the end are computed and dropped.
     float4 x[kIter];
 #pragma unroll
     for (int i = 0; i < kIter; ++i) {
-        const int32_t s = row0 + 2 * i;
-        x[i] = (s < sq.n_sent) ? *reinterpret_cast<const float4*>(base + (int64_t)s * kHeadDim)
-                               : make_float4(0.f, 0.f, 0.f, 0.f);
+        const int32_t s = min(row0 + 2 * i, sq.n_sent - 1);
+        x[i] = *reinterpret_cast<const float4*>(base + (int64_t)s * kHeadDim);
     }
     float p[kIter];
 #pragma unroll
@@ -317,24 +318,25 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(const char* __re
     const char* src = (blockIdx.z == 0 ? Kl : Vl) + (int64_t)h * T * kRowBytes;
     char* dst = (blockIdx.z == 0 ? Ks : Vs) + (int64_t)h * budget * kRowBytes;
     const int r = threadIdx.x / R::LPR, cc = threadIdx.x % R::LPR;
-    uint4 val[kIter];
-    bool ok[kIter];
+    if (T <= 0) return;
+    // Branch-free: indices and rows are clamped into range so every load can be issued up front
+    // (two dependent rounds: all indices, then all rows); only the stores are predicated.
+    int32_t x[kIter];
 #pragma unroll
     for (int i = 0; i < kIter; ++i) {
-        const int32_t j = j0 + i * kRowsPerIter + r;
-        ok[i] = false;
-        if (j < n) {
-            const int32_t x = tok_idx[(int64_t)h * budget + j];
-            if (x >= 0 && x < T) {
-                ok[i] = true;
-                val[i] = *reinterpret_cast<const uint4*>(src + (int64_t)x * kRowBytes + cc * 16);
-            }
-        }
+        const int32_t j = min(j0 + i * kRowsPerIter + r, n - 1);
+        x[i] = tok_idx[(int64_t)h * budget + j];
+    }
+    uint4 val[kIter];
+#pragma unroll
+    for (int i = 0; i < kIter; ++i) {
+        const int32_t xc = min(max(x[i], 0), T - 1);
+        val[i] = *reinterpret_cast<const uint4*>(src + (int64_t)xc * kRowBytes + cc * 16);
     }
 #pragma unroll
     for (int i = 0; i < kIter; ++i) {
         const int32_t j = j0 + i * kRowsPerIter + r;
-        if (ok[i]) *reinterpret_cast<uint4*>(dst + (int64_t)j * kRowBytes + cc * 16) = val[i];
+        if (j < n && x[i] >= 0 && x[i] < T) *reinterpret_cast<uint4*>(dst + (int64_t)j * kRowBytes + cc * 16) = val[i];
     }
 }
 
@@ -362,7 +364,7 @@ hipError_t launch_gather(Ctx* c, const void* K_layer, const void* V_layer, int32
 //   5. the un-normalised partial (m, l, acc) goes to the workspace; the last block to arrive for the
 //      (sequence, KV head) -- a device-scope counter, no spinning -- rescales and sums the partials.
 // ------------------------------------------------------------------------------------------------
-template <int EB, int G>
+template <int EB, int G, bool IND>
 __global__ __launch_bounds__(kAttThreads) void attend_kernel(const char* __restrict__ q, const char* __restrict__ Kb,
                                                              const char* __restrict__ Vb, const int32_t* __restrict__ tok_idx,
                                                              int32_t idx_stride, int32_t row_stride,
@@ -378,7 +380,9 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(const char* __restr
     constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
 
     __shared__ float sm_logit[G][kAttChunk];
-    __shared__ float sm_red[kWaves][G][kHeadDim];
+    constexpr int kRedFloats = (kWaves * G * kHeadDim > 1024) ? kWaves * G * kHeadDim : 1024;
+    __shared__ __attribute__((aligned(16))) float sm_red_flat[kRedFloats];
+    float (*sm_red)[G][kHeadDim] = reinterpret_cast<float (*)[G][kHeadDim]>(sm_red_flat);
     __shared__ int sm_last;
 
     const int bh = blockIdx.y, b = bh / Hkv, h = bh % Hkv, split = blockIdx.x;
@@ -389,7 +393,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(const char* __restr
     const Seq sq = seq_of(v, b);
 
     int32_t n = n_tok[bh];
-    n = min(n, tok_idx ? idx_stride : row_stride);
+    n = min(n, IND ? idx_stride : row_stride);
     if (n <= 0) {
         if (split == 0) {
             for (int i = tid; i < G * kHeadDim; i += kAttThreads) out[qhead0 * kHeadDim + i] = 0.f;
@@ -405,37 +409,35 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(const char* __restr
     // ---- 1. issue every load of the chunk ------------------------------------------------------------
     const char* Kh;
     const char* Vh;
-    if (tok_idx) {
+    if (IND) {
         Kh = Kb + ((int64_t)h * v.T_total + sq.tok_base) * kRowBytes;
         Vh = Vb + ((int64_t)h * v.T_total + sq.tok_base) * kRowBytes;
     } else {
         Kh = Kb + ((int64_t)bh * row_stride + j0) * kRowBytes;
         Vh = Vb + ((int64_t)bh * row_stride + j0) * kRowBytes;
     }
+    // Branch-free loads: rows past the chunk's end (and indices outside the sequence) are clamped to a
+    // valid row, loaded anyway and masked afterwards, so that all loads are in flight together.
     int32_t rowi[kIter];
+    bool live[kIter];
 #pragma unroll
     for (int i = 0; i < kIter; ++i) {
         const int jj = i * kRowsPerIter + w * R::RPW + r;
-        rowi[i] = -1;
-        if (jj < cnt) {
-            if (tok_idx) {
-                const int32_t x = tok_idx[(int64_t)bh * idx_stride + j0 + jj];
-                rowi[i] = (x >= 0 && x < sq.n_tok_ctx) ? x : -1;
-            } else {
-                rowi[i] = jj;
-            }
+        live[i] = jj < cnt;
+        const int jc = min(jj, cnt - 1);
+        if (IND) {
+            const int32_t x = tok_idx[(int64_t)bh * idx_stride + j0 + jc];
+            live[i] = live[i] && x >= 0 && x < sq.n_tok_ctx;
+            rowi[i] = min(max(x, 0), max(sq.n_tok_ctx - 1, 0));
+        } else {
+            rowi[i] = jc;
         }
     }
     uint4 kraw[kIter], vraw[kIter];
 #pragma unroll
     for (int i = 0; i < kIter; ++i) {
-        if (rowi[i] >= 0) {
-            kraw[i] = *reinterpret_cast<const uint4*>(Kh + (int64_t)rowi[i] * kRowBytes + cc * 16);
-            vraw[i] = *reinterpret_cast<const uint4*>(Vh + (int64_t)rowi[i] * kRowBytes + cc * 16);
-        } else {
-            kraw[i] = make_uint4(0, 0, 0, 0);
-            vraw[i] = make_uint4(0, 0, 0, 0);
-        }
+        kraw[i] = *reinterpret_cast<const uint4*>(Kh + (int64_t)rowi[i] * kRowBytes + cc * 16);
+        vraw[i] = *reinterpret_cast<const uint4*>(Vh + (int64_t)rowi[i] * kRowBytes + cc * 16);
     }
     float qf[G][R::EPL];
 #pragma unroll
@@ -466,7 +468,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(const char* __restr
         if (cc == 0) {
             const int jj = i * kRowsPerIter + w * R::RPW + r;
 #pragma unroll
-            for (int g = 0; g < G; ++g) sm_logit[g][jj] = (rowi[i] >= 0) ? s[g] * scale : -INFINITY;
+            for (int g = 0; g < G; ++g) sm_logit[g][jj] = live[i] ? s[g] * scale : -INFINITY;
         }
     }
     __syncthreads();
@@ -500,6 +502,10 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(const char* __restr
         const int jj = i * kRowsPerIter + w * R::RPW + r;
         float vf[R::EPL];
         R::unpack(vraw[i], vf);
+        if (!live[i]) {                                      // masked rows hold a clamped (foreign) row
+#pragma unroll
+            for (int e = 0; e < R::EPL; ++e) vf[e] = 0.f;
+        }
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             const float p = sm_logit[g][jj];
@@ -530,7 +536,8 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(const char* __restr
     }
 
     // ---- 5. last arrival combines ------------------------------------------------------------------
-    __threadfence();
+    // The barrier orders the block's partial stores before thread 0's device-scope acq_rel increment
+    // (which publishes them); the second barrier hands thread 0's acquire to the rest of the block.
     __syncthreads();
     if (tid == 0) {
         const unsigned int old = __hip_atomic_fetch_add(&counter[bh], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
@@ -538,23 +545,66 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(const char* __restr
     }
     __syncthreads();
     if (!sm_last) return;
-    __threadfence();
-    for (int i = tid; i < G * kHeadDim; i += kAttThreads) {
-        const int g = i / kHeadDim, d = i % kHeadDim;
-        const float* mlg = ml + ((qhead0 + g) * max_splits) * 2;
-        const float* pg = part + ((qhead0 + g) * max_splits) * kHeadDim + d;
+    // (a) per query head: global max, normaliser, and each split's weight (stored over its max);
+    //     one wave per head, lanes stride over the splits so their loads are independent.
+    for (int g = w; g < G; g += kWaves) {
+        float* mlg = ml + ((qhead0 + g) * max_splits) * 2;
         float M = -INFINITY;
-        for (int s = 0; s < nsplit; ++s) M = fmaxf(M, mlg[2 * s]);
-        float L = 0.f, O = 0.f;
-        for (int s = 0; s < nsplit; ++s) {
+        for (int s = lane; s < nsplit; s += kWave) M = fmaxf(M, mlg[2 * s]);
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
+        float L = 0.f;
+        for (int s = lane; s < nsplit; s += kWave) {
             const float ms = mlg[2 * s];
-            const float wgt = (ms == -INFINITY) ? 0.f : exp2f(ms - M);
-            L += wgt * mlg[2 * s + 1];
-            O += wgt * pg[(int64_t)s * kHeadDim];
+            L += (ms == -INFINITY) ? 0.f : exp2f(ms - M) * mlg[2 * s + 1];
         }
-        const bool empty = !(L > 0.f);      // every retrieved index was out of range
-        out[(qhead0 + g) * kHeadDim + d] = empty ? 0.f : O / L;
-        if (lse && d == 0) lse[qhead0 + g] = empty ? -INFINITY : (M + log2f(L)) * kLn2;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) L += __shfl_xor(L, off);
+        const bool empty = !(L > 0.f);                       // every retrieved index was out of range
+        const float inv = empty ? 0.f : 1.f / L;
+        for (int s = lane; s < nsplit; s += kWave) {
+            const float ms = mlg[2 * s];
+            mlg[2 * s] = (ms == -INFINITY) ? 0.f : exp2f(ms - M) * inv;
+        }
+        if (lse && lane == 0) lse[qhead0 + g] = empty ? -INFINITY : (M + log2f(L)) * kLn2;
+    }
+    __syncthreads();
+    // (b) out[g][:] = sum_s weight[g][s] * partial[g][s][:].  A thread owns one float4 column of one head
+    //     and every kGroups-th split; the groups are then summed through LDS.
+    constexpr int kCol4 = G * (kHeadDim / 4);                // float4 columns over the G heads
+    constexpr int kGroups = kAttThreads / kCol4;             // 8, 4, 2, 1 for G = 1, 2, 4, 8
+    {
+        const int col = tid % kCol4, grp = tid / kCol4;
+        const int g = col / (kHeadDim / 4), d4 = col % (kHeadDim / 4);
+        const float* mlg = ml + ((qhead0 + g) * max_splits) * 2;
+        const float4* pg = reinterpret_cast<const float4*>(part + ((qhead0 + g) * max_splits) * kHeadDim) + d4;
+        float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+        constexpr int kU = 8;
+        for (int s0 = grp; s0 < nsplit; s0 += kGroups * kU) {
+            float4 v[kU];
+            float wgt[kU];
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {                   // clamped, unconditional loads
+                const int sidx = min(s0 + u * kGroups, nsplit - 1);
+                v[u] = pg[(int64_t)sidx * (kHeadDim / 4)];
+                wgt[u] = (s0 + u * kGroups < nsplit) ? mlg[2 * sidx] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {
+                o.x += wgt[u] * v[u].x; o.y += wgt[u] * v[u].y; o.z += wgt[u] * v[u].z; o.w += wgt[u] * v[u].w;
+            }
+        }
+        reinterpret_cast<float4*>(sm_red_flat)[grp * kCol4 + col] = o;
+    }
+    __syncthreads();
+    if (tid < kCol4) {
+        float4 o = reinterpret_cast<const float4*>(sm_red_flat)[tid];
+#pragma unroll
+        for (int grp = 1; grp < kGroups; ++grp) {
+            const float4 t = reinterpret_cast<const float4*>(sm_red_flat)[grp * kCol4 + tid];
+            o.x += t.x; o.y += t.y; o.z += t.z; o.w += t.w;
+        }
+        reinterpret_cast<float4*>(out + qhead0 * kHeadDim)[tid] = o;
     }
     if (tid == 0) counter[bh] = 0;          // ready for the next call on this stream
 }
@@ -564,10 +614,15 @@ static hipError_t launch_attend_g(Ctx* c, const void* q, const void* Kbase, cons
                                   int32_t idx_stride, int32_t row_stride, const int32_t* n_tok, int32_t n_splits,
                                   const SeqView& v, float* out, float* lse) {
     const dim3 grid(n_splits, v.B * c->d.n_kv_heads), block(kAttThreads);
-#define SKV_ATT(GG)                                                                                                  \
-    hipLaunchKernelGGL((attend_kernel<EB, GG>), grid, block, 0, c->stream, (const char*)q, (const char*)Kbase,       \
+#define SKV_ATT_I(GG, IND)                                                                                            \
+    hipLaunchKernelGGL((attend_kernel<EB, GG, IND>), grid, block, 0, c->stream, (const char*)q, (const char*)Kbase,   \
                        (const char*)Vbase, tok_idx, idx_stride, row_stride, n_tok, v, c->d.n_kv_heads, c->max_splits, \
                        c->att_part, c->att_ml, c->att_counter, out, lse)
+#define SKV_ATT(GG)                    \
+    do {                               \
+        if (tok_idx) SKV_ATT_I(GG, true); \
+        else SKV_ATT_I(GG, false);     \
+    } while (0)
     switch (c->G) {
         case 1: SKV_ATT(1); break;
         case 2: SKV_ATT(2); break;
@@ -576,6 +631,7 @@ static hipError_t launch_attend_g(Ctx* c, const void* q, const void* Kbase, cons
         default: return hipErrorInvalidValue;
     }
 #undef SKV_ATT
+#undef SKV_ATT_I
     return hipGetLastError();
 }
 

@@ -182,7 +182,9 @@ __global__ __launch_bounds__(kSemvecWavesPerBlock * kWave) void semvec_kernel(co
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int32_t x = x0 + u * R::RPW;
-            v[u] = (x < e) ? *reinterpret_cast<const uint4*>(base + (int64_t)x * (kHeadDim * EB)) : make_uint4(0, 0, 0, 0);
+            // clamped address + masked value keeps the kUnroll loads independent of the bounds test
+            const uint4 t = *reinterpret_cast<const uint4*>(base + (int64_t)min(x, e - 1) * (kHeadDim * EB));
+            v[u] = (x < e) ? t : make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
