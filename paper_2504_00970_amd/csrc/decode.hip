@@ -2,7 +2,14 @@
 // retrieval, K/V row gather, split-K attention with an online-softmax combine.  gfx950, wave64.
 #include "skv_internal.h"
 
+// Phase markers: no-ops unless a profiling build pre-defines SKV_T(k) to record a timestamp.
+#ifndef SKV_T
+#define SKV_T(k)
+#endif
+
 namespace skv {
+
+static_assert(kSelectThreads == kAttThreads, "the fused kernel runs the selection with its own 256 threads");
 
 // Per-sequence slice of a ragged batch.
 struct Seq {
@@ -119,17 +126,26 @@ hipError_t launch_score(Ctx* c, const void* q, const float* semvec_layer, const 
 }
 
 // ------------------------------------------------------------------------------------------------
-// Selection.  One 1024-thread block per (sequence, KV head).
+// Selection (Sec. 4.2 ranking + budgeted retrieval) as a block-level routine for 256 threads, used by
+// the stand-alone select kernel (one block per sequence and KV head) and, redundantly per block, by
+// the fused attention kernel.
 //
 // Buckets are ranked by (score descending, id ascending) and taken along the ranking until the first
 // one that does not fit.  Because lengths are positive the running total along the ranking is
 // increasing, so the retrieved set is {i : (total length ranked before i) + len_i <= budget}.  The
 // first bucket that overflows (the "cut") is found without sorting, by a length-weighted radix select
-// on an order-preserving 32-bit image of the score: 11 + 11 + 10 bit digits, most significant first;
-// per pass a histogram of bucket lengths per digit, a suffix scan from the top digit, and the digit in
-// which the running total crosses the budget.  The search stops as soon as the crossing digit holds a
-// single bucket.  Buckets with exactly the cut's score are resolved in id order by a scan.
-// A final scan in id order compacts the selected ids (ascending) and their token ranges.
+// on an order-preserving 32-bit image of the score: 11 + 11 + 10 bit digits, most significant first.
+// Per pass: LDS atomics build a histogram of (count, total length) per digit; after ONE barrier every
+// wave scans the whole histogram by itself (32 digits per lane, a wave-level suffix scan, a ballot for
+// the digit in which the running total crosses the budget), so all waves hold the same result without
+// further synchronisation.  The three histograms are zeroed up front, while the scores are in flight.
+// The search stops as soon as the crossing digit holds a single bucket; buckets with exactly the
+// cut's score are resolved in id order by a scan.
+//
+// Thread t owns the kpt = ceil(S / 256) consecutive buckets [t*kpt, (t+1)*kpt): keys, lengths and
+// offsets of the first KREG of them live in registers (one global round trip for the whole routine);
+// buckets beyond KREG per thread are re-read from memory in every phase.  The blocked ownership makes
+// the id-ordered compaction a thread-local walk plus one block scan.
 // ------------------------------------------------------------------------------------------------
 
 __device__ __forceinline__ uint32_t score_key(float f) {
@@ -139,9 +155,24 @@ __device__ __forceinline__ uint32_t score_key(float f) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// Inclusive scan over the block's 1024 threads (thread order).  `sh` holds 16 wave totals.
-// Returns the inclusive value; *total receives the block total.  Contains two barriers.
-__device__ __forceinline__ unsigned long long block_scan_u64(unsigned long long val, unsigned long long* sh,
+constexpr int kSelWaves = kSelectThreads / kWave;
+constexpr int kSelKreg = 24;                                  // 256 threads x 24 buckets in registers: S <= 6144
+constexpr int kMaxDigitBits = 11;
+constexpr int kBins = 1 << kMaxDigitBits;
+constexpr int kHistStride = kBins + kBins / 32;               // one pad slot per 32 digits: lane-strided reads spread over banks
+constexpr unsigned long long kLenMask = (1ull << 40) - 1;
+
+struct SelectShared {
+    unsigned long long hist[3][kHistStride];                  // packed (count << 40 | total length) per digit
+    unsigned long long wave_tot[2][kSelWaves];
+};
+constexpr int kSelListCap = (int)(sizeof(unsigned long long) * 3 * kHistStride / sizeof(int4));
+
+__device__ __forceinline__ int hist_slot(int digit) { return digit + (digit >> 5); }
+
+// Inclusive scan over the block's 256 threads (thread order); one barrier.  `slot` must not be reused
+// within a kernel.  Returns the inclusive value; *total receives the block total.
+__device__ __forceinline__ unsigned long long block_scan_u64(unsigned long long val, unsigned long long* slot,
                                                              unsigned long long* total) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     unsigned long long x = val;
@@ -150,13 +181,12 @@ __device__ __forceinline__ unsigned long long block_scan_u64(unsigned long long 
         const unsigned long long t = __shfl_up(x, off);
         if (lane >= off) x += t;
     }
-    __syncthreads();                        // previous users of sh are done
-    if (lane == 63) sh[w] = x;
+    if (lane == 63) slot[w] = x;
     __syncthreads();
     unsigned long long pre = 0, tot = 0;
 #pragma unroll
-    for (int i = 0; i < kSelectThreads / kWave; ++i) {
-        const unsigned long long t = sh[i];
+    for (int i = 0; i < kSelWaves; ++i) {
+        const unsigned long long t = slot[i];
         if (i < w) pre += t;
         tot += t;
     }
@@ -164,136 +194,230 @@ __device__ __forceinline__ unsigned long long block_scan_u64(unsigned long long 
     return x + pre;
 }
 
-constexpr int kMaxDigitBits = 11;
-constexpr unsigned long long kLenMask = (1ull << 40) - 1;
+// One wave scans a finished histogram of 2^BITS digits from the top digit down and finds the digit in
+// which carry + (running total length) first exceeds the budget.  Returns false if the total fits.
+template <int BITS>
+__device__ __forceinline__ bool find_crossing(const unsigned long long* __restrict__ H, long long carry, long long budget,
+                                              int* digit, long long* new_carry, int* cnt) {
+    constexpr int kN = 1 << BITS, kPerLane = kN / kWave;
+    const int lane = threadIdx.x & 63;
+    unsigned long long hv[kPerLane];
+    unsigned int local = 0;
+#pragma unroll
+    for (int j = 0; j < kPerLane; ++j) {
+        hv[j] = H[hist_slot(kN - 1 - (lane * kPerLane + j))];     // lane order == descending digit order
+        local += (unsigned int)(hv[j] & kLenMask);
+    }
+    unsigned int incl = local;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const unsigned int t = __shfl_up(incl, off);
+        if (lane >= off) incl += t;
+    }
+    const long long above = carry + (long long)(incl - local);    // total length ranked above this lane's digits
+    const bool has = above <= budget && above + (long long)local > budget;
+    const unsigned long long mask = __ballot(has);
+    if (mask == 0) return false;
+    int d = 0, c = 0;
+    long long run = above, nc = 0;
+#pragma unroll
+    for (int j = 0; j < kPerLane; ++j) {
+        const long long l = (long long)(hv[j] & kLenMask);
+        if (l > 0 && run <= budget && run + l > budget) { d = kN - 1 - (lane * kPerLane + j); nc = run; c = (int)(hv[j] >> 40); }
+        run += l;
+    }
+    const int src = __ffsll((long long)mask) - 1;
+    *digit = __shfl(d, src);
+    *cnt = __shfl(c, src);
+    *new_carry = __shfl(nc, src);
+    return true;
+}
 
-__global__ __launch_bounds__(kSelectThreads) void select_kernel(const float* __restrict__ score,
-                                                                const int32_t* __restrict__ sent_off,
-                                                                const int32_t* __restrict__ sent_len, SeqView v,
-                                                                int32_t Hkv, int32_t max_sel,
-                                                                int32_t* __restrict__ sel_sent, int32_t* __restrict__ tokpos,
-                                                                int32_t* __restrict__ n_sel, int32_t* __restrict__ tok_idx,
-                                                                int32_t idx_stride, int32_t* __restrict__ n_tok) {
-    __shared__ unsigned long long hist[1 << kMaxDigitBits];
-    __shared__ unsigned long long sh_wave[kSelectThreads / kWave];
-    __shared__ int sh_digit;
-    __shared__ long long sh_carry;
-    __shared__ int sh_cnt;
-
-    const int bh = blockIdx.x, b = bh / Hkv, h = bh % Hkv;
+// emit(s, off_s, len_s, sel_pos, tok_pos) is called by the owner thread of every selected bucket,
+// sel_pos / tok_pos being the number of selected buckets / tokens with lower ids.
+// Every thread of the (256-thread) block must call this; *n_sel_out / *n_tok_out are block-uniform.
+template <int KREG, typename Emit>
+__device__ __forceinline__ void select_block(const float* __restrict__ sc, const int32_t* __restrict__ len,
+                                             const int32_t* __restrict__ off, int32_t S, long long budget,
+                                             SelectShared& sh, Emit emit, int* n_sel_out, long long* n_tok_out) {
     const int tid = threadIdx.x;
-    const Seq sq = seq_of(v, b);
-    const int32_t S = sq.n_sent;
-    const long long budget = min(sq.budget, idx_stride);     // tok_idx holds at most idx_stride positions
-    const float* sc = score + (int64_t)h * v.S_total + sq.sent_base;
-    const int32_t* len = sent_len + sq.sent_base;
-    const int32_t* off = sent_off + sq.sent_base + (v.cu_sent ? b : 0);
-    sel_sent += (int64_t)bh * max_sel;
-    tokpos += (int64_t)bh * max_sel;
-    tok_idx += (int64_t)bh * idx_stride;
-
     if (S <= 0 || budget <= 0) {
-        if (tid == 0) { n_sel[bh] = 0; n_tok[bh] = 0; }
+        *n_sel_out = 0;
+        *n_tok_out = 0;
         return;
     }
+    const int kpt = (S + kSelectThreads - 1) / kSelectThreads;
+    const int32_t s0 = tid * kpt;
 
-    // ---- weighted radix select of the cut --------------------------------------------------------
+    uint32_t rkey[KREG];
+    int32_t rlen[KREG], roff[KREG];
+#pragma unroll
+    for (int i = 0; i < KREG; ++i) {
+        rkey[i] = 0; rlen[i] = 0; roff[i] = 0;
+        if (i < kpt) {                                     // block-uniform; addresses clamped, loads unconditional
+            const int32_t sidx = min(s0 + i, S - 1);
+            rkey[i] = score_key(sc[sidx]);
+            rlen[i] = len[sidx];
+            roff[i] = off[sidx];
+        }
+    }
+    SKV_T(15);
+    // zero the histograms while the loads are in flight
+    {
+        unsigned long long* h = &sh.hist[0][0];
+        for (int i = tid; i < 3 * kHistStride; i += kSelectThreads) h[i] = 0;
+    }
+    __syncthreads();
+    SKV_T(1);
+
+    // fn(s, key, len, off) for every bucket s the thread owns, in id order
+    auto for_items = [&](auto&& fn) {
+#pragma unroll
+        for (int i = 0; i < KREG; ++i)
+            if (i < kpt && s0 + i < S) fn(s0 + i, rkey[i], rlen[i], roff[i]);
+        for (int i = KREG; i < kpt; ++i)
+            if (s0 + i < S) fn(s0 + i, score_key(sc[s0 + i]), len[s0 + i], off[s0 + i]);
+    };
+
+    // ---- weighted radix select of the cut ----------------------------------------------------------
     uint32_t prefix = 0;        // resolved high bits of the cut's key
     int shift = 32;             // number of unresolved low bits
     long long carry = 0;        // total length of the buckets ranked strictly above the current digit range
     int cut_cnt = 0;            // number of buckets sharing the resolved prefix
     bool select_all = false;
-    const int pass_bits[3] = {11, 11, 10};
-    for (int pass = 0; pass < 3; ++pass) {
-        const int bits = pass_bits[pass], nbins = 1 << bits, nshift = shift - bits;
-        for (int i = tid; i < nbins; i += kSelectThreads) hist[i] = 0;
-        if (tid == 0) sh_digit = -1;
+    {
+        int digit;
+        // pass 0: key bits 31..21
+        for_items([&](int32_t, uint32_t k, int32_t ln, int32_t) {
+            atomicAdd(&sh.hist[0][hist_slot(k >> 21)], (1ull << 40) | (unsigned long long)(uint32_t)ln);
+        });
+        SKV_T(10);
         __syncthreads();
-        for (int32_t s = tid; s < S; s += kSelectThreads) {
-            const uint32_t k = score_key(sc[s]);
-            if (shift == 32 || (k >> shift) == prefix) {
-                const int d = (k >> nshift) & (nbins - 1);
-                atomicAdd(&hist[d], (1ull << 40) | (unsigned long long)(uint32_t)len[s]);
+        SKV_T(11);
+        if (!find_crossing<11>(sh.hist[0], carry, budget, &digit, &carry, &cut_cnt)) {
+            select_all = true;                                  // everything fits
+        } else {
+            prefix = (uint32_t)digit;
+            shift = 21;
+            SKV_T(12);
+            if (cut_cnt > 1) {
+                // pass 1: key bits 20..10 of the buckets in the crossing digit
+                for_items([&](int32_t, uint32_t k, int32_t ln, int32_t) {
+                    if ((k >> 21) == prefix)
+                        atomicAdd(&sh.hist[1][hist_slot((k >> 10) & 2047)], (1ull << 40) | (unsigned long long)(uint32_t)ln);
+                });
+                SKV_T(13);
+                __syncthreads();
+                SKV_T(14);
+                find_crossing<11>(sh.hist[1], carry, budget, &digit, &carry, &cut_cnt);
+                prefix = (prefix << 11) | (uint32_t)digit;
+                shift = 10;
+                if (cut_cnt > 1) {
+                    // pass 2: key bits 9..0
+                    for_items([&](int32_t, uint32_t k, int32_t ln, int32_t) {
+                        if ((k >> 10) == prefix)
+                            atomicAdd(&sh.hist[2][hist_slot(k & 1023)], (1ull << 40) | (unsigned long long)(uint32_t)ln);
+                    });
+                    __syncthreads();
+                    find_crossing<10>(sh.hist[2], carry, budget, &digit, &carry, &cut_cnt);
+                    prefix = (prefix << 10) | (uint32_t)digit;
+                    shift = 0;
+                }
             }
         }
-        __syncthreads();
-        // thread t owns digits nbins-1-2t and nbins-2-2t: thread order == descending digit order
-        const int d1 = nbins - 1 - 2 * tid, d0 = d1 - 1;
-        const unsigned long long v1 = d1 >= 0 ? hist[d1] : 0ull, v0 = d0 >= 0 ? hist[d0] : 0ull;
-        const long long l1 = (long long)(v1 & kLenMask), l0 = (long long)(v0 & kLenMask);
-        unsigned long long total;
-        const long long incl = (long long)block_scan_u64((unsigned long long)(l1 + l0), sh_wave, &total);
-        const long long before1 = carry + incl - l1 - l0, after1 = before1 + l1, after0 = after1 + l0;
-        if (l1 > 0 && before1 <= budget && after1 > budget) { sh_digit = d1; sh_carry = before1; sh_cnt = (int)(v1 >> 40); }
-        if (l0 > 0 && after1 <= budget && after0 > budget) { sh_digit = d0; sh_carry = after1; sh_cnt = (int)(v0 >> 40); }
-        __syncthreads();
-        const int digit = sh_digit;
-        if (digit < 0) { select_all = true; break; }          // everything fits (only possible in pass 0)
-        prefix = (shift == 32) ? (uint32_t)digit : ((prefix << bits) | (uint32_t)digit);
-        carry = sh_carry;
-        cut_cnt = sh_cnt;
-        shift = nshift;
-        __syncthreads();                                       // sh_* are rewritten by the next pass
-        if (cut_cnt == 1) break;                               // the cut is unique: it is the bucket that overflows
     }
     const bool ties = !select_all && cut_cnt > 1;              // then shift == 0: several buckets share the cut's score
+    SKV_T(2);
 
-    // ---- compaction in id order ---------------------------------------------------------------------
-    long long tie_run = 0;          // length of tied buckets with lower ids
-    int run_cnt = 0;                // selected buckets so far
-    long long run_tok = 0;          // selected tokens so far
-    for (int32_t base = 0; base < S; base += kSelectThreads) {
-        const int32_t s = base + tid;
-        const bool live = s < S;
-        const uint32_t k = live ? score_key(sc[s]) : 0u;
-        const int32_t ln = live ? len[s] : 0;
-        bool sel = false;
-        if (live) {
-            if (select_all) sel = true;
-            else sel = (shift >= 32 ? 0u : (k >> shift)) > prefix;
-        }
-        if (ties) {
-            const bool tied = live && k == prefix;
-            unsigned long long tot;
-            const long long cum = (long long)block_scan_u64(tied ? (unsigned long long)(uint32_t)ln : 0ull, sh_wave, &tot);
-            if (tied && carry + tie_run + cum <= budget) sel = true;
-            tie_run += (long long)tot;
-        }
+    // ---- compaction in id order --------------------------------------------------------------------
+    long long tie_run = 0;          // length of tied buckets with lower ids (starts at the thread's base)
+    if (ties) {
+        long long mine = 0;
+        for_items([&](int32_t, uint32_t k, int32_t ln, int32_t) { if (k == prefix) mine += ln; });
         unsigned long long tot;
-        const unsigned long long mine = sel ? ((1ull << 40) | (unsigned long long)(uint32_t)ln) : 0ull;
-        const unsigned long long incl = block_scan_u64(mine, sh_wave, &tot);
-        if (sel) {
-            const unsigned long long excl = incl - mine;
-            const int pos = run_cnt + (int)(excl >> 40);
-            if (pos < max_sel) {
-                sel_sent[pos] = s;
-                tokpos[pos] = (int32_t)(run_tok + (long long)(excl & kLenMask));
-            }
-        }
-        run_cnt += (int)(tot >> 40);
-        run_tok += (long long)(tot & kLenMask);
+        tie_run = (long long)block_scan_u64((unsigned long long)mine, sh.wave_tot[0], &tot) - mine;
     }
-    const int nsel = min(run_cnt, max_sel);
-    if (tid == 0) { n_sel[bh] = nsel; n_tok[bh] = (int32_t)run_tok; }
-    __syncthreads();                                           // sel_sent / tokpos visible to the block
-
-    // ---- token positions of the selected buckets, ascending --------------------------------------------
-    const int32_t ntok = (int32_t)min(run_tok, (long long)idx_stride);
-    for (int32_t j = tid; j < ntok; j += kSelectThreads) {
-        int lo = 0, hi = nsel - 1;                             // last i with tokpos[i] <= j
-        while (lo < hi) {
-            const int mid = (lo + hi + 1) >> 1;
-            if (tokpos[mid] <= j) lo = mid; else hi = mid - 1;
+    auto chosen = [&](uint32_t k, int32_t ln, long long& tie_acc) -> bool {
+        if (select_all) return true;
+        const uint32_t hi = k >> shift;                        // shift < 32 here: at least one pass ran
+        if (hi > prefix) return true;
+        if (ties && k == prefix) {
+            tie_acc += ln;
+            return carry + tie_acc <= budget;
         }
-        tok_idx[j] = off[sel_sent[lo]] + (j - tokpos[lo]);
+        return false;
+    };
+    unsigned long long mine = 0;
+    {
+        long long t = tie_run;
+        for_items([&](int32_t, uint32_t k, int32_t ln, int32_t) {
+            if (chosen(k, ln, t)) mine += (1ull << 40) | (unsigned long long)(uint32_t)ln;
+        });
+    }
+    unsigned long long tot;
+    const unsigned long long incl = block_scan_u64(mine, sh.wave_tot[1], &tot);
+    {
+        unsigned long long pos = incl - mine;
+        long long t = tie_run;
+        for_items([&](int32_t s, uint32_t k, int32_t ln, int32_t o) {
+            if (chosen(k, ln, t)) {
+                emit(s, o, ln, (int)(pos >> 40), (long long)(pos & kLenMask));
+                pos += (1ull << 40) | (unsigned long long)(uint32_t)ln;
+            }
+        });
+    }
+    *n_sel_out = (int)(tot >> 40);
+    *n_tok_out = (long long)(tot & kLenMask);
+    SKV_T(3);
+}
+
+// Stand-alone selection: the selected buckets go through an LDS list (reusing the histograms' space) so
+// that the token positions of each bucket are written by a whole wave, coalesced.
+__global__ __launch_bounds__(kSelectThreads) void select_kernel(const float* __restrict__ score,
+                                                                const int32_t* __restrict__ sent_off,
+                                                                const int32_t* __restrict__ sent_len, SeqView v,
+                                                                int32_t Hkv, int32_t max_sel,
+                                                                int32_t* __restrict__ sel_sent, int32_t* __restrict__ n_sel,
+                                                                int32_t* __restrict__ tok_idx, int32_t idx_stride,
+                                                                int32_t* __restrict__ n_tok) {
+    __shared__ __attribute__((aligned(16))) SelectShared sh;
+    const int bh = blockIdx.x, b = bh / Hkv, h = bh % Hkv;
+    const Seq sq = seq_of(v, b);
+    const long long budget = min(sq.budget, idx_stride);     // tok_idx holds at most idx_stride positions
+    const float* sc = score + (int64_t)h * v.S_total + sq.sent_base;
+    const int32_t* len = sent_len + sq.sent_base;
+    const int32_t* off = sent_off + sq.sent_base + (v.cu_sent ? b : 0);
+    int32_t* my_sel = sel_sent + (int64_t)bh * max_sel;
+    int32_t* my_idx = tok_idx + (int64_t)bh * idx_stride;
+    int4* list = reinterpret_cast<int4*>(&sh.hist[0][0]);     // (bucket, offset, length, first output slot)
+    int nsel;
+    long long ntok;
+    select_block<kSelKreg>(
+        sc, len, off, sq.n_sent, budget, sh,
+        [&](int32_t s, int32_t o, int32_t ln, int sel_pos, long long tok_pos) {
+            if (sel_pos < max_sel) my_sel[sel_pos] = s;
+            if (sel_pos < kSelListCap) {
+                list[sel_pos] = make_int4(s, o, ln, (int32_t)tok_pos);
+            } else {                                          // list full: the owner writes its bucket's positions itself
+                for (int32_t t = 0; t < ln && tok_pos + t < idx_stride; ++t) my_idx[tok_pos + t] = o + t;
+            }
+        },
+        &nsel, &ntok);
+    if (threadIdx.x == 0) { n_sel[bh] = min(nsel, max_sel); n_tok[bh] = (int32_t)ntok; }
+    __syncthreads();
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int listed = min(nsel, kSelListCap);
+    for (int e = w; e < listed; e += kSelWaves) {
+        const int4 it = list[e];
+        for (int32_t t = lane; t < it.z && it.w + t < idx_stride; t += kWave) my_idx[it.w + t] = it.y + t;
     }
 }
 
 hipError_t launch_select(Ctx* c, const float* score, const int32_t* sent_off, const int32_t* sent_len,
-                         const SeqView& v, int32_t* sel_sent, int32_t* tokpos, int32_t* n_sel, int32_t* tok_idx,
-                         int32_t idx_stride, int32_t* n_tok) {
+                         const SeqView& v, int32_t* sel_sent, int32_t* n_sel, int32_t* tok_idx, int32_t idx_stride,
+                         int32_t* n_tok) {
     hipLaunchKernelGGL(select_kernel, dim3(v.B * c->d.n_kv_heads), dim3(kSelectThreads), 0, c->stream, score, sent_off,
-                       sent_len, v, c->d.n_kv_heads, c->max_sel, sel_sent, tokpos, n_sel, tok_idx, idx_stride, n_tok);
+                       sent_len, v, c->d.n_kv_heads, c->max_sel, sel_sent, n_sel, tok_idx, idx_stride, n_tok);
     return hipGetLastError();
 }
 
@@ -355,69 +479,131 @@ hipError_t launch_gather(Ctx* c, const void* K_layer, const void* V_layer, int32
 
 // ------------------------------------------------------------------------------------------------
 // Attention (Eq. 3), split-K flash decoding.  Block (split, sequence*KV head) handles kAttChunk = 64
-// consecutive retrieved tokens for the G query heads of its KV head:
+// consecutive retrieved tokens for the G query heads of its KV head.
+//   FUSED == false: rows come from K_sel/V_sel and n_tok from memory (skv_attend).
+//   FUSED == true : the block first runs the selection for its (sequence, head) from the scores
+//                   (redundantly with the other splits: the scores are a few KB in L2, and it saves a
+//                   launch plus a round trip through tok_idx), keeps the pool rows of its own 64 tokens
+//                   in LDS and reads K/V straight from the pool (skv_decode_step).
+// Then:
 //   1. every K and V lane chunk of the chunk is requested up front (16-byte loads, RPW rows per wave
-//      instruction), either from K_sel/V_sel or straight from the pool through tok_idx;
+//      instruction), on clamped addresses so that no load waits for a bounds test;
 //   2. logits for the G heads: per-lane partial dot products, reduced over the LPR lanes of a row;
 //   3. one wave per query head: max, exp2, sum over the 64 logits (softmax in log2 units);
 //   4. P.V with per-lane accumulators, reduced over the rows of a wave and over the 4 waves in LDS;
 //   5. the un-normalised partial (m, l, acc) goes to the workspace; the last block to arrive for the
-//      (sequence, KV head) -- a device-scope counter, no spinning -- rescales and sums the partials.
+//      (sequence, KV head) -- a device-scope counter, no spinning -- merges the partials with one
+//      round of independent loads and an online-softmax merge in registers and LDS.
 // ------------------------------------------------------------------------------------------------
-template <int EB, int G, bool IND>
-__global__ __launch_bounds__(kAttThreads) void attend_kernel(const char* __restrict__ q, const char* __restrict__ Kb,
-                                                             const char* __restrict__ Vb, const int32_t* __restrict__ tok_idx,
-                                                             int32_t idx_stride, int32_t row_stride,
-                                                             const int32_t* __restrict__ n_tok, SeqView v, int32_t Hkv,
-                                                             int32_t max_splits, float* __restrict__ part,
-                                                             float* __restrict__ ml, unsigned int* __restrict__ counter,
-                                                             float* __restrict__ out, float* __restrict__ lse) {
+
+// Split-K partials travel between blocks (possibly on different XCDs, each with its own L2) inside one
+// kernel.  They are written and read with device-scope relaxed atomic accesses, which go through to the
+// level all XCDs share, so no L2 write-back / invalidate is needed around the arrival counter.
+__device__ __forceinline__ void st_agent(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_agent(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+struct AttArgs {
+    const char* q;            // [B][Hq][D]
+    const char* Kb;           // FUSED: layer pool [Hkv][T_total][D]; else K_sel [B*Hkv][row_stride][D]
+    const char* Vb;
+    const int32_t* n_tok;     // !FUSED: [B*Hkv]
+    int32_t row_stride;       // !FUSED
+    const float* score;       // FUSED: [Hkv][S_total]
+    const int32_t* sent_off;  // FUSED
+    const int32_t* sent_len;  // FUSED
+    int32_t* tok_idx_out;     // FUSED, nullable: [B*Hkv][idx_stride]
+    int32_t* n_tok_out;       // FUSED, nullable: [B*Hkv]
+    int32_t idx_stride;       // FUSED: max_budget
+    SeqView v;
+    int32_t Hkv;
+    int32_t max_splits;
+    float* part;
+    float* ml;
+    unsigned int* counter;
+    float* out;
+    float* lse;
+};
+
+template <int EB, int G, bool FUSED>
+__global__ __launch_bounds__(kAttThreads) void attend_kernel(AttArgs a) {
     using R = Row<EB>;
     constexpr int kWaves = kAttThreads / kWave;
     constexpr int kRowsPerIter = kWaves * R::RPW;
     constexpr int kIter = kAttChunk / kRowsPerIter;
     constexpr int kRowBytes = kHeadDim * EB;
     constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
+    constexpr int kCol4 = G * (kHeadDim / 4);                // float4 columns over the G heads
+    constexpr int kGroups = kAttThreads / kCol4;             // 8, 4, 2, 1 for G = 1, 2, 4, 8
+    constexpr int kMergeFloats = kGroups * kCol4 * 6;        // O (float4), M, L per (group, column)
+    constexpr int kRedFloats = (kWaves * G * kHeadDim > kMergeFloats) ? kWaves * G * kHeadDim : kMergeFloats;
 
     __shared__ float sm_logit[G][kAttChunk];
-    constexpr int kRedFloats = (kWaves * G * kHeadDim > 1024) ? kWaves * G * kHeadDim : 1024;
     __shared__ __attribute__((aligned(16))) float sm_red_flat[kRedFloats];
-    float (*sm_red)[G][kHeadDim] = reinterpret_cast<float (*)[G][kHeadDim]>(sm_red_flat);
     __shared__ int sm_last;
+    __shared__ int32_t sm_row[kAttChunk];
+    float (*sm_red)[G][kHeadDim] = reinterpret_cast<float (*)[G][kHeadDim]>(sm_red_flat);
 
-    const int bh = blockIdx.y, b = bh / Hkv, h = bh % Hkv, split = blockIdx.x;
+    const int bh = blockIdx.y, b = bh / a.Hkv, h = bh % a.Hkv, split = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int r = lane / R::LPR, cc = lane % R::LPR;
-    const int Hq = Hkv * G;
+    const int Hq = a.Hkv * G;
     const int64_t qhead0 = (int64_t)b * Hq + (int64_t)h * G;      // first query head of the group
-    const Seq sq = seq_of(v, b);
+    const Seq sq = seq_of(a.v, b);
+    const int32_t j0 = split * kAttChunk;
+    SKV_T(0);
 
-    int32_t n = n_tok[bh];
-    n = min(n, IND ? idx_stride : row_stride);
+    int32_t n;                                                    // retrieved tokens of this (sequence, head)
+    if (FUSED) {
+        __shared__ SelectShared sel_sh;
+        const long long budget = min(sq.budget, a.idx_stride);
+        if (split > 0 && j0 >= budget) return;                    // n <= budget: nothing for this split
+        if (tid < kAttChunk) sm_row[tid] = -1;
+        int nsel;
+        long long ntok;
+        select_block<kSelKreg>(
+            a.score + (int64_t)h * a.v.S_total + sq.sent_base, a.sent_len + sq.sent_base,
+            a.sent_off + sq.sent_base + (a.v.cu_sent ? b : 0), sq.n_sent, budget, sel_sh,
+            [&](int32_t, int32_t o, int32_t ln, int, long long tok_pos) {
+                const long long lo = tok_pos > j0 ? tok_pos : j0;
+                const long long hi = (tok_pos + ln < j0 + kAttChunk) ? tok_pos + ln : j0 + kAttChunk;
+                for (long long t = lo; t < hi; ++t) sm_row[t - j0] = o + (int32_t)(t - tok_pos);
+            },
+            &nsel, &ntok);
+        n = (int32_t)ntok;
+        if (split == 0 && tid == 0 && a.n_tok_out) a.n_tok_out[bh] = n;
+        __syncthreads();                                          // sm_row complete
+        if (a.tok_idx_out && tid < kAttChunk && j0 + tid < n) a.tok_idx_out[(int64_t)bh * a.idx_stride + j0 + tid] = sm_row[tid];
+    } else {
+        n = min(a.n_tok[bh], a.row_stride);
+    }
     if (n <= 0) {
         if (split == 0) {
-            for (int i = tid; i < G * kHeadDim; i += kAttThreads) out[qhead0 * kHeadDim + i] = 0.f;
-            if (lse && tid < G) lse[qhead0 + tid] = -INFINITY;
+            for (int i = tid; i < G * kHeadDim; i += kAttThreads) a.out[qhead0 * kHeadDim + i] = 0.f;
+            if (a.lse && tid < G) a.lse[qhead0 + tid] = -INFINITY;
         }
         return;
     }
     const int nsplit = (n + kAttChunk - 1) / kAttChunk;
     if (split >= nsplit) return;
-    const int32_t j0 = split * kAttChunk;
     const int32_t cnt = min(kAttChunk, n - j0);
 
+    SKV_T(4);
     // ---- 1. issue every load of the chunk ------------------------------------------------------------
     const char* Kh;
     const char* Vh;
-    if (IND) {
-        Kh = Kb + ((int64_t)h * v.T_total + sq.tok_base) * kRowBytes;
-        Vh = Vb + ((int64_t)h * v.T_total + sq.tok_base) * kRowBytes;
+    if (FUSED) {
+        Kh = a.Kb + ((int64_t)h * a.v.T_total + sq.tok_base) * kRowBytes;
+        Vh = a.Vb + ((int64_t)h * a.v.T_total + sq.tok_base) * kRowBytes;
     } else {
-        Kh = Kb + ((int64_t)bh * row_stride + j0) * kRowBytes;
-        Vh = Vb + ((int64_t)bh * row_stride + j0) * kRowBytes;
+        Kh = a.Kb + ((int64_t)bh * a.row_stride + j0) * kRowBytes;
+        Vh = a.Vb + ((int64_t)bh * a.row_stride + j0) * kRowBytes;
     }
-    // Branch-free loads: rows past the chunk's end (and indices outside the sequence) are clamped to a
-    // valid row, loaded anyway and masked afterwards, so that all loads are in flight together.
+    // Rows past the chunk's end (and positions outside the sequence) are clamped to a valid row, loaded
+    // anyway and masked afterwards, so that all loads are in flight together.
     int32_t rowi[kIter];
     bool live[kIter];
 #pragma unroll
@@ -425,8 +611,8 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(const char* __restr
         const int jj = i * kRowsPerIter + w * R::RPW + r;
         live[i] = jj < cnt;
         const int jc = min(jj, cnt - 1);
-        if (IND) {
-            const int32_t x = tok_idx[(int64_t)bh * idx_stride + j0 + jc];
+        if (FUSED) {
+            const int32_t x = sm_row[jc];
             live[i] = live[i] && x >= 0 && x < sq.n_tok_ctx;
             rowi[i] = min(max(x, 0), max(sq.n_tok_ctx - 1, 0));
         } else {
@@ -442,10 +628,11 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(const char* __restr
     float qf[G][R::EPL];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-        const uint4 t = *reinterpret_cast<const uint4*>(q + ((qhead0 + g) * kHeadDim) * EB + cc * 16);
+        const uint4 t = *reinterpret_cast<const uint4*>(a.q + ((qhead0 + g) * kHeadDim) * EB + cc * 16);
         R::unpack(t, qf[g]);
     }
 
+    SKV_T(5);
     // ---- 2. logits ---------------------------------------------------------------------------------
     const float scale = kLog2e * rsqrtf((float)kHeadDim);
 #pragma unroll
@@ -455,10 +642,10 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(const char* __restr
         float s[G];
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            float a = 0.f;
+            float acc = 0.f;
 #pragma unroll
-            for (int e = 0; e < R::EPL; ++e) a += qf[g][e] * kf[e];
-            s[g] = a;
+            for (int e = 0; e < R::EPL; ++e) acc += qf[g][e] * kf[e];
+            s[g] = acc;
         }
 #pragma unroll
         for (int off = R::LPR / 2; off >= 1; off >>= 1) {
@@ -472,6 +659,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(const char* __restr
         }
     }
     __syncthreads();
+    SKV_T(6);
 
     // ---- 3. softmax over the chunk, one wave per query head --------------------------------------------
     for (int g = w; g < G; g += kWaves) {
@@ -485,8 +673,9 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(const char* __restr
         for (int off = 32; off >= 1; off >>= 1) l += __shfl_xor(l, off);
         sm_logit[g][lane] = p;
         if (lane == 0) {
-            float* dst = ml + (((qhead0 + g) * max_splits) + split) * 2;
-            dst[0] = m; dst[1] = l;
+            float* dst = a.ml + (((qhead0 + g) * a.max_splits) + split) * 2;
+            st_agent(dst, m);
+            st_agent(dst + 1, l);
         }
     }
     __syncthreads();
@@ -529,119 +718,125 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(const char* __restr
     __syncthreads();
     for (int i = tid; i < G * kHeadDim; i += kAttThreads) {
         const int g = i / kHeadDim, d = i % kHeadDim;
-        float a = 0.f;
+        float o = sm_red[0][g][d];
 #pragma unroll
-        for (int ww = 0; ww < kWaves; ++ww) a += sm_red[ww][g][d];
-        part[(((qhead0 + g) * max_splits) + split) * kHeadDim + d] = a;
+        for (int ww = 1; ww < kWaves; ++ww) o += sm_red[ww][g][d];
+        st_agent(a.part + (((qhead0 + g) * a.max_splits) + split) * kHeadDim + d, o);
     }
 
+    SKV_T(7);
     // ---- 5. last arrival combines ------------------------------------------------------------------
-    // The barrier orders the block's partial stores before thread 0's device-scope acq_rel increment
-    // (which publishes them); the second barrier hands thread 0's acquire to the rest of the block.
+    // The barrier (with its wait for outstanding stores) puts the block's write-through partial stores
+    // before thread 0's device-scope increment; whoever reads nsplit - 1 knows every partial is there.
     __syncthreads();
     if (tid == 0) {
-        const unsigned int old = __hip_atomic_fetch_add(&counter[bh], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned int old = __hip_atomic_fetch_add(&a.counter[bh], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         sm_last = (old == (unsigned int)(nsplit - 1));
     }
     __syncthreads();
+    SKV_T(8);
     if (!sm_last) return;
-    // (a) per query head: global max, normaliser, and each split's weight (stored over its max);
-    //     one wave per head, lanes stride over the splits so their loads are independent.
-    for (int g = w; g < G; g += kWaves) {
-        float* mlg = ml + ((qhead0 + g) * max_splits) * 2;
-        float M = -INFINITY;
-        for (int s = lane; s < nsplit; s += kWave) M = fmaxf(M, mlg[2 * s]);
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
-        float L = 0.f;
-        for (int s = lane; s < nsplit; s += kWave) {
-            const float ms = mlg[2 * s];
-            L += (ms == -INFINITY) ? 0.f : exp2f(ms - M) * mlg[2 * s + 1];
-        }
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) L += __shfl_xor(L, off);
-        const bool empty = !(L > 0.f);                       // every retrieved index was out of range
-        const float inv = empty ? 0.f : 1.f / L;
-        for (int s = lane; s < nsplit; s += kWave) {
-            const float ms = mlg[2 * s];
-            mlg[2 * s] = (ms == -INFINITY) ? 0.f : exp2f(ms - M) * inv;
-        }
-        if (lse && lane == 0) lse[qhead0 + g] = empty ? -INFINITY : (M + log2f(L)) * kLn2;
-    }
-    __syncthreads();
-    // (b) out[g][:] = sum_s weight[g][s] * partial[g][s][:].  A thread owns one float4 column of one head
-    //     and every kGroups-th split; the groups are then summed through LDS.
-    constexpr int kCol4 = G * (kHeadDim / 4);                // float4 columns over the G heads
-    constexpr int kGroups = kAttThreads / kCol4;             // 8, 4, 2, 1 for G = 1, 2, 4, 8
+    // A thread owns one float4 column of one head and every kGroups-th split: one batch of independent
+    // loads, merged online (running max M, normaliser L, output O) in registers; groups merge through LDS.
     {
         const int col = tid % kCol4, grp = tid / kCol4;
         const int g = col / (kHeadDim / 4), d4 = col % (kHeadDim / 4);
-        const float* mlg = ml + ((qhead0 + g) * max_splits) * 2;
-        const float4* pg = reinterpret_cast<const float4*>(part + ((qhead0 + g) * max_splits) * kHeadDim) + d4;
-        float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
-        constexpr int kU = 8;
+        const float* mlg = a.ml + ((qhead0 + g) * a.max_splits) * 2;
+        const float* pg = a.part + ((qhead0 + g) * a.max_splits) * kHeadDim + d4 * 4;
+        float M = -INFINITY, L = 0.f;
+        float4 O = make_float4(0.f, 0.f, 0.f, 0.f);
+        constexpr int kU = 16;
         for (int s0 = grp; s0 < nsplit; s0 += kGroups * kU) {
-            float4 v[kU];
-            float wgt[kU];
+            float4 pv[kU];
+            float2 mv[kU];
 #pragma unroll
             for (int u = 0; u < kU; ++u) {                   // clamped, unconditional loads
                 const int sidx = min(s0 + u * kGroups, nsplit - 1);
-                v[u] = pg[(int64_t)sidx * (kHeadDim / 4)];
-                wgt[u] = (s0 + u * kGroups < nsplit) ? mlg[2 * sidx] : 0.f;
+                const float* pp = pg + (int64_t)sidx * kHeadDim;
+                pv[u] = make_float4(ld_agent(pp), ld_agent(pp + 1), ld_agent(pp + 2), ld_agent(pp + 3));
+                mv[u] = make_float2(ld_agent(mlg + 2 * sidx), ld_agent(mlg + 2 * sidx + 1));
             }
 #pragma unroll
             for (int u = 0; u < kU; ++u) {
-                o.x += wgt[u] * v[u].x; o.y += wgt[u] * v[u].y; o.z += wgt[u] * v[u].z; o.w += wgt[u] * v[u].w;
+                const float ms = (s0 + u * kGroups < nsplit) ? mv[u].x : -INFINITY;
+                if (ms > -INFINITY) {
+                    const float nm = fmaxf(M, ms);
+                    const float ca = exp2f(M - nm), cb = exp2f(ms - nm);      // M == -inf gives ca == 0
+                    L = L * ca + mv[u].y * cb;
+                    O.x = O.x * ca + pv[u].x * cb; O.y = O.y * ca + pv[u].y * cb;
+                    O.z = O.z * ca + pv[u].z * cb; O.w = O.w * ca + pv[u].w * cb;
+                    M = nm;
+                }
             }
         }
-        reinterpret_cast<float4*>(sm_red_flat)[grp * kCol4 + col] = o;
+        reinterpret_cast<float4*>(sm_red_flat)[grp * kCol4 + col] = O;
+        sm_red_flat[kGroups * kCol4 * 4 + grp * kCol4 + col] = M;
+        sm_red_flat[kGroups * kCol4 * 5 + grp * kCol4 + col] = L;
     }
     __syncthreads();
     if (tid < kCol4) {
-        float4 o = reinterpret_cast<const float4*>(sm_red_flat)[tid];
+        float M = -INFINITY;
 #pragma unroll
-        for (int grp = 1; grp < kGroups; ++grp) {
-            const float4 t = reinterpret_cast<const float4*>(sm_red_flat)[grp * kCol4 + tid];
-            o.x += t.x; o.y += t.y; o.z += t.z; o.w += t.w;
+        for (int grp = 0; grp < kGroups; ++grp) M = fmaxf(M, sm_red_flat[kGroups * kCol4 * 4 + grp * kCol4 + tid]);
+        float L = 0.f;
+        float4 O = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int grp = 0; grp < kGroups; ++grp) {
+            const float mg = sm_red_flat[kGroups * kCol4 * 4 + grp * kCol4 + tid];
+            if (mg > -INFINITY) {
+                const float c = exp2f(mg - M);
+                const float4 t = reinterpret_cast<const float4*>(sm_red_flat)[grp * kCol4 + tid];
+                L += c * sm_red_flat[kGroups * kCol4 * 5 + grp * kCol4 + tid];
+                O.x += c * t.x; O.y += c * t.y; O.z += c * t.z; O.w += c * t.w;
+            }
         }
-        reinterpret_cast<float4*>(out + qhead0 * kHeadDim)[tid] = o;
+        const bool empty = !(L > 0.f);                       // every retrieved position was out of range
+        const float inv = empty ? 0.f : 1.f / L;
+        reinterpret_cast<float4*>(a.out + qhead0 * kHeadDim)[tid] = make_float4(O.x * inv, O.y * inv, O.z * inv, O.w * inv);
+        if (a.lse && (tid % (kHeadDim / 4)) == 0)
+            a.lse[qhead0 + tid / (kHeadDim / 4)] = empty ? -INFINITY : (M + log2f(L)) * kLn2;
     }
-    if (tid == 0) counter[bh] = 0;          // ready for the next call on this stream
+    if (tid == 0) __hip_atomic_store(&a.counter[bh], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next call
+    SKV_T(9);
 }
 
-template <int EB>
-static hipError_t launch_attend_g(Ctx* c, const void* q, const void* Kbase, const void* Vbase, const int32_t* tok_idx,
-                                  int32_t idx_stride, int32_t row_stride, const int32_t* n_tok, int32_t n_splits,
-                                  const SeqView& v, float* out, float* lse) {
-    const dim3 grid(n_splits, v.B * c->d.n_kv_heads), block(kAttThreads);
-#define SKV_ATT_I(GG, IND)                                                                                            \
-    hipLaunchKernelGGL((attend_kernel<EB, GG, IND>), grid, block, 0, c->stream, (const char*)q, (const char*)Kbase,   \
-                       (const char*)Vbase, tok_idx, idx_stride, row_stride, n_tok, v, c->d.n_kv_heads, c->max_splits, \
-                       c->att_part, c->att_ml, c->att_counter, out, lse)
-#define SKV_ATT(GG)                    \
-    do {                               \
-        if (tok_idx) SKV_ATT_I(GG, true); \
-        else SKV_ATT_I(GG, false);     \
-    } while (0)
+template <int EB, bool FUSED>
+static hipError_t launch_attend_g(Ctx* c, const AttArgs& a, int32_t n_splits) {
+    const dim3 grid(n_splits, a.v.B * c->d.n_kv_heads), block(kAttThreads);
     switch (c->G) {
-        case 1: SKV_ATT(1); break;
-        case 2: SKV_ATT(2); break;
-        case 4: SKV_ATT(4); break;
-        case 8: SKV_ATT(8); break;
+        case 1: hipLaunchKernelGGL((attend_kernel<EB, 1, FUSED>), grid, block, 0, c->stream, a); break;
+        case 2: hipLaunchKernelGGL((attend_kernel<EB, 2, FUSED>), grid, block, 0, c->stream, a); break;
+        case 4: hipLaunchKernelGGL((attend_kernel<EB, 4, FUSED>), grid, block, 0, c->stream, a); break;
+        case 8: hipLaunchKernelGGL((attend_kernel<EB, 8, FUSED>), grid, block, 0, c->stream, a); break;
         default: return hipErrorInvalidValue;
     }
-#undef SKV_ATT
-#undef SKV_ATT_I
     return hipGetLastError();
 }
 
-hipError_t launch_attend(Ctx* c, const void* q, const void* Kbase, const void* Vbase, const int32_t* tok_idx,
-                         int32_t idx_stride, int32_t row_stride, const int32_t* n_tok, int32_t n_splits,
-                         const SeqView& v, float* out, float* lse) {
+static AttArgs att_common(Ctx* c, const void* q, const void* Kbase, const void* Vbase, const SeqView& v, float* out,
+                          float* lse) {
+    AttArgs a{};
+    a.q = (const char*)q; a.Kb = (const char*)Kbase; a.Vb = (const char*)Vbase;
+    a.v = v; a.Hkv = c->d.n_kv_heads; a.max_splits = c->max_splits;
+    a.part = c->att_part; a.ml = c->att_ml; a.counter = c->att_counter; a.out = out; a.lse = lse;
+    return a;
+}
+
+hipError_t launch_attend(Ctx* c, const void* q, const void* K_sel, const void* V_sel, int32_t row_stride,
+                         const int32_t* n_tok, int32_t n_splits, const SeqView& v, float* out, float* lse) {
+    AttArgs a = att_common(c, q, K_sel, V_sel, v, out, lse);
+    a.n_tok = n_tok; a.row_stride = row_stride;
     if (n_splits < 1) n_splits = 1;       // block 0 still writes the empty-selection result
-    return c->d.kv_dtype == SKV_BF16
-               ? launch_attend_g<2>(c, q, Kbase, Vbase, tok_idx, idx_stride, row_stride, n_tok, n_splits, v, out, lse)
-               : launch_attend_g<4>(c, q, Kbase, Vbase, tok_idx, idx_stride, row_stride, n_tok, n_splits, v, out, lse);
+    return c->d.kv_dtype == SKV_BF16 ? launch_attend_g<2, false>(c, a, n_splits) : launch_attend_g<4, false>(c, a, n_splits);
+}
+
+hipError_t launch_select_attend(Ctx* c, const void* q, const void* K_layer, const void* V_layer, const float* score,
+                                const int32_t* sent_off, const int32_t* sent_len, const SeqView& v, float* out,
+                                float* lse, int32_t* tok_idx_out, int32_t* n_tok_out) {
+    AttArgs a = att_common(c, q, K_layer, V_layer, v, out, lse);
+    a.score = score; a.sent_off = sent_off; a.sent_len = sent_len;
+    a.tok_idx_out = tok_idx_out; a.n_tok_out = n_tok_out; a.idx_stride = c->d.max_budget;
+    return c->d.kv_dtype == SKV_BF16 ? launch_attend_g<2, true>(c, a, c->max_splits) : launch_attend_g<4, true>(c, a, c->max_splits);
 }
 
 }  // namespace skv

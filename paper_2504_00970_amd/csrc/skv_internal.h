@@ -22,7 +22,7 @@ constexpr int kScoreRowsPerWave = 8;
 constexpr int kScoreWavesPerBlock = 4;
 constexpr int kScoreRowsPerBlock = kScoreRowsPerWave * kScoreWavesPerBlock;   // 32 buckets per block
 
-constexpr int kSelectThreads = 1024;
+constexpr int kSelectThreads = 256;
 
 constexpr int kGatherRowsPerBlock = 64;
 constexpr int kGatherThreads = 256;
@@ -44,11 +44,6 @@ struct Ctx {
     float* att_ml;          // [max_batch * Hq][max_splits][2] (running max in log2 units, sum)
     unsigned int* att_counter;  // [max_batch * Hkv] arrivals per (sequence, KV head); zero between calls
     float* f_score;         // [Hkv][max_sentences] scores of the fused path
-    int32_t* sel_tokpos;    // [max_batch * Hkv][max_sel] first output slot of each selected bucket
-    int32_t* f_sel_sent;    // [max_batch * Hkv][max_sel]
-    int32_t* f_n_sel;       // [max_batch * Hkv]
-    int32_t* f_n_tok;       // [max_batch * Hkv]
-    int32_t* f_tok_idx;     // [max_batch * Hkv][max_budget]
 };
 
 // Ragged-batch view handed to the decode kernels.  For single-sequence calls cu_tok / cu_sent /
@@ -69,15 +64,17 @@ hipError_t launch_segment(Ctx* c, const int32_t* tok, int32_t T, const uint32_t*
 hipError_t launch_semvec(Ctx* c, const void* K_pool, int32_t T, const int32_t* sent_off, int32_t S, float* semvec);
 hipError_t launch_score(Ctx* c, const void* q, const float* semvec_layer, const SeqView& v, float* score);
 hipError_t launch_select(Ctx* c, const float* score, const int32_t* sent_off, const int32_t* sent_len,
-                         const SeqView& v, int32_t* sel_sent, int32_t* tokpos, int32_t* n_sel,
-                         int32_t* tok_idx, int32_t idx_stride, int32_t* n_tok);
+                         const SeqView& v, int32_t* sel_sent, int32_t* n_sel, int32_t* tok_idx, int32_t idx_stride,
+                         int32_t* n_tok);
 hipError_t launch_gather(Ctx* c, const void* K_layer, const void* V_layer, int32_t T, const int32_t* tok_idx,
                          const int32_t* n_tok, int32_t budget, void* K_sel, void* V_sel);
-// K/V rows come either from K_sel/V_sel [B*Hkv][row_stride][D] (tok_idx == null) or from the layer's
-// pool [Hkv][T_total][D] through tok_idx [B*Hkv][idx_stride] (positions local to the sequence).
-hipError_t launch_attend(Ctx* c, const void* q, const void* Kbase, const void* Vbase, const int32_t* tok_idx,
-                         int32_t idx_stride, int32_t row_stride, const int32_t* n_tok, int32_t n_splits,
-                         const SeqView& v, float* out, float* lse);
+// Attention over K_sel/V_sel [B*Hkv][row_stride][D] with n_tok [B*Hkv] from memory.
+hipError_t launch_attend(Ctx* c, const void* q, const void* K_sel, const void* V_sel, int32_t row_stride,
+                         const int32_t* n_tok, int32_t n_splits, const SeqView& v, float* out, float* lse);
+// Selection from `score` fused with attention over the layer's pool [Hkv][T_total][D].
+hipError_t launch_select_attend(Ctx* c, const void* q, const void* K_layer, const void* V_layer, const float* score,
+                                const int32_t* sent_off, const int32_t* sent_len, const SeqView& v, float* out,
+                                float* lse, int32_t* tok_idx_out, int32_t* n_tok_out);
 
 // A K/V row is D * EB bytes = LPR lanes of 16 bytes, so one wave-wide 128-bit load covers RPW
 // consecutive rows; each lane holds EPL elements of its row.
