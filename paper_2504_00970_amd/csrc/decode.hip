@@ -9,8 +9,6 @@
 
 namespace skv {
 
-static_assert(kSelectThreads == kAttThreads, "the fused kernel runs the selection with its own 256 threads");
-
 // Per-sequence slice of a ragged batch.
 struct Seq {
     int32_t tok_base, n_tok_ctx;     // first pool row and number of tokens of the sequence
@@ -126,26 +124,26 @@ hipError_t launch_score(Ctx* c, const void* q, const float* semvec_layer, const 
 }
 
 // ------------------------------------------------------------------------------------------------
-// Selection (Sec. 4.2 ranking + budgeted retrieval) as a block-level routine for 256 threads, used by
-// the stand-alone select kernel (one block per sequence and KV head) and, redundantly per block, by
-// the fused attention kernel.
+// Selection (Sec. 4.2 ranking + budgeted retrieval) as a block-level routine for kBlockThreads
+// threads, used by the stand-alone select kernel (one block per sequence and KV head) and, redundantly
+// per block, by the fused attention kernel.
 //
 // Buckets are ranked by (score descending, id ascending) and taken along the ranking until the first
 // one that does not fit.  Because lengths are positive the running total along the ranking is
 // increasing, so the retrieved set is {i : (total length ranked before i) + len_i <= budget}.  The
 // first bucket that overflows (the "cut") is found without sorting, by a length-weighted radix select
-// on an order-preserving 32-bit image of the score: 11 + 11 + 10 bit digits, most significant first.
-// Per pass: LDS atomics build a histogram of (count, total length) per digit; after ONE barrier every
-// wave scans the whole histogram by itself (32 digits per lane, a wave-level suffix scan, a ballot for
-// the digit in which the running total crosses the budget), so all waves hold the same result without
-// further synchronisation.  The three histograms are zeroed up front, while the scores are in flight.
-// The search stops as soon as the crossing digit holds a single bucket; buckets with exactly the
-// cut's score are resolved in id order by a scan.
+// on an order-preserving 32-bit image of the score, 8 bits per pass, most significant first.  Per pass:
+// LDS atomics build a 256-entry histogram of (count, total length) per digit, one wave scans it from
+// the top digit (4 digits per lane, wave suffix scan, ballot for the digit in which the running total
+// crosses the budget) and publishes (digit, carry, count).  The four histograms are zeroed up front.
+// The search stops as soon as the crossing digit holds a single bucket (typically after two passes);
+// buckets with exactly the cut's score are resolved in id order by a scan.
 //
-// Thread t owns the kpt = ceil(S / 256) consecutive buckets [t*kpt, (t+1)*kpt): keys, lengths and
-// offsets of the first KREG of them live in registers (one global round trip for the whole routine);
-// buckets beyond KREG per thread are re-read from memory in every phase.  The blocked ownership makes
-// the id-ordered compaction a thread-local walk plus one block scan.
+// The routine is written for few instructions per wave (a wave issues one instruction every 4+
+// cycles, so instruction count is latency): thread t owns the kpt = ceil(S / 1024) consecutive buckets
+// [t*kpt, (t+1)*kpt); keys, lengths and offsets of the first KREG of them live in registers (one
+// global round trip); buckets beyond KREG per thread are re-read from memory in every phase.  The
+// blocked ownership makes the id-ordered compaction a thread-local walk plus one block scan.
 // ------------------------------------------------------------------------------------------------
 
 __device__ __forceinline__ uint32_t score_key(float f) {
@@ -155,23 +153,20 @@ __device__ __forceinline__ uint32_t score_key(float f) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-constexpr int kSelWaves = kSelectThreads / kWave;
-constexpr int kSelKreg = 24;                                  // 256 threads x 24 buckets in registers: S <= 6144
-constexpr int kMaxDigitBits = 11;
-constexpr int kBins = 1 << kMaxDigitBits;
-constexpr int kHistStride = kBins + kBins / 32;               // one pad slot per 32 digits: lane-strided reads spread over banks
+constexpr int kBlockWaves = kBlockThreads / kWave;
+constexpr int kSelKreg = 6;                                   // 1024 threads x 6 buckets in registers: S <= 6144
+constexpr int kDigitBits = 8, kBins = 1 << kDigitBits, kPasses = 32 / kDigitBits;
 constexpr unsigned long long kLenMask = (1ull << 40) - 1;
 
 struct SelectShared {
-    unsigned long long hist[3][kHistStride];                  // packed (count << 40 | total length) per digit
-    unsigned long long wave_tot[2][kSelWaves];
+    unsigned long long hist[kPasses][kBins];                  // packed (count << 40 | total length) per digit
+    unsigned long long wave_tot[2][kBlockWaves];
+    long long carry;
+    int digit;
+    int cnt;
 };
-constexpr int kSelListCap = (int)(sizeof(unsigned long long) * 3 * kHistStride / sizeof(int4));
 
-__device__ __forceinline__ int hist_slot(int digit) { return digit + (digit >> 5); }
-
-// Inclusive scan over the block's 256 threads (thread order); one barrier.  `slot` must not be reused
-// within a kernel.  Returns the inclusive value; *total receives the block total.
+// Inclusive scan over the block's threads (thread order); one barrier.  A `slot` is used once per kernel.
 __device__ __forceinline__ unsigned long long block_scan_u64(unsigned long long val, unsigned long long* slot,
                                                              unsigned long long* total) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -185,7 +180,7 @@ __device__ __forceinline__ unsigned long long block_scan_u64(unsigned long long 
     __syncthreads();
     unsigned long long pre = 0, tot = 0;
 #pragma unroll
-    for (int i = 0; i < kSelWaves; ++i) {
+    for (int i = 0; i < kBlockWaves; ++i) {
         const unsigned long long t = slot[i];
         if (i < w) pre += t;
         tot += t;
@@ -194,18 +189,18 @@ __device__ __forceinline__ unsigned long long block_scan_u64(unsigned long long 
     return x + pre;
 }
 
-// One wave scans a finished histogram of 2^BITS digits from the top digit down and finds the digit in
-// which carry + (running total length) first exceeds the budget.  Returns false if the total fits.
-template <int BITS>
-__device__ __forceinline__ bool find_crossing(const unsigned long long* __restrict__ H, long long carry, long long budget,
-                                              int* digit, long long* new_carry, int* cnt) {
-    constexpr int kN = 1 << BITS, kPerLane = kN / kWave;
-    const int lane = threadIdx.x & 63;
+// Wave 0 scans a finished 256-digit histogram from the top digit down and publishes the digit in which
+// carry + (running total length) first exceeds the budget (digit = -1 if everything fits).
+__device__ __forceinline__ void find_crossing(SelectShared& sh, int pass, long long carry, long long budget) {
+    if (threadIdx.x >= kWave) return;
+    constexpr int kPerLane = kBins / kWave;                   // 4
+    const int lane = threadIdx.x;
+    const unsigned long long* H = sh.hist[pass];
     unsigned long long hv[kPerLane];
     unsigned int local = 0;
 #pragma unroll
     for (int j = 0; j < kPerLane; ++j) {
-        hv[j] = H[hist_slot(kN - 1 - (lane * kPerLane + j))];     // lane order == descending digit order
+        hv[j] = H[kBins - 1 - (lane * kPerLane + j)];         // lane order == descending digit order
         local += (unsigned int)(hv[j] & kLenMask);
     }
     unsigned int incl = local;
@@ -214,28 +209,23 @@ __device__ __forceinline__ bool find_crossing(const unsigned long long* __restri
         const unsigned int t = __shfl_up(incl, off);
         if (lane >= off) incl += t;
     }
-    const long long above = carry + (long long)(incl - local);    // total length ranked above this lane's digits
-    const bool has = above <= budget && above + (long long)local > budget;
-    const unsigned long long mask = __ballot(has);
-    if (mask == 0) return false;
-    int d = 0, c = 0;
-    long long run = above, nc = 0;
+    long long run = carry + (long long)(incl - local);        // total length ranked above this lane's digits
+    if (lane == 0) sh.digit = -1;
 #pragma unroll
     for (int j = 0; j < kPerLane; ++j) {
         const long long l = (long long)(hv[j] & kLenMask);
-        if (l > 0 && run <= budget && run + l > budget) { d = kN - 1 - (lane * kPerLane + j); nc = run; c = (int)(hv[j] >> 40); }
+        if (l > 0 && run <= budget && run + l > budget) {     // true for exactly one (lane, j) unless all fits
+            sh.digit = kBins - 1 - (lane * kPerLane + j);
+            sh.carry = run;
+            sh.cnt = (int)(hv[j] >> 40);
+        }
         run += l;
     }
-    const int src = __ffsll((long long)mask) - 1;
-    *digit = __shfl(d, src);
-    *cnt = __shfl(c, src);
-    *new_carry = __shfl(nc, src);
-    return true;
 }
 
 // emit(s, off_s, len_s, sel_pos, tok_pos) is called by the owner thread of every selected bucket,
 // sel_pos / tok_pos being the number of selected buckets / tokens with lower ids.
-// Every thread of the (256-thread) block must call this; *n_sel_out / *n_tok_out are block-uniform.
+// Every thread of the block must call this; *n_sel_out / *n_tok_out are block-uniform.
 template <int KREG, typename Emit>
 __device__ __forceinline__ void select_block(const float* __restrict__ sc, const int32_t* __restrict__ len,
                                              const int32_t* __restrict__ off, int32_t S, long long budget,
@@ -246,7 +236,7 @@ __device__ __forceinline__ void select_block(const float* __restrict__ sc, const
         *n_tok_out = 0;
         return;
     }
-    const int kpt = (S + kSelectThreads - 1) / kSelectThreads;
+    const int kpt = (S + kBlockThreads - 1) / kBlockThreads;
     const int32_t s0 = tid * kpt;
 
     uint32_t rkey[KREG];
@@ -256,18 +246,17 @@ __device__ __forceinline__ void select_block(const float* __restrict__ sc, const
         rkey[i] = 0; rlen[i] = 0; roff[i] = 0;
         if (i < kpt) {                                     // block-uniform; addresses clamped, loads unconditional
             const int32_t sidx = min(s0 + i, S - 1);
-            rkey[i] = score_key(sc[sidx]);
+            rkey[i] = __float_as_uint(sc[sidx]);
             rlen[i] = len[sidx];
             roff[i] = off[sidx];
         }
     }
-    SKV_T(15);
     // zero the histograms while the loads are in flight
-    {
-        unsigned long long* h = &sh.hist[0][0];
-        for (int i = tid; i < 3 * kHistStride; i += kSelectThreads) h[i] = 0;
-    }
+    static_assert(kPasses * kBins == kBlockThreads, "one histogram entry per thread");
+    (&sh.hist[0][0])[tid] = 0;
     __syncthreads();
+#pragma unroll
+    for (int i = 0; i < KREG; ++i) rkey[i] = score_key(__uint_as_float(rkey[i]));
     SKV_T(1);
 
     // fn(s, key, len, off) for every bucket s the thread owns, in id order
@@ -285,46 +274,23 @@ __device__ __forceinline__ void select_block(const float* __restrict__ sc, const
     long long carry = 0;        // total length of the buckets ranked strictly above the current digit range
     int cut_cnt = 0;            // number of buckets sharing the resolved prefix
     bool select_all = false;
-    {
-        int digit;
-        // pass 0: key bits 31..21
+    for (int pass = 0; pass < kPasses; ++pass) {
+        const int nshift = shift - kDigitBits;
+        unsigned long long* H = sh.hist[pass];
         for_items([&](int32_t, uint32_t k, int32_t ln, int32_t) {
-            atomicAdd(&sh.hist[0][hist_slot(k >> 21)], (1ull << 40) | (unsigned long long)(uint32_t)ln);
+            if (shift == 32 || (k >> shift) == prefix)
+                atomicAdd(&H[(k >> nshift) & (kBins - 1)], (1ull << 40) | (unsigned long long)(uint32_t)ln);
         });
-        SKV_T(10);
         __syncthreads();
-        SKV_T(11);
-        if (!find_crossing<11>(sh.hist[0], carry, budget, &digit, &carry, &cut_cnt)) {
-            select_all = true;                                  // everything fits
-        } else {
-            prefix = (uint32_t)digit;
-            shift = 21;
-            SKV_T(12);
-            if (cut_cnt > 1) {
-                // pass 1: key bits 20..10 of the buckets in the crossing digit
-                for_items([&](int32_t, uint32_t k, int32_t ln, int32_t) {
-                    if ((k >> 21) == prefix)
-                        atomicAdd(&sh.hist[1][hist_slot((k >> 10) & 2047)], (1ull << 40) | (unsigned long long)(uint32_t)ln);
-                });
-                SKV_T(13);
-                __syncthreads();
-                SKV_T(14);
-                find_crossing<11>(sh.hist[1], carry, budget, &digit, &carry, &cut_cnt);
-                prefix = (prefix << 11) | (uint32_t)digit;
-                shift = 10;
-                if (cut_cnt > 1) {
-                    // pass 2: key bits 9..0
-                    for_items([&](int32_t, uint32_t k, int32_t ln, int32_t) {
-                        if ((k >> 10) == prefix)
-                            atomicAdd(&sh.hist[2][hist_slot(k & 1023)], (1ull << 40) | (unsigned long long)(uint32_t)ln);
-                    });
-                    __syncthreads();
-                    find_crossing<10>(sh.hist[2], carry, budget, &digit, &carry, &cut_cnt);
-                    prefix = (prefix << 10) | (uint32_t)digit;
-                    shift = 0;
-                }
-            }
-        }
+        find_crossing(sh, pass, carry, budget);
+        __syncthreads();
+        const int digit = sh.digit;
+        if (digit < 0) { select_all = true; break; }          // everything fits (only possible in pass 0)
+        prefix = (shift == 32) ? (uint32_t)digit : ((prefix << kDigitBits) | (uint32_t)digit);
+        carry = sh.carry;
+        cut_cnt = sh.cnt;
+        shift = nshift;
+        if (cut_cnt == 1) break;                               // the cut is unique: it is the bucket that overflows
     }
     const bool ties = !select_all && cut_cnt > 1;              // then shift == 0: several buckets share the cut's score
     SKV_T(2);
@@ -356,7 +322,7 @@ __device__ __forceinline__ void select_block(const float* __restrict__ sc, const
     }
     unsigned long long tot;
     const unsigned long long incl = block_scan_u64(mine, sh.wave_tot[1], &tot);
-    {
+    if (mine != 0) {
         unsigned long long pos = incl - mine;
         long long t = tie_run;
         for_items([&](int32_t s, uint32_t k, int32_t ln, int32_t o) {
@@ -371,16 +337,19 @@ __device__ __forceinline__ void select_block(const float* __restrict__ sc, const
     SKV_T(3);
 }
 
-// Stand-alone selection: the selected buckets go through an LDS list (reusing the histograms' space) so
-// that the token positions of each bucket are written by a whole wave, coalesced.
-__global__ __launch_bounds__(kSelectThreads) void select_kernel(const float* __restrict__ score,
-                                                                const int32_t* __restrict__ sent_off,
-                                                                const int32_t* __restrict__ sent_len, SeqView v,
-                                                                int32_t Hkv, int32_t max_sel,
-                                                                int32_t* __restrict__ sel_sent, int32_t* __restrict__ n_sel,
-                                                                int32_t* __restrict__ tok_idx, int32_t idx_stride,
-                                                                int32_t* __restrict__ n_tok) {
-    __shared__ __attribute__((aligned(16))) SelectShared sh;
+// Stand-alone selection: the selected buckets go through an LDS list so that the token positions of
+// each bucket are written by a whole wave, coalesced.
+constexpr int kSelListCap = 2048;
+
+__global__ __launch_bounds__(kBlockThreads) void select_kernel(const float* __restrict__ score,
+                                                               const int32_t* __restrict__ sent_off,
+                                                               const int32_t* __restrict__ sent_len, SeqView v,
+                                                               int32_t Hkv, int32_t max_sel,
+                                                               int32_t* __restrict__ sel_sent, int32_t* __restrict__ n_sel,
+                                                               int32_t* __restrict__ tok_idx, int32_t idx_stride,
+                                                               int32_t* __restrict__ n_tok) {
+    __shared__ SelectShared sh;
+    __shared__ int4 list[kSelListCap];                        // (bucket, offset, length, first output slot)
     const int bh = blockIdx.x, b = bh / Hkv, h = bh % Hkv;
     const Seq sq = seq_of(v, b);
     const long long budget = min(sq.budget, idx_stride);     // tok_idx holds at most idx_stride positions
@@ -389,7 +358,6 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(const float* __r
     const int32_t* off = sent_off + sq.sent_base + (v.cu_sent ? b : 0);
     int32_t* my_sel = sel_sent + (int64_t)bh * max_sel;
     int32_t* my_idx = tok_idx + (int64_t)bh * idx_stride;
-    int4* list = reinterpret_cast<int4*>(&sh.hist[0][0]);     // (bucket, offset, length, first output slot)
     int nsel;
     long long ntok;
     select_block<kSelKreg>(
@@ -407,7 +375,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(const float* __r
     __syncthreads();
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int listed = min(nsel, kSelListCap);
-    for (int e = w; e < listed; e += kSelWaves) {
+    for (int e = w; e < listed; e += kBlockWaves) {
         const int4 it = list[e];
         for (int32_t t = lane; t < it.z && it.w + t < idx_stride; t += kWave) my_idx[it.w + t] = it.y + t;
     }
@@ -416,7 +384,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(const float* __r
 hipError_t launch_select(Ctx* c, const float* score, const int32_t* sent_off, const int32_t* sent_len,
                          const SeqView& v, int32_t* sel_sent, int32_t* n_sel, int32_t* tok_idx, int32_t idx_stride,
                          int32_t* n_tok) {
-    hipLaunchKernelGGL(select_kernel, dim3(v.B * c->d.n_kv_heads), dim3(kSelectThreads), 0, c->stream, score, sent_off,
+    hipLaunchKernelGGL(select_kernel, dim3(v.B * c->d.n_kv_heads), dim3(kBlockThreads), 0, c->stream, score, sent_off,
                        sent_len, v, c->d.n_kv_heads, c->max_sel, sel_sent, n_sel, tok_idx, idx_stride, n_tok);
     return hipGetLastError();
 }
@@ -478,22 +446,23 @@ hipError_t launch_gather(Ctx* c, const void* K_layer, const void* V_layer, int32
 }
 
 // ------------------------------------------------------------------------------------------------
-// Attention (Eq. 3), split-K flash decoding.  Block (split, sequence*KV head) handles kAttChunk = 64
-// consecutive retrieved tokens for the G query heads of its KV head.
+// Attention (Eq. 3), split-K flash decoding.  A 1024-thread block (split, sequence*KV head) handles
+// kAttChunk = 64 consecutive retrieved tokens for the G query heads of its KV head.
 //   FUSED == false: rows come from K_sel/V_sel and n_tok from memory (skv_attend).
 //   FUSED == true : the block first runs the selection for its (sequence, head) from the scores
 //                   (redundantly with the other splits: the scores are a few KB in L2, and it saves a
 //                   launch plus a round trip through tok_idx), keeps the pool rows of its own 64 tokens
 //                   in LDS and reads K/V straight from the pool (skv_decode_step).
-// Then:
-//   1. every K and V lane chunk of the chunk is requested up front (16-byte loads, RPW rows per wave
-//      instruction), on clamped addresses so that no load waits for a bounds test;
-//   2. logits for the G heads: per-lane partial dot products, reduced over the LPR lanes of a row;
-//   3. one wave per query head: max, exp2, sum over the 64 logits (softmax in log2 units);
-//   4. P.V with per-lane accumulators, reduced over the rows of a wave and over the 4 waves in LDS;
-//   5. the un-normalised partial (m, l, acc) goes to the workspace; the last block to arrive for the
-//      (sequence, KV head) -- a device-scope counter, no spinning -- merges the partials with one
-//      round of independent loads and an online-softmax merge in registers and LDS.
+// Lane mapping: a wave covers RPW consecutive rows; lane = chunk * RPW + row, chunk being the 16-byte
+// piece of the row.  The wave's loads still cover whole rows (coalesced), the P.V sum over a wave's
+// rows is a DPP quad exchange (no LDS), and the q.k sum over chunks is DPP row rotations plus two
+// cross-row shuffles.
+//   1. every K and V chunk is requested up front on clamped addresses (no load waits for a bounds test);
+//   2. logits for the G heads -> LDS;   3. one wave per query head: max, exp2, sum over the 64 logits;
+//   4. P.V in registers, reduced over the wave's rows by DPP and over the 16 waves through LDS;
+//   5. the un-normalised partial (m, l, acc) goes to the workspace with write-through stores; the last
+//      block to arrive for the (sequence, KV head) -- a device-scope counter, no spinning -- merges the
+//      partials with one round of independent loads and an online-softmax merge.
 // ------------------------------------------------------------------------------------------------
 
 // Split-K partials travel between blocks (possibly on different XCDs, each with its own L2) inside one
@@ -502,8 +471,34 @@ hipError_t launch_gather(Ctx* c, const void* K_layer, const void* V_layer, int32
 __device__ __forceinline__ void st_agent(float* p, float v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ float ld_agent(const float* p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+__device__ __forceinline__ unsigned long long ld_agent64(const float* p) {       // two consecutive floats
+    return __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float lo_f(unsigned long long v) { return __uint_as_float((uint32_t)v); }
+__device__ __forceinline__ float hi_f(unsigned long long v) { return __uint_as_float((uint32_t)(v >> 32)); }
+
+// x + (x moved by a DPP pattern): quad_perm [1,0,3,2] = 0xB1, [2,3,0,1] = 0x4E, row_ror:n = 0x120 + n
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x) {
+    const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false);
+    return x + __int_as_float(moved);
+}
+// sum over the RPW rows of a wave (lane bits below log2 RPW); every lane gets the total
+template <int RPW>
+__device__ __forceinline__ float sum_rows(float x) {
+    x = dpp_add<0xB1>(x);
+    if (RPW == 4) x = dpp_add<0x4E>(x);
+    return x;
+}
+// sum over the LPR chunks of a row (the remaining lane bits); every lane gets the total
+template <int RPW>
+__device__ __forceinline__ float sum_chunks(float x) {
+    if (RPW == 2) x = dpp_add<0x4E>(x);
+    x = dpp_add<0x124>(x);
+    x = dpp_add<0x128>(x);
+    x += __shfl_xor(x, 16);
+    x += __shfl_xor(x, 32);
+    return x;
 }
 
 struct AttArgs {
@@ -529,27 +524,27 @@ struct AttArgs {
 };
 
 template <int EB, int G, bool FUSED>
-__global__ __launch_bounds__(kAttThreads) void attend_kernel(AttArgs a) {
+__global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
     using R = Row<EB>;
-    constexpr int kWaves = kAttThreads / kWave;
-    constexpr int kRowsPerIter = kWaves * R::RPW;
+    constexpr int kRowsPerIter = kBlockWaves * R::RPW;        // 64 (bf16) or 32 (fp32)
     constexpr int kIter = kAttChunk / kRowsPerIter;
     constexpr int kRowBytes = kHeadDim * EB;
     constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
-    constexpr int kCol4 = G * (kHeadDim / 4);                // float4 columns over the G heads
-    constexpr int kGroups = kAttThreads / kCol4;             // 8, 4, 2, 1 for G = 1, 2, 4, 8
-    constexpr int kMergeFloats = kGroups * kCol4 * 6;        // O (float4), M, L per (group, column)
-    constexpr int kRedFloats = (kWaves * G * kHeadDim > kMergeFloats) ? kWaves * G * kHeadDim : kMergeFloats;
+    constexpr int kOut = G * kHeadDim;                        // outputs of the block
+    constexpr int kCol2 = kOut / 2;                           // float pairs over the G heads
+    constexpr int kGroups = kBlockThreads / kCol2;            // split groups of the merge: 16, 8, 4, 2 for G = 1, 2, 4, 8
+    static_assert(kIter >= 1 && kGroups >= 1, "block shape");
 
     __shared__ float sm_logit[G][kAttChunk];
-    __shared__ __attribute__((aligned(16))) float sm_red_flat[kRedFloats];
+    constexpr int kRedFloats = (kBlockWaves * G * kHeadDim > 4 * kBlockThreads) ? kBlockWaves * G * kHeadDim : 4 * kBlockThreads;
+    __shared__ __attribute__((aligned(16))) float sm_red_flat[kRedFloats];           // wave partial sums, later the merge scratch
+    float (*sm_red)[G][kHeadDim] = reinterpret_cast<float (*)[G][kHeadDim]>(sm_red_flat);
     __shared__ int sm_last;
     __shared__ int32_t sm_row[kAttChunk];
-    float (*sm_red)[G][kHeadDim] = reinterpret_cast<float (*)[G][kHeadDim]>(sm_red_flat);
 
     const int bh = blockIdx.y, b = bh / a.Hkv, h = bh % a.Hkv, split = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int r = lane / R::LPR, cc = lane % R::LPR;
+    const int r = lane % R::RPW, cc = lane / R::RPW;
     const int Hq = a.Hkv * G;
     const int64_t qhead0 = (int64_t)b * Hq + (int64_t)h * G;      // first query head of the group
     const Seq sq = seq_of(a.v, b);
@@ -582,7 +577,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(AttArgs a) {
     }
     if (n <= 0) {
         if (split == 0) {
-            for (int i = tid; i < G * kHeadDim; i += kAttThreads) a.out[qhead0 * kHeadDim + i] = 0.f;
+            for (int i = tid; i < kOut; i += kBlockThreads) a.out[qhead0 * kHeadDim + i] = 0.f;
             if (a.lse && tid < G) a.lse[qhead0 + tid] = -INFINITY;
         }
         return;
@@ -590,8 +585,8 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(AttArgs a) {
     const int nsplit = (n + kAttChunk - 1) / kAttChunk;
     if (split >= nsplit) return;
     const int32_t cnt = min(kAttChunk, n - j0);
-
     SKV_T(4);
+
     // ---- 1. issue every load of the chunk ------------------------------------------------------------
     const char* Kh;
     const char* Vh;
@@ -631,38 +626,29 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(AttArgs a) {
         const uint4 t = *reinterpret_cast<const uint4*>(a.q + ((qhead0 + g) * kHeadDim) * EB + cc * 16);
         R::unpack(t, qf[g]);
     }
-
     SKV_T(5);
+
     // ---- 2. logits ---------------------------------------------------------------------------------
     const float scale = kLog2e * rsqrtf((float)kHeadDim);
 #pragma unroll
     for (int i = 0; i < kIter; ++i) {
         float kf[R::EPL];
         R::unpack(kraw[i], kf);
-        float s[G];
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             float acc = 0.f;
 #pragma unroll
             for (int e = 0; e < R::EPL; ++e) acc += qf[g][e] * kf[e];
-            s[g] = acc;
-        }
-#pragma unroll
-        for (int off = R::LPR / 2; off >= 1; off >>= 1) {
-#pragma unroll
-            for (int g = 0; g < G; ++g) s[g] += __shfl_xor(s[g], off);
-        }
-        if (cc == 0) {
-            const int jj = i * kRowsPerIter + w * R::RPW + r;
-#pragma unroll
-            for (int g = 0; g < G; ++g) sm_logit[g][jj] = live[i] ? s[g] * scale : -INFINITY;
+            acc = sum_chunks<R::RPW>(acc);
+            if (cc == 0) sm_logit[g][i * kRowsPerIter + w * R::RPW + r] = live[i] ? acc * scale : -INFINITY;
         }
     }
     __syncthreads();
     SKV_T(6);
 
     // ---- 3. softmax over the chunk, one wave per query head --------------------------------------------
-    for (int g = w; g < G; g += kWaves) {
+    if (w < G) {
+        const int g = w;
         const float x = sm_logit[g][lane];
         float m = x;
 #pragma unroll
@@ -703,28 +689,27 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(AttArgs a) {
         }
     }
 #pragma unroll
-    for (int off = R::LPR; off < 64; off <<= 1) {
+    for (int g = 0; g < G; ++g)
 #pragma unroll
-        for (int g = 0; g < G; ++g)
-#pragma unroll
-            for (int e = 0; e < R::EPL; ++e) acc[g][e] += __shfl_xor(acc[g][e], off);
-    }
+        for (int e = 0; e < R::EPL; ++e) acc[g][e] = sum_rows<R::RPW>(acc[g][e]);
     if (r == 0) {
 #pragma unroll
         for (int g = 0; g < G; ++g)
 #pragma unroll
-            for (int e = 0; e < R::EPL; ++e) sm_red[w][g][cc * R::EPL + e] = acc[g][e];
+            for (int e = 0; e < R::EPL; e += 4)
+                *reinterpret_cast<float4*>(&sm_red[w][g][cc * R::EPL + e]) =
+                    make_float4(acc[g][e], acc[g][e + 1], acc[g][e + 2], acc[g][e + 3]);
     }
     __syncthreads();
-    for (int i = tid; i < G * kHeadDim; i += kAttThreads) {
+    for (int i = tid; i < kOut; i += kBlockThreads) {
         const int g = i / kHeadDim, d = i % kHeadDim;
         float o = sm_red[0][g][d];
 #pragma unroll
-        for (int ww = 1; ww < kWaves; ++ww) o += sm_red[ww][g][d];
+        for (int ww = 1; ww < kBlockWaves; ++ww) o += sm_red[ww][g][d];
         st_agent(a.part + (((qhead0 + g) * a.max_splits) + split) * kHeadDim + d, o);
     }
-
     SKV_T(7);
+
     // ---- 5. last arrival combines ------------------------------------------------------------------
     // The barrier (with its wait for outstanding stores) puts the block's write-through partial stores
     // before thread 0's device-scope increment; whoever reads nsplit - 1 knows every partial is there.
@@ -736,65 +721,59 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(AttArgs a) {
     __syncthreads();
     SKV_T(8);
     if (!sm_last) return;
-    // A thread owns one float4 column of one head and every kGroups-th split: one batch of independent
-    // loads, merged online (running max M, normaliser L, output O) in registers; groups merge through LDS.
+    // A thread owns one pair of output floats and every kGroups-th split: one batch of independent 8-byte
+    // loads, merged online (running max M, normaliser L, outputs) in registers; groups merge through LDS.
+    float4* scratch = reinterpret_cast<float4*>(sm_red_flat);               // (o0, o1, M, L) per thread
     {
-        const int col = tid % kCol4, grp = tid / kCol4;
-        const int g = col / (kHeadDim / 4), d4 = col % (kHeadDim / 4);
+        const int col = tid % kCol2, grp = tid / kCol2;
+        const int g = col / (kHeadDim / 2);
         const float* mlg = a.ml + ((qhead0 + g) * a.max_splits) * 2;
-        const float* pg = a.part + ((qhead0 + g) * a.max_splits) * kHeadDim + d4 * 4;
-        float M = -INFINITY, L = 0.f;
-        float4 O = make_float4(0.f, 0.f, 0.f, 0.f);
-        constexpr int kU = 16;
+        const float* pg = a.part + ((qhead0 + g) * a.max_splits) * kHeadDim + (col % (kHeadDim / 2)) * 2;
+        float M = -INFINITY, L = 0.f, o0 = 0.f, o1 = 0.f;
+        constexpr int kU = 8;
         for (int s0 = grp; s0 < nsplit; s0 += kGroups * kU) {
-            float4 pv[kU];
-            float2 mv[kU];
+            unsigned long long pv[kU], mv[kU];
 #pragma unroll
             for (int u = 0; u < kU; ++u) {                   // clamped, unconditional loads
                 const int sidx = min(s0 + u * kGroups, nsplit - 1);
-                const float* pp = pg + (int64_t)sidx * kHeadDim;
-                pv[u] = make_float4(ld_agent(pp), ld_agent(pp + 1), ld_agent(pp + 2), ld_agent(pp + 3));
-                mv[u] = make_float2(ld_agent(mlg + 2 * sidx), ld_agent(mlg + 2 * sidx + 1));
+                pv[u] = ld_agent64(pg + (int64_t)sidx * kHeadDim);
+                mv[u] = ld_agent64(mlg + 2 * sidx);
             }
 #pragma unroll
             for (int u = 0; u < kU; ++u) {
-                const float ms = (s0 + u * kGroups < nsplit) ? mv[u].x : -INFINITY;
+                const float ms = (s0 + u * kGroups < nsplit) ? lo_f(mv[u]) : -INFINITY;
                 if (ms > -INFINITY) {
                     const float nm = fmaxf(M, ms);
                     const float ca = exp2f(M - nm), cb = exp2f(ms - nm);      // M == -inf gives ca == 0
-                    L = L * ca + mv[u].y * cb;
-                    O.x = O.x * ca + pv[u].x * cb; O.y = O.y * ca + pv[u].y * cb;
-                    O.z = O.z * ca + pv[u].z * cb; O.w = O.w * ca + pv[u].w * cb;
+                    L = L * ca + hi_f(mv[u]) * cb;
+                    o0 = o0 * ca + lo_f(pv[u]) * cb;
+                    o1 = o1 * ca + hi_f(pv[u]) * cb;
                     M = nm;
                 }
             }
         }
-        reinterpret_cast<float4*>(sm_red_flat)[grp * kCol4 + col] = O;
-        sm_red_flat[kGroups * kCol4 * 4 + grp * kCol4 + col] = M;
-        sm_red_flat[kGroups * kCol4 * 5 + grp * kCol4 + col] = L;
+        __syncthreads();                                     // sm_red (partial sums) no longer read by anyone
+        scratch[grp * kCol2 + col] = make_float4(o0, o1, M, L);
     }
     __syncthreads();
-    if (tid < kCol4) {
+    if (tid < kCol2) {
         float M = -INFINITY;
 #pragma unroll
-        for (int grp = 0; grp < kGroups; ++grp) M = fmaxf(M, sm_red_flat[kGroups * kCol4 * 4 + grp * kCol4 + tid]);
-        float L = 0.f;
-        float4 O = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int grp = 0; grp < kGroups; ++grp) M = fmaxf(M, scratch[grp * kCol2 + tid].z);
+        float L = 0.f, o0 = 0.f, o1 = 0.f;
 #pragma unroll
         for (int grp = 0; grp < kGroups; ++grp) {
-            const float mg = sm_red_flat[kGroups * kCol4 * 4 + grp * kCol4 + tid];
-            if (mg > -INFINITY) {
-                const float c = exp2f(mg - M);
-                const float4 t = reinterpret_cast<const float4*>(sm_red_flat)[grp * kCol4 + tid];
-                L += c * sm_red_flat[kGroups * kCol4 * 5 + grp * kCol4 + tid];
-                O.x += c * t.x; O.y += c * t.y; O.z += c * t.z; O.w += c * t.w;
+            const float4 t = scratch[grp * kCol2 + tid];
+            if (t.z > -INFINITY) {
+                const float c = exp2f(t.z - M);
+                L += c * t.w; o0 += c * t.x; o1 += c * t.y;
             }
         }
         const bool empty = !(L > 0.f);                       // every retrieved position was out of range
         const float inv = empty ? 0.f : 1.f / L;
-        reinterpret_cast<float4*>(a.out + qhead0 * kHeadDim)[tid] = make_float4(O.x * inv, O.y * inv, O.z * inv, O.w * inv);
-        if (a.lse && (tid % (kHeadDim / 4)) == 0)
-            a.lse[qhead0 + tid / (kHeadDim / 4)] = empty ? -INFINITY : (M + log2f(L)) * kLn2;
+        reinterpret_cast<float2*>(a.out + qhead0 * kHeadDim)[tid] = make_float2(o0 * inv, o1 * inv);
+        if (a.lse && (tid % (kHeadDim / 2)) == 0)
+            a.lse[qhead0 + tid / (kHeadDim / 2)] = empty ? -INFINITY : (M + log2f(L)) * kLn2;
     }
     if (tid == 0) __hip_atomic_store(&a.counter[bh], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next call
     SKV_T(9);
@@ -802,7 +781,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(AttArgs a) {
 
 template <int EB, bool FUSED>
 static hipError_t launch_attend_g(Ctx* c, const AttArgs& a, int32_t n_splits) {
-    const dim3 grid(n_splits, a.v.B * c->d.n_kv_heads), block(kAttThreads);
+    const dim3 grid(n_splits, a.v.B * c->d.n_kv_heads), block(kBlockThreads);
     switch (c->G) {
         case 1: hipLaunchKernelGGL((attend_kernel<EB, 1, FUSED>), grid, block, 0, c->stream, a); break;
         case 2: hipLaunchKernelGGL((attend_kernel<EB, 2, FUSED>), grid, block, 0, c->stream, a); break;

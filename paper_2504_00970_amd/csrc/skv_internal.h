@@ -22,13 +22,12 @@ constexpr int kScoreRowsPerWave = 8;
 constexpr int kScoreWavesPerBlock = 4;
 constexpr int kScoreRowsPerBlock = kScoreRowsPerWave * kScoreWavesPerBlock;   // 32 buckets per block
 
-constexpr int kSelectThreads = 256;
+constexpr int kBlockThreads = 1024;   // select, attention and the fused select+attention kernel: 16 waves per block
 
 constexpr int kGatherRowsPerBlock = 64;
 constexpr int kGatherThreads = 256;
 
 constexpr int kAttChunk = 64;         // tokens per split-K block (one wave-width of logits)
-constexpr int kAttThreads = 256;
 
 struct Ctx {
     skv_desc d;
