@@ -132,18 +132,20 @@ hipError_t launch_score(Ctx* c, const void* q, const float* semvec_layer, const 
 // one that does not fit.  Because lengths are positive the running total along the ranking is
 // increasing, so the retrieved set is {i : (total length ranked before i) + len_i <= budget}.  The
 // first bucket that overflows (the "cut") is found without sorting, by a length-weighted radix select
-// on an order-preserving 32-bit image of the score, 8 bits per pass, most significant first.  Per pass:
-// LDS atomics build a 256-entry histogram of (count, total length) per digit, one wave scans it from
-// the top digit (4 digits per lane, wave suffix scan, ballot for the digit in which the running total
-// crosses the budget) and publishes (digit, carry, count).  The four histograms are zeroed up front.
-// The search stops as soon as the crossing digit holds a single bucket (typically after two passes);
-// buckets with exactly the cut's score are resolved in id order by a scan.
+// on an order-preserving 32-bit image of the score: 11 + 11 + 10 bit digits, most significant first.
+// Per pass: LDS atomics build a histogram of (count, total length) per digit; thread t owns digits
+// 2047-2t and 2046-2t, so a block-wide prefix sum in thread order (DPP wave scan + 16 wave totals) is
+// the running total from the top digit down, and exactly one thread sees the budget crossed inside
+// its two digits.  The three histograms are zeroed up front.  The search stops as soon as the crossing
+// digit holds a single bucket (typically after two passes); buckets with exactly the cut's score are
+// resolved in id order by a scan.
 //
 // The routine is written for few instructions per wave (a wave issues one instruction every 4+
-// cycles, so instruction count is latency): thread t owns the kpt = ceil(S / 1024) consecutive buckets
-// [t*kpt, (t+1)*kpt); keys, lengths and offsets of the first KREG of them live in registers (one
-// global round trip); buckets beyond KREG per thread are re-read from memory in every phase.  The
-// blocked ownership makes the id-ordered compaction a thread-local walk plus one block scan.
+// cycles, so instruction count is latency) and 32-bit arithmetic throughout (token totals < 2^31):
+// thread t owns the kpt = ceil(S / 1024) consecutive buckets [t*kpt, (t+1)*kpt); keys, lengths and
+// offsets of the first KREG of them live in registers (one global round trip); buckets beyond KREG per
+// thread are re-read from memory in every phase.  The blocked ownership makes the id-ordered
+// compaction a thread-local walk plus one block scan.
 // ------------------------------------------------------------------------------------------------
 
 __device__ __forceinline__ uint32_t score_key(float f) {
@@ -155,33 +157,40 @@ __device__ __forceinline__ uint32_t score_key(float f) {
 
 constexpr int kBlockWaves = kBlockThreads / kWave;
 constexpr int kSelKreg = 6;                                   // 1024 threads x 6 buckets in registers: S <= 6144
-constexpr int kDigitBits = 8, kBins = 1 << kDigitBits, kPasses = 32 / kDigitBits;
-constexpr unsigned long long kLenMask = (1ull << 40) - 1;
+constexpr int kBins = 2048;                                   // 11-bit digits (the last pass uses 1024)
 
 struct SelectShared {
-    unsigned long long hist[kPasses][kBins];                  // packed (count << 40 | total length) per digit
-    unsigned long long wave_tot[2][kBlockWaves];
-    long long carry;
-    int digit;
-    int cnt;
+    unsigned long long hist[3][kBins];                        // packed (count << 32 | total length) per digit
+    uint32_t wave_tot[6][kBlockWaves];                        // one slot per block scan
+    int32_t res[3][4];                                        // per pass: crossing digit (-1: none), carry, count
 };
 
-// Inclusive scan over the block's threads (thread order); one barrier.  A `slot` is used once per kernel.
-__device__ __forceinline__ unsigned long long block_scan_u64(unsigned long long val, unsigned long long* slot,
-                                                             unsigned long long* total) {
+// v + (v moved by a DPP pattern; lanes without a source, or rows masked out, add 0)
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_add_u32(uint32_t v) {
+    return v + (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, true);
+}
+// inclusive prefix sum over the 64 lanes of a wave: row_shr 1,2,4,8 then row_bcast 15 and 31
+__device__ __forceinline__ uint32_t wave_scan_u32(uint32_t v) {
+    v = dpp_add_u32<0x111, 0xf>(v);
+    v = dpp_add_u32<0x112, 0xf>(v);
+    v = dpp_add_u32<0x114, 0xf>(v);
+    v = dpp_add_u32<0x118, 0xf>(v);
+    v = dpp_add_u32<0x142, 0xa>(v);
+    v = dpp_add_u32<0x143, 0xc>(v);
+    return v;
+}
+// Inclusive scan over the block's threads (thread order); one barrier.  A `slot` is used once per call
+// of the selection.
+__device__ __forceinline__ uint32_t block_scan_u32(uint32_t val, uint32_t* slot, uint32_t* total) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    unsigned long long x = val;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const unsigned long long t = __shfl_up(x, off);
-        if (lane >= off) x += t;
-    }
+    const uint32_t x = wave_scan_u32(val);
     if (lane == 63) slot[w] = x;
     __syncthreads();
-    unsigned long long pre = 0, tot = 0;
+    uint32_t pre = 0, tot = 0;
 #pragma unroll
     for (int i = 0; i < kBlockWaves; ++i) {
-        const unsigned long long t = slot[i];
+        const uint32_t t = slot[i];
         if (i < w) pre += t;
         tot += t;
     }
@@ -189,53 +198,18 @@ __device__ __forceinline__ unsigned long long block_scan_u64(unsigned long long 
     return x + pre;
 }
 
-// Wave 0 scans a finished 256-digit histogram from the top digit down and publishes the digit in which
-// carry + (running total length) first exceeds the budget (digit = -1 if everything fits).
-__device__ __forceinline__ void find_crossing(SelectShared& sh, int pass, long long carry, long long budget) {
-    if (threadIdx.x >= kWave) return;
-    constexpr int kPerLane = kBins / kWave;                   // 4
-    const int lane = threadIdx.x;
-    const unsigned long long* H = sh.hist[pass];
-    unsigned long long hv[kPerLane];
-    unsigned int local = 0;
-#pragma unroll
-    for (int j = 0; j < kPerLane; ++j) {
-        hv[j] = H[kBins - 1 - (lane * kPerLane + j)];         // lane order == descending digit order
-        local += (unsigned int)(hv[j] & kLenMask);
-    }
-    unsigned int incl = local;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const unsigned int t = __shfl_up(incl, off);
-        if (lane >= off) incl += t;
-    }
-    long long run = carry + (long long)(incl - local);        // total length ranked above this lane's digits
-    if (lane == 0) sh.digit = -1;
-#pragma unroll
-    for (int j = 0; j < kPerLane; ++j) {
-        const long long l = (long long)(hv[j] & kLenMask);
-        if (l > 0 && run <= budget && run + l > budget) {     // true for exactly one (lane, j) unless all fits
-            sh.digit = kBins - 1 - (lane * kPerLane + j);
-            sh.carry = run;
-            sh.cnt = (int)(hv[j] >> 40);
-        }
-        run += l;
-    }
-}
-
 // emit(s, off_s, len_s, sel_pos, tok_pos) is called by the owner thread of every selected bucket,
-// sel_pos / tok_pos being the number of selected buckets / tokens with lower ids.
-// Every thread of the block must call this; *n_sel_out / *n_tok_out are block-uniform.
-template <int KREG, typename Emit>
+// sel_pos / tok_pos being the number of selected buckets / tokens with lower ids (sel_pos is only
+// computed when COUNT is set, else 0).  Every thread of the block must call this; *n_sel_out /
+// *n_tok_out are block-uniform.
+template <int KREG, bool COUNT, typename Emit>
 __device__ __forceinline__ void select_block(const float* __restrict__ sc, const int32_t* __restrict__ len,
-                                             const int32_t* __restrict__ off, int32_t S, long long budget,
-                                             SelectShared& sh, Emit emit, int* n_sel_out, long long* n_tok_out) {
+                                             const int32_t* __restrict__ off, int32_t S, int32_t budget,
+                                             SelectShared& sh, Emit emit, int32_t* n_sel_out, int32_t* n_tok_out) {
     const int tid = threadIdx.x;
-    if (S <= 0 || budget <= 0) {
-        *n_sel_out = 0;
-        *n_tok_out = 0;
-        return;
-    }
+    *n_sel_out = 0;
+    *n_tok_out = 0;
+    if (S <= 0 || budget <= 0) return;
     const int kpt = (S + kBlockThreads - 1) / kBlockThreads;
     const int32_t s0 = tid * kpt;
 
@@ -252,43 +226,62 @@ __device__ __forceinline__ void select_block(const float* __restrict__ sc, const
         }
     }
     // zero the histograms while the loads are in flight
-    static_assert(kPasses * kBins == kBlockThreads, "one histogram entry per thread");
-    (&sh.hist[0][0])[tid] = 0;
+    {
+        unsigned long long* h = &sh.hist[0][0];
+#pragma unroll
+        for (int i = 0; i < 3 * kBins / kBlockThreads; ++i) h[i * kBlockThreads + tid] = 0;
+        if (tid < 3) sh.res[tid][0] = -1;
+    }
     __syncthreads();
 #pragma unroll
-    for (int i = 0; i < KREG; ++i) rkey[i] = score_key(__uint_as_float(rkey[i]));
+    for (int i = 0; i < KREG; ++i) {
+        rkey[i] = score_key(__uint_as_float(rkey[i]));
+        if (s0 + i >= S) rlen[i] = 0;                      // slots past the end take part in nothing
+    }
     SKV_T(1);
-
-    // fn(s, key, len, off) for every bucket s the thread owns, in id order
-    auto for_items = [&](auto&& fn) {
-#pragma unroll
-        for (int i = 0; i < KREG; ++i)
-            if (i < kpt && s0 + i < S) fn(s0 + i, rkey[i], rlen[i], roff[i]);
-        for (int i = KREG; i < kpt; ++i)
-            if (s0 + i < S) fn(s0 + i, score_key(sc[s0 + i]), len[s0 + i], off[s0 + i]);
-    };
 
     // ---- weighted radix select of the cut ----------------------------------------------------------
     uint32_t prefix = 0;        // resolved high bits of the cut's key
     int shift = 32;             // number of unresolved low bits
-    long long carry = 0;        // total length of the buckets ranked strictly above the current digit range
-    int cut_cnt = 0;            // number of buckets sharing the resolved prefix
+    int32_t carry = 0;          // total length of the buckets ranked strictly above the current digit range
+    int32_t cut_cnt = 0;        // number of buckets sharing the resolved prefix
     bool select_all = false;
-    for (int pass = 0; pass < kPasses; ++pass) {
-        const int nshift = shift - kDigitBits;
+#pragma unroll
+    for (int pass = 0; pass < 3; ++pass) {
+        const int bits = pass < 2 ? 11 : 10, nbins = 1 << bits, nshift = shift - bits;
         unsigned long long* H = sh.hist[pass];
-        for_items([&](int32_t, uint32_t k, int32_t ln, int32_t) {
-            if (shift == 32 || (k >> shift) == prefix)
-                atomicAdd(&H[(k >> nshift) & (kBins - 1)], (1ull << 40) | (unsigned long long)(uint32_t)ln);
-        });
+#pragma unroll
+        for (int i = 0; i < KREG; ++i) {
+            if (i < kpt && rlen[i] > 0 && (pass == 0 || (rkey[i] >> shift) == prefix))
+                atomicAdd(&H[(rkey[i] >> nshift) & (nbins - 1)], (1ull << 32) | (unsigned long long)(uint32_t)rlen[i]);
+        }
+        for (int i = KREG; i < kpt; ++i) {
+            if (s0 + i < S) {
+                const uint32_t k = score_key(sc[s0 + i]);
+                if (pass == 0 || (k >> shift) == prefix)
+                    atomicAdd(&H[(k >> nshift) & (nbins - 1)], (1ull << 32) | (unsigned long long)(uint32_t)len[s0 + i]);
+            }
+        }
         __syncthreads();
-        find_crossing(sh, pass, carry, budget);
+        // thread order == descending digit order: thread t owns digits nbins-1-2t and nbins-2-2t
+        const int d1 = nbins - 1 - 2 * tid;
+        const unsigned long long v1 = d1 >= 0 ? H[d1] : 0ull, v0 = d1 >= 1 ? H[d1 - 1] : 0ull;
+        const uint32_t l1 = (uint32_t)v1, l0 = (uint32_t)v0;
+        uint32_t total;
+        const uint32_t incl = block_scan_u32(l1 + l0, sh.wave_tot[pass], &total);
+        const uint32_t above1 = (uint32_t)carry + incl - l1 - l0, above0 = above1 + l1;
+        if (l1 > 0 && above1 <= (uint32_t)budget && above1 + l1 > (uint32_t)budget) {
+            sh.res[pass][0] = d1; sh.res[pass][1] = (int32_t)above1; sh.res[pass][2] = (int32_t)(v1 >> 32);
+        }
+        if (l0 > 0 && above0 <= (uint32_t)budget && above0 + l0 > (uint32_t)budget) {
+            sh.res[pass][0] = d1 - 1; sh.res[pass][1] = (int32_t)above0; sh.res[pass][2] = (int32_t)(v0 >> 32);
+        }
         __syncthreads();
-        const int digit = sh.digit;
+        const int digit = sh.res[pass][0];
         if (digit < 0) { select_all = true; break; }          // everything fits (only possible in pass 0)
-        prefix = (shift == 32) ? (uint32_t)digit : ((prefix << kDigitBits) | (uint32_t)digit);
-        carry = sh.carry;
-        cut_cnt = sh.cnt;
+        prefix = (pass == 0) ? (uint32_t)digit : ((prefix << bits) | (uint32_t)digit);
+        carry = sh.res[pass][1];
+        cut_cnt = sh.res[pass][2];
         shift = nshift;
         if (cut_cnt == 1) break;                               // the cut is unique: it is the bucket that overflows
     }
@@ -296,44 +289,53 @@ __device__ __forceinline__ void select_block(const float* __restrict__ sc, const
     SKV_T(2);
 
     // ---- compaction in id order --------------------------------------------------------------------
-    long long tie_run = 0;          // length of tied buckets with lower ids (starts at the thread's base)
+    // fn(i, s, key, len, off) for every bucket the thread owns, in id order
+    auto for_items = [&](auto&& fn) {
+#pragma unroll
+        for (int i = 0; i < KREG; ++i)
+            if (i < kpt && rlen[i] > 0) fn(i, s0 + i, rkey[i], rlen[i], roff[i]);
+        for (int i = KREG; i < kpt; ++i)
+            if (s0 + i < S) fn(i, s0 + i, score_key(sc[s0 + i]), len[s0 + i], off[s0 + i]);
+    };
+    uint32_t tie_run = 0;          // length of tied buckets with lower ids (starts at the thread's base)
     if (ties) {
-        long long mine = 0;
-        for_items([&](int32_t, uint32_t k, int32_t ln, int32_t) { if (k == prefix) mine += ln; });
-        unsigned long long tot;
-        tie_run = (long long)block_scan_u64((unsigned long long)mine, sh.wave_tot[0], &tot) - mine;
+        uint32_t mine = 0;
+        for_items([&](int, int32_t, uint32_t k, int32_t ln, int32_t) { if (k == prefix) mine += (uint32_t)ln; });
+        uint32_t tot;
+        tie_run = block_scan_u32(mine, sh.wave_tot[3], &tot) - mine;
     }
-    auto chosen = [&](uint32_t k, int32_t ln, long long& tie_acc) -> bool {
+    auto chosen = [&](uint32_t k, int32_t ln, uint32_t& tie_acc) -> bool {
         if (select_all) return true;
-        const uint32_t hi = k >> shift;                        // shift < 32 here: at least one pass ran
-        if (hi > prefix) return true;
+        if ((k >> shift) > prefix) return true;                // shift < 32 here: at least one pass ran
         if (ties && k == prefix) {
-            tie_acc += ln;
-            return carry + tie_acc <= budget;
+            tie_acc += (uint32_t)ln;
+            return (uint32_t)carry + tie_acc <= (uint32_t)budget;
         }
         return false;
     };
-    unsigned long long mine = 0;
+    uint32_t my_tok = 0, my_cnt = 0;
     {
-        long long t = tie_run;
-        for_items([&](int32_t, uint32_t k, int32_t ln, int32_t) {
-            if (chosen(k, ln, t)) mine += (1ull << 40) | (unsigned long long)(uint32_t)ln;
+        uint32_t t = tie_run;
+        for_items([&](int, int32_t, uint32_t k, int32_t ln, int32_t) {
+            if (chosen(k, ln, t)) { my_tok += (uint32_t)ln; my_cnt += 1; }
         });
     }
-    unsigned long long tot;
-    const unsigned long long incl = block_scan_u64(mine, sh.wave_tot[1], &tot);
-    if (mine != 0) {
-        unsigned long long pos = incl - mine;
-        long long t = tie_run;
-        for_items([&](int32_t s, uint32_t k, int32_t ln, int32_t o) {
+    uint32_t tot_tok, tot_cnt = 0;
+    uint32_t pos_tok = block_scan_u32(my_tok, sh.wave_tot[4], &tot_tok) - my_tok;
+    uint32_t pos_cnt = 0;
+    if (COUNT) pos_cnt = block_scan_u32(my_cnt, sh.wave_tot[5], &tot_cnt) - my_cnt;
+    if (my_cnt != 0) {
+        uint32_t t = tie_run;
+        for_items([&](int, int32_t s, uint32_t k, int32_t ln, int32_t o) {
             if (chosen(k, ln, t)) {
-                emit(s, o, ln, (int)(pos >> 40), (long long)(pos & kLenMask));
-                pos += (1ull << 40) | (unsigned long long)(uint32_t)ln;
+                emit(s, o, ln, (int32_t)pos_cnt, (int32_t)pos_tok);
+                pos_tok += (uint32_t)ln;
+                pos_cnt += 1;
             }
         });
     }
-    *n_sel_out = (int)(tot >> 40);
-    *n_tok_out = (long long)(tot & kLenMask);
+    *n_sel_out = (int32_t)tot_cnt;
+    *n_tok_out = (int32_t)tot_tok;
     SKV_T(3);
 }
 
@@ -352,26 +354,25 @@ __global__ __launch_bounds__(kBlockThreads) void select_kernel(const float* __re
     __shared__ int4 list[kSelListCap];                        // (bucket, offset, length, first output slot)
     const int bh = blockIdx.x, b = bh / Hkv, h = bh % Hkv;
     const Seq sq = seq_of(v, b);
-    const long long budget = min(sq.budget, idx_stride);     // tok_idx holds at most idx_stride positions
+    const int32_t budget = min(sq.budget, idx_stride);       // tok_idx holds at most idx_stride positions
     const float* sc = score + (int64_t)h * v.S_total + sq.sent_base;
     const int32_t* len = sent_len + sq.sent_base;
     const int32_t* off = sent_off + sq.sent_base + (v.cu_sent ? b : 0);
     int32_t* my_sel = sel_sent + (int64_t)bh * max_sel;
     int32_t* my_idx = tok_idx + (int64_t)bh * idx_stride;
-    int nsel;
-    long long ntok;
-    select_block<kSelKreg>(
+    int32_t nsel, ntok;
+    select_block<kSelKreg, true>(
         sc, len, off, sq.n_sent, budget, sh,
-        [&](int32_t s, int32_t o, int32_t ln, int sel_pos, long long tok_pos) {
+        [&](int32_t s, int32_t o, int32_t ln, int32_t sel_pos, int32_t tok_pos) {
             if (sel_pos < max_sel) my_sel[sel_pos] = s;
             if (sel_pos < kSelListCap) {
-                list[sel_pos] = make_int4(s, o, ln, (int32_t)tok_pos);
+                list[sel_pos] = make_int4(s, o, ln, tok_pos);
             } else {                                          // list full: the owner writes its bucket's positions itself
                 for (int32_t t = 0; t < ln && tok_pos + t < idx_stride; ++t) my_idx[tok_pos + t] = o + t;
             }
         },
         &nsel, &ntok);
-    if (threadIdx.x == 0) { n_sel[bh] = min(nsel, max_sel); n_tok[bh] = (int32_t)ntok; }
+    if (threadIdx.x == 0) { n_sel[bh] = min(nsel, max_sel); n_tok[bh] = ntok; }
     __syncthreads();
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int listed = min(nsel, kSelListCap);
@@ -554,21 +555,19 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
     int32_t n;                                                    // retrieved tokens of this (sequence, head)
     if (FUSED) {
         __shared__ SelectShared sel_sh;
-        const long long budget = min(sq.budget, a.idx_stride);
+        const int32_t budget = min(sq.budget, a.idx_stride);
         if (split > 0 && j0 >= budget) return;                    // n <= budget: nothing for this split
         if (tid < kAttChunk) sm_row[tid] = -1;
-        int nsel;
-        long long ntok;
-        select_block<kSelKreg>(
+        int32_t nsel, ntok;
+        select_block<kSelKreg, false>(
             a.score + (int64_t)h * a.v.S_total + sq.sent_base, a.sent_len + sq.sent_base,
             a.sent_off + sq.sent_base + (a.v.cu_sent ? b : 0), sq.n_sent, budget, sel_sh,
-            [&](int32_t, int32_t o, int32_t ln, int, long long tok_pos) {
-                const long long lo = tok_pos > j0 ? tok_pos : j0;
-                const long long hi = (tok_pos + ln < j0 + kAttChunk) ? tok_pos + ln : j0 + kAttChunk;
-                for (long long t = lo; t < hi; ++t) sm_row[t - j0] = o + (int32_t)(t - tok_pos);
+            [&](int32_t, int32_t o, int32_t ln, int32_t, int32_t tok_pos) {
+                const int32_t lo = max(tok_pos, j0), hi = min(tok_pos + ln, j0 + kAttChunk);
+                for (int32_t t = lo; t < hi; ++t) sm_row[t - j0] = o + (t - tok_pos);
             },
             &nsel, &ntok);
-        n = (int32_t)ntok;
+        n = ntok;
         if (split == 0 && tid == 0 && a.n_tok_out) a.n_tok_out[bh] = n;
         __syncthreads();                                          // sm_row complete
         if (a.tok_idx_out && tid < kAttChunk && j0 + tid < n) a.tok_idx_out[(int64_t)bh * a.idx_stride + j0 + tid] = sm_row[tid];
