@@ -221,6 +221,87 @@ def run_single_sequence(args, wl, budget):
     }
 
 
+def run_ragged(args, wl):
+    """cfg4: a ragged batch of B sequences, one skv_decode_step call per layer.  Only `resident` layers of
+    the 80-layer pool are kept in HBM (the full pool would be ~190 GB); a step cycles through them."""
+    dev = "cuda:0"
+    R = args.resident_layers
+    L, H, Hq, D, B = wl.n_layers, wl.n_kv_heads, wl.n_q_heads, wl.head_dim, wl.batch
+    t0 = time.time()
+    inp = gen.ragged_inputs(wl, seed=args.seed, device=dev, resident_layers=R)
+    T_total, S_total = int(inp.cu_tok[-1]), int(inp.cu_sent[-1])
+    budget = int(inp.budget.max())
+    qsets = gen.queries(N_QUERY_SETS * R * B, Hq, D, wl.torch_dtype, args.seed + 1, dev).view(N_QUERY_SETS, R, B, Hq, D)
+    torch.cuda.synchronize()
+    gen_s = time.time() - t0
+    ctx = skv.Context(skv.Desc(n_layers=R, n_q_heads=Hq, n_kv_heads=H, kv_dtype=skv.dtype_code(wl.torch_dtype),
+                               max_tokens=T_total, max_sentences=S_total, max_budget=budget, max_batch=B))
+    glob_off = i32(gen.offsets_of(inp.sent_len), dev)
+    semvec = torch.empty(R, H, S_total, D, dtype=torch.float32, device=dev)
+    ctx.build_semvec(inp.K, glob_off, S_total, semvec)
+    torch.cuda.synchronize()
+    with Timer() as t_sv:
+        ctx.build_semvec(inp.K, glob_off, S_total, semvec)
+    d = [i32(x, dev) for x in (inp.cu_tok, inp.cu_sent, inp.sent_off, inp.sent_len, inp.budget)]
+    out = torch.empty(R, B, Hq, D, dtype=torch.float32, device=dev)
+    n_tok_rec = torch.zeros(R, B, H, dtype=torch.int32, device=dev)
+    q_cur = torch.empty(R, B, Hq, D, dtype=wl.torch_dtype, device=dev)
+
+    def layers(record=False):
+        for l in range(L):
+            r = l % R
+            ctx.decode_step(r, B, q_cur[r], q_cur[r], inp.K, inp.V, T_total, semvec, S_total, *d, out[r], None, None,
+                            n_tok_rec[r] if record else None)
+
+    q_cur.copy_(qsets[0])
+    layers(record=True)
+    torch.cuda.synchronize()
+
+    def timed(run_step):
+        for i in range(args.warmup):
+            q_cur.copy_(qsets[i % N_QUERY_SETS])
+            run_step()
+        torch.cuda.synchronize()
+        wall0 = time.perf_counter()
+        with Timer() as t:
+            for i in range(args.steps):
+                q_cur.copy_(qsets[i % N_QUERY_SETS])
+                run_step()
+        torch.cuda.synchronize()
+        return max(t.ms, (time.perf_counter() - wall0) * 1e3) / max(args.steps, 1)
+
+    ms_direct = timed(layers)
+    graph = capture(ctx, layers)
+    ms_graph = timed(graph.replay)
+    ms_per_step = ms_graph if args.launch == "graph" else ms_direct
+    n_tok_layer = float(n_tok_rec.sum().item()) / R
+    mean_len = float(inp.sent_len.mean())
+    bl = decode_bytes(wl, S_total, n_tok_layer, n_tok_layer / mean_len, fused=True)
+    bl["total"] += (B - 1) * wl.n_q_heads * D * (wl.elt_bytes * 2 + 4)          # q and out of the other sequences
+    us_per_layer = ms_per_step * 1e3 / L
+    gbps = bl["total"] / (us_per_layer * 1e-6) / 1e9
+    return {
+        "metric": "decode-step achieved HBM GB/s (score+select+gather+attn), ragged batch",
+        "value": round(gbps, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "layers": L, "resident_layers": R, "q_heads": Hq, "kv_heads": H, "head_dim": D,
+                   "batch": B, "tokens_total": T_total, "sentences_total": S_total, "budget": budget,
+                   "path": "skv_decode_step (one call per layer for the whole batch)", "kv_pool": "hbm",
+                   "launch": args.launch},
+        "us_per_layer": round(us_per_layer, 3),
+        "us_per_layer_direct_launch": round(ms_direct * 1e3 / L, 3),
+        "us_per_layer_hip_graph": round(ms_graph * 1e3 / L, 3),
+        "bytes_per_layer": int(bl["total"]), "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4),
+        "mean_tokens_selected_per_head": round(n_tok_layer / (B * H), 1),
+        "prefill": {"semvec_ms": round(t_sv.ms, 3),
+                    "semvec_GBps": round((R * H * T_total * D * wl.elt_bytes + R * H * S_total * D * 4) / (t_sv.ms * 1e-3) / 1e9, 1)},
+        "roofline": dict(bound="hbm", kernel="score_kernel + attend_kernel (fused step)", achieved=round(gbps, 1),
+                         peak=HBM_PEAK_GBPS, unit="GB/s", frac=round(gbps / HBM_PEAK_GBPS, 4), traffic=None),
+        "cpu_baseline": None, "input_gen_s": round(gen_s, 1),
+    }
+
+
 def _ctx_name(T):
     return "%dk" % (T // 1024) if T % 1024 == 0 else str(T)
 
@@ -260,7 +341,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2"])
+    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg4"])
+    ap.add_argument("--resident-layers", type=int, default=4, help="cfg4: layers of the pool kept in HBM")
     ap.add_argument("--budget", type=int, default=0, help="token budget (default: the workload's largest)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--launch", default="graph", choices=["graph", "direct"],
@@ -278,7 +360,7 @@ def main():
         sys.exit(2)
     wl = gen.CONFIGS[args.workload]
     budget = args.budget or max(wl.budgets)
-    res = run_single_sequence(args, wl, budget)
+    res = run_ragged(args, wl) if wl.batch > 1 else run_single_sequence(args, wl, budget)
     res["host"] = {"nproc": os.cpu_count()}
     print(json.dumps(res), flush=True)
 

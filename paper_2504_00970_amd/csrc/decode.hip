@@ -751,10 +751,12 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
                 }
             }
         }
+        SKV_T(10);
         __syncthreads();                                     // sm_red (partial sums) no longer read by anyone
         scratch[grp * kCol2 + col] = make_float4(o0, o1, M, L);
     }
     __syncthreads();
+    SKV_T(11);
     if (tid < kCol2) {
         float M = -INFINITY;
 #pragma unroll
