@@ -187,14 +187,11 @@ __device__ __forceinline__ uint32_t block_scan_u32(uint32_t val, uint32_t* slot,
     const uint32_t x = wave_scan_u32(val);
     if (lane == 63) slot[w] = x;
     __syncthreads();
-    uint32_t pre = 0, tot = 0;
-#pragma unroll
-    for (int i = 0; i < kBlockWaves; ++i) {
-        const uint32_t t = slot[i];
-        if (i < w) pre += t;
-        tot += t;
-    }
-    *total = tot;
+    // prefix over the 16 wave totals: one more wave scan instead of 16 reads per thread
+    const uint32_t t = slot[lane & (kBlockWaves - 1)];
+    const uint32_t ti = wave_scan_u32(lane < kBlockWaves ? t : 0u);
+    *total = (uint32_t)__builtin_amdgcn_readlane((int)ti, kBlockWaves - 1);
+    const uint32_t pre = (uint32_t)__builtin_amdgcn_readlane((int)(ti - t), w);     // lane w < 16 holds slot[w]
     return x + pre;
 }
 
@@ -361,17 +358,16 @@ __global__ __launch_bounds__(kBlockThreads) void select_kernel(const float* __re
     int32_t* my_sel = sel_sent + (int64_t)bh * max_sel;
     int32_t* my_idx = tok_idx + (int64_t)bh * idx_stride;
     int32_t nsel, ntok;
-    select_block<kSelKreg, true>(
-        sc, len, off, sq.n_sent, budget, sh,
-        [&](int32_t s, int32_t o, int32_t ln, int32_t sel_pos, int32_t tok_pos) {
-            if (sel_pos < max_sel) my_sel[sel_pos] = s;
-            if (sel_pos < kSelListCap) {
-                list[sel_pos] = make_int4(s, o, ln, tok_pos);
-            } else {                                          // list full: the owner writes its bucket's positions itself
-                for (int32_t t = 0; t < ln && tok_pos + t < idx_stride; ++t) my_idx[tok_pos + t] = o + t;
-            }
-        },
-        &nsel, &ntok);
+    auto emit = [&](int32_t s, int32_t o, int32_t ln, int32_t sel_pos, int32_t tok_pos) {
+        if (sel_pos < max_sel) my_sel[sel_pos] = s;
+        if (sel_pos < kSelListCap) {
+            list[sel_pos] = make_int4(s, o, ln, tok_pos);
+        } else {                                              // list full: the owner writes its bucket's positions itself
+            for (int32_t t = 0; t < ln && tok_pos + t < idx_stride; ++t) my_idx[tok_pos + t] = o + t;
+        }
+    };
+    if (sq.n_sent <= 2 * kBlockThreads) select_block<2, true>(sc, len, off, sq.n_sent, budget, sh, emit, &nsel, &ntok);
+    else select_block<kSelKreg, true>(sc, len, off, sq.n_sent, budget, sh, emit, &nsel, &ntok);
     if (threadIdx.x == 0) { n_sel[bh] = min(nsel, max_sel); n_tok[bh] = ntok; }
     __syncthreads();
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -559,18 +555,34 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
         if (split > 0 && j0 >= budget) return;                    // n <= budget: nothing for this split
         if (tid < kAttChunk) sm_row[tid] = -1;
         int32_t nsel, ntok;
-        select_block<kSelKreg, false>(
-            a.score + (int64_t)h * a.v.S_total + sq.sent_base, a.sent_len + sq.sent_base,
-            a.sent_off + sq.sent_base + (a.v.cu_sent ? b : 0), sq.n_sent, budget, sel_sh,
-            [&](int32_t, int32_t o, int32_t ln, int32_t, int32_t tok_pos) {
-                const int32_t lo = max(tok_pos, j0), hi = min(tok_pos + ln, j0 + kAttChunk);
-                for (int32_t t = lo; t < hi; ++t) sm_row[t - j0] = o + (t - tok_pos);
-            },
-            &nsel, &ntok);
+        // Each selected bucket that reaches into this block's 64 positions marks where it starts there
+        // and which pool row that is; one wave then fills the positions in between.
+        auto mark = [&](int32_t, int32_t o, int32_t ln, int32_t, int32_t tok_pos) {
+            const int32_t lo = max(tok_pos, j0);
+            if (lo < min(tok_pos + ln, j0 + kAttChunk)) sm_row[lo - j0] = o + (lo - tok_pos);
+        };
+        const float* sc = a.score + (int64_t)h * a.v.S_total + sq.sent_base;
+        const int32_t* len = a.sent_len + sq.sent_base;
+        const int32_t* off = a.sent_off + sq.sent_base + (a.v.cu_sent ? b : 0);
+        if (sq.n_sent <= 2 * kBlockThreads) select_block<2, false>(sc, len, off, sq.n_sent, budget, sel_sh, mark, &nsel, &ntok);
+        else select_block<kSelKreg, false>(sc, len, off, sq.n_sent, budget, sel_sh, mark, &nsel, &ntok);
         n = ntok;
         if (split == 0 && tid == 0 && a.n_tok_out) a.n_tok_out[bh] = n;
+        __syncthreads();                                          // bucket starts are marked
+        if (w == 0) {
+            const int32_t v = sm_row[lane];
+            int32_t hp = v >= 0 ? lane : -1;                      // position of the last bucket start at or before this lane
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int32_t t = __shfl_up(hp, o);
+                if (lane >= o) hp = max(hp, t);
+            }
+            const int32_t base = __shfl(v, max(hp, 0));
+            const int32_t row = hp >= 0 ? base + (lane - hp) : -1;
+            sm_row[lane] = row;
+            if (a.tok_idx_out && j0 + lane < n) a.tok_idx_out[(int64_t)bh * a.idx_stride + j0 + lane] = row;
+        }
         __syncthreads();                                          // sm_row complete
-        if (a.tok_idx_out && tid < kAttChunk && j0 + tid < n) a.tok_idx_out[(int64_t)bh * a.idx_stride + j0 + tid] = sm_row[tid];
     } else {
         n = min(a.n_tok[bh], a.row_stride);
     }
