@@ -83,6 +83,10 @@ int skv_create(skv_ctx** out, const skv_desc* desc, void* hip_stream) {
         round256(BQ * c.max_splits * 2 * sizeof(float)),                     // att_ml
         round256(BH * sizeof(unsigned int)),                                 // att_counter
         round256((size_t)desc->n_kv_heads * desc->max_sentences * sizeof(float)),  // f_score
+        round256(BH * c.max_sel * sizeof(int32_t)),                          // f_sel_sent
+        round256(BH * sizeof(int32_t)),                                      // f_n_sel
+        round256(BH * sizeof(int32_t)),                                      // f_n_tok
+        round256(BH * desc->max_budget * sizeof(int32_t)),                   // f_tok_idx
     };
     size_t total = 0;
     for (size_t s : sz) total += s;
@@ -97,6 +101,10 @@ int skv_create(skv_ctx** out, const skv_desc* desc, void* hip_stream) {
     c.att_ml = reinterpret_cast<float*>(p); p += sz[2];
     c.att_counter = reinterpret_cast<unsigned int*>(p); p += sz[3];
     c.f_score = reinterpret_cast<float*>(p); p += sz[4];
+    c.f_sel_sent = reinterpret_cast<int32_t*>(p); p += sz[5];
+    c.f_n_sel = reinterpret_cast<int32_t*>(p); p += sz[6];
+    c.f_n_tok = reinterpret_cast<int32_t*>(p); p += sz[7];
+    c.f_tok_idx = reinterpret_cast<int32_t*>(p); p += sz[8];
     *out = ctx;
     return SKV_OK;
 }
@@ -214,8 +222,7 @@ int skv_attend(skv_ctx* ctx, const void* q_attn, const void* K_sel, const void* 
     const int rc = check_ctx(ctx);
     if (rc != SKV_OK) return rc;
     const SeqView v{nullptr, nullptr, nullptr, 0, 0, budget, 1};
-    const int n_splits = (budget + skv::kAttChunk - 1) / skv::kAttChunk;
-    return hip_status(skv::launch_attend(&ctx->c, q_attn, K_sel, V_sel, budget, n_tok, n_splits, v, out, lse));
+    return hip_status(skv::launch_attend(&ctx->c, q_attn, K_sel, V_sel, budget, n_tok, budget, v, out, lse));
 }
 
 int skv_decode_step(skv_ctx* ctx, int32_t layer, int32_t B, const void* q_score, const void* q_attn,
@@ -242,8 +249,18 @@ int skv_decode_step(skv_ctx* ctx, int32_t layer, int32_t B, const void* q_score,
 
     hipError_t e = skv::launch_score(&c, q_score, sv, v, c.f_score);
     if (e != hipSuccess) return hip_status(e);
-    e = skv::launch_select_attend(&c, q_attn, (const char*)K_pool + pool_off, (const char*)V_pool + pool_off, c.f_score,
-                                  sent_off, sent_len, v, out, lse, tok_idx_out, n_tok_out);
+    const char* Kl = (const char*)K_pool + pool_off;
+    const char* Vl = (const char*)V_pool + pool_off;
+    if (B * c.d.n_kv_heads >= skv::kWideChunkMinHeads) {
+        // batch path: the selection runs once per (sequence, head); attention reads the pool through tok_idx
+        int32_t* tok_idx = tok_idx_out ? tok_idx_out : c.f_tok_idx;
+        int32_t* n_tok = n_tok_out ? n_tok_out : c.f_n_tok;
+        e = skv::launch_select(&c, c.f_score, sent_off, sent_len, v, c.f_sel_sent, c.f_n_sel, tok_idx, c.d.max_budget, n_tok);
+        if (e != hipSuccess) return hip_status(e);
+        return hip_status(skv::launch_attend_indirect(&c, q_attn, Kl, Vl, tok_idx, n_tok, v, out, lse));
+    }
+    // latency path: every attention block derives the selection itself (no launch, no tok_idx round trip)
+    e = skv::launch_select_attend(&c, q_attn, Kl, Vl, c.f_score, sent_off, sent_len, v, out, lse, tok_idx_out, n_tok_out);
     return hip_status(e);
 }
 

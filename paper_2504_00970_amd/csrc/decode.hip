@@ -500,19 +500,20 @@ __device__ __forceinline__ float sum_chunks(float x) {
 
 struct AttArgs {
     const char* q;            // [B][Hq][D]
-    const char* Kb;           // FUSED: layer pool [Hkv][T_total][D]; else K_sel [B*Hkv][row_stride][D]
+    const char* Kb;           // kDirect: K_sel [B*Hkv][row_stride][D]; else the layer's pool [Hkv][T_total][D]
     const char* Vb;
-    const int32_t* n_tok;     // !FUSED: [B*Hkv]
-    int32_t row_stride;       // !FUSED
-    const float* score;       // FUSED: [Hkv][S_total]
-    const int32_t* sent_off;  // FUSED
-    const int32_t* sent_len;  // FUSED
-    int32_t* tok_idx_out;     // FUSED, nullable: [B*Hkv][idx_stride]
-    int32_t* n_tok_out;       // FUSED, nullable: [B*Hkv]
-    int32_t idx_stride;       // FUSED: max_budget
+    const int32_t* n_tok;     // kDirect, kIndirect: [B*Hkv]
+    const int32_t* tok_idx;   // kIndirect: [B*Hkv][idx_stride] positions local to the sequence
+    int32_t row_stride;       // kDirect
+    const float* score;       // kFused: [Hkv][S_total]
+    const int32_t* sent_off;  // kFused
+    const int32_t* sent_len;  // kFused
+    int32_t* tok_idx_out;     // kFused, nullable: [B*Hkv][idx_stride]
+    int32_t* n_tok_out;       // kFused, nullable: [B*Hkv]
+    int32_t idx_stride;       // kFused, kIndirect: max_budget
     SeqView v;
     int32_t Hkv;
-    int32_t max_splits;
+    int32_t max_splits;       // partial slots per query head (counted in 64-token chunks)
     float* part;
     float* ml;
     unsigned int* counter;
@@ -520,24 +521,30 @@ struct AttArgs {
     float* lse;
 };
 
-template <int EB, int G, bool FUSED>
+enum { kDirect = 0, kFused = 1, kIndirect = 2 };
+
+// CHUNK = retrieved tokens per block: 64 for the latency-bound single-sequence step (most blocks in
+// flight), 256 for batches (fewer partials and arrivals per head, more loads in flight per block).
+template <int EB, int G, int MODE, int CHUNK>
 __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
     using R = Row<EB>;
     constexpr int kRowsPerIter = kBlockWaves * R::RPW;        // 64 (bf16) or 32 (fp32)
-    constexpr int kIter = kAttChunk / kRowsPerIter;
+    constexpr int kIter = CHUNK / kRowsPerIter;
     constexpr int kRowBytes = kHeadDim * EB;
     constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
+    constexpr int GH = G > 4 ? 4 : G, NH = G / GH;           // heads are processed GH at a time (register budget)
+    constexpr int kTPL = CHUNK / kWave;                       // logits per lane in the softmax
     constexpr int kOut = G * kHeadDim;                        // outputs of the block
     constexpr int kCol2 = kOut / 2;                           // float pairs over the G heads
     constexpr int kGroups = kBlockThreads / kCol2;            // split groups of the merge: 16, 8, 4, 2 for G = 1, 2, 4, 8
-    static_assert(kIter >= 1 && kGroups >= 1, "block shape");
+    static_assert(kIter >= 1 && kGroups >= 1 && (MODE != kFused || CHUNK == kWave), "block shape");
 
-    __shared__ float sm_logit[G][kAttChunk];
+    __shared__ float sm_logit[G][CHUNK];
     constexpr int kRedFloats = (kBlockWaves * G * kHeadDim > 4 * kBlockThreads) ? kBlockWaves * G * kHeadDim : 4 * kBlockThreads;
     __shared__ __attribute__((aligned(16))) float sm_red_flat[kRedFloats];           // wave partial sums, later the merge scratch
     float (*sm_red)[G][kHeadDim] = reinterpret_cast<float (*)[G][kHeadDim]>(sm_red_flat);
     __shared__ int sm_last;
-    __shared__ int32_t sm_row[kAttChunk];
+    __shared__ int32_t sm_row[kWave];
 
     const int bh = blockIdx.y, b = bh / a.Hkv, h = bh % a.Hkv, split = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -545,21 +552,22 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
     const int Hq = a.Hkv * G;
     const int64_t qhead0 = (int64_t)b * Hq + (int64_t)h * G;      // first query head of the group
     const Seq sq = seq_of(a.v, b);
-    const int32_t j0 = split * kAttChunk;
+    const int32_t j0 = split * CHUNK;
+    const int slot = split * (CHUNK / kWave);                     // partial slot (slots are counted in 64-token units)
     SKV_T(0);
 
     int32_t n;                                                    // retrieved tokens of this (sequence, head)
-    if (FUSED) {
+    if (MODE == kFused) {
         __shared__ SelectShared sel_sh;
         const int32_t budget = min(sq.budget, a.idx_stride);
         if (split > 0 && j0 >= budget) return;                    // n <= budget: nothing for this split
-        if (tid < kAttChunk) sm_row[tid] = -1;
+        if (tid < kWave) sm_row[tid] = -1;
         int32_t nsel, ntok;
         // Each selected bucket that reaches into this block's 64 positions marks where it starts there
         // and which pool row that is; one wave then fills the positions in between.
         auto mark = [&](int32_t, int32_t o, int32_t ln, int32_t, int32_t tok_pos) {
             const int32_t lo = max(tok_pos, j0);
-            if (lo < min(tok_pos + ln, j0 + kAttChunk)) sm_row[lo - j0] = o + (lo - tok_pos);
+            if (lo < min(tok_pos + ln, j0 + CHUNK)) sm_row[lo - j0] = o + (lo - tok_pos);
         };
         const float* sc = a.score + (int64_t)h * a.v.S_total + sq.sent_base;
         const int32_t* len = a.sent_len + sq.sent_base;
@@ -584,7 +592,7 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
         }
         __syncthreads();                                          // sm_row complete
     } else {
-        n = min(a.n_tok[bh], a.row_stride);
+        n = min(a.n_tok[bh], MODE == kDirect ? a.row_stride : a.idx_stride);
     }
     if (n <= 0) {
         if (split == 0) {
@@ -593,20 +601,20 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
         }
         return;
     }
-    const int nsplit = (n + kAttChunk - 1) / kAttChunk;
+    const int nsplit = (n + CHUNK - 1) / CHUNK;
     if (split >= nsplit) return;
-    const int32_t cnt = min(kAttChunk, n - j0);
+    const int32_t cnt = min(CHUNK, n - j0);
     SKV_T(4);
 
     // ---- 1. issue every load of the chunk ------------------------------------------------------------
     const char* Kh;
     const char* Vh;
-    if (FUSED) {
-        Kh = a.Kb + ((int64_t)h * a.v.T_total + sq.tok_base) * kRowBytes;
-        Vh = a.Vb + ((int64_t)h * a.v.T_total + sq.tok_base) * kRowBytes;
-    } else {
+    if (MODE == kDirect) {
         Kh = a.Kb + ((int64_t)bh * a.row_stride + j0) * kRowBytes;
         Vh = a.Vb + ((int64_t)bh * a.row_stride + j0) * kRowBytes;
+    } else {
+        Kh = a.Kb + ((int64_t)h * a.v.T_total + sq.tok_base) * kRowBytes;
+        Vh = a.Vb + ((int64_t)h * a.v.T_total + sq.tok_base) * kRowBytes;
     }
     // Rows past the chunk's end (and positions outside the sequence) are clamped to a valid row, loaded
     // anyway and masked afterwards, so that all loads are in flight together.
@@ -617,12 +625,12 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
         const int jj = i * kRowsPerIter + w * R::RPW + r;
         live[i] = jj < cnt;
         const int jc = min(jj, cnt - 1);
-        if (FUSED) {
-            const int32_t x = sm_row[jc];
+        if (MODE == kDirect) {
+            rowi[i] = jc;
+        } else {
+            const int32_t x = MODE == kFused ? sm_row[jc] : a.tok_idx[(int64_t)bh * a.idx_stride + j0 + jc];
             live[i] = live[i] && x >= 0 && x < sq.n_tok_ctx;
             rowi[i] = min(max(x, 0), max(sq.n_tok_ctx - 1, 0));
-        } else {
-            rowi[i] = jc;
         }
     }
     uint4 kraw[kIter], vraw[kIter];
@@ -631,27 +639,30 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
         kraw[i] = *reinterpret_cast<const uint4*>(Kh + (int64_t)rowi[i] * kRowBytes + cc * 16);
         vraw[i] = *reinterpret_cast<const uint4*>(Vh + (int64_t)rowi[i] * kRowBytes + cc * 16);
     }
-    float qf[G][R::EPL];
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-        const uint4 t = *reinterpret_cast<const uint4*>(a.q + ((qhead0 + g) * kHeadDim) * EB + cc * 16);
-        R::unpack(t, qf[g]);
-    }
     SKV_T(5);
 
     // ---- 2. logits ---------------------------------------------------------------------------------
     const float scale = kLog2e * rsqrtf((float)kHeadDim);
 #pragma unroll
-    for (int i = 0; i < kIter; ++i) {
-        float kf[R::EPL];
-        R::unpack(kraw[i], kf);
+    for (int hh = 0; hh < NH; ++hh) {
+        float qf[GH][R::EPL];
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            float acc = 0.f;
+        for (int g = 0; g < GH; ++g) {
+            const uint4 t = *reinterpret_cast<const uint4*>(a.q + ((qhead0 + hh * GH + g) * kHeadDim) * EB + cc * 16);
+            R::unpack(t, qf[g]);
+        }
 #pragma unroll
-            for (int e = 0; e < R::EPL; ++e) acc += qf[g][e] * kf[e];
-            acc = sum_chunks<R::RPW>(acc);
-            if (cc == 0) sm_logit[g][i * kRowsPerIter + w * R::RPW + r] = live[i] ? acc * scale : -INFINITY;
+        for (int i = 0; i < kIter; ++i) {
+            float kf[R::EPL];
+            R::unpack(kraw[i], kf);
+#pragma unroll
+            for (int g = 0; g < GH; ++g) {
+                float acc = 0.f;
+#pragma unroll
+                for (int e = 0; e < R::EPL; ++e) acc += qf[g][e] * kf[e];
+                acc = sum_chunks<R::RPW>(acc);
+                if (cc == 0) sm_logit[hh * GH + g][i * kRowsPerIter + w * R::RPW + r] = live[i] ? acc * scale : -INFINITY;
+            }
         }
     }
     __syncthreads();
@@ -660,17 +671,23 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
     // ---- 3. softmax over the chunk, one wave per query head --------------------------------------------
     if (w < G) {
         const int g = w;
-        const float x = sm_logit[g][lane];
-        float m = x;
+        float x[kTPL];
+        float m = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < kTPL; ++t) { x[t] = sm_logit[g][t * kWave + lane]; m = fmaxf(m, x[t]); }
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
-        const float p = (m == -INFINITY) ? 0.f : exp2f(x - m);
-        float l = p;
+        float l = 0.f;
+#pragma unroll
+        for (int t = 0; t < kTPL; ++t) {
+            const float p = (m == -INFINITY) ? 0.f : exp2f(x[t] - m);
+            sm_logit[g][t * kWave + lane] = p;
+            l += p;
+        }
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) l += __shfl_xor(l, off);
-        sm_logit[g][lane] = p;
         if (lane == 0) {
-            float* dst = a.ml + (((qhead0 + g) * a.max_splits) + split) * 2;
+            float* dst = a.ml + (((qhead0 + g) * a.max_splits) + slot) * 2;
             st_agent(dst, m);
             st_agent(dst + 1, l);
         }
@@ -678,38 +695,41 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
     __syncthreads();
 
     // ---- 4. P.V -------------------------------------------------------------------------------------
-    float acc[G][R::EPL];
 #pragma unroll
-    for (int g = 0; g < G; ++g)
+    for (int hh = 0; hh < NH; ++hh) {
+        float acc[GH][R::EPL];
 #pragma unroll
-        for (int e = 0; e < R::EPL; ++e) acc[g][e] = 0.f;
+        for (int g = 0; g < GH; ++g)
 #pragma unroll
-    for (int i = 0; i < kIter; ++i) {
-        const int jj = i * kRowsPerIter + w * R::RPW + r;
-        float vf[R::EPL];
-        R::unpack(vraw[i], vf);
-        if (!live[i]) {                                      // masked rows hold a clamped (foreign) row
+            for (int e = 0; e < R::EPL; ++e) acc[g][e] = 0.f;
 #pragma unroll
-            for (int e = 0; e < R::EPL; ++e) vf[e] = 0.f;
+        for (int i = 0; i < kIter; ++i) {
+            const int jj = i * kRowsPerIter + w * R::RPW + r;
+            float vf[R::EPL];
+            R::unpack(vraw[i], vf);
+            if (!live[i]) {                                      // masked rows hold a clamped (foreign) row
+#pragma unroll
+                for (int e = 0; e < R::EPL; ++e) vf[e] = 0.f;
+            }
+#pragma unroll
+            for (int g = 0; g < GH; ++g) {
+                const float p = sm_logit[hh * GH + g][jj];
+#pragma unroll
+                for (int e = 0; e < R::EPL; ++e) acc[g][e] += p * vf[e];
+            }
         }
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            const float p = sm_logit[g][jj];
+        for (int g = 0; g < GH; ++g)
 #pragma unroll
-            for (int e = 0; e < R::EPL; ++e) acc[g][e] += p * vf[e];
+            for (int e = 0; e < R::EPL; ++e) acc[g][e] = sum_rows<R::RPW>(acc[g][e]);
+        if (r == 0) {
+#pragma unroll
+            for (int g = 0; g < GH; ++g)
+#pragma unroll
+                for (int e = 0; e < R::EPL; e += 4)
+                    *reinterpret_cast<float4*>(&sm_red[w][hh * GH + g][cc * R::EPL + e]) =
+                        make_float4(acc[g][e], acc[g][e + 1], acc[g][e + 2], acc[g][e + 3]);
         }
-    }
-#pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int e = 0; e < R::EPL; ++e) acc[g][e] = sum_rows<R::RPW>(acc[g][e]);
-    if (r == 0) {
-#pragma unroll
-        for (int g = 0; g < G; ++g)
-#pragma unroll
-            for (int e = 0; e < R::EPL; e += 4)
-                *reinterpret_cast<float4*>(&sm_red[w][g][cc * R::EPL + e]) =
-                    make_float4(acc[g][e], acc[g][e + 1], acc[g][e + 2], acc[g][e + 3]);
     }
     __syncthreads();
     for (int i = tid; i < kOut; i += kBlockThreads) {
@@ -717,7 +737,7 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
         float o = sm_red[0][g][d];
 #pragma unroll
         for (int ww = 1; ww < kBlockWaves; ++ww) o += sm_red[ww][g][d];
-        st_agent(a.part + (((qhead0 + g) * a.max_splits) + split) * kHeadDim + d, o);
+        st_agent(a.part + (((qhead0 + g) * a.max_splits) + slot) * kHeadDim + d, o);
     }
     SKV_T(7);
 
@@ -746,7 +766,7 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
             unsigned long long pv[kU], mv[kU];
 #pragma unroll
             for (int u = 0; u < kU; ++u) {                   // clamped, unconditional loads
-                const int sidx = min(s0 + u * kGroups, nsplit - 1);
+                const int sidx = min(s0 + u * kGroups, nsplit - 1) * (CHUNK / kWave);
                 pv[u] = ld_agent64(pg + (int64_t)sidx * kHeadDim);
                 mv[u] = ld_agent64(mlg + 2 * sidx);
             }
@@ -792,14 +812,14 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
     SKV_T(9);
 }
 
-template <int EB, bool FUSED>
+template <int EB, int MODE, int CHUNK>
 static hipError_t launch_attend_g(Ctx* c, const AttArgs& a, int32_t n_splits) {
     const dim3 grid(n_splits, a.v.B * c->d.n_kv_heads), block(kBlockThreads);
     switch (c->G) {
-        case 1: hipLaunchKernelGGL((attend_kernel<EB, 1, FUSED>), grid, block, 0, c->stream, a); break;
-        case 2: hipLaunchKernelGGL((attend_kernel<EB, 2, FUSED>), grid, block, 0, c->stream, a); break;
-        case 4: hipLaunchKernelGGL((attend_kernel<EB, 4, FUSED>), grid, block, 0, c->stream, a); break;
-        case 8: hipLaunchKernelGGL((attend_kernel<EB, 8, FUSED>), grid, block, 0, c->stream, a); break;
+        case 1: hipLaunchKernelGGL((attend_kernel<EB, 1, MODE, CHUNK>), grid, block, 0, c->stream, a); break;
+        case 2: hipLaunchKernelGGL((attend_kernel<EB, 2, MODE, CHUNK>), grid, block, 0, c->stream, a); break;
+        case 4: hipLaunchKernelGGL((attend_kernel<EB, 4, MODE, CHUNK>), grid, block, 0, c->stream, a); break;
+        case 8: hipLaunchKernelGGL((attend_kernel<EB, 8, MODE, CHUNK>), grid, block, 0, c->stream, a); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -814,12 +834,30 @@ static AttArgs att_common(Ctx* c, const void* q, const void* Kbase, const void* 
     return a;
 }
 
+// Batches with many (sequence, head) pairs fill the GPU with 256-token blocks; below that 64-token blocks.
+static bool wide_chunks(const Ctx* c, const SeqView& v) { return v.B * c->d.n_kv_heads >= kWideChunkMinHeads; }
+
 hipError_t launch_attend(Ctx* c, const void* q, const void* K_sel, const void* V_sel, int32_t row_stride,
-                         const int32_t* n_tok, int32_t n_splits, const SeqView& v, float* out, float* lse) {
+                         const int32_t* n_tok, int32_t budget, const SeqView& v, float* out, float* lse) {
     AttArgs a = att_common(c, q, K_sel, V_sel, v, out, lse);
     a.n_tok = n_tok; a.row_stride = row_stride;
+    const int chunk = wide_chunks(c, v) ? kAttChunkWide : kAttChunk;
+    int n_splits = (budget + chunk - 1) / chunk;
     if (n_splits < 1) n_splits = 1;       // block 0 still writes the empty-selection result
-    return c->d.kv_dtype == SKV_BF16 ? launch_attend_g<2, false>(c, a, n_splits) : launch_attend_g<4, false>(c, a, n_splits);
+    if (wide_chunks(c, v))
+        return c->d.kv_dtype == SKV_BF16 ? launch_attend_g<2, kDirect, kAttChunkWide>(c, a, n_splits)
+                                         : launch_attend_g<4, kDirect, kAttChunkWide>(c, a, n_splits);
+    return c->d.kv_dtype == SKV_BF16 ? launch_attend_g<2, kDirect, kAttChunk>(c, a, n_splits)
+                                     : launch_attend_g<4, kDirect, kAttChunk>(c, a, n_splits);
+}
+
+hipError_t launch_attend_indirect(Ctx* c, const void* q, const void* K_layer, const void* V_layer, const int32_t* tok_idx,
+                                  const int32_t* n_tok, const SeqView& v, float* out, float* lse) {
+    AttArgs a = att_common(c, q, K_layer, V_layer, v, out, lse);
+    a.n_tok = n_tok; a.tok_idx = tok_idx; a.idx_stride = c->d.max_budget;
+    const int n_splits = (c->d.max_budget + kAttChunkWide - 1) / kAttChunkWide;
+    return c->d.kv_dtype == SKV_BF16 ? launch_attend_g<2, kIndirect, kAttChunkWide>(c, a, n_splits)
+                                     : launch_attend_g<4, kIndirect, kAttChunkWide>(c, a, n_splits);
 }
 
 hipError_t launch_select_attend(Ctx* c, const void* q, const void* K_layer, const void* V_layer, const float* score,
@@ -828,7 +866,8 @@ hipError_t launch_select_attend(Ctx* c, const void* q, const void* K_layer, cons
     AttArgs a = att_common(c, q, K_layer, V_layer, v, out, lse);
     a.score = score; a.sent_off = sent_off; a.sent_len = sent_len;
     a.tok_idx_out = tok_idx_out; a.n_tok_out = n_tok_out; a.idx_stride = c->d.max_budget;
-    return c->d.kv_dtype == SKV_BF16 ? launch_attend_g<2, true>(c, a, c->max_splits) : launch_attend_g<4, true>(c, a, c->max_splits);
+    return c->d.kv_dtype == SKV_BF16 ? launch_attend_g<2, kFused, kAttChunk>(c, a, c->max_splits)
+                                     : launch_attend_g<4, kFused, kAttChunk>(c, a, c->max_splits);
 }
 
 }  // namespace skv

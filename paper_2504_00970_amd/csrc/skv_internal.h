@@ -27,7 +27,9 @@ constexpr int kBlockThreads = 1024;   // select, attention and the fused select+
 constexpr int kGatherRowsPerBlock = 64;
 constexpr int kGatherThreads = 256;
 
-constexpr int kAttChunk = 64;         // tokens per split-K block (one wave-width of logits)
+constexpr int kAttChunk = 64;         // tokens per split-K block, single-sequence step (one wave-width of logits)
+constexpr int kAttChunkWide = 256;    // tokens per split-K block when many (sequence, head) pairs fill the GPU
+constexpr int kWideChunkMinHeads = 64;   // (sequences x KV heads) from which the batch path is used
 
 struct Ctx {
     skv_desc d;
@@ -43,6 +45,10 @@ struct Ctx {
     float* att_ml;          // [max_batch * Hq][max_splits][2] (running max in log2 units, sum)
     unsigned int* att_counter;  // [max_batch * Hkv] arrivals per (sequence, KV head); zero between calls
     float* f_score;         // [Hkv][max_sentences] scores of the fused path
+    int32_t* f_sel_sent;    // [max_batch * Hkv][max_sel]     selection of the batch path
+    int32_t* f_n_sel;       // [max_batch * Hkv]
+    int32_t* f_n_tok;       // [max_batch * Hkv]
+    int32_t* f_tok_idx;     // [max_batch * Hkv][max_budget]
 };
 
 // Ragged-batch view handed to the decode kernels.  For single-sequence calls cu_tok / cu_sent /
@@ -69,8 +75,11 @@ hipError_t launch_gather(Ctx* c, const void* K_layer, const void* V_layer, int32
                          const int32_t* n_tok, int32_t budget, void* K_sel, void* V_sel);
 // Attention over K_sel/V_sel [B*Hkv][row_stride][D] with n_tok [B*Hkv] from memory.
 hipError_t launch_attend(Ctx* c, const void* q, const void* K_sel, const void* V_sel, int32_t row_stride,
-                         const int32_t* n_tok, int32_t n_splits, const SeqView& v, float* out, float* lse);
-// Selection from `score` fused with attention over the layer's pool [Hkv][T_total][D].
+                         const int32_t* n_tok, int32_t budget, const SeqView& v, float* out, float* lse);
+// Attention over the layer's pool [Hkv][T_total][D] through tok_idx [B*Hkv][max_budget] (batch path).
+hipError_t launch_attend_indirect(Ctx* c, const void* q, const void* K_layer, const void* V_layer, const int32_t* tok_idx,
+                                  const int32_t* n_tok, const SeqView& v, float* out, float* lse);
+// Selection from `score` fused with attention over the layer's pool (single-sequence / small-batch path).
 hipError_t launch_select_attend(Ctx* c, const void* q, const void* K_layer, const void* V_layer, const float* score,
                                 const int32_t* sent_off, const int32_t* sent_len, const SeqView& v, float* out,
                                 float* lse, int32_t* tok_idx_out, int32_t* n_tok_out);

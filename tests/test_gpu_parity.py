@@ -357,6 +357,36 @@ def test_fused_ragged_batch_70b_heads(U, oracle32):
     _fused_case(U, oracle32, wl, seed=4, layers=[0, 1])
 
 
+@pytest.mark.parametrize("Hq", [32, 64])
+def test_fused_batch_path_many_heads(U, oracle32, Hq):
+    """Eight or more sequences x 8 KV heads take the batch path (one selection per head, 256-token blocks)."""
+    wl = gen.CFG4.scaled(n_layers=1, n_q_heads=Hq, batch=9, t_range=(200, 3000), budgets=(700,))
+    _fused_case(U, oracle32, wl, seed=6, layers=[0])
+
+
+def test_attend_batch_path_direct_rows(U, oracle32):
+    """skv_attend with n_kv_heads = 64 (>= the batch-path threshold): 256-token blocks on K_sel/V_sel."""
+    wl = gen.CFG0.scaled(dtype="bf16", n_q_heads=64, n_kv_heads=64)
+    H, Hq, D, budget = 64, 64, 128, 700
+    g = torch.Generator().manual_seed(5)
+    q = torch.randn(Hq, D, generator=g).to(wl.torch_dtype)
+    Ks = torch.randn(H, budget, D, generator=g).to(wl.torch_dtype)
+    Vs = torch.randn(H, budget, D, generator=g).to(wl.torch_dtype)
+    n_tok = np.array([(37 * i) % 701 for i in range(H)], dtype=np.int32)
+    n_tok[:4] = [0, 1, 256, 700]
+    ctx = U.make_ctx(wl, 4096, 64, budget)
+    out = torch.full((Hq, D), 5.0, device=U.DEV)
+    lse = torch.full((Hq,), 5.0, device=U.DEV)
+    for rep in range(2):
+        ctx.attend(q.to(U.DEV), Ks.to(U.DEV), Vs.to(U.DEV), U.i32(n_tok), budget, out, lse)
+        torch.cuda.synchronize()
+        out_ref, lse_ref = oracle32.attend(gen.to_numpy(q), gen.to_numpy(Ks), gen.to_numpy(Vs), n_tok)
+        assert np.abs(out.cpu().numpy() - out_ref).max() <= ATT_TOL["bf16"]
+        fin = np.isfinite(lse_ref)
+        assert np.array_equal(np.isfinite(lse.cpu().numpy()), fin)
+        assert np.abs(lse.cpu().numpy()[fin] - lse_ref[fin]).max() <= ATT_TOL["bf16"]
+
+
 # ----------------------------------------------------------------------------- full benchmark sizes
 
 def test_full_size_cfg1_sampled_layers(U, oracle32):
