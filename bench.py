@@ -64,6 +64,15 @@ def capture(ctx, fn):
     return g
 
 
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch from the committed rocprofv3 counter runs (profiles/), or None."""
+    try:
+        t = json.load(open(os.path.join(ROOT, "profiles", "traffic.json")))[workload][kernel]
+        return int(t["fetch_bytes"] + t["write_bytes"])
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def decode_bytes(wl, S, n_tok_sum, n_sel_sum, fused=True):
     """Algorithmic bytes of one layer's decode step (what the method itself has to move)."""
     H, D, e = wl.n_kv_heads, wl.head_dim, wl.elt_bytes
@@ -191,7 +200,7 @@ def run_single_sequence(args, wl, budget):
                for k, v in kern.items()}
     att = kernels["attend"]
     roofline = dict(bound="hbm", kernel="attend_kernel", achieved=att["GBps"], peak=HBM_PEAK_GBPS, unit="GB/s",
-                    frac=round(att["GBps"] / HBM_PEAK_GBPS, 4), traffic=None,
+                    frac=round(att["GBps"] / HBM_PEAK_GBPS, 4), traffic=measured_traffic(wl.name, "attend_kernel"),
                     bytes_per_launch=att["bytes"], us_per_launch=att["us"])
 
     cpu = cpu_baseline(args, wl, inp, semvec, lengths, qsets, budget) if not args.no_cpu_baseline else None
