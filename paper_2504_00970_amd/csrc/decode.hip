@@ -534,6 +534,10 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
     constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
     constexpr int GH = G > 4 ? 4 : G, NH = G / GH;           // heads are processed GH at a time (register budget)
     constexpr int kTPL = CHUNK / kWave;                       // logits per lane in the softmax
+    constexpr bool kMfma = (EB == 2);                         // bf16 runs on the matrix cores
+    constexpr int kTiles = CHUNK / 16;                        // 16-token MFMA tiles, one per wave
+    constexpr int kRedWaves = kMfma ? kTiles : kBlockWaves;   // waves that leave partial sums in sm_red
+    static_assert(kTiles <= kBlockWaves, "one tile per wave");
     constexpr int kOut = G * kHeadDim;                        // outputs of the block
     constexpr int kCol2 = kOut / 2;                           // float pairs over the G heads
     constexpr int kGroups = kBlockThreads / kCol2;            // split groups of the merge: 16, 8, 4, 2 for G = 1, 2, 4, 8
@@ -616,119 +620,233 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
         Kh = a.Kb + ((int64_t)h * a.v.T_total + sq.tok_base) * kRowBytes;
         Vh = a.Vb + ((int64_t)h * a.v.T_total + sq.tok_base) * kRowBytes;
     }
-    // Rows past the chunk's end (and positions outside the sequence) are clamped to a valid row, loaded
-    // anyway and masked afterwards, so that all loads are in flight together.
-    int32_t rowi[kIter];
-    bool live[kIter];
-#pragma unroll
-    for (int i = 0; i < kIter; ++i) {
-        const int jj = i * kRowsPerIter + w * R::RPW + r;
-        live[i] = jj < cnt;
-        const int jc = min(jj, cnt - 1);
-        if (MODE == kDirect) {
-            rowi[i] = jc;
-        } else {
-            const int32_t x = MODE == kFused ? sm_row[jc] : a.tok_idx[(int64_t)bh * a.idx_stride + j0 + jc];
-            live[i] = live[i] && x >= 0 && x < sq.n_tok_ctx;
-            rowi[i] = min(max(x, 0), max(sq.n_tok_ctx - 1, 0));
-        }
-    }
-    uint4 kraw[kIter], vraw[kIter];
-#pragma unroll
-    for (int i = 0; i < kIter; ++i) {
-        kraw[i] = *reinterpret_cast<const uint4*>(Kh + (int64_t)rowi[i] * kRowBytes + cc * 16);
-        vraw[i] = *reinterpret_cast<const uint4*>(Vh + (int64_t)rowi[i] * kRowBytes + cc * 16);
-    }
-    SKV_T(5);
-
-    // ---- 2. logits ---------------------------------------------------------------------------------
     const float scale = kLog2e * rsqrtf((float)kHeadDim);
+    if constexpr (kMfma) {
+        // ---- bf16: q.K^T and P.V on the matrix cores (v_mfma_f32_16x16x16_bf16) ------------------------------
+        // Wave w owns the 16 tokens [16w, 16w+16) of the chunk.  With t = lane % 16 and qd = lane / 16:
+        //  * S^T = K Q^T: A fragment = 4 consecutive dims of token t's key, B fragment = the same 4 dims of head t's
+        //    query (heads >= G are zero).  The dimension order inside the contraction is free as long as A and B agree,
+        //    so one 16-byte load of a row (dims 32s+8qd .. +7) feeds two MFMA steps; four loads cover the row.
+        //    The accumulator holds logit(token 4qd+j, head t), j = 0..3.
+        //  * O = P V: that accumulator layout IS the A-fragment layout (head t, tokens 4qd+j); the B fragment
+        //    V[token 4qd+j][16dt + t] is read from a wave-private LDS copy of the 16 value rows (padded pitch).
+        typedef short bf16x4 __attribute__((ext_vector_type(4)));
+        typedef float f32x4 __attribute__((ext_vector_type(4)));
+        constexpr int kVPitch = 2 * kHeadDim + 16;               // bytes; +16 spreads the four row groups over banks
+        __shared__ __attribute__((aligned(16))) char sm_v[kTiles][16 * kVPitch];
+        __shared__ float sm_wmax[kTiles][16], sm_wsum[kTiles][16];
+        const int t16 = lane & 15, qd = lane >> 4;
+        const bool tile = w < kTiles;
+        float sj[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+        bool lv[4] = {false, false, false, false};
+        if (tile) {
+            const int jj = 16 * w + t16;
+            bool liveK = jj < cnt;
+            const int jc = min(jj, cnt - 1);
+            int32_t rowK;
+            if (MODE == kDirect) {
+                rowK = jc;
+            } else {
+                const int32_t x = MODE == kFused ? sm_row[jc] : a.tok_idx[(int64_t)bh * a.idx_stride + j0 + jc];
+                liveK = liveK && x >= 0 && x < sq.n_tok_ctx;
+                rowK = min(max(x, 0), max(sq.n_tok_ctx - 1, 0));
+            }
+            uint4 kA[4], vR[4], qB[4];
 #pragma unroll
-    for (int hh = 0; hh < NH; ++hh) {
-        float qf[GH][R::EPL];
+            for (int s2 = 0; s2 < 4; ++s2) kA[s2] = *reinterpret_cast<const uint4*>(Kh + (int64_t)rowK * kRowBytes + 64 * s2 + 16 * qd);
 #pragma unroll
-        for (int g = 0; g < GH; ++g) {
-            const uint4 t = *reinterpret_cast<const uint4*>(a.q + ((qhead0 + hh * GH + g) * kHeadDim) * EB + cc * 16);
-            R::unpack(t, qf[g]);
-        }
+            for (int i = 0; i < 4; ++i) {
+                const int32_t rowV = __shfl(rowK, 4 * i + qd);     // lane 4i+qd (< 16) holds the row of token 4i+qd
+                vR[i] = *reinterpret_cast<const uint4*>(Vh + (int64_t)rowV * kRowBytes + 16 * t16);
+            }
 #pragma unroll
-        for (int i = 0; i < kIter; ++i) {
-            float kf[R::EPL];
-            R::unpack(kraw[i], kf);
+            for (int s2 = 0; s2 < 4; ++s2)
+                qB[s2] = *reinterpret_cast<const uint4*>(a.q + ((qhead0 + min(t16, G - 1)) * kHeadDim) * EB + 64 * s2 + 16 * qd);
+            const unsigned long long vm = __ballot(liveK);        // bit t (t < 16): token t of the tile is real
+            SKV_T(5);
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int g = 0; g < GH; ++g) {
-                float acc = 0.f;
+            for (int s2 = 0; s2 < 4; ++s2) {
+                uint4 qq = qB[s2];
+                if (t16 >= G) qq = make_uint4(0, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4, make_uint2(kA[s2].x, kA[s2].y)),
+                                                                __builtin_bit_cast(bf16x4, make_uint2(qq.x, qq.y)), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4, make_uint2(kA[s2].z, kA[s2].w)),
+                                                                __builtin_bit_cast(bf16x4, make_uint2(qq.z, qq.w)), acc, 0, 0, 0);
+            }
+            float mw = -INFINITY;
 #pragma unroll
-                for (int e = 0; e < R::EPL; ++e) acc += qf[g][e] * kf[e];
-                acc = sum_chunks<R::RPW>(acc);
-                if (cc == 0) sm_logit[hh * GH + g][i * kRowsPerIter + w * R::RPW + r] = live[i] ? acc * scale : -INFINITY;
+            for (int j = 0; j < 4; ++j) {
+                lv[j] = (vm >> (4 * qd + j)) & 1ull;
+                sj[j] = lv[j] ? acc[j] * scale : -INFINITY;
+                mw = fmaxf(mw, sj[j]);
+            }
+            mw = fmaxf(mw, __shfl_xor(mw, 16));
+            mw = fmaxf(mw, __shfl_xor(mw, 32));
+            if (qd == 0) sm_wmax[w][t16] = mw;
+            // the tile's value rows go to LDS (rows of masked tokens as zeros)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const bool lr = (vm >> (4 * i + qd)) & 1ull;
+                *reinterpret_cast<uint4*>(&sm_v[w][(4 * i + qd) * kVPitch + 16 * t16]) = lr ? vR[i] : make_uint4(0, 0, 0, 0);
             }
         }
-    }
-    __syncthreads();
-    SKV_T(6);
-
-    // ---- 3. softmax over the chunk, one wave per query head --------------------------------------------
-    if (w < G) {
-        const int g = w;
-        float x[kTPL];
-        float m = -INFINITY;
+        __syncthreads();
+        SKV_T(6);
+        if (tile) {
+            float mb = -INFINITY;
 #pragma unroll
-        for (int t = 0; t < kTPL; ++t) { x[t] = sm_logit[g][t * kWave + lane]; m = fmaxf(m, x[t]); }
+            for (int ww = 0; ww < kTiles; ++ww) mb = fmaxf(mb, sm_wmax[ww][t16]);
+            unsigned short pb[4];
+            float lw = 0.f;
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
-        float l = 0.f;
+            for (int j = 0; j < 4; ++j) {
+                const float p = (lv[j] && mb > -INFINITY) ? exp2f(sj[j] - mb) : 0.f;
+                uint32_t u = __float_as_uint(p);
+                u += 0x7fffu + ((u >> 16) & 1u);                  // round to nearest even bf16
+                pb[j] = (unsigned short)(u >> 16);
+                lw += __uint_as_float((uint32_t)pb[j] << 16);     // the normaliser sums the rounded weights
+            }
+            lw += __shfl_xor(lw, 16);
+            lw += __shfl_xor(lw, 32);
+            if (qd == 0) sm_wsum[w][t16] = lw;
+            const bf16x4 pa = {(short)pb[0], (short)pb[1], (short)pb[2], (short)pb[3]};
+            const unsigned short* vt = reinterpret_cast<const unsigned short*>(&sm_v[w][0]);
 #pragma unroll
-        for (int t = 0; t < kTPL; ++t) {
-            const float p = (m == -INFINITY) ? 0.f : exp2f(x[t] - m);
-            sm_logit[g][t * kWave + lane] = p;
-            l += p;
+            for (int dt = 0; dt < kHeadDim / 16; ++dt) {
+                bf16x4 vb;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) vb[j] = (short)vt[(4 * qd + j) * (kVPitch / 2) + 16 * dt + t16];
+                const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+                const f32x4 o = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, vb, zero, 0, 0, 0);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (4 * qd + j < G) sm_red[w][4 * qd + j][16 * dt + t16] = o[j];
+            }
         }
+        __syncthreads();
+        if (tid < G) {                                            // block max and normaliser of head tid
+            float mb = -INFINITY, lb = 0.f;
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) l += __shfl_xor(l, off);
-        if (lane == 0) {
-            float* dst = a.ml + (((qhead0 + g) * a.max_splits) + slot) * 2;
-            st_agent(dst, m);
-            st_agent(dst + 1, l);
+            for (int ww = 0; ww < kTiles; ++ww) { mb = fmaxf(mb, sm_wmax[ww][tid]); lb += sm_wsum[ww][tid]; }
+            float* dst = a.ml + (((qhead0 + tid) * a.max_splits) + slot) * 2;
+            st_agent(dst, mb);
+            st_agent(dst + 1, lb);
         }
-    }
-    __syncthreads();
-
-    // ---- 4. P.V -------------------------------------------------------------------------------------
-#pragma unroll
-    for (int hh = 0; hh < NH; ++hh) {
-        float acc[GH][R::EPL];
-#pragma unroll
-        for (int g = 0; g < GH; ++g)
-#pragma unroll
-            for (int e = 0; e < R::EPL; ++e) acc[g][e] = 0.f;
+    } else {
+        // Rows past the chunk's end (and positions outside the sequence) are clamped to a valid row, loaded
+        // anyway and masked afterwards, so that all loads are in flight together.
+        int32_t rowi[kIter];
+        bool live[kIter];
 #pragma unroll
         for (int i = 0; i < kIter; ++i) {
             const int jj = i * kRowsPerIter + w * R::RPW + r;
-            float vf[R::EPL];
-            R::unpack(vraw[i], vf);
-            if (!live[i]) {                                      // masked rows hold a clamped (foreign) row
-#pragma unroll
-                for (int e = 0; e < R::EPL; ++e) vf[e] = 0.f;
-            }
-#pragma unroll
-            for (int g = 0; g < GH; ++g) {
-                const float p = sm_logit[hh * GH + g][jj];
-#pragma unroll
-                for (int e = 0; e < R::EPL; ++e) acc[g][e] += p * vf[e];
+            live[i] = jj < cnt;
+            const int jc = min(jj, cnt - 1);
+            if (MODE == kDirect) {
+                rowi[i] = jc;
+            } else {
+                const int32_t x = MODE == kFused ? sm_row[jc] : a.tok_idx[(int64_t)bh * a.idx_stride + j0 + jc];
+                live[i] = live[i] && x >= 0 && x < sq.n_tok_ctx;
+                rowi[i] = min(max(x, 0), max(sq.n_tok_ctx - 1, 0));
             }
         }
+        uint4 kraw[kIter], vraw[kIter];
 #pragma unroll
-        for (int g = 0; g < GH; ++g)
+        for (int i = 0; i < kIter; ++i) {
+            kraw[i] = *reinterpret_cast<const uint4*>(Kh + (int64_t)rowi[i] * kRowBytes + cc * 16);
+            vraw[i] = *reinterpret_cast<const uint4*>(Vh + (int64_t)rowi[i] * kRowBytes + cc * 16);
+        }
+        SKV_T(5);
+
+        // ---- 2. logits ---------------------------------------------------------------------------------
 #pragma unroll
-            for (int e = 0; e < R::EPL; ++e) acc[g][e] = sum_rows<R::RPW>(acc[g][e]);
-        if (r == 0) {
+        for (int hh = 0; hh < NH; ++hh) {
+            float qf[GH][R::EPL];
+#pragma unroll
+            for (int g = 0; g < GH; ++g) {
+                const uint4 t = *reinterpret_cast<const uint4*>(a.q + ((qhead0 + hh * GH + g) * kHeadDim) * EB + cc * 16);
+                R::unpack(t, qf[g]);
+            }
+#pragma unroll
+            for (int i = 0; i < kIter; ++i) {
+                float kf[R::EPL];
+                R::unpack(kraw[i], kf);
+#pragma unroll
+                for (int g = 0; g < GH; ++g) {
+                    float acc = 0.f;
+#pragma unroll
+                    for (int e = 0; e < R::EPL; ++e) acc += qf[g][e] * kf[e];
+                    acc = sum_chunks<R::RPW>(acc);
+                    if (cc == 0) sm_logit[hh * GH + g][i * kRowsPerIter + w * R::RPW + r] = live[i] ? acc * scale : -INFINITY;
+                }
+            }
+        }
+        __syncthreads();
+        SKV_T(6);
+
+        // ---- 3. softmax over the chunk, one wave per query head --------------------------------------------
+        if (w < G) {
+            const int g = w;
+            float x[kTPL];
+            float m = -INFINITY;
+#pragma unroll
+            for (int t = 0; t < kTPL; ++t) { x[t] = sm_logit[g][t * kWave + lane]; m = fmaxf(m, x[t]); }
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+            float l = 0.f;
+#pragma unroll
+            for (int t = 0; t < kTPL; ++t) {
+                const float p = (m == -INFINITY) ? 0.f : exp2f(x[t] - m);
+                sm_logit[g][t * kWave + lane] = p;
+                l += p;
+            }
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) l += __shfl_xor(l, off);
+            if (lane == 0) {
+                float* dst = a.ml + (((qhead0 + g) * a.max_splits) + slot) * 2;
+                st_agent(dst, m);
+                st_agent(dst + 1, l);
+            }
+        }
+        __syncthreads();
+
+        // ---- 4. P.V -------------------------------------------------------------------------------------
+#pragma unroll
+        for (int hh = 0; hh < NH; ++hh) {
+            float acc[GH][R::EPL];
 #pragma unroll
             for (int g = 0; g < GH; ++g)
 #pragma unroll
-                for (int e = 0; e < R::EPL; e += 4)
-                    *reinterpret_cast<float4*>(&sm_red[w][hh * GH + g][cc * R::EPL + e]) =
-                        make_float4(acc[g][e], acc[g][e + 1], acc[g][e + 2], acc[g][e + 3]);
+                for (int e = 0; e < R::EPL; ++e) acc[g][e] = 0.f;
+#pragma unroll
+            for (int i = 0; i < kIter; ++i) {
+                const int jj = i * kRowsPerIter + w * R::RPW + r;
+                float vf[R::EPL];
+                R::unpack(vraw[i], vf);
+                if (!live[i]) {                                      // masked rows hold a clamped (foreign) row
+#pragma unroll
+                    for (int e = 0; e < R::EPL; ++e) vf[e] = 0.f;
+                }
+#pragma unroll
+                for (int g = 0; g < GH; ++g) {
+                    const float p = sm_logit[hh * GH + g][jj];
+#pragma unroll
+                    for (int e = 0; e < R::EPL; ++e) acc[g][e] += p * vf[e];
+                }
+            }
+#pragma unroll
+            for (int g = 0; g < GH; ++g)
+#pragma unroll
+                for (int e = 0; e < R::EPL; ++e) acc[g][e] = sum_rows<R::RPW>(acc[g][e]);
+            if (r == 0) {
+#pragma unroll
+                for (int g = 0; g < GH; ++g)
+#pragma unroll
+                    for (int e = 0; e < R::EPL; e += 4)
+                        *reinterpret_cast<float4*>(&sm_red[w][hh * GH + g][cc * R::EPL + e]) =
+                            make_float4(acc[g][e], acc[g][e + 1], acc[g][e + 2], acc[g][e + 3]);
+            }
         }
     }
     __syncthreads();
@@ -736,7 +854,7 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
         const int g = i / kHeadDim, d = i % kHeadDim;
         float o = sm_red[0][g][d];
 #pragma unroll
-        for (int ww = 1; ww < kBlockWaves; ++ww) o += sm_red[ww][g][d];
+        for (int ww = 1; ww < kRedWaves; ++ww) o += sm_red[ww][g][d];
         st_agent(a.part + (((qhead0 + g) * a.max_splits) + slot) * kHeadDim + d, o);
     }
     SKV_T(7);
