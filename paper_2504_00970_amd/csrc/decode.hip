@@ -544,9 +544,13 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
     static_assert(kIter >= 1 && kGroups >= 1 && (MODE != kFused || CHUNK == kWave), "block shape");
 
     __shared__ float sm_logit[G][CHUNK];
-    constexpr int kRedFloats = (kBlockWaves * G * kHeadDim > 4 * kBlockThreads) ? kBlockWaves * G * kHeadDim : 4 * kBlockThreads;
-    __shared__ __attribute__((aligned(16))) float sm_red_flat[kRedFloats];           // wave partial sums, later the merge scratch
-    float (*sm_red)[G][kHeadDim] = reinterpret_cast<float (*)[G][kHeadDim]>(sm_red_flat);
+    // Wave partial sums of P.V (wave ww, head g, dim d at sm_red_flat[ww * kRedStride + g * 128 + d]); later the
+    // merge scratch.  On the MFMA path each wave's partial sums reuse its own value tile.
+    constexpr int kVPitch = 2 * kHeadDim + 16;                // bytes per value row in LDS; +16 spreads row groups over banks
+    constexpr int kRedStride = kMfma ? 16 * kVPitch / 4 : G * kHeadDim;
+    constexpr int kRedFloats = (kRedWaves * kRedStride > 4 * kBlockThreads) ? kRedWaves * kRedStride : 4 * kBlockThreads;
+    static_assert(!kMfma || G * kHeadDim <= kRedStride, "a wave's partial sums fit in its value tile");
+    __shared__ __attribute__((aligned(16))) float sm_red_flat[kRedFloats];
     __shared__ int sm_last;
     __shared__ int32_t sm_row[kWave];
 
@@ -632,8 +636,7 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
         //    V[token 4qd+j][16dt + t] is read from a wave-private LDS copy of the 16 value rows (padded pitch).
         typedef short bf16x4 __attribute__((ext_vector_type(4)));
         typedef float f32x4 __attribute__((ext_vector_type(4)));
-        constexpr int kVPitch = 2 * kHeadDim + 16;               // bytes; +16 spreads the four row groups over banks
-        __shared__ __attribute__((aligned(16))) char sm_v[kTiles][16 * kVPitch];
+        char* sm_v = reinterpret_cast<char*>(sm_red_flat) + (size_t)w * 16 * kVPitch;       // this wave's value tile
         __shared__ float sm_wmax[kTiles][16], sm_wsum[kTiles][16];
         const int t16 = lane & 15, qd = lane >> 4;
         const bool tile = w < kTiles;
@@ -688,7 +691,7 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const bool lr = (vm >> (4 * i + qd)) & 1ull;
-                *reinterpret_cast<uint4*>(&sm_v[w][(4 * i + qd) * kVPitch + 16 * t16]) = lr ? vR[i] : make_uint4(0, 0, 0, 0);
+                *reinterpret_cast<uint4*>(sm_v + (4 * i + qd) * kVPitch + 16 * t16) = lr ? vR[i] : make_uint4(0, 0, 0, 0);
             }
         }
         __syncthreads();
@@ -711,18 +714,23 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
             lw += __shfl_xor(lw, 32);
             if (qd == 0) sm_wsum[w][t16] = lw;
             const bf16x4 pa = {(short)pb[0], (short)pb[1], (short)pb[2], (short)pb[3]};
-            const unsigned short* vt = reinterpret_cast<const unsigned short*>(&sm_v[w][0]);
+            const unsigned short* vt = reinterpret_cast<const unsigned short*>(sm_v);
+            f32x4 o[kHeadDim / 16];
 #pragma unroll
             for (int dt = 0; dt < kHeadDim / 16; ++dt) {
                 bf16x4 vb;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) vb[j] = (short)vt[(4 * qd + j) * (kVPitch / 2) + 16 * dt + t16];
                 const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-                const f32x4 o = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, vb, zero, 0, 0, 0);
+                o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, vb, zero, 0, 0, 0);
+            }
+            // the value tile has been consumed: its space takes the wave's partial sums
+            float* red = sm_red_flat + w * kRedStride;
+#pragma unroll
+            for (int dt = 0; dt < kHeadDim / 16; ++dt)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    if (4 * qd + j < G) sm_red[w][4 * qd + j][16 * dt + t16] = o[j];
-            }
+                    if (4 * qd + j < G) red[(4 * qd + j) * kHeadDim + 16 * dt + t16] = o[dt][j];
         }
         __syncthreads();
         if (tid < G) {                                            // block max and normaliser of head tid
@@ -844,7 +852,7 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
                 for (int g = 0; g < GH; ++g)
 #pragma unroll
                     for (int e = 0; e < R::EPL; e += 4)
-                        *reinterpret_cast<float4*>(&sm_red[w][hh * GH + g][cc * R::EPL + e]) =
+                        *reinterpret_cast<float4*>(&sm_red_flat[w * kRedStride + (hh * GH + g) * kHeadDim + cc * R::EPL + e]) =
                             make_float4(acc[g][e], acc[g][e + 1], acc[g][e + 2], acc[g][e + 3]);
             }
         }
@@ -852,9 +860,9 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
     __syncthreads();
     for (int i = tid; i < kOut; i += kBlockThreads) {
         const int g = i / kHeadDim, d = i % kHeadDim;
-        float o = sm_red[0][g][d];
+        float o = sm_red_flat[i];
 #pragma unroll
-        for (int ww = 1; ww < kRedWaves; ++ww) o += sm_red[ww][g][d];
+        for (int ww = 1; ww < kRedWaves; ++ww) o += sm_red_flat[ww * kRedStride + i];
         st_agent(a.part + (((qhead0 + g) * a.max_splits) + slot) * kHeadDim + d, o);
     }
     SKV_T(7);
