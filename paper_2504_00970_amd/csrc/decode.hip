@@ -36,21 +36,30 @@ __device__ __forceinline__ Seq seq_of(const SeqView& v, int b) {
     return s;
 }
 
+// x + (x moved by a DPP pattern): quad_perm [1,0,3,2] = 0xB1, [2,3,0,1] = 0x4E, row_ror:n = 0x120 + n
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x) {
+    const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false);
+    return x + __int_as_float(moved);
+}
+
 // ------------------------------------------------------------------------------------------------
 // Scores.  score[h][s] = sum_g q[hG+g] . semvec[h][s]  =  (sum_g q[hG+g]) . semvec[h][s].
 // A semantic vector is 512 bytes = 32 lanes x float4; a wave covers 2 buckets per load instruction
-// and keeps kScoreRowsPerWave / 2 loads in flight.  The group-summed query lives in registers.
+// and keeps RPWV / 2 loads in flight (RPWV = buckets per wave; 8 measured best from 1.3 k to 26 k
+// buckets per head: 4 and 32 were both slower).  The group-summed query lives in registers.
 // Blocks are aligned to sequences: block x -> (sequence b, local block) by walking cu_sent.
 // ------------------------------------------------------------------------------------------------
-template <int EB, int G>
+template <int EB, int G, int RPWV>
 __global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_kernel(const char* __restrict__ q,
                                                                             const float* __restrict__ semvec, SeqView v,
                                                                             int32_t Hq, float* __restrict__ score) {
+    constexpr int kRowsPerBlock = RPWV * kScoreWavesPerBlock;
     int blk = blockIdx.x, b = 0;
     Seq sq{};
     for (; b < v.B; ++b) {
         sq = seq_of(v, b);
-        const int nb = (sq.n_sent + kScoreRowsPerBlock - 1) / kScoreRowsPerBlock;
+        const int nb = (sq.n_sent + kRowsPerBlock - 1) / kRowsPerBlock;
         if (blk < nb) break;
         blk -= nb;
     }
@@ -73,8 +82,8 @@ __global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_kernel(cons
         }
     }
 
-    constexpr int kIter = kScoreRowsPerWave / 2;
-    const int32_t row0 = blk * kScoreRowsPerBlock + w * kScoreRowsPerWave + half;
+    constexpr int kIter = RPWV / 2;
+    const int32_t row0 = blk * kRowsPerBlock + w * RPWV + half;
     const float* base = semvec + ((int64_t)h * v.S_total + sq.sent_base) * kHeadDim + c * 4;
     // Addresses are clamped into the sequence instead of predicating the loads, so that all of a
     // lane's loads are issued back to back; rows past the end are computed and dropped.
@@ -88,9 +97,12 @@ __global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_kernel(cons
 #pragma unroll
     for (int i = 0; i < kIter; ++i) p[i] = x[i].x * qs[0] + x[i].y * qs[1] + x[i].z * qs[2] + x[i].w * qs[3];
 #pragma unroll
-    for (int off = 16; off >= 1; off >>= 1) {
-#pragma unroll
-        for (int i = 0; i < kIter; ++i) p[i] += __shfl_xor(p[i], off);
+    for (int i = 0; i < kIter; ++i) {                     // sum over the 32 lanes of a bucket
+        p[i] = dpp_add<0xB1>(p[i]);
+        p[i] = dpp_add<0x4E>(p[i]);
+        p[i] = dpp_add<0x124>(p[i]);
+        p[i] = dpp_add<0x128>(p[i]);
+        p[i] += __shfl_xor(p[i], 16);
     }
     if (c == 0) {
         float* out = score + (int64_t)h * v.S_total + sq.sent_base;
@@ -102,16 +114,17 @@ __global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_kernel(cons
     }
 }
 
-template <int EB>
+template <int EB, int RPWV>
 static hipError_t launch_score_g(Ctx* c, const void* q, const float* semvec_layer, const SeqView& v, float* score) {
-    const int blocks = (v.S_total + kScoreRowsPerBlock - 1) / kScoreRowsPerBlock + v.B;   // bound on sum_b ceil(S_b/R)
+    constexpr int kRowsPerBlock = RPWV * kScoreWavesPerBlock;
+    const int blocks = (v.S_total + kRowsPerBlock - 1) / kRowsPerBlock + v.B;   // bound on sum_b ceil(S_b/R)
     const dim3 grid(blocks, c->d.n_kv_heads), block(kScoreWavesPerBlock * kWave);
     const char* qp = (const char*)q;
     switch (c->G) {
-        case 1: hipLaunchKernelGGL((score_kernel<EB, 1>), grid, block, 0, c->stream, qp, semvec_layer, v, c->d.n_q_heads, score); break;
-        case 2: hipLaunchKernelGGL((score_kernel<EB, 2>), grid, block, 0, c->stream, qp, semvec_layer, v, c->d.n_q_heads, score); break;
-        case 4: hipLaunchKernelGGL((score_kernel<EB, 4>), grid, block, 0, c->stream, qp, semvec_layer, v, c->d.n_q_heads, score); break;
-        case 8: hipLaunchKernelGGL((score_kernel<EB, 8>), grid, block, 0, c->stream, qp, semvec_layer, v, c->d.n_q_heads, score); break;
+        case 1: hipLaunchKernelGGL((score_kernel<EB, 1, RPWV>), grid, block, 0, c->stream, qp, semvec_layer, v, c->d.n_q_heads, score); break;
+        case 2: hipLaunchKernelGGL((score_kernel<EB, 2, RPWV>), grid, block, 0, c->stream, qp, semvec_layer, v, c->d.n_q_heads, score); break;
+        case 4: hipLaunchKernelGGL((score_kernel<EB, 4, RPWV>), grid, block, 0, c->stream, qp, semvec_layer, v, c->d.n_q_heads, score); break;
+        case 8: hipLaunchKernelGGL((score_kernel<EB, 8, RPWV>), grid, block, 0, c->stream, qp, semvec_layer, v, c->d.n_q_heads, score); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -119,8 +132,8 @@ static hipError_t launch_score_g(Ctx* c, const void* q, const float* semvec_laye
 
 hipError_t launch_score(Ctx* c, const void* q, const float* semvec_layer, const SeqView& v, float* score) {
     if (v.S_total == 0) return hipSuccess;
-    return c->d.kv_dtype == SKV_BF16 ? launch_score_g<2>(c, q, semvec_layer, v, score)
-                                     : launch_score_g<4>(c, q, semvec_layer, v, score);
+    return c->d.kv_dtype == SKV_BF16 ? launch_score_g<2, kScoreRowsPerWave>(c, q, semvec_layer, v, score)
+                                     : launch_score_g<4, kScoreRowsPerWave>(c, q, semvec_layer, v, score);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -474,12 +487,6 @@ __device__ __forceinline__ unsigned long long ld_agent64(const float* p) {      
 __device__ __forceinline__ float lo_f(unsigned long long v) { return __uint_as_float((uint32_t)v); }
 __device__ __forceinline__ float hi_f(unsigned long long v) { return __uint_as_float((uint32_t)(v >> 32)); }
 
-// x + (x moved by a DPP pattern): quad_perm [1,0,3,2] = 0xB1, [2,3,0,1] = 0x4E, row_ror:n = 0x120 + n
-template <int CTRL>
-__device__ __forceinline__ float dpp_add(float x) {
-    const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false);
-    return x + __int_as_float(moved);
-}
 // sum over the RPW rows of a wave (lane bits below log2 RPW); every lane gets the total
 template <int RPW>
 __device__ __forceinline__ float sum_rows(float x) {

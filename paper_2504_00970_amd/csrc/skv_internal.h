@@ -18,9 +18,8 @@ constexpr int kSegTokPerBlock = kSegThreads * kSegTokPerThread;      // 1024 tok
 
 constexpr int kSemvecWavesPerBlock = 4;                               // one wave per (layer*head, bucket)
 
-constexpr int kScoreRowsPerWave = 8;
+constexpr int kScoreRowsPerWave = 8;          // buckets per wave (32 per block)
 constexpr int kScoreWavesPerBlock = 4;
-constexpr int kScoreRowsPerBlock = kScoreRowsPerWave * kScoreWavesPerBlock;   // 32 buckets per block
 
 constexpr int kBlockThreads = 1024;   // select, attention and the fused select+attention kernel: 16 waves per block
 
