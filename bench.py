@@ -204,6 +204,7 @@ def run_single_sequence(args, wl, budget):
                     bytes_per_launch=att["bytes"], us_per_launch=att["us"])
 
     cpu = cpu_baseline(args, wl, inp, semvec, lengths, qsets, budget) if not args.no_cpu_baseline else None
+    host_pool = host_pool_gather(args, wl, ctx, inp, tok_idx, n_tok, budget, K_sel) if args.host_pool_layers > 0 else None
 
     return {
         "metric": "decode-step achieved HBM GB/s (score+select+gather+attn) at %s ctx" % _ctx_name(T),
@@ -226,8 +227,50 @@ def run_single_sequence(args, wl, budget):
                     "semvec_GBps": round(semvec_bytes / (t_sv.ms * 1e-3) / 1e9, 1)},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "host_pool_gather": host_pool,
         "input_gen_s": round(gen_s, 1),
     }
+
+
+def host_pool_gather(args, wl, ctx, inp, tok_idx, n_tok, budget, ref_K_sel):
+    """skv_gather with the K/V pool in pinned, device-mapped host memory (the paper's CPU-offloaded store):
+    the kernel's 16-byte loads cross PCIe.  Reported next to the pinned host-to-device copy rate."""
+    dev = "cuda:0"
+    n = min(args.host_pool_layers, wl.n_layers)
+    H, D, T = wl.n_kv_heads, wl.head_dim, wl.n_tokens
+    # the host pool keeps the [L][Hkv][T][D] layout; only the first n layers are filled and used
+    Kh = torch.empty(n, H, T, D, dtype=wl.torch_dtype, pin_memory=True).copy_(inp.K[:n])
+    Vh = torch.empty(n, H, T, D, dtype=wl.torch_dtype, pin_memory=True).copy_(inp.V[:n])
+    K_sel = torch.zeros(n, H, budget, D, dtype=wl.torch_dtype, device=dev)
+    V_sel = torch.zeros_like(K_sel)
+    torch.cuda.synchronize()
+
+    def run():
+        for l in range(n):
+            ctx.gather(l, Kh, Vh, T, tok_idx[l], n_tok[l], budget, K_sel[l], V_sel[l], pool_in_host=True)
+
+    run()
+    torch.cuda.synchronize()
+    reps = 5
+    with Timer() as t:
+        for _ in range(reps):
+            run()
+    us = t.ms * 1e3 / (reps * n)
+    rows = float(n_tok[:n, :H].sum().item()) / n
+    pcie_bytes = 2 * rows * D * wl.elt_bytes
+    valid = torch.arange(budget, device=dev)[None, :] < n_tok[0, :H, None]                   # rows the gather wrote
+    same = bool(torch.equal(K_sel[0].view(torch.int16)[valid], ref_K_sel[0].view(torch.int16)[valid]))
+    big = torch.empty(256 << 20, dtype=torch.uint8, pin_memory=True)
+    dst = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+    dst.copy_(big, non_blocking=True)
+    torch.cuda.synchronize()
+    with Timer() as tc:
+        for _ in range(4):
+            dst.copy_(big, non_blocking=True)
+    h2d = 4 * (256 << 20) / (tc.ms * 1e-3) / 1e9
+    return {"layers": n, "us_per_layer": round(us, 2), "bytes_over_pcie_per_layer": int(pcie_bytes),
+            "GBps": round(pcie_bytes / (us * 1e-6) / 1e9, 2), "pinned_h2d_copy_GBps": round(h2d, 2),
+            "frac_of_h2d_copy": round(pcie_bytes / (us * 1e-6) / 1e9 / h2d, 3), "rows_match_hbm_pool": same}
 
 
 def run_ragged(args, wl):
@@ -359,6 +402,9 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--cpu-layers", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--host-pool-layers", type=int, default=-1,
+                    help="layers of the K/V pool also kept in pinned host memory for the host-pool gather measurement "
+                         "(default: 2 for cfg2, 0 otherwise)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the path has no multi-GPU form in this build (run with --gpus 1)",
@@ -368,6 +414,8 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     wl = gen.CONFIGS[args.workload]
+    if args.host_pool_layers < 0:
+        args.host_pool_layers = 2 if args.workload == "cfg2" else 0
     budget = args.budget or max(wl.budgets)
     res = run_ragged(args, wl) if wl.batch > 1 else run_single_sequence(args, wl, budget)
     res["host"] = {"nproc": os.cpu_count()}
