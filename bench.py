@@ -354,6 +354,75 @@ def run_ragged(args, wl):
     }
 
 
+def run_prefill(args, wl):
+    """cfg3: sentence segmentation of a token stream and the mean-key table of every layer and KV head."""
+    dev = "cuda:0"
+    L, H, D, T = wl.n_layers, wl.n_kv_heads, wl.head_dim, wl.n_tokens
+    p = gen.prefill_inputs(wl, seed=args.seed, device=dev)
+    S_cap = len(p.lengths) + 64
+    ctx = skv.Context(skv.Desc(n_layers=L, n_q_heads=wl.n_q_heads, n_kv_heads=H, kv_dtype=skv.dtype_code(wl.torch_dtype),
+                               max_tokens=T, max_sentences=S_cap, max_budget=16, max_batch=1))
+    d_tok, d_bm = i32(p.tok, dev), torch.as_tensor(p.bitmap.view(np.int32)).to(dev)
+    seg_id = torch.empty(T, dtype=torch.int32, device=dev)
+    sent_off = torch.empty(S_cap + 1, dtype=torch.int32, device=dev)
+    sent_len = torch.empty(S_cap, dtype=torch.int32, device=dev)
+    n_sent = torch.empty(4, dtype=torch.int32, device=dev)
+    S = ctx.segment(d_tok, d_bm, wl.vocab, seg_id, sent_off, sent_len, n_sent)
+    assert S == len(p.lengths)
+    semvec = torch.empty(L, H, S, D, dtype=torch.float32, device=dev)
+
+    def step():
+        ctx.segment(d_tok, d_bm, wl.vocab, seg_id, sent_off, sent_len, n_sent, sync=False)
+        ctx.build_semvec(p.K, sent_off, S, semvec)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    with Timer() as t:
+        for _ in range(args.steps):
+            step()
+    ms = t.ms / max(args.steps, 1)
+    with Timer() as t_seg:
+        for _ in range(10):
+            ctx.segment(d_tok, d_bm, wl.vocab, seg_id, sent_off, sent_len, n_sent, sync=False)
+    with Timer() as t_sv:
+        for _ in range(10):
+            ctx.build_semvec(p.K, sent_off, S, semvec)
+    sv_bytes = L * H * T * D * wl.elt_bytes + L * H * S * D * 4
+    seg_bytes = 2 * 4 * T + 4 * T + 8 * S
+    gbps = (sv_bytes + seg_bytes) / (ms * 1e-3) / 1e9
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        orc = oracle.get("f32")
+        K0 = gen.to_numpy(p.K[:1])
+        t0 = time.perf_counter()
+        _, off, _, _ = orc.segment(p.tok, p.bitmap, wl.vocab)
+        n = 0
+        while True:
+            orc.semvec(K0, off)
+            n += 1
+            if time.perf_counter() - t0 > args.cpu_seconds:
+                break
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(n * (sv_bytes / L) / dt / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "sample": "segmentation once + mean keys of layer 0 (%d of %d layers) %d times, single thread, fp32" % (1, L, n)}
+    sv_gbps = sv_bytes / (t_sv.ms / 10 * 1e-3) / 1e9
+    return {
+        "metric": "prefill segmentation + semantic-vector build, achieved HBM GB/s at %s tokens" % _ctx_name(T),
+        "value": round(gbps, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "layers": L, "kv_heads": H, "head_dim": D, "tokens": T, "sentences": S,
+                   "path": "skv_segment + skv_build_semvec"},
+        "segment_us": round(t_seg.ms * 100, 2), "semvec_ms": round(t_sv.ms / 10, 4), "bytes_per_step": int(sv_bytes + seg_bytes),
+        "roofline": dict(bound="hbm", kernel="semvec_kernel", achieved=round(sv_gbps, 1), peak=HBM_PEAK_GBPS, unit="GB/s",
+                         frac=round(sv_gbps / HBM_PEAK_GBPS, 4), traffic=measured_traffic(wl.name, "semvec_kernel"),
+                         bytes_per_launch=int(sv_bytes)),
+        "cpu_baseline": cpu,
+    }
+
+
 def _ctx_name(T):
     return "%dk" % (T // 1024) if T % 1024 == 0 else str(T)
 
@@ -393,7 +462,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg4"])
+    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4"])
     ap.add_argument("--resident-layers", type=int, default=4, help="cfg4: layers of the pool kept in HBM")
     ap.add_argument("--budget", type=int, default=0, help="token budget (default: the workload's largest)")
     ap.add_argument("--seed", type=int, default=0)
@@ -416,8 +485,12 @@ def main():
     wl = gen.CONFIGS[args.workload]
     if args.host_pool_layers < 0:
         args.host_pool_layers = 2 if args.workload == "cfg2" else 0
-    budget = args.budget or max(wl.budgets)
-    res = run_ragged(args, wl) if wl.batch > 1 else run_single_sequence(args, wl, budget)
+    if args.workload == "cfg3":
+        res = run_prefill(args, wl)
+    elif wl.batch > 1:
+        res = run_ragged(args, wl)
+    else:
+        res = run_single_sequence(args, wl, args.budget or max(wl.budgets))
     res["host"] = {"nproc": os.cpu_count()}
     print(json.dumps(res), flush=True)
 
