@@ -397,3 +397,40 @@ def test_full_size_cfg1_sampled_layers(U, oracle32):
     for budget in wl.budgets:
         total_ties += _chain_case(U, oracle32, wl, seed=0, budget=budget, layers=[0, 13, 31])
     _say("full-size cfg1 documented ties:", total_ties)
+
+
+def test_full_size_cfg2_128k_sampled_layers(U, oracle32):
+    """cfg2 at its real size (32 layers x 131072 tokens, budget 2048): the 4-call chain on two layers of the
+    17 GB pool, and the fused decode step (selection with more than 2048 buckets per head) on two layers."""
+    _chain_case(U, oracle32, gen.CFG2, seed=0, budget=2048, layers=[0, 31])
+    torch.cuda.empty_cache()
+    wl = gen.CFG2.scaled(n_layers=2, batch=1, t_range=(131072, 131072), budgets=(2048,))
+    _fused_case(U, oracle32, wl, seed=1, layers=[0, 1])
+
+
+def test_full_size_cfg3_prefill(U, oracle32):
+    """cfg3 at its real size: 32768-token stream over a 128k vocabulary, keys [32][8][32768][128] bf16; segment ids,
+    offsets and lengths bit-exact, mean keys of three sampled layers against the oracle."""
+    wl = gen.CFG3
+    p = gen.prefill_inputs(wl, seed=0, device=U.DEV)
+    seg_ref, off_ref, len_ref, S_ref = oracle32.segment(p.tok, p.bitmap, wl.vocab)
+    ctx = U.make_ctx(wl, wl.n_tokens, S_ref + 8, 16)
+    seg, off, ln, S_host, S_dev = U.gpu_segment(ctx, p.tok, p.bitmap, wl.vocab, S_ref + 8)
+    assert S_host == S_ref == S_dev == len(p.lengths)
+    assert np.array_equal(seg, seg_ref) and np.array_equal(off[:S_ref + 1], off_ref) and np.array_equal(ln[:S_ref], len_ref)
+    sv = torch.zeros(wl.n_layers, wl.n_kv_heads, S_ref, 128, dtype=torch.float32, device=U.DEV)
+    ctx.build_semvec(p.K, U.i32(off[:S_ref + 1]), S_ref, sv)
+    torch.cuda.synchronize()
+    for l in (0, 17, 31):
+        _say("cfg3 semvec layer", l)
+        ref = oracle32.semvec(gen.to_numpy(p.K[l:l + 1]), off_ref)[0]
+        got = sv[l].cpu().numpy()
+        kmax = float(p.K[l].float().abs().max())
+        bound = (2.0 * np.maximum(len_ref - 1, 0) * 2.0 ** -24 * kmax + 2.0 ** -22 * kmax)[None, :, None]
+        assert np.all(np.abs(got - ref) <= bound), float(np.abs(got - ref).max())
+
+
+def test_full_size_cfg4_ragged_batch(U, oracle32):
+    """cfg4 at its real shapes (64 q heads / 8 KV heads, 16 sequences of 8192..65536 tokens, budget 2048) on two
+    resident layers: every sequence's selection and attention output against the oracle."""
+    _fused_case(U, oracle32, gen.CFG4.scaled(n_layers=2), seed=0, layers=[0, 1])
