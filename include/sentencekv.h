@@ -99,6 +99,20 @@ int skv_build_semvec(skv_ctx* ctx, const void* K_pool, int32_t T, const int32_t*
                      float* semvec);
 
 /* ---------------------------------------------------------------------------------------------
+ * Sec. 4.2 "Sentence-level query aggregation", Eq. 2, and Alg. 1 decoding phase (append q_t to Q_s, compute
+ * q-bar, reset Q_s at a sentence boundary).  The sentence cache Q_s is kept as a running sum and a count per
+ * sequence (one state per layer, owned by the caller, zero-initialised).  One call per generated token and layer:
+ *     q_sum[b] += q_t[b];  q_cnt[b] += 1;  q_bar[b] = q_sum[b] / q_cnt[b]   (fp32, rounded once to kv_dtype)
+ *     then, if the generated token tok_t[b] is a terminator (same bitmap convention as skv_segment), the state
+ *     of sequence b is cleared, so the next token starts a new sentence.  q_bar still includes the terminator's query.
+ * q_t    dev [B][Hq][D] kv_dtype      tok_t  dev [B] int32       term_bitmap dev [ceil(vocab/32)]
+ * q_sum  dev [B][Hq][D] fp32 (in/out)  q_cnt  dev [B] int32 (in/out)
+ * q_bar  dev [B][Hq][D] kv_dtype (out; pass it as q_score of the calls below).  Asynchronous.
+ * Errors: SKV_EINVAL (null / misaligned pointers, B < 1, vocab <= 0), SKV_ECAPACITY (B > max_batch). */
+int skv_query_update(skv_ctx* ctx, int32_t B, const void* q_t, const int32_t* tok_t, const uint32_t* term_bitmap,
+                     int32_t vocab, float* q_sum, int32_t* q_cnt, void* q_bar);
+
+/* ---------------------------------------------------------------------------------------------
  * (2) Sec. 4.2 "Semantic similarity and token retrieval": score[h][s] = sum over the G query heads j
  * of KV head h of q_score[j]^T semvec[layer][h][s].  No scaling, no normalisation.  q_score is the
  * mean query q-bar of Eq. 2 (or the current query: the choice is the caller's).

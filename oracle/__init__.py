@@ -79,6 +79,8 @@ class Oracle:
         L.skvo_gather.restype = None
         L.skvo_attend.argtypes = [_vp, _vp, _vp, _ci, _i, _i, _i, _i32p, _i, _f32p, _f32p]
         L.skvo_attend.restype = None
+        L.skvo_query_cache_step.argtypes = [_vp, _ci, _i, _i, _u32p, _i, _f32p, _i, _i32p, _f32p, _vp]
+        L.skvo_query_cache_step.restype = _ci
         L.skvo_real_bytes.restype = _ci
         assert L.skvo_real_bytes() == (4 if real == "f32" else 8)
 
@@ -112,6 +114,10 @@ class Oracle:
         return out
 
     # -- decode ----------------------------------------------------------------------------
+    def query_cache(self, per: int, cap: int = 4096) -> "QueryCache":
+        """An empty sentence cache Q_s for one sequence and layer (per = Hq * D elements per token)."""
+        return QueryCache(self, per, cap)
+
     def score(self, q: np.ndarray, semvec: np.ndarray) -> np.ndarray:
         """q [Hq][D], semvec [Hkv][S][D] float32 -> score float32 [Hkv][S]."""
         q = np.ascontiguousarray(q)
@@ -178,6 +184,32 @@ class Oracle:
         out, lse = self.attend(q_attn, Ks, Vs, n_tok)
         return dict(score=sc, sel_sent=sel, n_sel=n_sel, tok_idx=tok_idx, n_tok=n_tok, K_sel=Ks, V_sel=Vs,
                     out=out, lse=lse)
+
+
+class QueryCache:
+    """The sentence cache Q_s of Eq. 2 for one sequence: the list of queries since the last boundary."""
+
+    def __init__(self, oracle: Oracle, per: int, cap: int):
+        self.o, self.per, self.cap = oracle, per, cap
+        self.cache = np.zeros((cap, per), dtype=np.float32)
+        self.n = np.zeros(1, dtype=np.int32)
+
+    def __len__(self) -> int:
+        return int(self.n[0])
+
+    def step(self, q_t: np.ndarray, tok: int, bitmap: np.ndarray, vocab: int):
+        """Append q_t, -> (q-bar float32, q-bar in q_t's storage type); Q_s is emptied if tok is a terminator."""
+        q_t = np.ascontiguousarray(q_t)
+        assert q_t.size == self.per
+        bitmap = np.ascontiguousarray(bitmap, dtype=np.uint32)
+        qbar = np.zeros(q_t.shape, dtype=np.float32)
+        store = np.zeros(q_t.shape, dtype=q_t.dtype)
+        rc = self.o.lib.skvo_query_cache_step(q_t.ctypes.data_as(_vp), _dtype_of(q_t), self.per, int(tok),
+                                              _ptr(bitmap, _u32p), vocab, _ptr(self.cache, _f32p), self.cap,
+                                              _ptr(self.n, _i32p), _ptr(qbar, _f32p), store.ctypes.data_as(_vp))
+        if rc != 0:
+            raise OverflowError(f"sentence cache holds {self.cap} queries already")
+        return qbar, store
 
 
 _cache = {}

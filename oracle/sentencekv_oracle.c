@@ -14,6 +14,8 @@
  *   skvo_segment  sentence buckets from a token stream          (Sec. 4.1 "split ... into sentences
  *                                                                according to punctuation"; Alg. 1 prefill)
  *   skvo_semvec   mean key vector k-bar_{s,h} per bucket, head  (Eq. 1)
+ *   skvo_query_cache_step  sentence cache Q_s and its mean query q-bar  (Sec. 4.2 "Sentence-level query aggregation",
+ *                                                                Eq. 2; Alg. 1 decoding phase)
  *   skvo_score    S(q-bar, k-bar_{s,h}) = q-bar^T k-bar_{s,h}   (Sec. 4.2 "Semantic similarity and token retrieval")
  *   skvo_select   rank buckets by score, take whole buckets in descending order until the token
  *                 budget tau is reached                        (Sec. 4.2; App. "Effect of Sentence Length")
@@ -34,7 +36,9 @@
  *     first bucket that does not fit the remaining budget (no skipping ahead, no partial
  *     bucket); NaN scores rank lowest; -0 == +0;
  *   - gathered tokens are in ascending position order;
- *   - an empty selection gives O = 0 and lse = -inf.
+ *   - an empty selection gives O = 0 and lse = -inf;
+ *   - the query of the token that ends a generated sentence still belongs to that sentence: Q_s is
+ *     reset after q-bar of that step has been formed; q-bar is rounded once to the storage type.
  *
  * Parity pins: every function here is pinned by tests/test_oracle_*.py (hand-built streams,
  * float64 brute force from raw keys, an independent O(S^2) characterisation of the selection,
@@ -110,6 +114,47 @@ void skvo_semvec(const void* K, int dtype, int32_t L, int32_t Hkv, int32_t T, in
                 for (int32_t d = 0; d < D; ++d) out[d] = (float)(acc[d] / n);
             }
     free(acc);
+}
+
+/* nearest bf16 to a finite float, ties to the even bit pattern */
+static uint16_t to_bf16(float f) {
+    uint32_t bits;
+    memcpy(&bits, &f, sizeof bits);
+    uint32_t below = bits & 0xffff0000u;             /* neighbour towards zero */
+    uint32_t above = below + 0x00010000u;            /* neighbour away from zero */
+    uint32_t rest = bits & 0x0000ffffu;              /* distance from `below`, in units of 2^-16 bf16 ulp */
+    uint32_t pick;
+    if (rest < 0x8000u) pick = below;
+    else if (rest > 0x8000u) pick = above;
+    else pick = ((below >> 16) & 1u) ? above : below;
+    return (uint16_t)(pick >> 16);
+}
+
+/* Sec. 4.2 "Sentence-level query aggregation", Eq. 2, Alg. 1 decoding phase.  Q_s is kept literally: a list of
+ * the query vectors of the tokens generated since the last sentence boundary (cache is [cap][per], *n_cached
+ * entries used; per = Hq * D elements of one token's queries).  One call = one generated token:
+ *   append q_t to Q_s;  q-bar = (1/|Q_s|) sum_{t in Q_s} q_t, summed in the order of generation;
+ *   if the generated token is a terminator, Q_s is emptied for the next sentence.
+ * qbar_real receives the mean as float; qbar_store (nullable) the same rounded to the storage type.
+ * Returns -1 (and changes nothing) if Q_s is full. */
+int skvo_query_cache_step(const void* q_t, int dtype, int32_t per, int32_t tok, const uint32_t* bitmap, int32_t vocab,
+                          float* cache, int32_t cap, int32_t* n_cached, float* qbar_real, void* qbar_store) {
+    int32_t n = *n_cached;
+    if (n >= cap) return -1;
+    for (int32_t i = 0; i < per; ++i) cache[(int64_t)n * per + i] = (float)load_elt(q_t, dtype, i);
+    n = n + 1;
+    for (int32_t i = 0; i < per; ++i) {
+        real sum = 0;
+        for (int32_t t = 0; t < n; ++t) sum = sum + (real)cache[(int64_t)t * per + i];
+        float mean = (float)(sum / (real)n);
+        qbar_real[i] = mean;
+        if (qbar_store) {
+            if (dtype == SKVO_F32) ((float*)qbar_store)[i] = mean;
+            else ((uint16_t*)qbar_store)[i] = to_bf16(mean);
+        }
+    }
+    *n_cached = is_terminator(bitmap, vocab, tok) ? 0 : n;
+    return 0;
 }
 
 /* Sec. 4.2: score[h][s] = sum_{g<G} q[hG+g]^T semvec[h][s]  (one layer; semvec is [Hkv][S][D]). */

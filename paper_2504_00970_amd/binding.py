@@ -41,6 +41,7 @@ _SIGNATURES = {
     "skv_workspace_bytes": (_i64, [_vp]),
     "skv_segment": (_int, [_vp, _vp, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _vp]),
     "skv_build_semvec": (_int, [_vp, _vp, _i32, _vp, _i32, _vp]),
+    "skv_query_update": (_int, [_vp, _i32, _vp, _vp, _vp, _i32, _vp, _vp, _vp]),
     "skv_score": (_int, [_vp, _i32, _vp, _vp, _i32, _vp]),
     "skv_select": (_int, [_vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp]),
     "skv_gather": (_int, [_vp, _i32, _vp, _vp, _i32, _int, _vp, _vp, _i32, _vp, _vp]),
@@ -150,6 +151,11 @@ class Context:
     def build_semvec(self, K_pool, sent_off, S: int, semvec) -> None:
         T = K_pool.shape[2]
         _check(_lib().skv_build_semvec(self._h, _p(K_pool), T, _p(sent_off), S, _p(semvec)), "skv_build_semvec")
+
+    # ---- sentence query cache (Eq. 2) ----------------------------------------------------------------
+    def query_update(self, B: int, q_t, tok_t, term_bitmap, vocab: int, q_sum, q_cnt, q_bar) -> None:
+        _check(_lib().skv_query_update(self._h, B, _p(q_t), _p(tok_t), _p(term_bitmap), vocab, _p(q_sum), _p(q_cnt),
+                                       _p(q_bar)), "skv_query_update")
 
     # ---- (2)-(5) decode, one layer, one sequence ---------------------------------------------------
     def score(self, layer: int, q_score, semvec, S: int, score) -> None:

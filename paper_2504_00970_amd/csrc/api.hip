@@ -155,6 +155,18 @@ int skv_build_semvec(skv_ctx* ctx, const void* K_pool, int32_t T, const int32_t*
     return hip_status(skv::launch_semvec(&ctx->c, K_pool, T, sent_off, S, semvec));
 }
 
+int skv_query_update(skv_ctx* ctx, int32_t B, const void* q_t, const int32_t* tok_t, const uint32_t* term_bitmap,
+                     int32_t vocab, float* q_sum, int32_t* q_cnt, void* q_bar) {
+    if (!ctx) return SKV_EINVAL;
+    if (B < 1 || vocab <= 0) return SKV_EINVAL;
+    if (bad_ptr(q_t) || bad_ptr(tok_t) || bad_ptr(term_bitmap) || bad_ptr(q_sum) || bad_ptr(q_cnt) || bad_ptr(q_bar))
+        return SKV_EINVAL;
+    if (B > ctx->c.d.max_batch) return SKV_ECAPACITY;
+    const int rc = check_ctx(ctx);
+    if (rc != SKV_OK) return rc;
+    return hip_status(skv::launch_query_update(&ctx->c, B, q_t, tok_t, term_bitmap, vocab, q_sum, q_cnt, q_bar));
+}
+
 int skv_score(skv_ctx* ctx, int32_t layer, const void* q_score, const float* semvec, int32_t S, float* score) {
     if (!ctx) return SKV_EINVAL;
     if (layer < 0 || layer >= ctx->c.d.n_layers || S < 0) return SKV_EINVAL;

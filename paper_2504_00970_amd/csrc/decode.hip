@@ -36,6 +36,65 @@ __device__ __forceinline__ Seq seq_of(const SeqView& v, int b) {
     return s;
 }
 
+// ------------------------------------------------------------------------------------------------
+// Sentence query cache (Eq. 2; Alg. 1 decoding phase): running sum and count per sequence, mean query
+// out, state cleared when the generated token ends a sentence.  One thread per 4 elements.
+// ------------------------------------------------------------------------------------------------
+template <int EB>
+__global__ __launch_bounds__(kBlockThreads) void query_update_kernel(const char* __restrict__ q_t, const int32_t* __restrict__ tok_t,
+                                                                     const uint32_t* __restrict__ bitmap, int32_t vocab,
+                                                                     int32_t per_seq /* Hq * D */, float* __restrict__ q_sum,
+                                                                     int32_t* __restrict__ q_cnt, char* __restrict__ q_bar) {
+    const int b = blockIdx.x;                                        // one block per sequence
+    const int32_t id = tok_t[b];
+    const bool term = id >= 0 && id < vocab && ((bitmap[id >> 5] >> (id & 31)) & 1u);
+    const int32_t n = q_cnt[b] + 1;
+    const float fn = (float)n;
+    for (int i4 = threadIdx.x * 4; i4 < per_seq; i4 += kBlockThreads * 4) {
+        const int64_t e = (int64_t)b * per_seq + i4;
+        float4 s = *reinterpret_cast<const float4*>(q_sum + e);
+        float x[4];
+        if (EB == 4) {
+            const float4 t = *reinterpret_cast<const float4*>(q_t + e * 4);
+            x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+        } else {
+            const uint2 t = *reinterpret_cast<const uint2*>(q_t + e * 2);
+            x[0] = __uint_as_float(t.x << 16); x[1] = __uint_as_float(t.x & 0xffff0000u);
+            x[2] = __uint_as_float(t.y << 16); x[3] = __uint_as_float(t.y & 0xffff0000u);
+        }
+        s.x += x[0]; s.y += x[1]; s.z += x[2]; s.w += x[3];
+        const float m[4] = {s.x / fn, s.y / fn, s.z / fn, s.w / fn};
+        if (EB == 4) {
+            *reinterpret_cast<float4*>(q_bar + e * 4) = make_float4(m[0], m[1], m[2], m[3]);
+        } else {
+            uint32_t r[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {                             // round to nearest even bf16 (inputs are finite)
+                uint32_t u = __float_as_uint(m[k]);
+                u += 0x7fffu + ((u >> 16) & 1u);
+                r[k] = u >> 16;
+            }
+            *reinterpret_cast<uint2*>(q_bar + e * 2) = make_uint2(r[0] | (r[1] << 16), r[2] | (r[3] << 16));
+        }
+        *reinterpret_cast<float4*>(q_sum + e) = term ? make_float4(0.f, 0.f, 0.f, 0.f) : s;
+    }
+    __syncthreads();                                                  // every thread has read q_cnt[b]
+    if (threadIdx.x == 0) q_cnt[b] = term ? 0 : n;
+}
+
+hipError_t launch_query_update(Ctx* c, int32_t B, const void* q_t, const int32_t* tok_t, const uint32_t* bitmap,
+                               int32_t vocab, float* q_sum, int32_t* q_cnt, void* q_bar) {
+    const int per_seq = c->d.n_q_heads * kHeadDim;
+    const dim3 grid(B), block(kBlockThreads);
+    if (c->d.kv_dtype == SKV_BF16)
+        hipLaunchKernelGGL(query_update_kernel<2>, grid, block, 0, c->stream, (const char*)q_t, tok_t, bitmap, vocab, per_seq,
+                           q_sum, q_cnt, (char*)q_bar);
+    else
+        hipLaunchKernelGGL(query_update_kernel<4>, grid, block, 0, c->stream, (const char*)q_t, tok_t, bitmap, vocab, per_seq,
+                           q_sum, q_cnt, (char*)q_bar);
+    return hipGetLastError();
+}
+
 // x + (x moved by a DPP pattern): quad_perm [1,0,3,2] = 0xB1, [2,3,0,1] = 0x4E, row_ror:n = 0x120 + n
 template <int CTRL>
 __device__ __forceinline__ float dpp_add(float x) {

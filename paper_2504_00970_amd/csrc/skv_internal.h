@@ -66,6 +66,8 @@ struct SeqView {
 hipError_t launch_segment(Ctx* c, const int32_t* tok, int32_t T, const uint32_t* bitmap, int32_t vocab,
                           int32_t* seg_id, int32_t* sent_off, int32_t* sent_len, int32_t* n_sent_dev);
 hipError_t launch_semvec(Ctx* c, const void* K_pool, int32_t T, const int32_t* sent_off, int32_t S, float* semvec);
+hipError_t launch_query_update(Ctx* c, int32_t B, const void* q_t, const int32_t* tok_t, const uint32_t* bitmap,
+                               int32_t vocab, float* q_sum, int32_t* q_cnt, void* q_bar);
 hipError_t launch_score(Ctx* c, const void* q, const float* semvec_layer, const SeqView& v, float* score);
 hipError_t launch_select(Ctx* c, const float* score, const int32_t* sent_off, const int32_t* sent_len,
                          const SeqView& v, int32_t* sel_sent, int32_t* n_sel, int32_t* tok_idx, int32_t idx_stride,
