@@ -1004,6 +1004,268 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
     SKV_T(9);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Streaming form of the bf16 attention for batches (rows through tok_idx).  Measured on the 1024-thread kernel
+// above with 16 sequences x 8 heads: all blocks start together, load together (memory saturated for 5 us) and then
+// compute together (memory idle for 7 us), twice.  Here a block is 4 waves, a wave owns 64 consecutive retrieved
+// tokens and walks them in four 16-token MFMA tiles -- the next tile's K and V rows are requested as soon as the
+// current ones have been consumed (K by the logit MFMAs, V by its copy to LDS) -- carrying a running (max,
+// normaliser, output) per head as in flash decoding; all blocks of the launch are resident at once (16 waves per
+// CU, each with 8 KB in flight).
+// Tile arithmetic is that of the kernel above: S^T = K Q^T with K rows as A fragments, P rounded to bf16 with the
+// normaliser summing the rounded weights, V through a wave-private LDS tile into B fragments.
+// ------------------------------------------------------------------------------------------------
+constexpr int kStreamWaves = 4;
+constexpr int kStreamThreads = kStreamWaves * kWave;
+constexpr int kStreamTiles = 4;                                   // 16-token tiles per wave
+static_assert(kStreamWaves * kStreamTiles * 16 == kAttChunkWide, "a streaming block covers one wide chunk");
+
+template <int G>
+__global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void attend_stream_kernel(AttArgs a) {
+    constexpr int CHUNK = kAttChunkWide;
+    constexpr int kRowBytes = kHeadDim * 2;
+    constexpr int kVPitch = 2 * kHeadDim + 16;                    // bytes per value row in LDS
+    constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
+    constexpr int kOut = G * kHeadDim, kCol2 = kOut / 2;
+    constexpr int kColsPerThread = (kCol2 + kStreamThreads - 1) / kStreamThreads;
+    typedef short bf16x4 __attribute__((ext_vector_type(4)));
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    static_assert(G * kHeadDim * 4 <= 16 * kVPitch, "a wave's partial sums fit in its value tile");
+
+    __shared__ __attribute__((aligned(16))) char sm_v[kStreamWaves][16 * kVPitch];   // value tile, later the wave's partial sums
+    __shared__ __attribute__((aligned(16))) unsigned short sm_q[16][kHeadDim];       // the group's queries, rows >= G zero
+    __shared__ float sm_wmax[kStreamWaves][16], sm_wsum[kStreamWaves][16];
+    __shared__ int sm_last;
+
+    const int bh = blockIdx.y, b = bh / a.Hkv, h = bh % a.Hkv, split = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int t16 = lane & 15, qd = lane >> 4;
+    const int Hq = a.Hkv * G;
+    const int64_t qhead0 = (int64_t)b * Hq + (int64_t)h * G;
+    const Seq sq = seq_of(a.v, b);
+    const int32_t j0 = split * CHUNK;
+    const int slot = split * (CHUNK / kWave);
+    SKV_T(0);
+    const int32_t n = min(a.n_tok[bh], a.idx_stride);
+    if (n <= 0) {
+        if (split == 0) {
+            for (int i = tid; i < kOut; i += kStreamThreads) a.out[qhead0 * kHeadDim + i] = 0.f;
+            if (a.lse && tid < G) a.lse[qhead0 + tid] = -INFINITY;
+        }
+        return;
+    }
+    const int nsplit = (n + CHUNK - 1) / CHUNK;
+    if (split >= nsplit) return;
+    const int32_t cnt = min(CHUNK, n - j0);
+
+    // this lane's token of the wave's 64 (clamped; validity travels as a ballot)
+    const int jw = kWave * w + lane;
+    const int32_t xi = a.tok_idx[(int64_t)bh * a.idx_stride + j0 + min(jw, cnt - 1)];
+    const bool lv_lane = jw < cnt && xi >= 0 && xi < sq.n_tok_ctx;
+    const int32_t row_lane = min(max(xi, 0), max(sq.n_tok_ctx - 1, 0));
+    {   // queries of the group -> LDS (16 bytes per thread: 16 rows x 256 bytes)
+        const int row = tid >> 4, piece = tid & 15;
+        uint4 t = make_uint4(0, 0, 0, 0);
+        if (row < G) t = *reinterpret_cast<const uint4*>(a.q + ((qhead0 + row) * kHeadDim) * 2 + 16 * piece);
+        *reinterpret_cast<uint4*>(&sm_q[row][8 * piece]) = t;
+    }
+    const unsigned long long vmask = __ballot(lv_lane);
+    const char* Kh = a.Kb + ((int64_t)h * a.v.T_total + sq.tok_base) * kRowBytes;
+    const char* Vh = a.Vb + ((int64_t)h * a.v.T_total + sq.tok_base) * kRowBytes;
+    const float scale = kLog2e * rsqrtf((float)kHeadDim);
+    SKV_T(4);
+
+    uint4 kA[4], vR[4];
+    auto issue = [&](int i, uint4* k, uint4* v) {
+        // 32-bit byte offsets from the (head, sequence) base: the host only uses this kernel below 2^24 tokens
+        const uint32_t offK = (uint32_t)__shfl(row_lane, 16 * i + t16) * kRowBytes + 16u * qd;
+#pragma unroll
+        for (int s2 = 0; s2 < 4; ++s2) k[s2] = *reinterpret_cast<const uint4*>(Kh + (offK + 64u * s2));
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii) {
+            const uint32_t offV = (uint32_t)__shfl(row_lane, 16 * i + 4 * ii + qd) * kRowBytes + 16u * t16;
+            v[ii] = *reinterpret_cast<const uint4*>(Vh + offV);
+        }
+    };
+    issue(0, kA, vR);
+    __syncthreads();                                              // sm_q is complete
+    SKV_T(5);
+
+    float m_run = -INFINITY, l_run = 0.f;                         // per head t16; l_run covers this lane's tokens only
+    f32x4 o[kHeadDim / 16];
+#pragma unroll
+    for (int dt = 0; dt < kHeadDim / 16; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    char* vt_b = sm_v[w];
+    const unsigned short* vt = reinterpret_cast<const unsigned short*>(vt_b);
+
+#pragma unroll
+    for (int i = 0; i < kStreamTiles; ++i) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s2 = 0; s2 < 4; ++s2) {
+            const uint4 qq = *reinterpret_cast<const uint4*>(&sm_q[t16][32 * s2 + 8 * qd]);
+            acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4, make_uint2(kA[s2].x, kA[s2].y)),
+                                                            __builtin_bit_cast(bf16x4, make_uint2(qq.x, qq.y)), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4, make_uint2(kA[s2].z, kA[s2].w)),
+                                                            __builtin_bit_cast(bf16x4, make_uint2(qq.z, qq.w)), acc, 0, 0, 0);
+        }
+        const unsigned int tm = (unsigned int)(vmask >> (16 * i)) & 0xffffu;   // bit t: token t of the tile is real
+        // the tile's value rows go to the wave's LDS tile (rows of masked tokens as zeros) ...
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii) {
+            const bool lr = (tm >> (4 * ii + qd)) & 1u;
+            *reinterpret_cast<uint4*>(vt_b + (4 * ii + qd) * kVPitch + 16 * t16) = lr ? vR[ii] : make_uint4(0, 0, 0, 0);
+        }
+        // ... which frees the row registers for the next tile: its loads fly during this tile's softmax and P.V
+        if (i + 1 < kStreamTiles) issue(i + 1, kA, vR);
+        float sj[4], mt = -INFINITY;
+        bool lv[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            lv[j] = (tm >> (4 * qd + j)) & 1u;
+            sj[j] = lv[j] ? acc[j] * scale : -INFINITY;
+            mt = fmaxf(mt, sj[j]);
+        }
+        mt = fmaxf(mt, __shfl_xor(mt, 16));
+        mt = fmaxf(mt, __shfl_xor(mt, 32));
+        const float m_new = fmaxf(m_run, mt);
+        const float alpha = (m_new > -INFINITY) ? exp2f(m_run - m_new) : 1.f;   // m_run == -inf gives 0
+        unsigned short pb[4];
+        float lw = 0.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float p = lv[j] ? exp2f(sj[j] - m_new) : 0.f;
+            uint32_t u = __float_as_uint(p);
+            u += 0x7fffu + ((u >> 16) & 1u);                      // round to nearest even bf16
+            pb[j] = (unsigned short)(u >> 16);
+            lw += __uint_as_float((uint32_t)pb[j] << 16);         // the normaliser sums the rounded weights
+        }
+        l_run = l_run * alpha + lw;
+        m_run = m_new;
+        // running outputs: row 4qd+j of o is head 4qd+j, whose factor sits in lane 4qd+j
+        float ar[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) ar[j] = __shfl(alpha, 4 * qd + j);
+#pragma unroll
+        for (int dt = 0; dt < kHeadDim / 16; ++dt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) o[dt][j] *= ar[j];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");    // the tile is private to the wave: order only
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const bf16x4 pa = {(short)pb[0], (short)pb[1], (short)pb[2], (short)pb[3]};
+#pragma unroll
+        for (int dt = 0; dt < kHeadDim / 16; ++dt) {
+            bf16x4 vb;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) vb[j] = (short)vt[(4 * qd + j) * (kVPitch / 2) + 16 * dt + t16];
+            o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, vb, o[dt], 0, 0, 0);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");    // reads of this tile precede the next tile's writes
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+    SKV_T(6);
+
+    // ---- the block's four waves combine: common max per head, partial sums through the value tiles ----------
+    l_run += __shfl_xor(l_run, 16);
+    l_run += __shfl_xor(l_run, 32);
+    if (qd == 0) sm_wmax[w][t16] = m_run;
+    __syncthreads();
+    float mb = -INFINITY;
+#pragma unroll
+    for (int ww = 0; ww < kStreamWaves; ++ww) mb = fmaxf(mb, sm_wmax[ww][t16]);
+    const float cw = (m_run > -INFINITY) ? exp2f(m_run - mb) : 0.f;
+    if (qd == 0) sm_wsum[w][t16] = l_run * cw;
+    {
+        float cr[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) cr[j] = __shfl(cw, 4 * qd + j);
+        float* red = reinterpret_cast<float*>(vt_b);
+#pragma unroll
+        for (int dt = 0; dt < kHeadDim / 16; ++dt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (4 * qd + j < G) red[(4 * qd + j) * kHeadDim + 16 * dt + t16] = o[dt][j] * cr[j];
+    }
+    __syncthreads();
+    if (tid < G) {
+        float lb = 0.f, mh = -INFINITY;
+#pragma unroll
+        for (int ww = 0; ww < kStreamWaves; ++ww) { lb += sm_wsum[ww][tid]; mh = fmaxf(mh, sm_wmax[ww][tid]); }
+        float* dst = a.ml + (((qhead0 + tid) * a.max_splits) + slot) * 2;
+        st_agent(dst, mh);
+        st_agent(dst + 1, lb);
+    }
+    for (int i = tid; i < kOut; i += kStreamThreads) {
+        const int g = i / kHeadDim, d = i % kHeadDim;
+        float sum = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < kStreamWaves; ++ww) sum += reinterpret_cast<const float*>(sm_v[ww])[i];
+        st_agent(a.part + (((qhead0 + g) * a.max_splits) + slot) * kHeadDim + d, sum);
+    }
+    SKV_T(7);
+
+    // ---- last arrival combines (same protocol as attend_kernel) ------------------------------------------------
+    __syncthreads();
+    if (tid == 0) {
+        const unsigned int old = __hip_atomic_fetch_add(&a.counter[bh], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sm_last = (old == (unsigned int)(nsplit - 1));
+    }
+    __syncthreads();
+    SKV_T(8);
+    if (!sm_last) return;
+#pragma unroll
+    for (int c = 0; c < kColsPerThread; ++c) {
+        const int col = tid + c * kStreamThreads;
+        if (col >= kCol2) break;
+        const int g = col / (kHeadDim / 2);
+        const float* mlg = a.ml + ((qhead0 + g) * a.max_splits) * 2;
+        const float* pg = a.part + ((qhead0 + g) * a.max_splits) * kHeadDim + (col % (kHeadDim / 2)) * 2;
+        float M = -INFINITY, L = 0.f, o0 = 0.f, o1 = 0.f;
+        constexpr int kU = 8;
+        for (int s0 = 0; s0 < nsplit; s0 += kU) {
+            unsigned long long pv[kU], mv[kU];
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {                        // clamped, unconditional loads
+                const int sidx = min(s0 + u, nsplit - 1) * (CHUNK / kWave);
+                pv[u] = ld_agent64(pg + (int64_t)sidx * kHeadDim);
+                mv[u] = ld_agent64(mlg + 2 * sidx);
+            }
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {
+                const float ms = (s0 + u < nsplit) ? lo_f(mv[u]) : -INFINITY;
+                if (ms > -INFINITY) {
+                    const float nm = fmaxf(M, ms);
+                    const float ca = exp2f(M - nm), cb = exp2f(ms - nm);
+                    L = L * ca + hi_f(mv[u]) * cb;
+                    o0 = o0 * ca + lo_f(pv[u]) * cb;
+                    o1 = o1 * ca + hi_f(pv[u]) * cb;
+                    M = nm;
+                }
+            }
+        }
+        const bool empty = !(L > 0.f);                            // every retrieved position was out of range
+        const float inv = empty ? 0.f : 1.f / L;
+        reinterpret_cast<float2*>(a.out + qhead0 * kHeadDim)[col] = make_float2(o0 * inv, o1 * inv);
+        if (a.lse && (col % (kHeadDim / 2)) == 0) a.lse[qhead0 + g] = empty ? -INFINITY : (M + log2f(L)) * kLn2;
+    }
+    if (tid == 0) __hip_atomic_store(&a.counter[bh], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next call
+    SKV_T(9);
+}
+
+static hipError_t launch_attend_stream(Ctx* c, const AttArgs& a, int32_t n_splits) {
+    const dim3 grid(n_splits, a.v.B * c->d.n_kv_heads), block(kStreamThreads);
+    switch (c->G) {
+        case 1: hipLaunchKernelGGL(attend_stream_kernel<1>, grid, block, 0, c->stream, a); break;
+        case 2: hipLaunchKernelGGL(attend_stream_kernel<2>, grid, block, 0, c->stream, a); break;
+        case 4: hipLaunchKernelGGL(attend_stream_kernel<4>, grid, block, 0, c->stream, a); break;
+        case 8: hipLaunchKernelGGL(attend_stream_kernel<8>, grid, block, 0, c->stream, a); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 template <int EB, int MODE, int CHUNK>
 static hipError_t launch_attend_g(Ctx* c, const AttArgs& a, int32_t n_splits) {
     const dim3 grid(n_splits, a.v.B * c->d.n_kv_heads), block(kBlockThreads);
@@ -1048,8 +1310,10 @@ hipError_t launch_attend_indirect(Ctx* c, const void* q, const void* K_layer, co
     AttArgs a = att_common(c, q, K_layer, V_layer, v, out, lse);
     a.n_tok = n_tok; a.tok_idx = tok_idx; a.idx_stride = c->d.max_budget;
     const int n_splits = (c->d.max_budget + kAttChunkWide - 1) / kAttChunkWide;
-    return c->d.kv_dtype == SKV_BF16 ? launch_attend_g<2, kIndirect, kAttChunkWide>(c, a, n_splits)
-                                     : launch_attend_g<4, kIndirect, kAttChunkWide>(c, a, n_splits);
+    if (c->d.kv_dtype != SKV_BF16) return launch_attend_g<4, kIndirect, kAttChunkWide>(c, a, n_splits);
+    // the streaming kernel addresses rows with 32-bit byte offsets inside a (head, sequence) slab
+    if (v.T_total < (1 << 24)) return launch_attend_stream(c, a, n_splits);
+    return launch_attend_g<2, kIndirect, kAttChunkWide>(c, a, n_splits);
 }
 
 hipError_t launch_select_attend(Ctx* c, const void* q, const void* K_layer, const void* V_layer, const float* score,

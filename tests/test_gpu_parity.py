@@ -357,11 +357,20 @@ def test_fused_ragged_batch_70b_heads(U, oracle32):
     _fused_case(U, oracle32, wl, seed=4, layers=[0, 1])
 
 
-@pytest.mark.parametrize("Hq", [32, 64])
+@pytest.mark.parametrize("Hq", [8, 16, 32, 64])
 def test_fused_batch_path_many_heads(U, oracle32, Hq):
-    """Eight or more sequences x 8 KV heads take the batch path (one selection per head, 256-token blocks)."""
+    """Eight or more sequences x 8 KV heads take the batch path (one selection per head, 256-token blocks; the
+    streaming MFMA kernel for bf16), for every group size."""
     wl = gen.CFG4.scaled(n_layers=1, n_q_heads=Hq, batch=9, t_range=(200, 3000), budgets=(700,))
     _fused_case(U, oracle32, wl, seed=6, layers=[0])
+
+
+@pytest.mark.parametrize("dtype,budget", [("f32", 700), ("bf16", 2), ("bf16", 256), ("bf16", 257), ("bf16", 5000)])
+def test_fused_batch_path_edges(U, oracle32, dtype, budget):
+    """Batch path with fp32 inputs (the VALU kernel), a budget no bucket fits (empty selections), budgets at and
+    just past one 256-token block, and a budget above every context length (all tokens retrieved)."""
+    wl = gen.CFG4.scaled(n_layers=1, n_q_heads=32, batch=8, t_range=(150, 2500), budgets=(budget,), dtype=dtype)
+    _fused_case(U, oracle32, wl, seed=9, layers=[0])
 
 
 def test_attend_batch_path_direct_rows(U, oracle32):
