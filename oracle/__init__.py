@@ -81,6 +81,10 @@ class Oracle:
         L.skvo_attend.restype = None
         L.skvo_query_cache_step.argtypes = [_vp, _ci, _i, _i, _u32p, _i, _f32p, _i, _i32p, _f32p, _vp]
         L.skvo_query_cache_step.restype = _ci
+        L.skvo_token_importance.argtypes = [_vp, _vp, _ci, _i, _i, _i, _i, _i, _f32p]
+        L.skvo_token_importance.restype = None
+        L.skvo_retain.argtypes = [_f32p, _i, _i, _i32p, _i, _i32p, _i32p, _i32p, _i32p]
+        L.skvo_retain.restype = None
         L.skvo_real_bytes.restype = _ci
         assert L.skvo_real_bytes() == (4 if real == "f32" else 8)
 
@@ -112,6 +116,31 @@ class Oracle:
         self.lib.skvo_semvec(K.ctypes.data_as(_vp), _dtype_of(K), L, H, T, D, _ptr(sent_off, _i32p), S,
                              _ptr(out, _f32p))
         return out
+
+    def token_importance(self, q_obs: np.ndarray, K: np.ndarray) -> np.ndarray:
+        """q_obs [Hq][N][D], K [Hkv][T][D] (one layer) -> alpha float32 [T - N]."""
+        q_obs, K = np.ascontiguousarray(q_obs), np.ascontiguousarray(K)
+        Hq, N, D = q_obs.shape
+        H, T, D2 = K.shape
+        assert D == D2 and Hq % H == 0 and _dtype_of(q_obs) == _dtype_of(K)
+        alpha = np.zeros(max(T - N, 0), dtype=np.float32)
+        self.lib.skvo_token_importance(q_obs.ctypes.data_as(_vp), K.ctypes.data_as(_vp), _dtype_of(K), Hq, H, T, N, D,
+                                       _ptr(alpha, _f32p))
+        return alpha
+
+    def retain(self, alpha: np.ndarray, k: int, seg_id: np.ndarray, S: int):
+        """-> (keep_idx[min(k, Tp)] ascending, ret_off[S+1], ret_len[S])."""
+        alpha = np.ascontiguousarray(alpha, dtype=np.float32)
+        seg_id = np.ascontiguousarray(seg_id, dtype=np.int32)
+        Tp = alpha.shape[0]
+        assert seg_id.shape[0] >= Tp
+        keep = np.zeros(max(min(k, Tp), 1), dtype=np.int32)
+        n = np.zeros(1, dtype=np.int32)
+        off = np.zeros(S + 1, dtype=np.int32)
+        ln = np.zeros(max(S, 1), dtype=np.int32)
+        self.lib.skvo_retain(_ptr(alpha, _f32p), Tp, k, _ptr(seg_id, _i32p), S, _ptr(keep, _i32p), _ptr(n, _i32p),
+                             _ptr(off, _i32p), _ptr(ln, _i32p))
+        return keep[: int(n[0])].copy(), off, ln[:S].copy()
 
     # -- decode ----------------------------------------------------------------------------
     def query_cache(self, per: int, cap: int = 4096) -> "QueryCache":

@@ -13,6 +13,10 @@
  * Steps (names follow the paper's notation):
  *   skvo_segment  sentence buckets from a token stream          (Sec. 4.1 "split ... into sentences
  *                                                                according to punctuation"; Alg. 1 prefill)
+ *   skvo_token_importance  alpha_i from the observation window  (Sec. 4.1 "Token importance measurement")
+ *   skvo_retain   global top floor(r tau) tokens and the buckets of the retained tokens
+ *                                                               (Sec. 4.1 "Token selection within sentence buckets";
+ *                                                                App. "Effect of Sentence Length")
  *   skvo_semvec   mean key vector k-bar_{s,h} per bucket, head  (Eq. 1)
  *   skvo_query_cache_step  sentence cache Q_s and its mean query q-bar  (Sec. 4.2 "Sentence-level query aggregation",
  *                                                                Eq. 2; Alg. 1 decoding phase)
@@ -37,6 +41,12 @@
  *     bucket); NaN scores rank lowest; -0 == +0;
  *   - gathered tokens are in ascending position order;
  *   - an empty selection gives O = 0 and lse = -inf;
+ *   - observation window: the window queries see every earlier token and, causally, the window itself (the
+ *     attention of the model's forward pass); alpha_i is defined for the tokens before the window only and sums the
+ *     probabilities over the window's queries and over ALL query heads, so one set of tokens is retained per layer;
+ *     no pooling of alpha; the window's own tokens are not part of the retained pool;
+ *   - a bucket none of whose tokens is retained does not exist: its length is 0, its mean key vector is stored as
+ *     zeros, and the selection never lists it;
  *   - the query of the token that ends a generated sentence still belongs to that sentence: Q_s is
  *     reset after q-bar of that step has been formed; q-bar is rounded once to the storage type.
  *
@@ -111,7 +121,7 @@ void skvo_semvec(const void* K, int dtype, int32_t L, int32_t Hkv, int32_t T, in
                 }
                 real n = (real)(e - b);
                 float* out = semvec + (((int64_t)l * Hkv + h) * S + s) * D;
-                for (int32_t d = 0; d < D; ++d) out[d] = (float)(acc[d] / n);
+                for (int32_t d = 0; d < D; ++d) out[d] = e > b ? (float)(acc[d] / n) : 0.0f;   /* no retained token: no bucket */
             }
     free(acc);
 }
@@ -211,6 +221,7 @@ void skvo_select(const float* score, const int32_t* sent_off, const int32_t* sen
         int32_t used = 0, cnt = 0;
         for (int32_t r = 0; r < S; ++r) {
             int32_t len = sent_len[order[r].id];
+            if (len <= 0) continue;                  /* a bucket without retained tokens does not exist */
             if (used + len > budget) break;          /* first bucket that does not fit ends the walk */
             used += len;
             chosen[cnt++] = order[r].id;
@@ -228,6 +239,65 @@ void skvo_select(const float* score, const int32_t* sent_off, const int32_t* sen
     }
     free(order);
     free(chosen);
+}
+
+/* Sec. 4.1 "Token importance measurement" for one layer.  The last N tokens of the prompt (positions Tp .. T-1,
+ * Tp = T - N) are the observation window.  Window query n of query head j (KV head floor(j/G)) attends, as in the
+ * model's forward pass, to the keys of positions 0 .. Tp + n with softmax(q k / sqrt(D)); alpha_i, i < Tp, is the
+ * sum of the probabilities token i receives from all N window queries of all Hq heads.
+ * q_obs [Hq][N][D], K [Hkv][T][D] (dtype), alpha [Tp] float. */
+void skvo_token_importance(const void* q_obs, const void* K, int dtype, int32_t Hq, int32_t Hkv, int32_t T,
+                           int32_t N, int32_t D, float* alpha) {
+    int32_t Tp = T - N, G = Hq / Hkv;
+    if (Tp <= 0) return;
+    real* total = (real*)calloc((size_t)Tp, sizeof(real));
+    real* logit = (real*)malloc(sizeof(real) * (size_t)T);
+    real inv_sqrt_d = (real)1 / (real)sqrt((double)D);
+    for (int32_t j = 0; j < Hq; ++j) {
+        int32_t h = j / G;
+        for (int32_t n = 0; n < N; ++n) {
+            int32_t visible = Tp + n + 1;                      /* keys of positions 0 .. Tp + n */
+            real m = -INFINITY;
+            for (int32_t x = 0; x < visible; ++x) {
+                real dot = 0;
+                for (int32_t d = 0; d < D; ++d) {
+                    real prod = load_elt(q_obs, dtype, ((int64_t)j * N + n) * D + d) * load_elt(K, dtype, ((int64_t)h * T + x) * D + d);
+                    dot = dot + prod;
+                }
+                logit[x] = dot * inv_sqrt_d;
+                if (logit[x] > m) m = logit[x];
+            }
+            real z = 0;
+            for (int32_t x = 0; x < visible; ++x) z = z + (real)exp((double)(logit[x] - m));
+            for (int32_t i = 0; i < Tp; ++i) total[i] = total[i] + (real)exp((double)(logit[i] - m)) / z;
+        }
+    }
+    for (int32_t i = 0; i < Tp; ++i) alpha[i] = (float)total[i];
+    free(total);
+    free(logit);
+}
+
+/* Sec. 4.1 "Token selection within sentence buckets", App. "Effect of Sentence Length": the floor(r tau) = k tokens
+ * with the highest alpha over the whole prefix are retained, regardless of sentence boundaries (equal alpha: lower
+ * position first; NaN last).  keep_idx [min(k, Tp)] receives their positions in ascending order.  The buckets of
+ * the retained pool keep the numbering of the prompt's buckets: ret_len[s] = retained tokens of bucket s (0 for a
+ * bucket that vanished), ret_off[s] = retained tokens of all earlier buckets, ret_off[S] = n_keep.
+ * seg_id [>= Tp] as produced by skvo_segment. */
+void skvo_retain(const float* alpha, int32_t Tp, int32_t k, const int32_t* seg_id, int32_t S,
+                 int32_t* keep_idx, int32_t* n_keep, int32_t* ret_off, int32_t* ret_len) {
+    int32_t keep = k < Tp ? k : Tp;
+    if (keep < 0) keep = 0;
+    ranked* order = (ranked*)malloc(sizeof(ranked) * (size_t)(Tp > 0 ? Tp : 1));
+    for (int32_t i = 0; i < Tp; ++i) { order[i].score = alpha[i]; order[i].id = i; }
+    qsort(order, (size_t)(Tp > 0 ? Tp : 0), sizeof(ranked), rank_before);
+    for (int32_t r = 0; r < keep; ++r) keep_idx[r] = order[r].id;
+    qsort(keep_idx, (size_t)keep, sizeof(int32_t), by_id);
+    for (int32_t s = 0; s < S; ++s) ret_len[s] = 0;
+    for (int32_t r = 0; r < keep; ++r) ret_len[seg_id[keep_idx[r]]] += 1;
+    ret_off[0] = 0;
+    for (int32_t s = 0; s < S; ++s) ret_off[s + 1] = ret_off[s] + ret_len[s];
+    *n_keep = keep;
+    free(order);
 }
 
 /* Alg. 1 decode "load keys and values of the corresponding tokens": row copy.
