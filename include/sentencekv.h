@@ -98,6 +98,49 @@ int skv_segment(skv_ctx* ctx, const int32_t* tok, int32_t T, const uint32_t* ter
 int skv_build_semvec(skv_ctx* ctx, const void* K_pool, int32_t T, const int32_t* sent_off, int32_t S,
                      float* semvec);
 
+/* Eq. 1 over a retained pool: as skv_build_semvec, but every layer has its own offset table (the retained
+ * tokens differ per layer) and a bucket may hold no token (its vector is stored as zeros; skv_select and
+ * skv_decode_step never list a bucket of length 0).
+ * K_pool dev [L][Hkv][T][D] kv_dtype      sent_off dev [L][S + 1]      semvec dev [L][Hkv][S][D] fp32
+ * Errors: SKV_EINVAL, SKV_ECAPACITY (T > max_tokens or S > max_sentences). */
+int skv_build_semvec_layers(skv_ctx* ctx, const void* K_pool, int32_t T, const int32_t* sent_off, int32_t S, float* semvec);
+
+/* ---------------------------------------------------------------------------------------------
+ * Prefill-side token retention: Sec. 4.1 "Token importance measurement" and "Token selection within sentence
+ * buckets", App. "Effect of Sentence Length", Alg. 1 prefilling phase.
+ *
+ * skv_token_importance: the last N tokens of the T-token prompt are the observation window (Tp = T - N tokens
+ * precede it).  Window query n of query head j attends, as in the model's forward pass, to the keys of positions
+ * 0 .. Tp + n of KV head floor(j / G) with softmax(q k^T / sqrt(D)); alpha[l][i], i < Tp, is the sum over all N window
+ * queries and all Hq heads of the probability token i receives.  One importance per token and layer.
+ * q_obs  dev [L][Hq][N][D] kv_dtype    K_pool dev [L][Hkv][T][D] kv_dtype    alpha dev [L][Tp] fp32
+ * work   dev scratch of at least skv_token_importance_work_bytes(ctx, T, N) bytes (caller-owned; nothing is kept in
+ *        it between calls).  G * N <= 256.  Asynchronous.
+ * Errors: SKV_EINVAL (null / misaligned pointers, N < 1, N >= T, work too small), SKV_ECAPACITY (T > max_tokens,
+ * G * N > 256).  skv_token_importance_work_bytes returns -1 for arguments the call would reject. */
+int64_t skv_token_importance_work_bytes(const skv_ctx* ctx, int32_t T, int32_t N);
+int skv_token_importance(skv_ctx* ctx, const void* q_obs, const void* K_pool, int32_t T, int32_t N, float* alpha, void* work,
+                         int64_t work_bytes);
+
+/* skv_retain: per layer, the k = floor(r tau) tokens with the highest importance over the whole prefix are retained,
+ * regardless of bucket boundaries (equal importance: lower position first; NaN last).  The buckets of the retained
+ * pool keep the prompt's numbering.
+ * alpha    dev [L][Tp] fp32               seg_id  dev [>= Tp] bucket id per token (as produced by skv_segment)
+ * keep_idx dev [L][max(k,1)] retained positions, ascending; n_keep dev [L] = min(k, Tp)
+ * ret_len  dev [L][S] retained tokens per bucket (0: the bucket vanished)
+ * ret_off  dev [L][S + 1] exclusive prefix sum of ret_len = first row of the bucket in the compacted pool.
+ * Errors: SKV_EINVAL (null / misaligned pointers, Tp < 1, k < 0, S < 1), SKV_ECAPACITY (Tp > max_tokens, S > max_sentences). */
+int skv_retain(skv_ctx* ctx, const float* alpha, int32_t Tp, int32_t k, const int32_t* seg_id, int32_t S, int32_t* keep_idx,
+               int32_t* n_keep, int32_t* ret_off, int32_t* ret_len);
+
+/* skv_compact_pool: K_ret[l][h][j] = K_pool[l][h][keep_idx[l][j]] for j < n_keep[l], same for V (the pool the paper
+ * offloads; here it stays in HBM).  Rows j >= n_keep[l] are not written.
+ * K_pool, V_pool dev [L][Hkv][T][D]      K_ret, V_ret dev [L][Hkv][k][D]      keep_idx dev [L][max(k,1)], n_keep dev [L]
+ * The retained pool is then used with T = k, sent_off = ret_off + l * (S + 1) and sent_len = ret_len + l * S in
+ * skv_build_semvec_layers, skv_select, skv_gather and skv_decode_step. */
+int skv_compact_pool(skv_ctx* ctx, const void* K_pool, const void* V_pool, int32_t T, const int32_t* keep_idx, int32_t k,
+                     const int32_t* n_keep, void* K_ret, void* V_ret);
+
 /* ---------------------------------------------------------------------------------------------
  * Sec. 4.2 "Sentence-level query aggregation", Eq. 2, and Alg. 1 decoding phase (append q_t to Q_s, compute
  * q-bar, reset Q_s at a sentence boundary).  The sentence cache Q_s is kept as a running sum and a count per

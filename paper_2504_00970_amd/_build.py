@@ -9,8 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libsentencekv.so")
-SOURCES = ["api.hip", "prefill.hip", "decode.hip"]
-HEADERS = [os.path.join(CSRC, "skv_internal.h"), os.path.join(INCLUDE, "sentencekv.h")]
+SOURCES = ["api.hip", "prefill.hip", "decode.hip", "retain.hip"]
+HEADERS = [os.path.join(CSRC, "skv_internal.h"), os.path.join(CSRC, "skv_device.h"), os.path.join(INCLUDE, "sentencekv.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -41,6 +41,11 @@ _SIGNATURES = {
     "skv_workspace_bytes": (_i64, [_vp]),
     "skv_segment": (_int, [_vp, _vp, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _vp]),
     "skv_build_semvec": (_int, [_vp, _vp, _i32, _vp, _i32, _vp]),
+    "skv_build_semvec_layers": (_int, [_vp, _vp, _i32, _vp, _i32, _vp]),
+    "skv_token_importance_work_bytes": (_i64, [_vp, _i32, _i32]),
+    "skv_token_importance": (_int, [_vp, _vp, _vp, _i32, _i32, _vp, _vp, _i64]),
+    "skv_retain": (_int, [_vp, _vp, _i32, _i32, _vp, _i32, _vp, _vp, _vp, _vp]),
+    "skv_compact_pool": (_int, [_vp, _vp, _vp, _i32, _vp, _i32, _vp, _vp, _vp]),
     "skv_query_update": (_int, [_vp, _i32, _vp, _vp, _vp, _i32, _vp, _vp, _vp]),
     "skv_score": (_int, [_vp, _i32, _vp, _vp, _i32, _vp]),
     "skv_select": (_int, [_vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp]),
@@ -151,6 +156,26 @@ class Context:
     def build_semvec(self, K_pool, sent_off, S: int, semvec) -> None:
         T = K_pool.shape[2]
         _check(_lib().skv_build_semvec(self._h, _p(K_pool), T, _p(sent_off), S, _p(semvec)), "skv_build_semvec")
+
+    def build_semvec_layers(self, K_pool, sent_off, S: int, semvec) -> None:
+        T = K_pool.shape[2]
+        _check(_lib().skv_build_semvec_layers(self._h, _p(K_pool), T, _p(sent_off), S, _p(semvec)), "skv_build_semvec_layers")
+
+    # ---- prefill-side token retention (Sec. 4.1) ---------------------------------------------------------
+    def token_importance_work_bytes(self, T: int, N: int) -> int:
+        return int(_lib().skv_token_importance_work_bytes(self._h, T, N))
+
+    def token_importance(self, q_obs, K_pool, T: int, N: int, alpha, work) -> None:
+        _check(_lib().skv_token_importance(self._h, _p(q_obs), _p(K_pool), T, N, _p(alpha), _p(work),
+                                           work.numel() * work.element_size()), "skv_token_importance")
+
+    def retain(self, alpha, Tp: int, k: int, seg_id, S: int, keep_idx, n_keep, ret_off, ret_len) -> None:
+        _check(_lib().skv_retain(self._h, _p(alpha), Tp, k, _p(seg_id), S, _p(keep_idx), _p(n_keep), _p(ret_off),
+                                 _p(ret_len)), "skv_retain")
+
+    def compact_pool(self, K_pool, V_pool, T: int, keep_idx, k: int, n_keep, K_ret, V_ret) -> None:
+        _check(_lib().skv_compact_pool(self._h, _p(K_pool), _p(V_pool), T, _p(keep_idx), k, _p(n_keep), _p(K_ret),
+                                       _p(V_ret)), "skv_compact_pool")
 
     # ---- sentence query cache (Eq. 2) ----------------------------------------------------------------
     def query_update(self, B: int, q_t, tok_t, term_bitmap, vocab: int, q_sum, q_cnt, q_bar) -> None:

@@ -152,7 +152,59 @@ int skv_build_semvec(skv_ctx* ctx, const void* K_pool, int32_t T, const int32_t*
     if (T > ctx->c.d.max_tokens || S > ctx->c.d.max_sentences) return SKV_ECAPACITY;
     const int rc = check_ctx(ctx);
     if (rc != SKV_OK) return rc;
-    return hip_status(skv::launch_semvec(&ctx->c, K_pool, T, sent_off, S, semvec));
+    return hip_status(skv::launch_semvec(&ctx->c, K_pool, T, sent_off, 0, S, semvec));
+}
+
+int skv_build_semvec_layers(skv_ctx* ctx, const void* K_pool, int32_t T, const int32_t* sent_off, int32_t S, float* semvec) {
+    if (!ctx) return SKV_EINVAL;
+    if (T < 0 || S < 0) return SKV_EINVAL;
+    if (S > 0 && (bad_ptr(K_pool) || bad_ptr(sent_off) || bad_ptr(semvec))) return SKV_EINVAL;
+    if (T > ctx->c.d.max_tokens || S > ctx->c.d.max_sentences) return SKV_ECAPACITY;
+    const int rc = check_ctx(ctx);
+    if (rc != SKV_OK) return rc;
+    return hip_status(skv::launch_semvec(&ctx->c, K_pool, T, sent_off, S + 1, S, semvec));
+}
+
+int64_t skv_token_importance_work_bytes(const skv_ctx* ctx, int32_t T, int32_t N) {
+    if (!ctx || T < 1 || N < 1 || N >= T || ctx->c.G * N > skv::kImportanceMaxRows) return -1;
+    return (int64_t)round256((size_t)skv::importance_work_bytes(&ctx->c, T, N));
+}
+
+int skv_token_importance(skv_ctx* ctx, const void* q_obs, const void* K_pool, int32_t T, int32_t N, float* alpha, void* work,
+                         int64_t work_bytes) {
+    if (!ctx) return SKV_EINVAL;
+    if (T < 1 || N < 1 || N >= T) return SKV_EINVAL;
+    if (ctx->c.G * N > skv::kImportanceMaxRows) return SKV_ECAPACITY;
+    if (bad_ptr(q_obs) || bad_ptr(K_pool) || bad_ptr(alpha) || bad_ptr(work)) return SKV_EINVAL;
+    if (T > ctx->c.d.max_tokens) return SKV_ECAPACITY;
+    if (work_bytes < skv::importance_work_bytes(&ctx->c, T, N)) return SKV_EINVAL;
+    const int rc = check_ctx(ctx);
+    if (rc != SKV_OK) return rc;
+    return hip_status(skv::launch_importance(&ctx->c, q_obs, K_pool, T, N, alpha, work));
+}
+
+int skv_retain(skv_ctx* ctx, const float* alpha, int32_t Tp, int32_t k, const int32_t* seg_id, int32_t S, int32_t* keep_idx,
+               int32_t* n_keep, int32_t* ret_off, int32_t* ret_len) {
+    if (!ctx) return SKV_EINVAL;
+    if (Tp < 1 || k < 0 || S < 1) return SKV_EINVAL;
+    if (bad_ptr(alpha) || bad_ptr(seg_id) || bad_ptr(keep_idx) || bad_ptr(n_keep) || bad_ptr(ret_off) || bad_ptr(ret_len))
+        return SKV_EINVAL;
+    if (Tp > ctx->c.d.max_tokens || S > ctx->c.d.max_sentences) return SKV_ECAPACITY;
+    const int rc = check_ctx(ctx);
+    if (rc != SKV_OK) return rc;
+    return hip_status(skv::launch_retain(&ctx->c, alpha, Tp, k, seg_id, S, keep_idx, n_keep, ret_off, ret_len));
+}
+
+int skv_compact_pool(skv_ctx* ctx, const void* K_pool, const void* V_pool, int32_t T, const int32_t* keep_idx, int32_t k,
+                     const int32_t* n_keep, void* K_ret, void* V_ret) {
+    if (!ctx) return SKV_EINVAL;
+    if (T < 1 || k < 0) return SKV_EINVAL;
+    if (k > 0 && (bad_ptr(K_pool) || bad_ptr(V_pool) || bad_ptr(keep_idx) || bad_ptr(n_keep) || bad_ptr(K_ret) || bad_ptr(V_ret)))
+        return SKV_EINVAL;
+    if (T > ctx->c.d.max_tokens) return SKV_ECAPACITY;
+    const int rc = check_ctx(ctx);
+    if (rc != SKV_OK) return rc;
+    return hip_status(skv::launch_compact_pool(&ctx->c, K_pool, V_pool, T, keep_idx, k, n_keep, K_ret, V_ret));
 }
 
 int skv_query_update(skv_ctx* ctx, int32_t B, const void* q_t, const int32_t* tok_t, const uint32_t* term_bitmap,

@@ -1,6 +1,7 @@
 // Decode-step kernels (Sec. 4.2, Eq. 3, Alg. 1 decoding phase): bucket scores, ranking + budgeted
 // retrieval, K/V row gather, split-K attention with an online-softmax combine.  gfx950, wave64.
 #include "skv_internal.h"
+#include "skv_device.h"
 
 // Phase markers: no-ops unless a profiling build pre-defines SKV_T(k) to record a timestamp.
 #ifndef SKV_T
@@ -93,13 +94,6 @@ hipError_t launch_query_update(Ctx* c, int32_t B, const void* q_t, const int32_t
         hipLaunchKernelGGL(query_update_kernel<4>, grid, block, 0, c->stream, (const char*)q_t, tok_t, bitmap, vocab, per_seq,
                            q_sum, q_cnt, (char*)q_bar);
     return hipGetLastError();
-}
-
-// x + (x moved by a DPP pattern): quad_perm [1,0,3,2] = 0xB1, [2,3,0,1] = 0x4E, row_ror:n = 0x120 + n
-template <int CTRL>
-__device__ __forceinline__ float dpp_add(float x) {
-    const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false);
-    return x + __int_as_float(moved);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -220,14 +214,6 @@ hipError_t launch_score(Ctx* c, const void* q, const float* semvec_layer, const 
 // compaction a thread-local walk plus one block scan.
 // ------------------------------------------------------------------------------------------------
 
-__device__ __forceinline__ uint32_t score_key(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return 0u;          // NaN ranks below everything
-    if (u == 0x80000000u) u = 0u;                             // -0 == +0
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
-constexpr int kBlockWaves = kBlockThreads / kWave;
 constexpr int kSelKreg = 6;                                   // 1024 threads x 6 buckets in registers: S <= 6144
 constexpr int kBins = 2048;                                   // 11-bit digits (the last pass uses 1024)
 
@@ -236,36 +222,6 @@ struct SelectShared {
     uint32_t wave_tot[6][kBlockWaves];                        // one slot per block scan
     int32_t res[3][4];                                        // per pass: crossing digit (-1: none), carry, count
 };
-
-// v + (v moved by a DPP pattern; lanes without a source, or rows masked out, add 0)
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ uint32_t dpp_add_u32(uint32_t v) {
-    return v + (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, true);
-}
-// inclusive prefix sum over the 64 lanes of a wave: row_shr 1,2,4,8 then row_bcast 15 and 31
-__device__ __forceinline__ uint32_t wave_scan_u32(uint32_t v) {
-    v = dpp_add_u32<0x111, 0xf>(v);
-    v = dpp_add_u32<0x112, 0xf>(v);
-    v = dpp_add_u32<0x114, 0xf>(v);
-    v = dpp_add_u32<0x118, 0xf>(v);
-    v = dpp_add_u32<0x142, 0xa>(v);
-    v = dpp_add_u32<0x143, 0xc>(v);
-    return v;
-}
-// Inclusive scan over the block's threads (thread order); one barrier.  A `slot` is used once per call
-// of the selection.
-__device__ __forceinline__ uint32_t block_scan_u32(uint32_t val, uint32_t* slot, uint32_t* total) {
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const uint32_t x = wave_scan_u32(val);
-    if (lane == 63) slot[w] = x;
-    __syncthreads();
-    // prefix over the 16 wave totals: one more wave scan instead of 16 reads per thread
-    const uint32_t t = slot[lane & (kBlockWaves - 1)];
-    const uint32_t ti = wave_scan_u32(lane < kBlockWaves ? t : 0u);
-    *total = (uint32_t)__builtin_amdgcn_readlane((int)ti, kBlockWaves - 1);
-    const uint32_t pre = (uint32_t)__builtin_amdgcn_readlane((int)(ti - t), w);     // lane w < 16 holds slot[w]
-    return x + pre;
-}
 
 // emit(s, off_s, len_s, sel_pos, tok_pos) is called by the owner thread of every selected bucket,
 // sel_pos / tok_pos being the number of selected buckets / tokens with lower ids (sel_pos is only
@@ -325,7 +281,7 @@ __device__ __forceinline__ void select_block(const float* __restrict__ sc, const
                 atomicAdd(&H[(rkey[i] >> nshift) & (nbins - 1)], (1ull << 32) | (unsigned long long)(uint32_t)rlen[i]);
         }
         for (int i = KREG; i < kpt; ++i) {
-            if (s0 + i < S) {
+            if (s0 + i < S && len[s0 + i] > 0) {               // a bucket without tokens takes part in nothing
                 const uint32_t k = score_key(sc[s0 + i]);
                 if (pass == 0 || (k >> shift) == prefix)
                     atomicAdd(&H[(k >> nshift) & (nbins - 1)], (1ull << 32) | (unsigned long long)(uint32_t)len[s0 + i]);
@@ -364,7 +320,7 @@ __device__ __forceinline__ void select_block(const float* __restrict__ sc, const
         for (int i = 0; i < KREG; ++i)
             if (i < kpt && rlen[i] > 0) fn(i, s0 + i, rkey[i], rlen[i], roff[i]);
         for (int i = KREG; i < kpt; ++i)
-            if (s0 + i < S) fn(i, s0 + i, score_key(sc[s0 + i]), len[s0 + i], off[s0 + i]);
+            if (s0 + i < S && len[s0 + i] > 0) fn(i, s0 + i, score_key(sc[s0 + i]), len[s0 + i], off[s0 + i]);
     };
     uint32_t tie_run = 0;          // length of tied buckets with lower ids (starts at the thread's base)
     if (ties) {

@@ -161,7 +161,8 @@ hipError_t launch_segment(Ctx* c, const int32_t* tok, int32_t T, const uint32_t*
 
 template <int EB>
 __global__ __launch_bounds__(kSemvecWavesPerBlock * kWave) void semvec_kernel(const char* __restrict__ K, int32_t T,
-                                                                              const int32_t* __restrict__ sent_off,
+                                                                              const int32_t* __restrict__ sent_off_all,
+                                                                              int32_t off_layer_stride, int32_t Hkv,
                                                                               int32_t S, float* __restrict__ semvec) {
     using R = Row<EB>;
     constexpr int kUnroll = 4;
@@ -169,6 +170,7 @@ __global__ __launch_bounds__(kSemvecWavesPerBlock * kWave) void semvec_kernel(co
     const int32_t s = blockIdx.x * kSemvecWavesPerBlock + (threadIdx.x >> 6);
     if (s >= S) return;                                   // wave-uniform
     const int64_t lh = blockIdx.y;
+    const int32_t* sent_off = sent_off_all + (int64_t)(blockIdx.y / Hkv) * off_layer_stride;   // the layer's table
     const int32_t b = max(sent_off[s], 0), e = min(sent_off[s + 1], T);   // never read outside the pool
     const int r = lane / R::LPR, cc = lane % R::LPR;
     const char* base = K + (lh * T) * (int64_t)(kHeadDim * EB) + (int64_t)cc * 16;
@@ -200,7 +202,7 @@ __global__ __launch_bounds__(kSemvecWavesPerBlock * kWave) void semvec_kernel(co
         for (int i = 0; i < R::EPL; ++i) acc[i] += __shfl_xor(acc[i], off);
     }
     if (r == 0) {
-        const float n = (e > b) ? (float)(e - b) : 1.f;      // an (invalid) empty bucket yields zeros
+        const float n = (e > b) ? (float)(e - b) : 1.f;      // a bucket without tokens yields zeros
         float* out = semvec + (lh * S + s) * (int64_t)kHeadDim + cc * R::EPL;
 #pragma unroll
         for (int i = 0; i < R::EPL; i += 4) {
@@ -210,14 +212,17 @@ __global__ __launch_bounds__(kSemvecWavesPerBlock * kWave) void semvec_kernel(co
     }
 }
 
-hipError_t launch_semvec(Ctx* c, const void* K_pool, int32_t T, const int32_t* sent_off, int32_t S, float* semvec) {
+hipError_t launch_semvec(Ctx* c, const void* K_pool, int32_t T, const int32_t* sent_off, int32_t off_layer_stride, int32_t S,
+                         float* semvec) {
     if (S == 0) return hipSuccess;
     const dim3 grid((S + kSemvecWavesPerBlock - 1) / kSemvecWavesPerBlock, c->d.n_layers * c->d.n_kv_heads);
     const dim3 block(kSemvecWavesPerBlock * kWave);
     if (c->d.kv_dtype == SKV_BF16)
-        hipLaunchKernelGGL(semvec_kernel<2>, grid, block, 0, c->stream, (const char*)K_pool, T, sent_off, S, semvec);
+        hipLaunchKernelGGL(semvec_kernel<2>, grid, block, 0, c->stream, (const char*)K_pool, T, sent_off, off_layer_stride,
+                           c->d.n_kv_heads, S, semvec);
     else
-        hipLaunchKernelGGL(semvec_kernel<4>, grid, block, 0, c->stream, (const char*)K_pool, T, sent_off, S, semvec);
+        hipLaunchKernelGGL(semvec_kernel<4>, grid, block, 0, c->stream, (const char*)K_pool, T, sent_off, off_layer_stride,
+                           c->d.n_kv_heads, S, semvec);
     return hipGetLastError();
 }
 

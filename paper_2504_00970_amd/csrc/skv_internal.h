@@ -65,7 +65,17 @@ struct SeqView {
 // ---- launchers (defined in prefill.hip / decode.hip); each returns the hipError_t of its launch -----
 hipError_t launch_segment(Ctx* c, const int32_t* tok, int32_t T, const uint32_t* bitmap, int32_t vocab,
                           int32_t* seg_id, int32_t* sent_off, int32_t* sent_len, int32_t* n_sent_dev);
-hipError_t launch_semvec(Ctx* c, const void* K_pool, int32_t T, const int32_t* sent_off, int32_t S, float* semvec);
+// off_layer_stride: 0 = one offset table for all layers, else the distance (in entries) between the layers' tables
+hipError_t launch_semvec(Ctx* c, const void* K_pool, int32_t T, const int32_t* sent_off, int32_t off_layer_stride, int32_t S,
+                         float* semvec);
+// prefill-side token retention (retain.hip)
+constexpr int kImportanceMaxRows = 256;   // query rows (G * window tokens) per KV head
+int64_t importance_work_bytes(const Ctx* c, int32_t T, int32_t N);
+hipError_t launch_importance(Ctx* c, const void* q_obs, const void* K_pool, int32_t T, int32_t N, float* alpha, void* work);
+hipError_t launch_retain(Ctx* c, const float* alpha, int32_t Tp, int32_t k, const int32_t* seg_id, int32_t S, int32_t* keep_idx,
+                         int32_t* n_keep, int32_t* ret_off, int32_t* ret_len);
+hipError_t launch_compact_pool(Ctx* c, const void* K_pool, const void* V_pool, int32_t T, const int32_t* keep_idx, int32_t k,
+                               const int32_t* n_keep, void* K_ret, void* V_ret);
 hipError_t launch_query_update(Ctx* c, int32_t B, const void* q_t, const int32_t* tok_t, const uint32_t* bitmap,
                                int32_t vocab, float* q_sum, int32_t* q_cnt, void* q_bar);
 hipError_t launch_score(Ctx* c, const void* q, const float* semvec_layer, const SeqView& v, float* score);
