@@ -423,6 +423,96 @@ def run_prefill(args, wl):
     }
 
 
+def run_retention(args, wl):
+    """Prefill-side token retention on cfg3's prompt: observation-window importance (N = 32 window tokens), global
+    top-k with k = 2 x 2048 (r = 2, budget 2048), pool compaction and the mean keys of the retained buckets."""
+    dev = "cuda:0"
+    L, H, Hq, D, T = wl.n_layers, wl.n_kv_heads, wl.n_q_heads, wl.head_dim, wl.n_tokens
+    N, k = args.window, args.keep
+    Tp = T - N
+    p = gen.prefill_inputs(wl, seed=args.seed, device=dev)
+    V = torch.empty_like(p.K)
+    for l in range(L):
+        V[l].copy_(gen.kv_layer(p.lengths, H, D, wl.torch_dtype, args.seed, l, dev)[1])
+    q_obs = gen.queries(L * Hq, N, D, wl.torch_dtype, args.seed + 2, dev).view(L, Hq, N, D)
+    S_cap = len(p.lengths) + 64
+    ctx = skv.Context(skv.Desc(n_layers=L, n_q_heads=Hq, n_kv_heads=H, kv_dtype=skv.dtype_code(wl.torch_dtype),
+                               max_tokens=T, max_sentences=S_cap, max_budget=16, max_batch=1))
+    d_tok, d_bm = i32(p.tok, dev), torch.as_tensor(p.bitmap.view(np.int32)).to(dev)
+    seg_id = torch.empty(T, dtype=torch.int32, device=dev)
+    sent_off = torch.empty(S_cap + 1, dtype=torch.int32, device=dev)
+    sent_len = torch.empty(S_cap, dtype=torch.int32, device=dev)
+    n_sent = torch.empty(4, dtype=torch.int32, device=dev)
+    S = ctx.segment(d_tok, d_bm, wl.vocab, seg_id, sent_off, sent_len, n_sent)
+    alpha = torch.empty(L, Tp, dtype=torch.float32, device=dev)
+    work = torch.empty(ctx.token_importance_work_bytes(T, N), dtype=torch.uint8, device=dev)
+    keep = torch.empty(L, k, dtype=torch.int32, device=dev)
+    n_keep = torch.empty(max(L, 4), dtype=torch.int32, device=dev)
+    r_off = torch.empty(L, S + 1, dtype=torch.int32, device=dev)
+    r_len = torch.empty(L, S, dtype=torch.int32, device=dev)
+    K_ret = torch.empty(L, H, k, D, dtype=wl.torch_dtype, device=dev)
+    V_ret = torch.empty_like(K_ret)
+    semvec = torch.empty(L, H, S, D, dtype=torch.float32, device=dev)
+
+    stages = {
+        "importance": lambda: ctx.token_importance(q_obs, p.K, T, N, alpha, work),
+        "retain": lambda: ctx.retain(alpha, Tp, k, seg_id, S, keep, n_keep, r_off, r_len),
+        "compact": lambda: ctx.compact_pool(p.K, V, T, keep, k, n_keep, K_ret, V_ret),
+        "semvec": lambda: ctx.build_semvec_layers(K_ret, r_off, S, semvec),
+    }
+
+    def step():
+        for fn in stages.values():
+            fn()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    with Timer() as t:
+        for _ in range(args.steps):
+            step()
+    ms = t.ms / max(args.steps, 1)
+    stage_ms = {}
+    for name, fn in stages.items():
+        with Timer() as ts:
+            for _ in range(5):
+                fn()
+        stage_ms[name] = round(ts.ms / 5, 4)
+    e = wl.elt_bytes
+    flops = 2.0 * 2 * L * Hq * N * T * D                      # two sweeps (row statistics, column sums) of Q K^T
+    imp_bytes = L * H * T * D * e + L * Hq * N * D * e + L * Tp * 4      # keys once, window queries, alpha
+    step_bytes = imp_bytes + L * Tp * 4 + L * k * 4 + 2 * 2 * L * H * k * D * e + L * H * k * D * e + L * H * S * D * 4
+    imp_s = stage_ms["importance"] * 1e-3
+    tflops = flops / imp_s / 1e12
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        orc = oracle.get("f32")
+        q0, K0 = gen.to_numpy(q_obs[0]), gen.to_numpy(p.K[0])
+        t0 = time.perf_counter()
+        a0 = orc.token_importance(q0, K0)
+        orc.retain(a0, k, seg_id.cpu().numpy(), S)
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(flops / 2 / L / dt / 1e12, 6), "unit": "TFLOP/s", "cores": 1, "kind": "oracle",
+               "ms_per_layer": round(dt * 1e3, 1),
+               "sample": "importance + retention of layer 0 (1 of %d layers), one sweep of Q K^T, single thread, fp32" % L}
+    return {
+        "metric": "prefill token retention (importance + top-k + compaction + mean keys), ms per prompt at %s tokens" % _ctx_name(T),
+        "value": round(ms, 4), "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 4), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name + "_retention", "layers": L, "q_heads": Hq, "kv_heads": H, "head_dim": D, "tokens": T,
+                   "window": N, "keep": k, "sentences": S,
+                   "path": "skv_token_importance + skv_retain + skv_compact_pool + skv_build_semvec_layers"},
+        "stage_ms": stage_ms, "bytes_per_step": int(step_bytes), "GBps": round(step_bytes / (ms * 1e-3) / 1e9, 1),
+        "roofline": dict(bound="mfma", kernel="importance_stats_kernel + importance_colsum_kernel", achieved=round(tflops, 1),
+                         peak=2500.0, unit="TFLOP/s", frac=round(tflops / 2500.0, 4), traffic=None,
+                         flops_per_launch=int(flops), hbm_bytes_algorithmic=int(imp_bytes),
+                         hbm_GBps=round(imp_bytes / imp_s / 1e9, 1), hbm_frac=round(imp_bytes / imp_s / 1e9 / HBM_PEAK_GBPS, 4)),
+        "cpu_baseline": cpu,
+    }
+
+
 def _ctx_name(T):
     return "%dk" % (T // 1024) if T % 1024 == 0 else str(T)
 
@@ -462,7 +552,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4"])
+    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg3-retain", "cfg4"])
+    ap.add_argument("--window", type=int, default=32, help="cfg3-retain: observation-window tokens")
+    ap.add_argument("--keep", type=int, default=4096, help="cfg3-retain: tokens retained per layer (floor(r tau))")
     ap.add_argument("--resident-layers", type=int, default=4, help="cfg4: layers of the pool kept in HBM")
     ap.add_argument("--budget", type=int, default=0, help="token budget (default: the workload's largest)")
     ap.add_argument("--seed", type=int, default=0)
@@ -482,10 +574,13 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
-    wl = gen.CONFIGS[args.workload]
+    retain = args.workload == "cfg3-retain"
+    wl = gen.CONFIGS["cfg3" if retain else args.workload]
     if args.host_pool_layers < 0:
         args.host_pool_layers = 2 if args.workload == "cfg2" else 0
-    if args.workload == "cfg3":
+    if retain:
+        res = run_retention(args, wl)
+    elif args.workload == "cfg3":
         res = run_prefill(args, wl)
     elif wl.batch > 1:
         res = run_ragged(args, wl)

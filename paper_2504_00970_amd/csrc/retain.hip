@@ -11,20 +11,23 @@ namespace skv {
 // Importance.  For one layer and KV head h the window's R = G*N query rows (row = g*N + n: query head
 // h*G+g, window token n, contiguous in q_obs) meet all T keys: S^T = K Q^T / sqrt(D) on
 // v_mfma_f32_16x16x32_bf16, keys as A fragments straight from 16-byte row loads (lane (t, qd): key t of
-// the tile, dims 32s+8qd..+7), query rows as B fragments from an LDS copy.  fp32 inputs are
-// split exactly into three bf16 terms -- see Frag -- so that the products keep fp32 accuracy.
-//   pass 1 (stats):   per row, max and sum of exp2 over the keys visible to it (positions <= Tp + n),
-//                     per block of keys; partials combined by a small second kernel;
-//   pass 2 (colsum):  alpha_i = sum over the 8 KV heads (in order) and their rows of
-//                     exp2(s - m_row) / l_row, i < Tp; one block owns 256 keys for all heads.
-// A wave owns 64 keys (four 16-key tiles, 64 VGPRs of fragments; 16 keys for fp32) and walks the row tiles.
+// the tile, dims 32s+8qd..+7), query rows as B fragments from an LDS copy.  fp32 inputs are split
+// exactly into three bf16 terms -- see Frag -- so that the products keep fp32 accuracy.
+//   pass 1 (stats):   per row, max and sum of exp2 over the keys visible to it (positions <= Tp + n), per block
+//                     of kKeysPerBlock keys; the partials are combined per row by importance_combine_kernel;
+//   pass 2 (colsum):  per KV head, the column sums of exp2(s - m_row) / l_row over the head's rows, for the Tp
+//                     prefix keys; importance_sum_heads_kernel adds the heads in ascending order (deterministic).
+// A wave owns 16*KT keys per sweep and walks the row tiles; a block makes kImpSubs sweeps, the next sweep's key
+// fragments being requested before the current sweep is computed (bf16: two register buffers of 32 VGPRs).
+// Both passes of a layer run before the next layer starts, so the second sweep over a layer's keys (67 MB at 32K
+// tokens) follows the first closely.
 // ------------------------------------------------------------------------------------------------
 constexpr int kImpThreads = 256;
 constexpr int kImpWaves = kImpThreads / kWave;
-constexpr int kImpSubs = 2;                                    // sweeps of a stats block
-// 16-key tiles per wave: four for bf16 (64 VGPRs of key fragments); one for fp32, whose fragments are three times as wide
+constexpr int kImpSubs = 4;                                    // sweeps of a block
 template <int EB> struct Imp {
-    static constexpr int KT = EB == 2 ? 4 : 1;
+    static constexpr int KT = EB == 2 ? 2 : 1;                 // 16-key tiles per wave and sweep
+    static constexpr int NB = EB == 2 ? 2 : 1;                 // register buffers of key fragments
     static constexpr int kKeysPerWave = 16 * KT;
     static constexpr int kKeysPerSub = kImpWaves * kKeysPerWave;
     static constexpr int kKeysPerBlock = kKeysPerSub * kImpSubs;
@@ -36,6 +39,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ f32x4 mfma_bf16(const uint4& a, const uint4& b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
+// 2^x for x <= 0 (a probability): the bare instruction; results below the normal range flush to zero
+__device__ __forceinline__ float exp2_neg(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // 8 consecutive elements of a row as bf16 fragments.  bf16 storage: one 16-byte load.  fp32 storage: each value
 // is split exactly into three bf16 terms by truncation (8 + 8 + 8 mantissa bits: x = a + b + c), and x*y is evaluated
@@ -90,13 +95,24 @@ __device__ __forceinline__ void stage_queries(const char* __restrict__ q_head /*
     }
 }
 
+// Key fragments of one sweep of a wave: keys key0 + 16 kt + t16 (clamped to the last valid row: never out of bounds).
+template <int EB>
+__device__ __forceinline__ void load_keys(Frag<EB> (&kf)[Imp<EB>::KT][4], const char* Kh, int32_t key0, int32_t last, int t16, int qd) {
+#pragma unroll
+    for (int kt = 0; kt < Imp<EB>::KT; ++kt) {
+        const char* row = Kh + (int64_t)min(key0 + 16 * kt + t16, last) * (kHeadDim * EB);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) kf[kt][s].load(row, 32 * s + 8 * qd);
+    }
+}
+
 // pass 1.  grid (ceil(T / Imp<EB>::kKeysPerBlock), Hkv); part [Hkv][chunks][RT*16][2] = (max in log2 units, sum).
 template <int EB, int RT>
 __global__ __launch_bounds__(kImpThreads) void importance_stats_kernel(const char* __restrict__ q_layer, const char* __restrict__ K_layer,
                                                                      int32_t T, int32_t N, int32_t G, float* __restrict__ part) {
     constexpr int kRowBytes = kHeadDim * EB, kPitch = kRowBytes + 16;
     constexpr int kRows = RT * 16;
-    constexpr int KT = Imp<EB>::KT;
+    constexpr int KT = Imp<EB>::KT, NB = Imp<EB>::NB;
     constexpr float kLog2e = 1.4426950408889634f;
     extern __shared__ __attribute__((aligned(16))) char sm_dyn[];
     char* sm_q = sm_dyn;                                              // [kRows][kPitch]
@@ -105,55 +121,58 @@ __global__ __launch_bounds__(kImpThreads) void importance_stats_kernel(const cha
     const int h = blockIdx.y, chunk = blockIdx.x, nchunks = gridDim.x;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, t16 = lane & 15, qd = lane >> 4;
     const int R = G * N, Tp = T - N;
+    const char* Kh = K_layer + (int64_t)h * T * kRowBytes;
+    const int32_t wave_key0 = chunk * Imp<EB>::kKeysPerBlock + Imp<EB>::kKeysPerWave * w;
+    Frag<EB> kf[NB][KT][4];
+    if (NB == 2) load_keys<EB>(kf[0], Kh, wave_key0, T - 1, t16, qd);
     stage_queries<EB>(q_layer + (int64_t)h * R * kRowBytes, R, kRows, sm_q);
     const float scale = kLog2e * rsqrtf((float)kHeadDim);
-    const char* Kh = K_layer + (int64_t)h * T * kRowBytes;
 
     float m_run[RT], l_run[RT];
+    int32_t limit[RT];                                                // last position visible to the lane's row of tile rt
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) { m_run[rt] = -INFINITY; l_run[rt] = 0.f; }
+    for (int rt = 0; rt < RT; ++rt) {
+        m_run[rt] = -INFINITY; l_run[rt] = 0.f;
+        limit[rt] = min(Tp + (16 * rt + t16) % N, T - 1);
+    }
     __syncthreads();
 
-#pragma unroll 1
+#pragma unroll
     for (int sub = 0; sub < kImpSubs; ++sub) {
-        const int32_t key0 = chunk * Imp<EB>::kKeysPerBlock + sub * Imp<EB>::kKeysPerSub + Imp<EB>::kKeysPerWave * w;
-        if (key0 >= T) break;                                         // wave-uniform
-        Frag<EB> kf[KT][4];
-#pragma unroll
-        for (int kt = 0; kt < KT; ++kt) {
-            const char* row = Kh + (int64_t)min(key0 + 16 * kt + t16, T - 1) * kRowBytes;
-#pragma unroll
-            for (int s = 0; s < 4; ++s) kf[kt][s].load(row, 32 * s + 8 * qd);
-        }
+        const int32_t key0 = wave_key0 + sub * Imp<EB>::kKeysPerSub;
+        const int cur = NB == 2 ? (sub & 1) : 0;
+        if (NB == 2) { if (sub + 1 < kImpSubs) load_keys<EB>(kf[cur ^ 1], Kh, key0 + Imp<EB>::kKeysPerSub, T - 1, t16, qd); }
+        else load_keys<EB>(kf[0], Kh, key0, T - 1, t16, qd);
+        if (key0 >= T) continue;                                      // wave-uniform: nothing of this sweep exists
+        const bool open = key0 + Imp<EB>::kKeysPerWave <= Tp;         // wave-uniform: every key visible to every row
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
             Frag<EB> qf[4];
 #pragma unroll
             for (int s = 0; s < 4; ++s) qf[s].load(sm_q + (16 * rt + t16) * kPitch, 32 * s + 8 * qd);
-            const int32_t limit = min(Tp + (16 * rt + t16) % N, T - 1);   // last position visible to this row
             float sv[KT][4], mt = -INFINITY;
 #pragma unroll
             for (int kt = 0; kt < KT; ++kt) {
                 f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int s = 0; s < 4; ++s) acc = frag_mma<EB>(kf[kt][s], qf[s], acc);
+                for (int s = 0; s < 4; ++s) acc = frag_mma<EB>(kf[cur][kt][s], qf[s], acc);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const int32_t key = key0 + 16 * kt + 4 * qd + j;
-                    sv[kt][j] = key <= limit ? acc[j] * scale : -INFINITY;
+                    sv[kt][j] = acc[j] * scale;
+                    if (!open && key0 + 16 * kt + 4 * qd + j > limit[rt]) sv[kt][j] = -INFINITY;
                     mt = fmaxf(mt, sv[kt][j]);
                 }
             }
             mt = fmaxf(mt, __shfl_xor(mt, 16));
             mt = fmaxf(mt, __shfl_xor(mt, 32));
             const float m_new = fmaxf(m_run[rt], mt);
-            if (m_new > -INFINITY) {                                  // uniform over the 4 lanes of a row; harmless divergence
+            if (m_new > -INFINITY) {                                  // per-lane code only: divergence is harmless
                 float sum = 0.f;
 #pragma unroll
                 for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) sum += exp2f(sv[kt][j] - m_new);      // exp2(-inf) = 0
-                l_run[rt] = l_run[rt] * exp2f(m_run[rt] - m_new) + sum;
+                    for (int j = 0; j < 4; ++j) sum += exp2_neg(sv[kt][j] - m_new);   // exp2(-inf) = 0
+                l_run[rt] = l_run[rt] * exp2_neg(m_run[rt] - m_new) + sum;
                 m_run[rt] = m_new;
             }
         }
@@ -174,109 +193,128 @@ __global__ __launch_bounds__(kImpThreads) void importance_stats_kernel(const cha
         float l = 0.f;
 #pragma unroll
         for (int ww = 0; ww < kImpWaves; ++ww)
-            if (sm_m[ww][row] > -INFINITY) l += sm_l[ww][row] * exp2f(sm_m[ww][row] - m);
+            if (sm_m[ww][row] > -INFINITY) l += sm_l[ww][row] * exp2_neg(sm_m[ww][row] - m);
         float* dst = part + (((int64_t)h * nchunks + chunk) * kRows + row) * 2;
         dst[0] = m;
         dst[1] = l;
     }
 }
 
-// Combines the per-chunk partials of one layer: rowstat [Hkv][rows][2] = (max, 1 / sum).  grid (Hkv).
+// Combines the per-chunk partials of one layer: rowstat [Hkv][rows][2] = (max, 1 / sum).  One wave per row, the
+// chunks spread over its lanes.  grid (ceil(Hkv * rows / 4)).
 __global__ __launch_bounds__(kImpThreads) void importance_combine_kernel(const float* __restrict__ part, int32_t nchunks, int32_t rows,
-                                                                       float* __restrict__ rowstat) {
-    const int h = blockIdx.x;
-    for (int row = threadIdx.x; row < rows; row += kImpThreads) {
-        float M = -INFINITY, L = 0.f;
-        for (int c = 0; c < nchunks; ++c) {
-            const float2 p = *reinterpret_cast<const float2*>(part + (((int64_t)h * nchunks + c) * rows + row) * 2);
-            if (p.x > -INFINITY) {
-                const float nm = fmaxf(M, p.x);
-                L = L * exp2f(M - nm) + p.y * exp2f(p.x - nm);
-                M = nm;
-            }
+                                                                       int32_t Hkv, float* __restrict__ rowstat) {
+    const int lane = threadIdx.x & 63;
+    const int item = blockIdx.x * kImpWaves + (threadIdx.x >> 6);     // (head, row)
+    if (item >= Hkv * rows) return;
+    const int h = item / rows, row = item % rows;
+    float M = -INFINITY, L = 0.f;
+    for (int c = lane; c < nchunks; c += kWave) {
+        const float2 p = *reinterpret_cast<const float2*>(part + (((int64_t)h * nchunks + c) * rows + row) * 2);
+        if (p.x > -INFINITY) {
+            const float nm = fmaxf(M, p.x);
+            L = L * exp2_neg(M - nm) + p.y * exp2_neg(p.x - nm);
+            M = nm;
         }
+    }
+    float Mw = M;
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) Mw = fmaxf(Mw, __shfl_xor(Mw, o));
+    float Lw = M > -INFINITY ? L * exp2_neg(M - Mw) : 0.f;
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) Lw += __shfl_xor(Lw, o);
+    if (lane == 0) {
         float* dst = rowstat + ((int64_t)h * rows + row) * 2;
-        dst[0] = M;
-        dst[1] = L > 0.f ? 1.f / L : 0.f;
+        dst[0] = Mw;
+        dst[1] = Lw > 0.f ? 1.f / Lw : 0.f;
     }
 }
 
-// pass 2.  grid (ceil(Tp / Imp<EB>::kKeysPerSub)); one block owns that many prefix keys and walks the KV heads in order.
+// pass 2.  grid (ceil(Tp / Imp<EB>::kKeysPerBlock), Hkv); alpha_h [Hkv][Tp].
 template <int EB, int RT>
 __global__ __launch_bounds__(kImpThreads) void importance_colsum_kernel(const char* __restrict__ q_layer, const char* __restrict__ K_layer,
-                                                                      int32_t T, int32_t N, int32_t G, int32_t Hkv,
-                                                                      const float* __restrict__ rowstat, float* __restrict__ alpha) {
+                                                                      int32_t T, int32_t N, int32_t G,
+                                                                      const float* __restrict__ rowstat, float* __restrict__ alpha_h) {
     constexpr int kRowBytes = kHeadDim * EB, kPitch = kRowBytes + 16;
     constexpr int kRows = RT * 16;
-    constexpr int KT = Imp<EB>::KT;
+    constexpr int KT = Imp<EB>::KT, NB = Imp<EB>::NB;
     constexpr float kLog2e = 1.4426950408889634f;
     extern __shared__ __attribute__((aligned(16))) char sm_dyn[];
     char* sm_q = sm_dyn;
     __shared__ float2 sm_stat[kRows];
 
+    const int h = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, t16 = lane & 15, qd = lane >> 4;
     const int R = G * N, Tp = T - N;
-    const int32_t key0 = blockIdx.x * Imp<EB>::kKeysPerSub + Imp<EB>::kKeysPerWave * w;
+    const char* Kh = K_layer + (int64_t)h * T * kRowBytes;
+    const int32_t wave_key0 = blockIdx.x * Imp<EB>::kKeysPerBlock + Imp<EB>::kKeysPerWave * w;
+    Frag<EB> kf[NB][KT][4];
+    if (NB == 2) load_keys<EB>(kf[0], Kh, wave_key0, Tp - 1, t16, qd);
+    stage_queries<EB>(q_layer + (int64_t)h * R * kRowBytes, R, kRows, sm_q);
+    for (int row = tid; row < kRows; row += kImpThreads)       // rows >= R: 1 / sum = 0, so they add nothing
+        sm_stat[row] = row < R ? *reinterpret_cast<const float2*>(rowstat + ((int64_t)h * kRows + row) * 2) : make_float2(0.f, 0.f);
     const float scale = kLog2e * rsqrtf((float)kHeadDim);
-    float ps[KT][4];
-#pragma unroll
-    for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) ps[kt][j] = 0.f;
+    __syncthreads();
 
-#pragma unroll 1
-    for (int h = 0; h < Hkv; ++h) {
-        __syncthreads();                                              // the previous head's LDS reads are done
-        stage_queries<EB>(q_layer + (int64_t)h * R * kRowBytes, R, kRows, sm_q);
-        for (int row = tid; row < kRows; row += kImpThreads)
-            sm_stat[row] = row < R ? *reinterpret_cast<const float2*>(rowstat + ((int64_t)h * kRows + row) * 2) : make_float2(0.f, 0.f);
-        __syncthreads();
-        if (key0 >= Tp) continue;                                     // wave-uniform; barriers stay matched
-        const char* Kh = K_layer + (int64_t)h * T * kRowBytes;
-        Frag<EB> kf[KT][4];
 #pragma unroll
-        for (int kt = 0; kt < KT; ++kt) {
-            const char* row = Kh + (int64_t)min(key0 + 16 * kt + t16, Tp - 1) * kRowBytes;
+    for (int sub = 0; sub < kImpSubs; ++sub) {
+        const int32_t key0 = wave_key0 + sub * Imp<EB>::kKeysPerSub;
+        const int cur = NB == 2 ? (sub & 1) : 0;
+        if (NB == 2) { if (sub + 1 < kImpSubs) load_keys<EB>(kf[cur ^ 1], Kh, key0 + Imp<EB>::kKeysPerSub, Tp - 1, t16, qd); }
+        else load_keys<EB>(kf[0], Kh, key0, Tp - 1, t16, qd);
+        if (key0 >= Tp) continue;                                     // wave-uniform
+        float ps[KT][4];
 #pragma unroll
-            for (int s = 0; s < 4; ++s) kf[kt][s].load(row, 32 * s + 8 * qd);
-        }
+        for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
+            for (int j = 0; j < 4; ++j) ps[kt][j] = 0.f;
+#pragma unroll 2
         for (int rt = 0; rt < RT; ++rt) {
             Frag<EB> qf[4];
 #pragma unroll
             for (int s = 0; s < 4; ++s) qf[s].load(sm_q + (16 * rt + t16) * kPitch, 32 * s + 8 * qd);
-            const float2 st = sm_stat[16 * rt + t16];                 // rows >= R: 1/sum = 0
+            const float2 st = sm_stat[16 * rt + t16];
 #pragma unroll
             for (int kt = 0; kt < KT; ++kt) {
                 f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int s = 0; s < 4; ++s) acc = frag_mma<EB>(kf[kt][s], qf[s], acc);
+                for (int s = 0; s < 4; ++s) acc = frag_mma<EB>(kf[cur][kt][s], qf[s], acc);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) ps[kt][j] += exp2f(acc[j] * scale - st.x) * st.y;
+                for (int j = 0; j < 4; ++j) ps[kt][j] += exp2_neg(acc[j] * scale - st.x) * st.y;   // prefix keys: s <= row max
             }
         }
+        // sum over the 16 rows of the tile layout (the lanes of a DPP row); lane t16 == 0 stores its four keys
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float v = ps[kt][j];
+                v = dpp_add<0xB1>(v);
+                v = dpp_add<0x4E>(v);
+                v = dpp_add<0x124>(v);
+                v = dpp_add<0x128>(v);
+                const int32_t key = key0 + 16 * kt + 4 * qd + j;
+                if (t16 == 0 && key < Tp) alpha_h[(int64_t)h * Tp + key] = v;
+            }
     }
-    // sum over the 16 rows of the tile layout (lanes of a DPP row), then lane t16 == 0 stores its four keys
-#pragma unroll
-    for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            float v = ps[kt][j];
-            v = dpp_add<0xB1>(v);
-            v = dpp_add<0x4E>(v);
-            v = dpp_add<0x124>(v);
-            v = dpp_add<0x128>(v);
-            const int32_t key = key0 + 16 * kt + 4 * qd + j;
-            if (t16 == 0 && key < Tp) alpha[key] = v;
-        }
+}
+
+// alpha[i] = sum over the KV heads, in ascending order, of alpha_h[h][i].
+__global__ __launch_bounds__(kImpThreads) void importance_sum_heads_kernel(const float* __restrict__ alpha_h, int32_t Tp, int32_t Hkv,
+                                                                         float* __restrict__ alpha) {
+    const int32_t i = blockIdx.x * kImpThreads + threadIdx.x;
+    if (i >= Tp) return;
+    float v = 0.f;
+    for (int h = 0; h < Hkv; ++h) v += alpha_h[(int64_t)h * Tp + i];
+    alpha[i] = v;
 }
 
 template <int EB, int RT>
 static hipError_t launch_importance_rt(Ctx* c, const char* q_layer, const char* K_layer, int32_t T, int32_t N, float* alpha,
-                                       float* part, float* rowstat) {
-    const int Hkv = c->d.n_kv_heads, G = c->G;
+                                       float* part, float* rowstat, float* alpha_h) {
+    const int Hkv = c->d.n_kv_heads, G = c->G, rows = RT * 16;
     const int nchunks = (T + Imp<EB>::kKeysPerBlock - 1) / Imp<EB>::kKeysPerBlock;
-    const size_t lds = (size_t)RT * 16 * (kHeadDim * EB + 16);
+    const size_t lds = (size_t)rows * (kHeadDim * EB + 16);
     static bool raised = false;                                        // dynamic LDS above 64 KB needs the opt-in once
     if (!raised) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&importance_stats_kernel<EB, RT>),
@@ -287,52 +325,54 @@ static hipError_t launch_importance_rt(Ctx* c, const char* q_layer, const char* 
         if (e != hipSuccess) return e;
         raised = true;
     }
+    const int Tp = T - N;
     hipLaunchKernelGGL((importance_stats_kernel<EB, RT>), dim3(nchunks, Hkv), dim3(kImpThreads), lds, c->stream, q_layer, K_layer, T, N,
                        G, part);
-    hipLaunchKernelGGL(importance_combine_kernel, dim3(Hkv), dim3(kImpThreads), 0, c->stream, part, nchunks, RT * 16, rowstat);
-    const int Tp = T - N;
-    hipLaunchKernelGGL((importance_colsum_kernel<EB, RT>), dim3((Tp + Imp<EB>::kKeysPerSub - 1) / Imp<EB>::kKeysPerSub), dim3(kImpThreads), lds,
-                       c->stream, q_layer, K_layer, T, N, G, Hkv, rowstat, alpha);
+    hipLaunchKernelGGL(importance_combine_kernel, dim3((Hkv * rows + kImpWaves - 1) / kImpWaves), dim3(kImpThreads), 0, c->stream, part,
+                       nchunks, rows, Hkv, rowstat);
+    hipLaunchKernelGGL((importance_colsum_kernel<EB, RT>), dim3((Tp + Imp<EB>::kKeysPerBlock - 1) / Imp<EB>::kKeysPerBlock, Hkv),
+                       dim3(kImpThreads), lds, c->stream, q_layer, K_layer, T, N, G, rowstat, alpha_h);
+    hipLaunchKernelGGL(importance_sum_heads_kernel, dim3((Tp + kImpThreads - 1) / kImpThreads), dim3(kImpThreads), 0, c->stream, alpha_h,
+                       Tp, Hkv, alpha);
     return hipGetLastError();
 }
 
 template <int EB>
 static hipError_t launch_importance_eb(Ctx* c, const char* q_layer, const char* K_layer, int32_t T, int32_t N, float* alpha,
-                                       float* part, float* rowstat) {
+                                       float* part, float* rowstat, float* alpha_h) {
     const int R = c->G * N;
-    if (R <= 32) return launch_importance_rt<EB, 2>(c, q_layer, K_layer, T, N, alpha, part, rowstat);
-    if (R <= 64) return launch_importance_rt<EB, 4>(c, q_layer, K_layer, T, N, alpha, part, rowstat);
-    if (R <= 128) return launch_importance_rt<EB, 8>(c, q_layer, K_layer, T, N, alpha, part, rowstat);
-    if (R <= 256) return launch_importance_rt<EB, 16>(c, q_layer, K_layer, T, N, alpha, part, rowstat);
+    if (R <= 32) return launch_importance_rt<EB, 2>(c, q_layer, K_layer, T, N, alpha, part, rowstat, alpha_h);
+    if (R <= 64) return launch_importance_rt<EB, 4>(c, q_layer, K_layer, T, N, alpha, part, rowstat, alpha_h);
+    if (R <= 128) return launch_importance_rt<EB, 8>(c, q_layer, K_layer, T, N, alpha, part, rowstat, alpha_h);
+    if (R <= 256) return launch_importance_rt<EB, 16>(c, q_layer, K_layer, T, N, alpha, part, rowstat, alpha_h);
     return hipErrorInvalidValue;
 }
 
-int importance_row_tiles(int rows) { return rows <= 32 ? 2 : rows <= 64 ? 4 : rows <= 128 ? 8 : 16; }
+static int importance_rows(int rows) { return (rows <= 32 ? 2 : rows <= 64 ? 4 : rows <= 128 ? 8 : 16) * 16; }
 
 static int64_t importance_chunks(const Ctx* c, int32_t T) {
     const int per = c->d.kv_dtype == SKV_BF16 ? Imp<2>::kKeysPerBlock : Imp<4>::kKeysPerBlock;
     return (T + per - 1) / per;
 }
 
+// work = part [Hkv][chunks][rows][2] | rowstat [Hkv][rows][2] | alpha_h [Hkv][Tp], floats
 int64_t importance_work_bytes(const Ctx* c, int32_t T, int32_t N) {
-    const int rows = importance_row_tiles(c->G * N) * 16;
-    const int64_t nchunks = importance_chunks(c, T);
-    return ((int64_t)c->d.n_kv_heads * nchunks * rows * 2 + (int64_t)c->d.n_kv_heads * rows * 2) * (int64_t)sizeof(float);
+    const int64_t rows = importance_rows(c->G * N), Hkv = c->d.n_kv_heads;
+    return (Hkv * importance_chunks(c, T) * rows * 2 + Hkv * rows * 2 + Hkv * (int64_t)(T - N)) * (int64_t)sizeof(float);
 }
 
-// Layers are processed one after the other so that the second sweep over a layer's keys follows the first closely.
 hipError_t launch_importance(Ctx* c, const void* q_obs, const void* K_pool, int32_t T, int32_t N, float* alpha, void* work) {
     const int Hkv = c->d.n_kv_heads, Hq = c->d.n_q_heads, eb = c->d.kv_dtype == SKV_BF16 ? 2 : 4;
-    const int rows = importance_row_tiles(c->G * N) * 16;
-    const int64_t nchunks = importance_chunks(c, T);
+    const int64_t rows = importance_rows(c->G * N);
     float* part = (float*)work;
-    float* rowstat = part + (int64_t)Hkv * nchunks * rows * 2;
+    float* rowstat = part + Hkv * importance_chunks(c, T) * rows * 2;
+    float* alpha_h = rowstat + Hkv * rows * 2;
     const int32_t Tp = T - N;
     for (int l = 0; l < c->d.n_layers; ++l) {
         const char* ql = (const char*)q_obs + (int64_t)l * Hq * N * kHeadDim * eb;
         const char* Kl = (const char*)K_pool + (int64_t)l * Hkv * T * kHeadDim * eb;
-        const hipError_t e = eb == 2 ? launch_importance_eb<2>(c, ql, Kl, T, N, alpha + (int64_t)l * Tp, part, rowstat)
-                                     : launch_importance_eb<4>(c, ql, Kl, T, N, alpha + (int64_t)l * Tp, part, rowstat);
+        const hipError_t e = eb == 2 ? launch_importance_eb<2>(c, ql, Kl, T, N, alpha + (int64_t)l * Tp, part, rowstat, alpha_h)
+                                     : launch_importance_eb<4>(c, ql, Kl, T, N, alpha + (int64_t)l * Tp, part, rowstat, alpha_h);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
