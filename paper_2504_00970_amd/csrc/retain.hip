@@ -19,8 +19,7 @@ namespace skv {
 //                     prefix keys; importance_sum_heads_kernel adds the heads in ascending order (deterministic).
 // A wave owns 16*KT keys per sweep and walks the row tiles; a block makes kImpSubs sweeps, the next sweep's key
 // fragments being requested before the current sweep is computed (bf16: two register buffers of 32 VGPRs).
-// Both passes of a layer run before the next layer starts, so the second sweep over a layer's keys (67 MB at 32K
-// tokens) follows the first closely.
+// Each pass covers all layers in one launch (grid z = layer).
 // ------------------------------------------------------------------------------------------------
 constexpr int kImpThreads = 256;
 constexpr int kImpWaves = kImpThreads / kWave;
@@ -84,14 +83,22 @@ __device__ __forceinline__ f32x4 frag_mma(const Frag<EB>& k, const Frag<EB>& q, 
 }
 
 // Query rows of KV head h -> LDS as fragments' source (rows >= R are zero).  Row pitch padded by 16 bytes.
-template <int EB>
-__device__ __forceinline__ void stage_queries(const char* __restrict__ q_head /* [R][D] */, int R, int rows_padded, char* sm_q) {
+// All loads are issued before the first LDS write, on clamped addresses (a predicated load in a loop costs one
+// full memory latency per iteration).
+template <int EB, int ROWS>
+__device__ __forceinline__ void stage_queries(const char* __restrict__ q_head /* [R][D] */, int R, char* sm_q) {
     constexpr int kRowBytes = kHeadDim * EB, kPitch = kRowBytes + 16, kPieces = kRowBytes / 16;
-    for (int i = threadIdx.x; i < rows_padded * kPieces; i += kImpThreads) {
-        const int row = i / kPieces, piece = i % kPieces;
-        uint4 t = make_uint4(0, 0, 0, 0);
-        if (row < R) t = *reinterpret_cast<const uint4*>(q_head + (int64_t)row * kRowBytes + piece * 16);
-        *reinterpret_cast<uint4*>(sm_q + row * kPitch + piece * 16) = t;
+    constexpr int kIter = (ROWS * kPieces + kImpThreads - 1) / kImpThreads;
+    uint4 t[kIter];
+#pragma unroll
+    for (int it = 0; it < kIter; ++it) {
+        const int i = threadIdx.x + it * kImpThreads, row = i / kPieces, piece = i % kPieces;
+        t[it] = *reinterpret_cast<const uint4*>(q_head + (int64_t)min(row, R - 1) * kRowBytes + piece * 16);
+    }
+#pragma unroll
+    for (int it = 0; it < kIter; ++it) {
+        const int i = threadIdx.x + it * kImpThreads, row = i / kPieces, piece = i % kPieces;
+        if (i < ROWS * kPieces) *reinterpret_cast<uint4*>(sm_q + row * kPitch + piece * 16) = row < R ? t[it] : make_uint4(0, 0, 0, 0);
     }
 }
 
@@ -106,9 +113,9 @@ __device__ __forceinline__ void load_keys(Frag<EB> (&kf)[Imp<EB>::KT][4], const 
     }
 }
 
-// pass 1.  grid (ceil(T / Imp<EB>::kKeysPerBlock), Hkv); part [Hkv][chunks][RT*16][2] = (max in log2 units, sum).
+// pass 1.  grid (ceil(T / Imp<EB>::kKeysPerBlock), Hkv, L); part [L][Hkv][chunks][RT*16][2] = (max in log2 units, sum).
 template <int EB, int RT>
-__global__ __launch_bounds__(kImpThreads) void importance_stats_kernel(const char* __restrict__ q_layer, const char* __restrict__ K_layer,
+__global__ __launch_bounds__(kImpThreads) void importance_stats_kernel(const char* __restrict__ q_obs, const char* __restrict__ K_pool,
                                                                      int32_t T, int32_t N, int32_t G, float* __restrict__ part) {
     constexpr int kRowBytes = kHeadDim * EB, kPitch = kRowBytes + 16;
     constexpr int kRows = RT * 16;
@@ -119,22 +126,22 @@ __global__ __launch_bounds__(kImpThreads) void importance_stats_kernel(const cha
     __shared__ float sm_m[kImpWaves][kRows], sm_l[kImpWaves][kRows];
 
     const int h = blockIdx.y, chunk = blockIdx.x, nchunks = gridDim.x;
+    const int64_t lh = (int64_t)blockIdx.z * gridDim.y + h;              // (layer, KV head)
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, t16 = lane & 15, qd = lane >> 4;
     const int R = G * N, Tp = T - N;
-    const char* Kh = K_layer + (int64_t)h * T * kRowBytes;
+    const char* Kh = K_pool + lh * T * kRowBytes;
+    const char* q_layer = q_obs + (int64_t)blockIdx.z * gridDim.y * R * kRowBytes;
     const int32_t wave_key0 = chunk * Imp<EB>::kKeysPerBlock + Imp<EB>::kKeysPerWave * w;
     Frag<EB> kf[NB][KT][4];
     if (NB == 2) load_keys<EB>(kf[0], Kh, wave_key0, T - 1, t16, qd);
-    stage_queries<EB>(q_layer + (int64_t)h * R * kRowBytes, R, kRows, sm_q);
+    stage_queries<EB, kRows>(q_layer + (int64_t)h * R * kRowBytes, R, sm_q);
     const float scale = kLog2e * rsqrtf((float)kHeadDim);
 
+    // Running statistics are kept per LANE (a lane sees the keys 4qd..4qd+3 of every tile of its row), in raw logit
+    // units for the max: the four lanes of a row meet only once, after the last sweep.
     float m_run[RT], l_run[RT];
-    int32_t limit[RT];                                                // last position visible to the lane's row of tile rt
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-        m_run[rt] = -INFINITY; l_run[rt] = 0.f;
-        limit[rt] = min(Tp + (16 * rt + t16) % N, T - 1);
-    }
+    for (int rt = 0; rt < RT; ++rt) { m_run[rt] = -INFINITY; l_run[rt] = 0.f; }
     __syncthreads();
 
 #pragma unroll
@@ -150,40 +157,50 @@ __global__ __launch_bounds__(kImpThreads) void importance_stats_kernel(const cha
             Frag<EB> qf[4];
 #pragma unroll
             for (int s = 0; s < 4; ++s) qf[s].load(sm_q + (16 * rt + t16) * kPitch, 32 * s + 8 * qd);
-            float sv[KT][4], mt = -INFINITY;
+            float sv[KT][4];
 #pragma unroll
             for (int kt = 0; kt < KT; ++kt) {
                 f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int s = 0; s < 4; ++s) acc = frag_mma<EB>(kf[cur][kt][s], qf[s], acc);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    sv[kt][j] = acc[j] * scale;
-                    if (!open && key0 + 16 * kt + 4 * qd + j > limit[rt]) sv[kt][j] = -INFINITY;
-                    mt = fmaxf(mt, sv[kt][j]);
-                }
+                for (int j = 0; j < 4; ++j) sv[kt][j] = acc[j];
             }
-            mt = fmaxf(mt, __shfl_xor(mt, 16));
-            mt = fmaxf(mt, __shfl_xor(mt, 32));
-            const float m_new = fmaxf(m_run[rt], mt);
-            if (m_new > -INFINITY) {                                  // per-lane code only: divergence is harmless
+            if (!open) {                                              // the sweep touches the window or the end of the prompt
+                const int32_t limit = min(Tp + (16 * rt + t16) % N, T - 1);   // last position visible to this lane's row
+#pragma unroll
+                for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (key0 + 16 * kt + 4 * qd + j > limit) sv[kt][j] = -INFINITY;
+            }
+            float mt = m_run[rt];
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) mt = fmaxf(mt, sv[kt][j]);
+            if (open || mt > -INFINITY) {                             // per-lane code only: divergence is harmless
+                const float ms = mt * scale;
                 float sum = 0.f;
 #pragma unroll
                 for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) sum += exp2_neg(sv[kt][j] - m_new);   // exp2(-inf) = 0
-                l_run[rt] = l_run[rt] * exp2_neg(m_run[rt] - m_new) + sum;
-                m_run[rt] = m_new;
+                    for (int j = 0; j < 4; ++j) sum += exp2_neg(sv[kt][j] * scale - ms);     // exp2(-inf) = 0
+                l_run[rt] = l_run[rt] * exp2_neg(m_run[rt] * scale - ms) + sum;
+                m_run[rt] = mt;
             }
         }
     }
-    // rows live in lanes t16 (all qd hold the same max; sums are per-lane partials)
+    // the four lanes of a row (qd = 0..3), then the block's waves
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
-        float l = l_run[rt];
+        float m = m_run[rt];
+        m = fmaxf(m, __shfl_xor(m, 16));
+        m = fmaxf(m, __shfl_xor(m, 32));
+        float l = m_run[rt] > -INFINITY ? l_run[rt] * exp2_neg((m_run[rt] - m) * scale) : 0.f;
         l += __shfl_xor(l, 16);
         l += __shfl_xor(l, 32);
-        if (qd == 0) { sm_m[w][16 * rt + t16] = m_run[rt]; sm_l[w][16 * rt + t16] = l; }
+        if (qd == 0) { sm_m[w][16 * rt + t16] = m * scale; sm_l[w][16 * rt + t16] = l; }
     }
     __syncthreads();
     for (int row = tid; row < kRows; row += kImpThreads) {
@@ -194,14 +211,14 @@ __global__ __launch_bounds__(kImpThreads) void importance_stats_kernel(const cha
 #pragma unroll
         for (int ww = 0; ww < kImpWaves; ++ww)
             if (sm_m[ww][row] > -INFINITY) l += sm_l[ww][row] * exp2_neg(sm_m[ww][row] - m);
-        float* dst = part + (((int64_t)h * nchunks + chunk) * kRows + row) * 2;
+        float* dst = part + ((lh * nchunks + chunk) * kRows + row) * 2;
         dst[0] = m;
         dst[1] = l;
     }
 }
 
-// Combines the per-chunk partials of one layer: rowstat [Hkv][rows][2] = (max, 1 / sum).  One wave per row, the
-// chunks spread over its lanes.  grid (ceil(Hkv * rows / 4)).
+// Combines the per-chunk partials: rowstat [L * Hkv][rows][2] = (max, 1 / sum).  One wave per row, the chunks
+// spread over its lanes.  grid (ceil(L * Hkv * rows / 4)); `Hkv` below counts (layer, head) pairs.
 __global__ __launch_bounds__(kImpThreads) void importance_combine_kernel(const float* __restrict__ part, int32_t nchunks, int32_t rows,
                                                                        int32_t Hkv, float* __restrict__ rowstat) {
     const int lane = threadIdx.x & 63;
@@ -230,9 +247,9 @@ __global__ __launch_bounds__(kImpThreads) void importance_combine_kernel(const f
     }
 }
 
-// pass 2.  grid (ceil(Tp / Imp<EB>::kKeysPerBlock), Hkv); alpha_h [Hkv][Tp].
+// pass 2.  grid (ceil(Tp / Imp<EB>::kKeysPerBlock), Hkv, L); alpha_h [L][Hkv][Tp].
 template <int EB, int RT>
-__global__ __launch_bounds__(kImpThreads) void importance_colsum_kernel(const char* __restrict__ q_layer, const char* __restrict__ K_layer,
+__global__ __launch_bounds__(kImpThreads) void importance_colsum_kernel(const char* __restrict__ q_obs, const char* __restrict__ K_pool,
                                                                       int32_t T, int32_t N, int32_t G,
                                                                       const float* __restrict__ rowstat, float* __restrict__ alpha_h) {
     constexpr int kRowBytes = kHeadDim * EB, kPitch = kRowBytes + 16;
@@ -244,15 +261,17 @@ __global__ __launch_bounds__(kImpThreads) void importance_colsum_kernel(const ch
     __shared__ float2 sm_stat[kRows];
 
     const int h = blockIdx.y;
+    const int64_t lh = (int64_t)blockIdx.z * gridDim.y + h;              // (layer, KV head)
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, t16 = lane & 15, qd = lane >> 4;
     const int R = G * N, Tp = T - N;
-    const char* Kh = K_layer + (int64_t)h * T * kRowBytes;
+    const char* Kh = K_pool + lh * T * kRowBytes;
+    const char* q_layer = q_obs + (int64_t)blockIdx.z * gridDim.y * R * kRowBytes;
     const int32_t wave_key0 = blockIdx.x * Imp<EB>::kKeysPerBlock + Imp<EB>::kKeysPerWave * w;
     Frag<EB> kf[NB][KT][4];
     if (NB == 2) load_keys<EB>(kf[0], Kh, wave_key0, Tp - 1, t16, qd);
-    stage_queries<EB>(q_layer + (int64_t)h * R * kRowBytes, R, kRows, sm_q);
+    stage_queries<EB, kRows>(q_layer + (int64_t)h * R * kRowBytes, R, sm_q);
     for (int row = tid; row < kRows; row += kImpThreads)       // rows >= R: 1 / sum = 0, so they add nothing
-        sm_stat[row] = row < R ? *reinterpret_cast<const float2*>(rowstat + ((int64_t)h * kRows + row) * 2) : make_float2(0.f, 0.f);
+        sm_stat[row] = row < R ? *reinterpret_cast<const float2*>(rowstat + (lh * kRows + row) * 2) : make_float2(0.f, 0.f);
     const float scale = kLog2e * rsqrtf((float)kHeadDim);
     __syncthreads();
 
@@ -294,25 +313,26 @@ __global__ __launch_bounds__(kImpThreads) void importance_colsum_kernel(const ch
                 v = dpp_add<0x124>(v);
                 v = dpp_add<0x128>(v);
                 const int32_t key = key0 + 16 * kt + 4 * qd + j;
-                if (t16 == 0 && key < Tp) alpha_h[(int64_t)h * Tp + key] = v;
+                if (t16 == 0 && key < Tp) alpha_h[lh * Tp + key] = v;
             }
     }
 }
 
-// alpha[i] = sum over the KV heads, in ascending order, of alpha_h[h][i].
+// alpha[l][i] = sum over the KV heads, in ascending order, of alpha_h[l][h][i].  grid (ceil(Tp / 256), L).
 __global__ __launch_bounds__(kImpThreads) void importance_sum_heads_kernel(const float* __restrict__ alpha_h, int32_t Tp, int32_t Hkv,
                                                                          float* __restrict__ alpha) {
     const int32_t i = blockIdx.x * kImpThreads + threadIdx.x;
+    const int64_t l = blockIdx.y;
     if (i >= Tp) return;
     float v = 0.f;
-    for (int h = 0; h < Hkv; ++h) v += alpha_h[(int64_t)h * Tp + i];
-    alpha[i] = v;
+    for (int h = 0; h < Hkv; ++h) v += alpha_h[(l * Hkv + h) * Tp + i];
+    alpha[l * Tp + i] = v;
 }
 
 template <int EB, int RT>
-static hipError_t launch_importance_rt(Ctx* c, const char* q_layer, const char* K_layer, int32_t T, int32_t N, float* alpha,
-                                       float* part, float* rowstat, float* alpha_h) {
-    const int Hkv = c->d.n_kv_heads, G = c->G, rows = RT * 16;
+static hipError_t launch_importance_rt(Ctx* c, const char* q_obs, const char* K_pool, int32_t T, int32_t N, float* alpha, float* part,
+                                       float* rowstat, float* alpha_h) {
+    const int Hkv = c->d.n_kv_heads, L = c->d.n_layers, G = c->G, rows = RT * 16;
     const int nchunks = (T + Imp<EB>::kKeysPerBlock - 1) / Imp<EB>::kKeysPerBlock;
     const size_t lds = (size_t)rows * (kHeadDim * EB + 16);
     static bool raised = false;                                        // dynamic LDS above 64 KB needs the opt-in once
@@ -326,25 +346,25 @@ static hipError_t launch_importance_rt(Ctx* c, const char* q_layer, const char* 
         raised = true;
     }
     const int Tp = T - N;
-    hipLaunchKernelGGL((importance_stats_kernel<EB, RT>), dim3(nchunks, Hkv), dim3(kImpThreads), lds, c->stream, q_layer, K_layer, T, N,
-                       G, part);
-    hipLaunchKernelGGL(importance_combine_kernel, dim3((Hkv * rows + kImpWaves - 1) / kImpWaves), dim3(kImpThreads), 0, c->stream, part,
-                       nchunks, rows, Hkv, rowstat);
-    hipLaunchKernelGGL((importance_colsum_kernel<EB, RT>), dim3((Tp + Imp<EB>::kKeysPerBlock - 1) / Imp<EB>::kKeysPerBlock, Hkv),
-                       dim3(kImpThreads), lds, c->stream, q_layer, K_layer, T, N, G, rowstat, alpha_h);
-    hipLaunchKernelGGL(importance_sum_heads_kernel, dim3((Tp + kImpThreads - 1) / kImpThreads), dim3(kImpThreads), 0, c->stream, alpha_h,
-                       Tp, Hkv, alpha);
+    hipLaunchKernelGGL((importance_stats_kernel<EB, RT>), dim3(nchunks, Hkv, L), dim3(kImpThreads), lds, c->stream, q_obs, K_pool, T, N, G,
+                       part);
+    hipLaunchKernelGGL(importance_combine_kernel, dim3((L * Hkv * rows + kImpWaves - 1) / kImpWaves), dim3(kImpThreads), 0, c->stream,
+                       part, nchunks, rows, L * Hkv, rowstat);
+    hipLaunchKernelGGL((importance_colsum_kernel<EB, RT>), dim3((Tp + Imp<EB>::kKeysPerBlock - 1) / Imp<EB>::kKeysPerBlock, Hkv, L),
+                       dim3(kImpThreads), lds, c->stream, q_obs, K_pool, T, N, G, rowstat, alpha_h);
+    hipLaunchKernelGGL(importance_sum_heads_kernel, dim3((Tp + kImpThreads - 1) / kImpThreads, L), dim3(kImpThreads), 0, c->stream,
+                       alpha_h, Tp, Hkv, alpha);
     return hipGetLastError();
 }
 
 template <int EB>
-static hipError_t launch_importance_eb(Ctx* c, const char* q_layer, const char* K_layer, int32_t T, int32_t N, float* alpha,
-                                       float* part, float* rowstat, float* alpha_h) {
+static hipError_t launch_importance_eb(Ctx* c, const char* q_obs, const char* K_pool, int32_t T, int32_t N, float* alpha, float* part,
+                                       float* rowstat, float* alpha_h) {
     const int R = c->G * N;
-    if (R <= 32) return launch_importance_rt<EB, 2>(c, q_layer, K_layer, T, N, alpha, part, rowstat, alpha_h);
-    if (R <= 64) return launch_importance_rt<EB, 4>(c, q_layer, K_layer, T, N, alpha, part, rowstat, alpha_h);
-    if (R <= 128) return launch_importance_rt<EB, 8>(c, q_layer, K_layer, T, N, alpha, part, rowstat, alpha_h);
-    if (R <= 256) return launch_importance_rt<EB, 16>(c, q_layer, K_layer, T, N, alpha, part, rowstat, alpha_h);
+    if (R <= 32) return launch_importance_rt<EB, 2>(c, q_obs, K_pool, T, N, alpha, part, rowstat, alpha_h);
+    if (R <= 64) return launch_importance_rt<EB, 4>(c, q_obs, K_pool, T, N, alpha, part, rowstat, alpha_h);
+    if (R <= 128) return launch_importance_rt<EB, 8>(c, q_obs, K_pool, T, N, alpha, part, rowstat, alpha_h);
+    if (R <= 256) return launch_importance_rt<EB, 16>(c, q_obs, K_pool, T, N, alpha, part, rowstat, alpha_h);
     return hipErrorInvalidValue;
 }
 
@@ -355,27 +375,21 @@ static int64_t importance_chunks(const Ctx* c, int32_t T) {
     return (T + per - 1) / per;
 }
 
-// work = part [Hkv][chunks][rows][2] | rowstat [Hkv][rows][2] | alpha_h [Hkv][Tp], floats
+// work = part [L][Hkv][chunks][rows][2] | rowstat [L][Hkv][rows][2] | alpha_h [L][Hkv][Tp], floats
 int64_t importance_work_bytes(const Ctx* c, int32_t T, int32_t N) {
-    const int64_t rows = importance_rows(c->G * N), Hkv = c->d.n_kv_heads;
-    return (Hkv * importance_chunks(c, T) * rows * 2 + Hkv * rows * 2 + Hkv * (int64_t)(T - N)) * (int64_t)sizeof(float);
+    const int64_t rows = importance_rows(c->G * N), LH = (int64_t)c->d.n_layers * c->d.n_kv_heads;
+    return (LH * importance_chunks(c, T) * rows * 2 + LH * rows * 2 + LH * (int64_t)(T - N)) * (int64_t)sizeof(float);
 }
 
+// Four launches cover all layers: statistics, their combination, column sums per head, the ordered sum over heads.
 hipError_t launch_importance(Ctx* c, const void* q_obs, const void* K_pool, int32_t T, int32_t N, float* alpha, void* work) {
-    const int Hkv = c->d.n_kv_heads, Hq = c->d.n_q_heads, eb = c->d.kv_dtype == SKV_BF16 ? 2 : 4;
-    const int64_t rows = importance_rows(c->G * N);
+    const int64_t rows = importance_rows(c->G * N), LH = (int64_t)c->d.n_layers * c->d.n_kv_heads;
     float* part = (float*)work;
-    float* rowstat = part + Hkv * importance_chunks(c, T) * rows * 2;
-    float* alpha_h = rowstat + Hkv * rows * 2;
-    const int32_t Tp = T - N;
-    for (int l = 0; l < c->d.n_layers; ++l) {
-        const char* ql = (const char*)q_obs + (int64_t)l * Hq * N * kHeadDim * eb;
-        const char* Kl = (const char*)K_pool + (int64_t)l * Hkv * T * kHeadDim * eb;
-        const hipError_t e = eb == 2 ? launch_importance_eb<2>(c, ql, Kl, T, N, alpha + (int64_t)l * Tp, part, rowstat, alpha_h)
-                                     : launch_importance_eb<4>(c, ql, Kl, T, N, alpha + (int64_t)l * Tp, part, rowstat, alpha_h);
-        if (e != hipSuccess) return e;
-    }
-    return hipSuccess;
+    float* rowstat = part + LH * importance_chunks(c, T) * rows * 2;
+    float* alpha_h = rowstat + LH * rows * 2;
+    return c->d.kv_dtype == SKV_BF16
+               ? launch_importance_eb<2>(c, (const char*)q_obs, (const char*)K_pool, T, N, alpha, part, rowstat, alpha_h)
+               : launch_importance_eb<4>(c, (const char*)q_obs, (const char*)K_pool, T, N, alpha, part, rowstat, alpha_h);
 }
 
 // ------------------------------------------------------------------------------------------------
