@@ -212,6 +212,17 @@ int skv_decode_step(skv_ctx* ctx, int32_t layer, int32_t B, const void* q_score,
                     const int32_t* cu_tok, const int32_t* cu_sent, const int32_t* sent_off, const int32_t* sent_len,
                     const int32_t* budget, float* out, float* lse, int32_t* tok_idx_out, int32_t* n_tok_out);
 
+/* Eq. 3 over the union of two disjoint token sets from the two partial results (each side's `out` and `lse` as
+ * written by skv_attend or skv_decode_step): out = (Z_a out_a + Z_b out_b) / (Z_a + Z_b), lse = log(Z_a + Z_b),
+ * Z = exp(lse).  The paper's Eq. 3 sees the retrieved prompt tokens only; a caller that also keeps a contiguous
+ * window of recent tokens resident attends it with skv_attend (K_sel/V_sel = the window's rows) and merges here.
+ * A side with lse = -inf is empty and its `out` is ignored; both empty gives out = 0, lse = -inf.
+ * n_heads = number of query heads covered (e.g. B * Hq);  out_a, out_b, out dev [n_heads][D] fp32 (out may alias
+ * either input);  lse_a, lse_b dev [n_heads];  lse dev [n_heads] or NULL.  Asynchronous.
+ * Errors: SKV_EINVAL (null / misaligned pointers, n_heads < 1), SKV_ECAPACITY (n_heads > max_batch * Hq). */
+int skv_merge_lse(skv_ctx* ctx, int32_t n_heads, const float* out_a, const float* lse_a, const float* out_b, const float* lse_b,
+                  float* out, float* lse);
+
 #ifdef __cplusplus
 }
 #endif

@@ -85,6 +85,8 @@ class Oracle:
         L.skvo_token_importance.restype = None
         L.skvo_retain.argtypes = [_f32p, _i, _i, _i32p, _i, _i32p, _i32p, _i32p, _i32p]
         L.skvo_retain.restype = None
+        L.skvo_merge_lse.argtypes = [_f32p, _f32p, _f32p, _f32p, _i, _i, _f32p, _f32p]
+        L.skvo_merge_lse.restype = None
         L.skvo_real_bytes.restype = _ci
         assert L.skvo_real_bytes() == (4 if real == "f32" else 8)
 
@@ -202,6 +204,16 @@ class Oracle:
         lse = np.zeros(Hq, dtype=np.float32)
         self.lib.skvo_attend(q.ctypes.data_as(_vp), K_sel.ctypes.data_as(_vp), V_sel.ctypes.data_as(_vp),
                              _dtype_of(q), Hq, H, D, _ptr(n_tok, _i32p), stride, _ptr(out, _f32p), _ptr(lse, _f32p))
+        return out, lse
+
+    def merge_lse(self, out_a: np.ndarray, lse_a: np.ndarray, out_b: np.ndarray, lse_b: np.ndarray):
+        """Two partial attention results over disjoint token sets -> (out, lse) over their union."""
+        out_a, out_b = np.ascontiguousarray(out_a, np.float32), np.ascontiguousarray(out_b, np.float32)
+        lse_a, lse_b = np.ascontiguousarray(lse_a, np.float32), np.ascontiguousarray(lse_b, np.float32)
+        n, D = out_a.shape
+        out, lse = np.zeros((n, D), np.float32), np.zeros(n, np.float32)
+        self.lib.skvo_merge_lse(_ptr(out_a, _f32p), _ptr(lse_a, _f32p), _ptr(out_b, _f32p), _ptr(lse_b, _f32p), n, D,
+                                _ptr(out, _f32p), _ptr(lse, _f32p))
         return out, lse
 
     def decode_step(self, q_score, q_attn, K_layer, V_layer, semvec_layer, sent_off, sent_len, budget):

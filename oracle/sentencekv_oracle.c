@@ -25,6 +25,7 @@
  *                 budget tau is reached                        (Sec. 4.2; App. "Effect of Sentence Length")
  *   skvo_gather   K_tau, V_tau = rows of the selected tokens    (Sec. 4.2 "loaded ... back to the GPU"; Alg. 1)
  *   skvo_attend   O = softmax(q K_tau^T / sqrt(d)) V_tau        (Eq. 3)
+ *   skvo_merge_lse  Eq. 3 over the union of two disjoint token sets from the two partial results
  *
  * Readings taken where the paper is silent (each is a documented constant of this oracle):
  *   - the terminator set is input data (a bitmap over the vocabulary);
@@ -361,6 +362,30 @@ void skvo_attend(const void* q, const void* K_sel, const void* V_sel, int dtype,
     }
     free(logit);
     free(acc);
+}
+
+/* Eq. 3 over the union of two disjoint token sets A and B, given each side's output and log-sum-exp:
+ * softmax over A u B weights side A by Z_A / (Z_A + Z_B) with Z = exp(lse).  A side with lse = -inf is empty.
+ * out_a, out_b, out are [n_heads][D]; lse_a, lse_b, lse are [n_heads]. */
+void skvo_merge_lse(const float* out_a, const float* lse_a, const float* out_b, const float* lse_b, int32_t n_heads,
+                    int32_t D, float* out, float* lse) {
+    for (int32_t j = 0; j < n_heads; ++j) {
+        real la = (real)lse_a[j], lb = (real)lse_b[j];
+        real m = la > lb ? la : lb;
+        if (!(m > -INFINITY)) {                       /* both sides empty */
+            for (int32_t d = 0; d < D; ++d) out[(int64_t)j * D + d] = 0.0f;
+            lse[j] = -INFINITY;
+            continue;
+        }
+        real za = (real)exp((double)(la - m)), zb = (real)exp((double)(lb - m));   /* exp(-inf) = 0 */
+        real z = za + zb;
+        for (int32_t d = 0; d < D; ++d) {
+            real a = za > 0 ? za * (real)out_a[(int64_t)j * D + d] : 0;
+            real b = zb > 0 ? zb * (real)out_b[(int64_t)j * D + d] : 0;
+            out[(int64_t)j * D + d] = (float)((a + b) / z);
+        }
+        lse[j] = (float)(m + (real)log((double)z));
+    }
 }
 
 /* size of REAL in this build (4 = float, 8 = double), so a loader can tell the two libraries apart */

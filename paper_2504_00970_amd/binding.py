@@ -51,6 +51,7 @@ _SIGNATURES = {
     "skv_select": (_int, [_vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp]),
     "skv_gather": (_int, [_vp, _i32, _vp, _vp, _i32, _int, _vp, _vp, _i32, _vp, _vp]),
     "skv_attend": (_int, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp]),
+    "skv_merge_lse": (_int, [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
     "skv_decode_step": (_int, [_vp, _i32, _i32, _vp, _vp, _vp, _vp, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp,
                                _vp, _vp, _vp]),
 }
@@ -205,3 +206,7 @@ class Context:
         _check(_lib().skv_decode_step(self._h, layer, B, _p(q_score), _p(q_attn), _p(K_pool), _p(V_pool), T_total,
                                       _p(semvec), S_total, _p(cu_tok), _p(cu_sent), _p(sent_off), _p(sent_len),
                                       _p(budget), _p(out), _p(lse), _p(tok_idx_out), _p(n_tok_out)), "skv_decode_step")
+
+    def merge_lse(self, n_heads: int, out_a, lse_a, out_b, lse_b, out, lse=None) -> None:
+        _check(_lib().skv_merge_lse(self._h, n_heads, _p(out_a), _p(lse_a), _p(out_b), _p(lse_b), _p(out), _p(lse)),
+               "skv_merge_lse")

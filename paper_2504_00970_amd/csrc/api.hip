@@ -328,4 +328,16 @@ int skv_decode_step(skv_ctx* ctx, int32_t layer, int32_t B, const void* q_score,
     return hip_status(e);
 }
 
+int skv_merge_lse(skv_ctx* ctx, int32_t n_heads, const float* out_a, const float* lse_a, const float* out_b, const float* lse_b,
+                  float* out, float* lse) {
+    if (!ctx) return SKV_EINVAL;
+    if (n_heads < 1) return SKV_EINVAL;
+    if (bad_ptr(out_a) || bad_ptr(lse_a) || bad_ptr(out_b) || bad_ptr(lse_b) || bad_ptr(out)) return SKV_EINVAL;
+    if (lse && !aligned16(lse)) return SKV_EINVAL;
+    if (n_heads > ctx->c.d.max_batch * ctx->c.d.n_q_heads) return SKV_ECAPACITY;
+    const int rc = check_ctx(ctx);
+    if (rc != SKV_OK) return rc;
+    return hip_status(skv::launch_merge_lse(&ctx->c, out_a, lse_a, out_b, lse_b, n_heads, out, lse));
+}
+
 }  // extern "C"

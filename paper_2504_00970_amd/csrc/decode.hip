@@ -1282,4 +1282,38 @@ hipError_t launch_select_attend(Ctx* c, const void* q, const void* K_layer, cons
                                      : launch_attend_g<4, kFused, kAttChunk>(c, a, c->max_splits);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Merge of two partial attention results over disjoint token sets (Eq. 3 over their union): the retrieved tokens and,
+// for instance, a contiguous window of recent tokens attended with skv_attend.  One thread per output pair.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void merge_lse_kernel(const float* __restrict__ out_a, const float* __restrict__ lse_a,
+                                                        const float* __restrict__ out_b, const float* __restrict__ lse_b,
+                                                        int32_t n_heads, float* __restrict__ out, float* __restrict__ lse) {
+    const int32_t i = blockIdx.x * 256 + threadIdx.x;                  // pair index: head * (D / 2) + pair
+    if (i >= n_heads * (kHeadDim / 2)) return;
+    const int32_t j = i / (kHeadDim / 2);
+    const float la = lse_a[j], lb = lse_b[j];
+    const float m = fmaxf(la, lb);
+    float2 r = make_float2(0.f, 0.f);
+    float l = -INFINITY;
+    if (m > -INFINITY) {
+        const float za = expf(la - m), zb = expf(lb - m);              // an empty side has lse = -inf: weight 0
+        const float inv = 1.f / (za + zb);
+        const float2 a = reinterpret_cast<const float2*>(out_a)[i], b = reinterpret_cast<const float2*>(out_b)[i];
+        r.x = ((za > 0.f ? za * a.x : 0.f) + (zb > 0.f ? zb * b.x : 0.f)) * inv;
+        r.y = ((za > 0.f ? za * a.y : 0.f) + (zb > 0.f ? zb * b.y : 0.f)) * inv;
+        l = m + logf(za + zb);
+    }
+    reinterpret_cast<float2*>(out)[i] = r;
+    if (lse && (i % (kHeadDim / 2)) == 0) lse[j] = l;
+}
+
+hipError_t launch_merge_lse(Ctx* c, const float* out_a, const float* lse_a, const float* out_b, const float* lse_b,
+                            int32_t n_heads, float* out, float* lse) {
+    const int n = n_heads * (kHeadDim / 2);
+    hipLaunchKernelGGL(merge_lse_kernel, dim3((n + 255) / 256), dim3(256), 0, c->stream, out_a, lse_a, out_b, lse_b, n_heads, out,
+                       lse);
+    return hipGetLastError();
+}
+
 }  // namespace skv

@@ -95,6 +95,9 @@ hipError_t launch_select_attend(Ctx* c, const void* q, const void* K_layer, cons
                                 const int32_t* sent_off, const int32_t* sent_len, const SeqView& v, float* out,
                                 float* lse, int32_t* tok_idx_out, int32_t* n_tok_out);
 
+hipError_t launch_merge_lse(Ctx* c, const float* out_a, const float* lse_a, const float* out_b, const float* lse_b,
+                            int32_t n_heads, float* out, float* lse);
+
 // A K/V row is D * EB bytes = LPR lanes of 16 bytes, so one wave-wide 128-bit load covers RPW
 // consecutive rows; each lane holds EPL elements of its row.
 template <int EB> struct Row;

@@ -443,3 +443,62 @@ def test_full_size_cfg4_ragged_batch(U, oracle32):
     """cfg4 at its real shapes (64 q heads / 8 KV heads, 16 sequences of 8192..65536 tokens, budget 2048) on two
     resident layers: every sequence's selection and attention output against the oracle."""
     _fused_case(U, oracle32, gen.CFG4.scaled(n_layers=2), seed=0, layers=[0, 1])
+
+
+# ----------------------------------------------------------------------------- local window merge, equal chunks
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_decode_plus_local_window_merge(U, oracle32, dtype):
+    """Retrieved prompt tokens (fused decode step) merged by lse with a contiguous window of recent tokens attended by
+    skv_attend: equals the oracle's attention over the union of both token sets; empty sides handled."""
+    wl = gen.CFG1.scaled(n_layers=1, n_tokens=5000, dtype=dtype)
+    inp = gen.decode_inputs(wl, seed=21, device=U.DEV)
+    S, T, H, Hq, D, budget, W = len(inp.lengths), wl.n_tokens, wl.n_kv_heads, wl.n_q_heads, 128, 512, 100
+    ctx = U.make_ctx(wl, T, S, budget)
+    sv = torch.zeros(1, H, S, D, dtype=torch.float32, device=U.DEV)
+    ctx.build_semvec(inp.K, U.i32(inp.sent_off), S, sv)
+    q = inp.q[0]
+    g = torch.Generator(device=U.DEV).manual_seed(5)
+    Kw = torch.randn(H, budget, D, generator=g, device=U.DEV).to(wl.torch_dtype)      # the window's rows (first W used)
+    Vw = torch.randn(H, budget, D, generator=g, device=U.DEV).to(wl.torch_dtype)
+    out_r, lse_r = torch.zeros(Hq, D, device=U.DEV), torch.zeros(Hq, device=U.DEV)
+    out_w, lse_w = torch.zeros(Hq, D, device=U.DEV), torch.zeros(Hq, device=U.DEV)
+    out, lse = torch.zeros(Hq, D, device=U.DEV), torch.zeros(Hq, device=U.DEV)
+    tok_idx, n_tok = U.empty_i32(H, budget, fill=-1), U.empty_i32(8, fill=-5)
+    for w_len, bud in ((W, budget), (0, budget), (W, 2)):                                # both, window empty, retrieval empty
+        _say("local window merge", dtype, "window", w_len, "budget", bud)
+        ctx.decode_step(0, 1, q, q, inp.K, inp.V, T, sv, S, U.i32([0, T]), U.i32([0, S]), U.i32(inp.sent_off),
+                        U.i32(inp.lengths), U.i32([bud]), out_r, lse_r, tok_idx, n_tok)
+        ctx.attend(q, Kw, Vw, U.i32([w_len] * 8), budget, out_w, lse_w)
+        ctx.merge_lse(Hq, out_r, lse_r, out_w, lse_w, out, lse)
+        torch.cuda.synchronize()
+        nt, ti = n_tok.cpu().numpy()[:H], tok_idx.cpu().numpy()
+        K, V = gen.to_numpy(inp.K[0]), gen.to_numpy(inp.V[0])
+        Ks = np.zeros((H, budget + W, D), dtype=K.dtype)
+        Vs = np.zeros_like(Ks)
+        for h in range(H):                                             # union: the GPU's retrieved rows, then the window
+            Ks[h, :nt[h]], Vs[h, :nt[h]] = K[h, ti[h, :nt[h]]], V[h, ti[h, :nt[h]]]
+            Ks[h, nt[h]:nt[h] + w_len], Vs[h, nt[h]:nt[h] + w_len] = U.np_of(Kw[h, :w_len]), U.np_of(Vw[h, :w_len])
+        ref, lref = oracle32.attend(U.np_of(q), Ks, Vs, (nt + w_len).astype(np.int32))
+        assert np.abs(out.cpu().numpy() - ref).max() <= ATT_TOL[dtype]
+        fin = np.isfinite(lref)
+        assert np.array_equal(np.isfinite(lse.cpu().numpy()), fin)
+        assert np.abs(lse.cpu().numpy()[fin] - lref[fin]).max() <= ATT_TOL[dtype]
+        # the merge itself against the oracle's merge of the GPU's partial results: fp32 arithmetic on both sides
+        m_ref, ml_ref = oracle32.merge_lse(out_r.cpu().numpy(), lse_r.cpu().numpy(), out_w.cpu().numpy(), lse_w.cpu().numpy())
+        assert np.abs(out.cpu().numpy() - m_ref).max() <= 1e-5
+    # both sides empty
+    ctx.decode_step(0, 1, q, q, inp.K, inp.V, T, sv, S, U.i32([0, T]), U.i32([0, S]), U.i32(inp.sent_off),
+                    U.i32(inp.lengths), U.i32([2]), out_r, lse_r, None, None)
+    ctx.attend(q, Kw, Vw, U.i32([0] * 8), budget, out_w, lse_w)
+    out.fill_(9.0)
+    ctx.merge_lse(Hq, out_r, lse_r, out_w, lse_w, out, lse)
+    torch.cuda.synchronize()
+    assert torch.all(out == 0) and torch.all(torch.isinf(lse) & (lse < 0))
+
+
+def test_equal_size_chunk_mode(U, oracle32):
+    """The paper's equal-size-chunk ablation is the same path with uniform bucket offsets (16-token chunks)."""
+    wl = gen.CFG1.scaled(n_layers=1, n_tokens=4096 + 7, len_dist=("fixed", 16))
+    _chain_case(U, oracle32, wl, seed=23, budget=512)
+    _fused_case(U, oracle32, wl.scaled(batch=1, t_range=(4103, 4103), budgets=(512,)), seed=23, layers=[0])

@@ -261,3 +261,37 @@ def test_pool_bytes_per_token_reproduce_the_papers_kv_cache_size():
     per_token = wl.n_layers * wl.n_kv_heads * wl.head_dim * 2 * wl.elt_bytes
     assert abs(per_token * kv["context_tokens_256k"] / 1e9 - kv["kv_cache_gb_256k"]) < 0.01
     assert math.floor(kv["r"] * kv["tau"]) == kv["retained"]
+
+
+# ----------------------------------------------------------------------------- merge of partial results
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_merge_lse_equals_attention_over_the_union(oracle32, oracle64, dtype):
+    """Eq. 3 over A u B from the two partial results == Eq. 3 computed on the concatenated rows."""
+    Hq, H, D, nA, nB = 8, 2, 128, 37, 90
+    q = _randn((Hq, D), 40, dtype)
+    K, V = _randn((H, nA + nB, D), 41, dtype), _randn((H, nA + nB, D), 42, dtype)
+    qn, Kn, Vn = gen.to_numpy(q), gen.to_numpy(K), gen.to_numpy(V)
+    for o, tol in ((oracle64, 2e-6), (oracle32, 2e-5)):
+        oa, la = o.attend(qn, np.ascontiguousarray(Kn[:, :nA]), np.ascontiguousarray(Vn[:, :nA]), np.full(H, nA, np.int32))
+        ob, lb = o.attend(qn, np.ascontiguousarray(Kn[:, nA:]), np.ascontiguousarray(Vn[:, nA:]), np.full(H, nB, np.int32))
+        want, lw = o.attend(qn, Kn, Vn, np.full(H, nA + nB, np.int32))
+        got, lg = o.merge_lse(oa, la, ob, lb)
+        assert np.abs(got - want).max() <= tol and np.abs(lg - lw).max() <= tol * 10
+    # against scipy on the raw logits
+    from scipy.special import logsumexp
+    logits = np.einsum("jd,jtd->jt", q.double().numpy(), K.double().numpy()[np.repeat(np.arange(H), Hq // H)]) / math.sqrt(D)
+    assert np.abs(lg - logsumexp(logits, axis=1)).max() <= 1e-4
+
+
+def test_merge_lse_empty_sides(oracle32):
+    rng = np.random.default_rng(3)
+    oa, ob = rng.standard_normal((4, 128)).astype(np.float32), rng.standard_normal((4, 128)).astype(np.float32)
+    la = np.array([0.5, -np.inf, -np.inf, 3.0], np.float32)
+    lb = np.array([-np.inf, 1.5, -np.inf, 3.0], np.float32)
+    oa[1] = np.nan                                                # an empty side's output must not leak, whatever it holds
+    out, lse = oracle32.merge_lse(oa, la, ob, lb)
+    assert np.array_equal(out[0], oa[0]) and lse[0] == np.float32(0.5)
+    assert np.array_equal(out[1], ob[1]) and lse[1] == np.float32(1.5)
+    assert np.all(out[2] == 0) and lse[2] == -np.inf
+    assert np.allclose(out[3], 0.5 * (oa[3] + ob[3]), atol=1e-6) and abs(lse[3] - (3.0 + math.log(2.0))) < 1e-6
