@@ -71,6 +71,10 @@ class Oracle:
         L.skvo_segment.restype = _ci
         L.skvo_semvec.argtypes = [_vp, _ci, _i, _i, _i, _i, _i32p, _i, _f32p]
         L.skvo_semvec.restype = None
+        L.skvo_semvec_to.argtypes = [_vp, _ci, _i, _i, _i, _i, _i32p, _i, _ci, _vp]
+        L.skvo_semvec_to.restype = None
+        L.skvo_score_from.argtypes = [_vp, _ci, _i, _i, _i, _vp, _ci, _i, _f32p]
+        L.skvo_score_from.restype = None
         L.skvo_score.argtypes = [_vp, _ci, _i, _i, _i, _f32p, _i, _f32p]
         L.skvo_score.restype = None
         L.skvo_select.argtypes = [_f32p, _i32p, _i32p, _i, _i, _i, _i32p, _i, _i32p, _i32p, _i, _i32p]
@@ -108,15 +112,15 @@ class Oracle:
             raise OverflowError(f"{S} sentences exceed capacity {cap}")
         return seg_id, off[: S + 1].copy(), ln[:S].copy(), S
 
-    def semvec(self, K: np.ndarray, sent_off: np.ndarray) -> np.ndarray:
-        """K [L][Hkv][T][D] (float32 or bf16 bits) -> semvec float32 [L][Hkv][S][D]."""
+    def semvec(self, K: np.ndarray, sent_off: np.ndarray, sv_dtype: str = "f32") -> np.ndarray:
+        """K [L][Hkv][T][D] (float32 or bf16 bits) -> semvec [L][Hkv][S][D], float32 or (sv_dtype="bf16") bf16 bits."""
         K = np.ascontiguousarray(K)
         L, H, T, D = K.shape
         sent_off = np.ascontiguousarray(sent_off, dtype=np.int32)
         S = sent_off.shape[0] - 1
-        out = np.zeros((L, H, S, D), dtype=np.float32)
-        self.lib.skvo_semvec(K.ctypes.data_as(_vp), _dtype_of(K), L, H, T, D, _ptr(sent_off, _i32p), S,
-                             _ptr(out, _f32p))
+        out = np.zeros((L, H, S, D), dtype=np.float32 if sv_dtype == "f32" else np.uint16)
+        self.lib.skvo_semvec_to(K.ctypes.data_as(_vp), _dtype_of(K), L, H, T, D, _ptr(sent_off, _i32p), S, _dtype_of(out),
+                                out.ctypes.data_as(_vp))
         return out
 
     def token_importance(self, q_obs: np.ndarray, K: np.ndarray) -> np.ndarray:
@@ -150,14 +154,15 @@ class Oracle:
         return QueryCache(self, per, cap)
 
     def score(self, q: np.ndarray, semvec: np.ndarray) -> np.ndarray:
-        """q [Hq][D], semvec [Hkv][S][D] float32 -> score float32 [Hkv][S]."""
+        """q [Hq][D], semvec [Hkv][S][D] float32 or bf16 bits -> score float32 [Hkv][S]."""
         q = np.ascontiguousarray(q)
-        semvec = np.ascontiguousarray(semvec, dtype=np.float32)
+        semvec = np.ascontiguousarray(semvec)
         Hq, D = q.shape
         H, S, D2 = semvec.shape
         assert D == D2 and Hq % H == 0
         out = np.zeros((H, S), dtype=np.float32)
-        self.lib.skvo_score(q.ctypes.data_as(_vp), _dtype_of(q), Hq, H, D, _ptr(semvec, _f32p), S, _ptr(out, _f32p))
+        self.lib.skvo_score_from(q.ctypes.data_as(_vp), _dtype_of(q), Hq, H, D, semvec.ctypes.data_as(_vp), _dtype_of(semvec), S,
+                                 _ptr(out, _f32p))
         return out
 
     def select(self, score: np.ndarray, sent_off: np.ndarray, sent_len: np.ndarray, budget: int,

@@ -84,6 +84,20 @@ static int is_terminator(const uint32_t* bitmap, int32_t vocab, int32_t id) {
     return (int)((bitmap[id >> 5] >> (id & 31)) & 1u);
 }
 
+/* nearest bf16 to a finite float, ties to the even bit pattern */
+static uint16_t to_bf16(float f) {
+    uint32_t bits;
+    memcpy(&bits, &f, sizeof bits);
+    uint32_t below = bits & 0xffff0000u;             /* neighbour towards zero */
+    uint32_t above = below + 0x00010000u;            /* neighbour away from zero */
+    uint32_t rest = bits & 0x0000ffffu;              /* distance from `below`, in units of 2^-16 bf16 ulp */
+    uint32_t pick;
+    if (rest < 0x8000u) pick = below;
+    else if (rest > 0x8000u) pick = above;
+    else pick = ((below >> 16) & 1u) ? above : below;
+    return (uint16_t)(pick >> 16);
+}
+
 /* Sec. 4.1 / Alg. 1 prefill: sentence buckets.  seg_id[i] = number of terminators strictly before i.
  * sent_off has room for cap_sent + 1 entries, sent_len for cap_sent.  *n_sent receives S even if
  * S > cap_sent (then only the first cap_sent buckets are written and -1 is returned). */
@@ -107,9 +121,11 @@ int skvo_segment(const int32_t* tok, int32_t T, const uint32_t* bitmap, int32_t 
     return seg <= cap_sent ? 0 : -1;
 }
 
-/* Eq. 1: semvec[l][h][s][:] = (1/|S_s|) sum_{x in S_s} k_{x,h}, S_s = all tokens of sentence s. */
-void skvo_semvec(const void* K, int dtype, int32_t L, int32_t Hkv, int32_t T, int32_t D,
-                 const int32_t* sent_off, int32_t S, float* semvec) {
+/* Eq. 1: semvec[l][h][s][:] = (1/|S_s|) sum_{x in S_s} k_{x,h}, S_s = the tokens of bucket s in the pool.
+ * sv_dtype selects the storage of the table: float, or bf16 (the float mean rounded once, to nearest even: the
+ * mixed-precision sentence vectors the paper names as future work). */
+void skvo_semvec_to(const void* K, int dtype, int32_t L, int32_t Hkv, int32_t T, int32_t D,
+                    const int32_t* sent_off, int32_t S, int sv_dtype, void* semvec) {
     real* acc = (real*)malloc(sizeof(real) * (size_t)D);
     for (int32_t l = 0; l < L; ++l)
         for (int32_t h = 0; h < Hkv; ++h)
@@ -121,24 +137,19 @@ void skvo_semvec(const void* K, int dtype, int32_t L, int32_t Hkv, int32_t T, in
                     for (int32_t d = 0; d < D; ++d) acc[d] = acc[d] + load_elt(K, dtype, row + d);
                 }
                 real n = (real)(e - b);
-                float* out = semvec + (((int64_t)l * Hkv + h) * S + s) * D;
-                for (int32_t d = 0; d < D; ++d) out[d] = e > b ? (float)(acc[d] / n) : 0.0f;   /* no retained token: no bucket */
+                int64_t o = (((int64_t)l * Hkv + h) * S + s) * D;
+                for (int32_t d = 0; d < D; ++d) {
+                    float mean = e > b ? (float)(acc[d] / n) : 0.0f;   /* no retained token: no bucket */
+                    if (sv_dtype == SKVO_F32) ((float*)semvec)[o + d] = mean;
+                    else ((uint16_t*)semvec)[o + d] = to_bf16(mean);
+                }
             }
     free(acc);
 }
 
-/* nearest bf16 to a finite float, ties to the even bit pattern */
-static uint16_t to_bf16(float f) {
-    uint32_t bits;
-    memcpy(&bits, &f, sizeof bits);
-    uint32_t below = bits & 0xffff0000u;             /* neighbour towards zero */
-    uint32_t above = below + 0x00010000u;            /* neighbour away from zero */
-    uint32_t rest = bits & 0x0000ffffu;              /* distance from `below`, in units of 2^-16 bf16 ulp */
-    uint32_t pick;
-    if (rest < 0x8000u) pick = below;
-    else if (rest > 0x8000u) pick = above;
-    else pick = ((below >> 16) & 1u) ? above : below;
-    return (uint16_t)(pick >> 16);
+void skvo_semvec(const void* K, int dtype, int32_t L, int32_t Hkv, int32_t T, int32_t D,
+                 const int32_t* sent_off, int32_t S, float* semvec) {
+    skvo_semvec_to(K, dtype, L, Hkv, T, D, sent_off, S, SKVO_F32, semvec);
 }
 
 /* Sec. 4.2 "Sentence-level query aggregation", Eq. 2, Alg. 1 decoding phase.  Q_s is kept literally: a list of
@@ -168,21 +179,26 @@ int skvo_query_cache_step(const void* q_t, int dtype, int32_t per, int32_t tok, 
     return 0;
 }
 
-/* Sec. 4.2: score[h][s] = sum_{g<G} q[hG+g]^T semvec[h][s]  (one layer; semvec is [Hkv][S][D]). */
-void skvo_score(const void* q, int dtype, int32_t Hq, int32_t Hkv, int32_t D,
-                const float* semvec, int32_t S, float* score) {
+/* Sec. 4.2: score[h][s] = sum_{g<G} q[hG+g]^T semvec[h][s]  (one layer; semvec is [Hkv][S][D], float or bf16). */
+void skvo_score_from(const void* q, int dtype, int32_t Hq, int32_t Hkv, int32_t D,
+                     const void* semvec, int sv_dtype, int32_t S, float* score) {
     int32_t G = Hq / Hkv;
     for (int32_t h = 0; h < Hkv; ++h)
         for (int32_t s = 0; s < S; ++s) {
-            const float* kbar = semvec + ((int64_t)h * S + s) * D;
+            int64_t kbar = ((int64_t)h * S + s) * D;
             real acc = 0;
             for (int32_t g = 0; g < G; ++g)
                 for (int32_t d = 0; d < D; ++d) {
-                    real prod = load_elt(q, dtype, (int64_t)(h * G + g) * D + d) * (real)kbar[d];
+                    real prod = load_elt(q, dtype, (int64_t)(h * G + g) * D + d) * load_elt(semvec, sv_dtype, kbar + d);
                     acc = acc + prod;
                 }
             score[(int64_t)h * S + s] = (float)acc;
         }
+}
+
+void skvo_score(const void* q, int dtype, int32_t Hq, int32_t Hkv, int32_t D,
+                const float* semvec, int32_t S, float* score) {
+    skvo_score_from(q, dtype, Hq, Hkv, D, semvec, SKVO_F32, S, score);
 }
 
 /* ranking order of the buckets: higher score first, NaN last, equal scores by lower id */

@@ -145,3 +145,31 @@ def test_semvec_tracks_sentence_centres_of_the_synthetic_keys(oracle32):
     sv = oracle32.semvec(K.unsqueeze(0).numpy(), gen.offsets_of(lens))[0]
     bound = 5.0 * 0.5 / np.sqrt(lens.astype(np.float64))
     assert np.all(np.abs(sv - centres).max(axis=2) <= bound[None, :])
+
+
+# ----------------------------------------------------------------------------- bf16 mean key vectors
+
+def test_bf16_semvec_is_the_float_mean_rounded_once(oracle32):
+    """Mixed-precision sentence vectors: the stored bf16 value is torch's float32 -> bfloat16 conversion of the oracle's
+    own float mean; scores from the bf16 table equal a float64 dot product with the widened values."""
+    import torch
+    lens = np.array([3, 1, 40, 7, 25, 12, 2], dtype=np.int32)
+    off = gen.offsets_of(lens)
+    g = torch.Generator().manual_seed(31)
+    K = torch.randn(2, 2, int(lens.sum()), 128, generator=g).to(torch.bfloat16)
+    sv32 = oracle32.semvec(gen.to_numpy(K), off)
+    sv16 = oracle32.semvec(gen.to_numpy(K), off, sv_dtype="bf16")
+    assert sv16.dtype == np.uint16 and sv16.shape == sv32.shape
+    assert np.array_equal(sv16, gen.to_numpy(torch.from_numpy(sv32).to(torch.bfloat16)))
+    one = lens == 1
+    assert np.array_equal(sv16[:, :, one], gen.to_numpy(K)[:, :, off[:-1][one]])          # bf16 keys of length-1 buckets survive exactly
+    q = torch.randn(8, 128, generator=g).to(torch.bfloat16)
+    got = oracle32.score(gen.to_numpy(q), sv16[0])
+    wide = torch.from_numpy(sv16[0].astype(np.int32) << 16).view(torch.float32).double().numpy()
+    qd = q.double().numpy()
+    want = np.stack([wide[h] @ qd[4 * h:4 * h + 4].sum(axis=0) for h in range(2)])
+    assert np.abs(got - want).max() <= 1e-5 * np.abs(want).max()
+    # the rounding is really there: the bf16 scores differ from the float-table scores, by about 2^-9 relative per term
+    ref = oracle32.score(gen.to_numpy(q), sv32[0])
+    d = np.abs(got - ref).max()
+    assert 0 < d <= 2.0 ** -7 * np.abs(qd).sum(axis=1).max() * np.abs(sv32).max()
