@@ -73,11 +73,11 @@ def measured_traffic(workload, kernel):
         return None
 
 
-def decode_bytes(wl, S, n_tok_sum, n_sel_sum, fused=True):
+def decode_bytes(wl, S, n_tok_sum, n_sel_sum, fused=True, sv_bytes=4):
     """Algorithmic bytes of one layer's decode step (what the method itself has to move)."""
     H, D, e = wl.n_kv_heads, wl.head_dim, wl.elt_bytes
     q_bytes = wl.n_q_heads * D * e
-    score = S * H * D * 4 + S * H * 4 + q_bytes
+    score = S * H * D * sv_bytes + S * H * 4 + q_bytes
     select = S * H * 4 + S * 8 + (n_tok_sum + 2 * n_sel_sum) * 4
     kv = 2 * n_tok_sum * D * e
     attend = kv + n_tok_sum * 4 + q_bytes + wl.n_q_heads * D * 4
@@ -99,8 +99,11 @@ def run_single_sequence(args, wl, budget):
     gen_s = time.time() - t0
 
     S_cap = len(lengths) + 8
+    sv16 = args.semvec_dtype == "bf16"
+    sv_bytes = 2 if sv16 else 4
     ctx = skv.Context(skv.Desc(n_layers=L, n_q_heads=Hq, n_kv_heads=H, kv_dtype=skv.dtype_code(wl.torch_dtype),
-                               max_tokens=T, max_sentences=S_cap, max_budget=budget, max_batch=1))
+                               max_tokens=T, max_sentences=S_cap, max_budget=budget, max_batch=1,
+                               semvec_dtype=skv.SKV_BF16 if sv16 else skv.SKV_F32))
 
     # ---- prefill: segmentation + semantic vectors (HIP path), timed once -----------------------------
     d_tok, d_bm = i32(tok, dev), torch.as_tensor(bitmap.view(np.int32)).to(dev)
@@ -110,14 +113,14 @@ def run_single_sequence(args, wl, budget):
     n_sent = torch.empty(4, dtype=torch.int32, device=dev)
     S = ctx.segment(d_tok, d_bm, wl.vocab, seg_id, sent_off, sent_len, n_sent)
     assert S == len(lengths), (S, len(lengths))
-    semvec = torch.empty(L, H, S, D, dtype=torch.float32, device=dev)
+    semvec = torch.empty(L, H, S, D, dtype=torch.bfloat16 if sv16 else torch.float32, device=dev)
     ctx.build_semvec(inp.K, sent_off, S, semvec)
     torch.cuda.synchronize()
     with Timer() as t_seg:
         ctx.segment(d_tok, d_bm, wl.vocab, seg_id, sent_off, sent_len, n_sent, sync=False)
     with Timer() as t_sv:
         ctx.build_semvec(inp.K, sent_off, S, semvec)
-    semvec_bytes = L * H * T * D * wl.elt_bytes + L * H * S * D * 4
+    semvec_bytes = L * H * T * D * wl.elt_bytes + L * H * S * D * sv_bytes
 
     # ---- decode ---------------------------------------------------------------------------------------
     cu_tok, cu_sent = i32([0, T], dev), i32([0, S], dev)
@@ -160,7 +163,7 @@ def run_single_sequence(args, wl, budget):
     used = [i % N_QUERY_SETS for i in range(args.steps)]
     n_tok_layer = float(n_tok_all[used].sum(axis=2).mean()) if used else 0.0     # sum over heads, mean over layer-steps
     n_sel_layer = n_tok_layer / float(lengths.mean())
-    bytes_layer = decode_bytes(wl, S, n_tok_layer, n_sel_layer, fused=True)
+    bytes_layer = decode_bytes(wl, S, n_tok_layer, n_sel_layer, fused=True, sv_bytes=sv_bytes)
     us_per_layer = ms_per_step * 1e3 / L
     gbps = bytes_layer["total"] / (us_per_layer * 1e-6) / 1e9
 
@@ -195,7 +198,7 @@ def run_single_sequence(args, wl, budget):
                 g.replay()
         kern[name] = t.ms * 1e3 / (reps * L)
     nt_chain = float(n_tok[:, :H].sum().item()) / L
-    b_unf = decode_bytes(wl, S, nt_chain, nt_chain / float(lengths.mean()), fused=False)
+    b_unf = decode_bytes(wl, S, nt_chain, nt_chain / float(lengths.mean()), fused=False, sv_bytes=sv_bytes)
     kernels = {k: dict(us=round(v, 3), bytes=int(b_unf[k]), GBps=round(b_unf[k] / (v * 1e-6) / 1e9, 1))
                for k, v in kern.items()}
     att = kernels["attend"]
@@ -213,7 +216,7 @@ def run_single_sequence(args, wl, budget):
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "layers": L, "q_heads": Hq, "kv_heads": H, "head_dim": D, "context": T,
                    "sentences": S, "budget": budget, "batch": 1, "path": "skv_decode_step (score+select+attend from pool)",
-                   "kv_pool": "hbm", "launch": args.launch},
+                   "kv_pool": "hbm", "launch": args.launch, "semvec_dtype": args.semvec_dtype},
         "us_per_layer": round(us_per_layer, 3),
         "us_per_layer_direct_launch": round(ms_direct * 1e3 / L, 3),
         "us_per_layer_hip_graph": round(ms_graph * 1e3 / L, 3),
@@ -286,10 +289,13 @@ def run_ragged(args, wl):
     qsets = gen.queries(N_QUERY_SETS * R * B, Hq, D, wl.torch_dtype, args.seed + 1, dev).view(N_QUERY_SETS, R, B, Hq, D)
     torch.cuda.synchronize()
     gen_s = time.time() - t0
+    sv16 = args.semvec_dtype == "bf16"
+    sv_bytes = 2 if sv16 else 4
     ctx = skv.Context(skv.Desc(n_layers=R, n_q_heads=Hq, n_kv_heads=H, kv_dtype=skv.dtype_code(wl.torch_dtype),
-                               max_tokens=T_total, max_sentences=S_total, max_budget=budget, max_batch=B))
+                               max_tokens=T_total, max_sentences=S_total, max_budget=budget, max_batch=B,
+                               semvec_dtype=skv.SKV_BF16 if sv16 else skv.SKV_F32))
     glob_off = i32(gen.offsets_of(inp.sent_len), dev)
-    semvec = torch.empty(R, H, S_total, D, dtype=torch.float32, device=dev)
+    semvec = torch.empty(R, H, S_total, D, dtype=torch.bfloat16 if sv16 else torch.float32, device=dev)
     ctx.build_semvec(inp.K, glob_off, S_total, semvec)
     torch.cuda.synchronize()
     with Timer() as t_sv:
@@ -328,7 +334,7 @@ def run_ragged(args, wl):
     ms_per_step = ms_graph if args.launch == "graph" else ms_direct
     n_tok_layer = float(n_tok_rec.sum().item()) / R
     mean_len = float(inp.sent_len.mean())
-    bl = decode_bytes(wl, S_total, n_tok_layer, n_tok_layer / mean_len, fused=True)
+    bl = decode_bytes(wl, S_total, n_tok_layer, n_tok_layer / mean_len, fused=True, sv_bytes=sv_bytes)
     bl["total"] += (B - 1) * wl.n_q_heads * D * (wl.elt_bytes * 2 + 4)          # q and out of the other sequences
     us_per_layer = ms_per_step * 1e3 / L
     gbps = bl["total"] / (us_per_layer * 1e-6) / 1e9
@@ -340,14 +346,14 @@ def run_ragged(args, wl):
         "config": {"workload": wl.name, "layers": L, "resident_layers": R, "q_heads": Hq, "kv_heads": H, "head_dim": D,
                    "batch": B, "tokens_total": T_total, "sentences_total": S_total, "budget": budget,
                    "path": "skv_decode_step (one call per layer for the whole batch)", "kv_pool": "hbm",
-                   "launch": args.launch},
+                   "launch": args.launch, "semvec_dtype": args.semvec_dtype},
         "us_per_layer": round(us_per_layer, 3),
         "us_per_layer_direct_launch": round(ms_direct * 1e3 / L, 3),
         "us_per_layer_hip_graph": round(ms_graph * 1e3 / L, 3),
         "bytes_per_layer": int(bl["total"]), "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4),
         "mean_tokens_selected_per_head": round(n_tok_layer / (B * H), 1),
         "prefill": {"semvec_ms": round(t_sv.ms, 3),
-                    "semvec_GBps": round((R * H * T_total * D * wl.elt_bytes + R * H * S_total * D * 4) / (t_sv.ms * 1e-3) / 1e9, 1)},
+                    "semvec_GBps": round((R * H * T_total * D * wl.elt_bytes + R * H * S_total * D * sv_bytes) / (t_sv.ms * 1e-3) / 1e9, 1)},
         "roofline": dict(bound="hbm", kernel="score_kernel + attend_kernel (fused step)", achieved=round(gbps, 1),
                          peak=HBM_PEAK_GBPS, unit="GB/s", frac=round(gbps / HBM_PEAK_GBPS, 4), traffic=None),
         "cpu_baseline": None, "input_gen_s": round(gen_s, 1),
@@ -530,7 +536,7 @@ def cpu_baseline(args, wl, inp, semvec, lengths, qsets, budget):
     n_layers = min(L, args.cpu_layers)
     Kh = [gen.to_numpy(inp.K[l]) for l in range(n_layers)]
     Vh = [gen.to_numpy(inp.V[l]) for l in range(n_layers)]
-    svh = [semvec[l].cpu().numpy() for l in range(n_layers)]
+    svh = [gen.to_numpy(semvec[l]) for l in range(n_layers)]
     qh = [gen.to_numpy(qsets[0, l]) for l in range(n_layers)]
     done, t_total, n_tok_sum = 0, 0.0, 0
     t_end = time.perf_counter() + args.cpu_seconds
@@ -562,6 +568,8 @@ def main():
     ap.add_argument("--resident-layers", type=int, default=4, help="cfg4: layers of the pool kept in HBM")
     ap.add_argument("--budget", type=int, default=0, help="token budget (default: the workload's largest)")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--semvec-dtype", default="f32", choices=["f32", "bf16"],
+                    help="storage of the mean key vectors (decode workloads); bf16 = the fp32 mean rounded once")
     ap.add_argument("--launch", default="graph", choices=["graph", "direct"],
                     help="graph: the step's launches replayed as one HIP graph; direct: one host call per layer")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)

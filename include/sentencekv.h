@@ -54,6 +54,9 @@ typedef struct {
     int32_t max_sentences;  /* largest S (S_total for a ragged batch) any call will pass */
     int32_t max_budget;     /* largest per-sequence token budget tau any call will pass */
     int32_t max_batch;      /* largest number of sequences in one skv_decode_step (>= 1) */
+    int32_t semvec_dtype;   /* skv_dtype of the semantic-vector table: SKV_F32, or SKV_BF16 = the fp32 mean rounded once to
+                               nearest even (the mixed-precision sentence vectors of the paper's "Future Work"; halves the
+                               bytes the scoring step reads) */
 } skv_desc;
 
 typedef struct skv_ctx skv_ctx;   /* opaque */
@@ -93,17 +96,17 @@ int skv_segment(skv_ctx* ctx, const int32_t* tok, int32_t T, const uint32_t* ter
 /* Eq. 1: semvec[l][h][s][:] = mean over the tokens x of bucket s of K_pool[l][h][x][:], accumulated
  * in fp32.  The pool holds the full context, so the set S_s of Eq. 1 is the whole bucket.
  * K_pool  dev [L][Hkv][T][D] kv_dtype          sent_off  dev [S + 1] (as produced by skv_segment)
- * semvec  dev [L][Hkv][S][D] fp32
+ * semvec  dev [L][Hkv][S][D] semvec_dtype
  * Errors: SKV_EINVAL, SKV_ECAPACITY (T > max_tokens or S > max_sentences).  S == 0 is a no-op. */
 int skv_build_semvec(skv_ctx* ctx, const void* K_pool, int32_t T, const int32_t* sent_off, int32_t S,
-                     float* semvec);
+                     void* semvec);
 
 /* Eq. 1 over a retained pool: as skv_build_semvec, but every layer has its own offset table (the retained
  * tokens differ per layer) and a bucket may hold no token (its vector is stored as zeros; skv_select and
  * skv_decode_step never list a bucket of length 0).
- * K_pool dev [L][Hkv][T][D] kv_dtype      sent_off dev [L][S + 1]      semvec dev [L][Hkv][S][D] fp32
+ * K_pool dev [L][Hkv][T][D] kv_dtype      sent_off dev [L][S + 1]      semvec dev [L][Hkv][S][D] semvec_dtype
  * Errors: SKV_EINVAL, SKV_ECAPACITY (T > max_tokens or S > max_sentences). */
-int skv_build_semvec_layers(skv_ctx* ctx, const void* K_pool, int32_t T, const int32_t* sent_off, int32_t S, float* semvec);
+int skv_build_semvec_layers(skv_ctx* ctx, const void* K_pool, int32_t T, const int32_t* sent_off, int32_t S, void* semvec);
 
 /* ---------------------------------------------------------------------------------------------
  * Prefill-side token retention: Sec. 4.1 "Token importance measurement" and "Token selection within sentence
@@ -159,9 +162,9 @@ int skv_query_update(skv_ctx* ctx, int32_t B, const void* q_t, const int32_t* to
  * (2) Sec. 4.2 "Semantic similarity and token retrieval": score[h][s] = sum over the G query heads j
  * of KV head h of q_score[j]^T semvec[layer][h][s].  No scaling, no normalisation.  q_score is the
  * mean query q-bar of Eq. 2 (or the current query: the choice is the caller's).
- * q_score dev [Hq][D] kv_dtype;  semvec dev [L][Hkv][S][D] fp32 (whole table; `layer` selects the slice);
+ * q_score dev [Hq][D] kv_dtype;  semvec dev [L][Hkv][S][D] semvec_dtype (whole table; `layer` selects the slice);
  * score   dev [Hkv][S] fp32. */
-int skv_score(skv_ctx* ctx, int32_t layer, const void* q_score, const float* semvec, int32_t S, float* score);
+int skv_score(skv_ctx* ctx, int32_t layer, const void* q_score, const void* semvec, int32_t S, float* score);
 
 /* (3) Sec. 4.2 ranking and budgeted retrieval, App. "Effect of Sentence Length": per KV head, buckets
  * are ranked by score (descending; equal scores by ascending id; NaN last; -0 == +0) and whole buckets
@@ -208,7 +211,7 @@ int skv_attend(skv_ctx* ctx, const void* q_attn, const void* K_sel, const void* 
  * tok_idx_out dev [B][Hkv][max_budget] or NULL: positions (local to the sequence) of the retrieved
  *             tokens;  n_tok_out dev [B][Hkv] or NULL. */
 int skv_decode_step(skv_ctx* ctx, int32_t layer, int32_t B, const void* q_score, const void* q_attn,
-                    const void* K_pool, const void* V_pool, int32_t T_total, const float* semvec, int32_t S_total,
+                    const void* K_pool, const void* V_pool, int32_t T_total, const void* semvec, int32_t S_total,
                     const int32_t* cu_tok, const int32_t* cu_sent, const int32_t* sent_off, const int32_t* sent_len,
                     const int32_t* budget, float* out, float* lse, int32_t* tok_idx_out, int32_t* n_tok_out);
 

@@ -27,7 +27,7 @@ class SkvError(RuntimeError):
 
 class _Desc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("n_layers", "n_q_heads", "n_kv_heads", "head_dim", "kv_dtype",
-                                              "max_tokens", "max_sentences", "max_budget", "max_batch")]
+                                              "max_tokens", "max_sentences", "max_budget", "max_batch", "semvec_dtype")]
 
 
 _LIB = None
@@ -99,6 +99,7 @@ class Desc:
     max_sentences: int = 1
     max_budget: int = 1
     max_batch: int = 1
+    semvec_dtype: int = SKV_F32
 
     @property
     def max_sel(self) -> int:
@@ -120,7 +121,7 @@ class Context:
         lib = _lib()
         self.desc = desc
         d = _Desc(desc.n_layers, desc.n_q_heads, desc.n_kv_heads, desc.head_dim, desc.kv_dtype, desc.max_tokens,
-                  desc.max_sentences, desc.max_budget, desc.max_batch)
+                  desc.max_sentences, desc.max_budget, desc.max_batch, desc.semvec_dtype)
         h = _vp()
         if stream is None:
             stream = torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else 0

@@ -18,6 +18,7 @@ int check_desc(const skv_desc* d) {
     if (d->n_layers < 1 || d->n_q_heads < 1 || d->n_kv_heads < 1) return SKV_EINVAL;
     if (d->head_dim != skv::kHeadDim) return SKV_EINVAL;
     if (d->kv_dtype != SKV_F32 && d->kv_dtype != SKV_BF16) return SKV_EINVAL;
+    if (d->semvec_dtype != SKV_F32 && d->semvec_dtype != SKV_BF16) return SKV_EINVAL;
     if (d->n_q_heads % d->n_kv_heads != 0) return SKV_EINVAL;
     const int G = d->n_q_heads / d->n_kv_heads;
     if (G != 1 && G != 2 && G != 4 && G != 8) return SKV_EINVAL;
@@ -41,6 +42,7 @@ int check_ctx(const skv_ctx* ctx) {
 
 inline int64_t layer_elems(const Ctx& c, int64_t rows) { return (int64_t)c.d.n_kv_heads * rows * skv::kHeadDim; }
 inline int elt_bytes(const Ctx& c) { return c.d.kv_dtype == SKV_BF16 ? 2 : 4; }
+inline int sv_bytes(const Ctx& c) { return c.d.semvec_dtype == SKV_BF16 ? 2 : 4; }
 
 }  // namespace
 
@@ -144,7 +146,7 @@ int skv_segment(skv_ctx* ctx, const int32_t* tok, int32_t T, const uint32_t* ter
     return *n_sent_host > ctx->c.d.max_sentences ? SKV_ECAPACITY : SKV_OK;
 }
 
-int skv_build_semvec(skv_ctx* ctx, const void* K_pool, int32_t T, const int32_t* sent_off, int32_t S, float* semvec) {
+int skv_build_semvec(skv_ctx* ctx, const void* K_pool, int32_t T, const int32_t* sent_off, int32_t S, void* semvec) {
     if (!ctx) return SKV_EINVAL;
     if (T < 0 || S < 0) return SKV_EINVAL;
     if (S > 0 && (bad_ptr(K_pool) || bad_ptr(sent_off) || bad_ptr(semvec))) return SKV_EINVAL;
@@ -155,7 +157,7 @@ int skv_build_semvec(skv_ctx* ctx, const void* K_pool, int32_t T, const int32_t*
     return hip_status(skv::launch_semvec(&ctx->c, K_pool, T, sent_off, 0, S, semvec));
 }
 
-int skv_build_semvec_layers(skv_ctx* ctx, const void* K_pool, int32_t T, const int32_t* sent_off, int32_t S, float* semvec) {
+int skv_build_semvec_layers(skv_ctx* ctx, const void* K_pool, int32_t T, const int32_t* sent_off, int32_t S, void* semvec) {
     if (!ctx) return SKV_EINVAL;
     if (T < 0 || S < 0) return SKV_EINVAL;
     if (S > 0 && (bad_ptr(K_pool) || bad_ptr(sent_off) || bad_ptr(semvec))) return SKV_EINVAL;
@@ -219,7 +221,7 @@ int skv_query_update(skv_ctx* ctx, int32_t B, const void* q_t, const int32_t* to
     return hip_status(skv::launch_query_update(&ctx->c, B, q_t, tok_t, term_bitmap, vocab, q_sum, q_cnt, q_bar));
 }
 
-int skv_score(skv_ctx* ctx, int32_t layer, const void* q_score, const float* semvec, int32_t S, float* score) {
+int skv_score(skv_ctx* ctx, int32_t layer, const void* q_score, const void* semvec, int32_t S, float* score) {
     if (!ctx) return SKV_EINVAL;
     if (layer < 0 || layer >= ctx->c.d.n_layers || S < 0) return SKV_EINVAL;
     if (S > 0 && (bad_ptr(q_score) || bad_ptr(semvec) || bad_ptr(score))) return SKV_EINVAL;
@@ -227,7 +229,7 @@ int skv_score(skv_ctx* ctx, int32_t layer, const void* q_score, const float* sem
     const int rc = check_ctx(ctx);
     if (rc != SKV_OK) return rc;
     const SeqView v{nullptr, nullptr, nullptr, 0, S, 0, 1};
-    const float* sv = semvec + (int64_t)layer * layer_elems(ctx->c, S);
+    const char* sv = (const char*)semvec + (int64_t)layer * layer_elems(ctx->c, S) * sv_bytes(ctx->c);
     return hip_status(skv::launch_score(&ctx->c, q_score, sv, v, score));
 }
 
@@ -290,7 +292,7 @@ int skv_attend(skv_ctx* ctx, const void* q_attn, const void* K_sel, const void* 
 }
 
 int skv_decode_step(skv_ctx* ctx, int32_t layer, int32_t B, const void* q_score, const void* q_attn,
-                    const void* K_pool, const void* V_pool, int32_t T_total, const float* semvec, int32_t S_total,
+                    const void* K_pool, const void* V_pool, int32_t T_total, const void* semvec, int32_t S_total,
                     const int32_t* cu_tok, const int32_t* cu_sent, const int32_t* sent_off, const int32_t* sent_len,
                     const int32_t* budget, float* out, float* lse, int32_t* tok_idx_out, int32_t* n_tok_out) {
     if (!ctx) return SKV_EINVAL;
@@ -308,7 +310,7 @@ int skv_decode_step(skv_ctx* ctx, int32_t layer, int32_t B, const void* q_score,
     if (rc != SKV_OK) return rc;
 
     const SeqView v{cu_tok, cu_sent, budget, T_total, S_total, 0, B};
-    const float* sv = semvec + (int64_t)layer * layer_elems(c, S_total);
+    const char* sv = (const char*)semvec + (int64_t)layer * layer_elems(c, S_total) * sv_bytes(c);
     const int64_t pool_off = (int64_t)layer * layer_elems(c, T_total) * elt_bytes(c);
 
     hipError_t e = skv::launch_score(&c, q_score, sv, v, c.f_score);

@@ -167,23 +167,108 @@ __global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_kernel(cons
     }
 }
 
+// The same scores from a bf16 table: a vector is 256 bytes = 16 lanes x 16 bytes (8 dims per lane), a wave load covers
+// 4 buckets, 16 buckets per wave keep 4 loads in flight; the sum over a bucket's 16 lanes stays inside a DPP row.
+constexpr int kScoreRowsPerWave16 = 16;
+
+template <int EB, int G>
+__global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_sv16_kernel(const char* __restrict__ q,
+                                                                                 const char* __restrict__ semvec, SeqView v,
+                                                                                 int32_t Hq, float* __restrict__ score) {
+    constexpr int kRowsPerBlock = kScoreRowsPerWave16 * kScoreWavesPerBlock;
+    int blk = blockIdx.x, b = 0;
+    Seq sq{};
+    for (; b < v.B; ++b) {
+        sq = seq_of(v, b);
+        const int nb = (sq.n_sent + kRowsPerBlock - 1) / kRowsPerBlock;
+        if (blk < nb) break;
+        blk -= nb;
+    }
+    if (b >= v.B) return;
+    const int h = blockIdx.y;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int c = lane & 15, sub = lane >> 4;
+
+    float qs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const char* qrow = q + ((int64_t)(b * Hq + h * G + g) * kHeadDim + c * 8) * EB;
+        if (EB == 4) {
+            const float4 t0 = *reinterpret_cast<const float4*>(qrow), t1 = *reinterpret_cast<const float4*>(qrow + 16);
+            qs[0] += t0.x; qs[1] += t0.y; qs[2] += t0.z; qs[3] += t0.w;
+            qs[4] += t1.x; qs[5] += t1.y; qs[6] += t1.z; qs[7] += t1.w;
+        } else {
+            float f[8];
+            Row<2>::unpack(*reinterpret_cast<const uint4*>(qrow), f);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) qs[i] += f[i];
+        }
+    }
+    constexpr int kIter = kScoreRowsPerWave16 / 4;
+    const int32_t row0 = blk * kRowsPerBlock + w * kScoreRowsPerWave16 + sub;
+    const char* base = semvec + (((int64_t)h * v.S_total + sq.sent_base) * kHeadDim + c * 8) * 2;
+    uint4 x[kIter];
+#pragma unroll
+    for (int i = 0; i < kIter; ++i) {                       // clamped addresses: all loads issued back to back
+        const int32_t s = min(row0 + 4 * i, sq.n_sent - 1);
+        x[i] = *reinterpret_cast<const uint4*>(base + (int64_t)s * (kHeadDim * 2));
+    }
+    float p[kIter];
+#pragma unroll
+    for (int i = 0; i < kIter; ++i) {
+        float f[8];
+        Row<2>::unpack(x[i], f);
+        p[i] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) p[i] += f[e] * qs[e];
+    }
+#pragma unroll
+    for (int i = 0; i < kIter; ++i) {                       // sum over the 16 lanes of a bucket
+        p[i] = dpp_add<0xB1>(p[i]);
+        p[i] = dpp_add<0x4E>(p[i]);
+        p[i] = dpp_add<0x124>(p[i]);
+        p[i] = dpp_add<0x128>(p[i]);
+    }
+    if (c == 0) {
+        float* out = score + (int64_t)h * v.S_total + sq.sent_base;
+#pragma unroll
+        for (int i = 0; i < kIter; ++i) {
+            const int32_t s = row0 + 4 * i;
+            if (s < sq.n_sent) out[s] = p[i];
+        }
+    }
+}
+
 template <int EB, int RPWV>
-static hipError_t launch_score_g(Ctx* c, const void* q, const float* semvec_layer, const SeqView& v, float* score) {
-    constexpr int kRowsPerBlock = RPWV * kScoreWavesPerBlock;
-    const int blocks = (v.S_total + kRowsPerBlock - 1) / kRowsPerBlock + v.B;   // bound on sum_b ceil(S_b/R)
+static hipError_t launch_score_g(Ctx* c, const void* q, const void* semvec_layer, const SeqView& v, float* score) {
+    const bool sv16 = c->d.semvec_dtype == SKV_BF16;
+    const int rows_per_block = (sv16 ? kScoreRowsPerWave16 : RPWV) * kScoreWavesPerBlock;
+    const int blocks = (v.S_total + rows_per_block - 1) / rows_per_block + v.B;   // bound on sum_b ceil(S_b/R)
     const dim3 grid(blocks, c->d.n_kv_heads), block(kScoreWavesPerBlock * kWave);
     const char* qp = (const char*)q;
+    const char* sv = (const char*)semvec_layer;
+    if (sv16) {
+        switch (c->G) {
+            case 1: hipLaunchKernelGGL((score_sv16_kernel<EB, 1>), grid, block, 0, c->stream, qp, sv, v, c->d.n_q_heads, score); break;
+            case 2: hipLaunchKernelGGL((score_sv16_kernel<EB, 2>), grid, block, 0, c->stream, qp, sv, v, c->d.n_q_heads, score); break;
+            case 4: hipLaunchKernelGGL((score_sv16_kernel<EB, 4>), grid, block, 0, c->stream, qp, sv, v, c->d.n_q_heads, score); break;
+            case 8: hipLaunchKernelGGL((score_sv16_kernel<EB, 8>), grid, block, 0, c->stream, qp, sv, v, c->d.n_q_heads, score); break;
+            default: return hipErrorInvalidValue;
+        }
+        return hipGetLastError();
+    }
+    const float* svf = (const float*)semvec_layer;
     switch (c->G) {
-        case 1: hipLaunchKernelGGL((score_kernel<EB, 1, RPWV>), grid, block, 0, c->stream, qp, semvec_layer, v, c->d.n_q_heads, score); break;
-        case 2: hipLaunchKernelGGL((score_kernel<EB, 2, RPWV>), grid, block, 0, c->stream, qp, semvec_layer, v, c->d.n_q_heads, score); break;
-        case 4: hipLaunchKernelGGL((score_kernel<EB, 4, RPWV>), grid, block, 0, c->stream, qp, semvec_layer, v, c->d.n_q_heads, score); break;
-        case 8: hipLaunchKernelGGL((score_kernel<EB, 8, RPWV>), grid, block, 0, c->stream, qp, semvec_layer, v, c->d.n_q_heads, score); break;
+        case 1: hipLaunchKernelGGL((score_kernel<EB, 1, RPWV>), grid, block, 0, c->stream, qp, svf, v, c->d.n_q_heads, score); break;
+        case 2: hipLaunchKernelGGL((score_kernel<EB, 2, RPWV>), grid, block, 0, c->stream, qp, svf, v, c->d.n_q_heads, score); break;
+        case 4: hipLaunchKernelGGL((score_kernel<EB, 4, RPWV>), grid, block, 0, c->stream, qp, svf, v, c->d.n_q_heads, score); break;
+        case 8: hipLaunchKernelGGL((score_kernel<EB, 8, RPWV>), grid, block, 0, c->stream, qp, svf, v, c->d.n_q_heads, score); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
-hipError_t launch_score(Ctx* c, const void* q, const float* semvec_layer, const SeqView& v, float* score) {
+hipError_t launch_score(Ctx* c, const void* q, const void* semvec_layer, const SeqView& v, float* score) {
     if (v.S_total == 0) return hipSuccess;
     return c->d.kv_dtype == SKV_BF16 ? launch_score_g<2, kScoreRowsPerWave>(c, q, semvec_layer, v, score)
                                      : launch_score_g<4, kScoreRowsPerWave>(c, q, semvec_layer, v, score);

@@ -159,11 +159,11 @@ hipError_t launch_segment(Ctx* c, const int32_t* tok, int32_t T, const uint32_t*
 // consecutive rows fully coalesced.  Four such loads are kept in flight per lane.
 // ------------------------------------------------------------------------------------------------
 
-template <int EB>
+template <int EB, int SVB>     // SVB: bytes per stored element of the table (4 = fp32, 2 = bf16, rounded to nearest even)
 __global__ __launch_bounds__(kSemvecWavesPerBlock * kWave) void semvec_kernel(const char* __restrict__ K, int32_t T,
                                                                               const int32_t* __restrict__ sent_off_all,
                                                                               int32_t off_layer_stride, int32_t Hkv,
-                                                                              int32_t S, float* __restrict__ semvec) {
+                                                                              int32_t S, char* __restrict__ semvec) {
     using R = Row<EB>;
     constexpr int kUnroll = 4;
     const int lane = threadIdx.x & 63;
@@ -203,26 +203,44 @@ __global__ __launch_bounds__(kSemvecWavesPerBlock * kWave) void semvec_kernel(co
     }
     if (r == 0) {
         const float n = (e > b) ? (float)(e - b) : 1.f;      // a bucket without tokens yields zeros
-        float* out = semvec + (lh * S + s) * (int64_t)kHeadDim + cc * R::EPL;
+        const int64_t o = (lh * S + s) * (int64_t)kHeadDim + cc * R::EPL;      // element index of the lane's first output
 #pragma unroll
         for (int i = 0; i < R::EPL; i += 4) {
-            float4 o = make_float4(acc[i] / n, acc[i + 1] / n, acc[i + 2] / n, acc[i + 3] / n);
-            *reinterpret_cast<float4*>(out + i) = o;
+            const float m[4] = {acc[i] / n, acc[i + 1] / n, acc[i + 2] / n, acc[i + 3] / n};
+            if (SVB == 4) {
+                *reinterpret_cast<float4*>(semvec + (o + i) * 4) = make_float4(m[0], m[1], m[2], m[3]);
+            } else {
+                uint32_t rb[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    uint32_t u = __float_as_uint(m[k]);
+                    u += 0x7fffu + ((u >> 16) & 1u);               // round to nearest even bf16 (means are finite)
+                    rb[k] = u >> 16;
+                }
+                *reinterpret_cast<uint2*>(semvec + (o + i) * 2) = make_uint2(rb[0] | (rb[1] << 16), rb[2] | (rb[3] << 16));
+            }
         }
     }
 }
 
+template <int EB>
+static void launch_semvec_eb(Ctx* c, dim3 grid, dim3 block, const void* K_pool, int32_t T, const int32_t* sent_off,
+                             int32_t off_layer_stride, int32_t S, void* semvec) {
+    if (c->d.semvec_dtype == SKV_BF16)
+        hipLaunchKernelGGL((semvec_kernel<EB, 2>), grid, block, 0, c->stream, (const char*)K_pool, T, sent_off, off_layer_stride,
+                           c->d.n_kv_heads, S, (char*)semvec);
+    else
+        hipLaunchKernelGGL((semvec_kernel<EB, 4>), grid, block, 0, c->stream, (const char*)K_pool, T, sent_off, off_layer_stride,
+                           c->d.n_kv_heads, S, (char*)semvec);
+}
+
 hipError_t launch_semvec(Ctx* c, const void* K_pool, int32_t T, const int32_t* sent_off, int32_t off_layer_stride, int32_t S,
-                         float* semvec) {
+                         void* semvec) {
     if (S == 0) return hipSuccess;
     const dim3 grid((S + kSemvecWavesPerBlock - 1) / kSemvecWavesPerBlock, c->d.n_layers * c->d.n_kv_heads);
     const dim3 block(kSemvecWavesPerBlock * kWave);
-    if (c->d.kv_dtype == SKV_BF16)
-        hipLaunchKernelGGL(semvec_kernel<2>, grid, block, 0, c->stream, (const char*)K_pool, T, sent_off, off_layer_stride,
-                           c->d.n_kv_heads, S, semvec);
-    else
-        hipLaunchKernelGGL(semvec_kernel<4>, grid, block, 0, c->stream, (const char*)K_pool, T, sent_off, off_layer_stride,
-                           c->d.n_kv_heads, S, semvec);
+    if (c->d.kv_dtype == SKV_BF16) launch_semvec_eb<2>(c, grid, block, K_pool, T, sent_off, off_layer_stride, S, semvec);
+    else launch_semvec_eb<4>(c, grid, block, K_pool, T, sent_off, off_layer_stride, S, semvec);
     return hipGetLastError();
 }
 

@@ -67,7 +67,7 @@ hipError_t launch_segment(Ctx* c, const int32_t* tok, int32_t T, const uint32_t*
                           int32_t* seg_id, int32_t* sent_off, int32_t* sent_len, int32_t* n_sent_dev);
 // off_layer_stride: 0 = one offset table for all layers, else the distance (in entries) between the layers' tables
 hipError_t launch_semvec(Ctx* c, const void* K_pool, int32_t T, const int32_t* sent_off, int32_t off_layer_stride, int32_t S,
-                         float* semvec);
+                         void* semvec);
 // prefill-side token retention (retain.hip)
 constexpr int kImportanceMaxRows = 256;   // query rows (G * window tokens) per KV head
 int64_t importance_work_bytes(const Ctx* c, int32_t T, int32_t N);
@@ -78,7 +78,7 @@ hipError_t launch_compact_pool(Ctx* c, const void* K_pool, const void* V_pool, i
                                const int32_t* n_keep, void* K_ret, void* V_ret);
 hipError_t launch_query_update(Ctx* c, int32_t B, const void* q_t, const int32_t* tok_t, const uint32_t* bitmap,
                                int32_t vocab, float* q_sum, int32_t* q_cnt, void* q_bar);
-hipError_t launch_score(Ctx* c, const void* q, const float* semvec_layer, const SeqView& v, float* score);
+hipError_t launch_score(Ctx* c, const void* q, const void* semvec_layer, const SeqView& v, float* score);
 hipError_t launch_select(Ctx* c, const float* score, const int32_t* sent_off, const int32_t* sent_len,
                          const SeqView& v, int32_t* sel_sent, int32_t* n_sel, int32_t* tok_idx, int32_t idx_stride,
                          int32_t* n_tok);

@@ -22,10 +22,22 @@ def empty_i32(*shape, fill=None):
     return t
 
 
-def make_ctx(wl: gen.Workload, T, S, budget, batch=1):
+def make_ctx(wl: gen.Workload, T, S, budget, batch=1, sv_dtype="f32"):
     return skv.Context(skv.Desc(n_layers=wl.n_layers, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
                                 kv_dtype=skv.dtype_code(wl.torch_dtype), max_tokens=max(T, 1),
-                                max_sentences=max(S, 1), max_budget=max(budget, 1), max_batch=batch))
+                                max_sentences=max(S, 1), max_budget=max(budget, 1), max_batch=batch,
+                                semvec_dtype=skv.SKV_BF16 if sv_dtype == "bf16" else skv.SKV_F32))
+
+
+def sv_torch_dtype(sv_dtype):
+    return torch.bfloat16 if sv_dtype == "bf16" else torch.float32
+
+
+def bf16_table_close(got_bits: np.ndarray, ref_bits: np.ndarray) -> bool:
+    """Two bf16 tables that round fp32 means differing in summation order: equal almost everywhere, one ulp apart at most."""
+    g, r = got_bits.astype(np.int32), ref_bits.astype(np.int32)
+    same = float((g == r).mean())
+    return bool(np.abs(g - r).max() <= 1 and same >= 0.995)
 
 
 def np_of(t: torch.Tensor) -> np.ndarray:

@@ -106,11 +106,11 @@ def test_semvec_matches_oracle(U, oracle32, dtype, dist):
 
 # ----------------------------------------------------------------------------- decode chain, per stage
 
-def _chain_case(U, oracle32, wl, seed, budget, pool_in_host=False, layers=None):
+def _chain_case(U, oracle32, wl, seed, budget, pool_in_host=False, layers=None, sv_dtype="f32"):
     """Runs the 4-call chain on the GPU for some layers and checks each stage against the oracle."""
     inp = gen.decode_inputs(wl, seed=seed, device=U.DEV)          # generated on the GPU; the oracle reads copies
     S, T = len(inp.lengths), wl.n_tokens
-    ctx = U.make_ctx(wl, T, S, budget)
+    ctx = U.make_ctx(wl, T, S, budget, sv_dtype=sv_dtype)
     if pool_in_host:
         Kd = torch.empty(inp.K.shape, dtype=inp.K.dtype, pin_memory=True).copy_(inp.K)
         Vd = torch.empty(inp.V.shape, dtype=inp.V.dtype, pin_memory=True).copy_(inp.V)
@@ -119,10 +119,10 @@ def _chain_case(U, oracle32, wl, seed, budget, pool_in_host=False, layers=None):
         Kd, Vd = inp.K.to(U.DEV), inp.V.to(U.DEV)
         Kdev_for_semvec = Kd
     qd = inp.q.to(U.DEV)
-    sv = torch.zeros(wl.n_layers, wl.n_kv_heads, max(S, 1), 128, dtype=torch.float32, device=U.DEV)
+    sv = torch.zeros(wl.n_layers, wl.n_kv_heads, max(S, 1), 128, dtype=U.sv_torch_dtype(sv_dtype), device=U.DEV)
     ctx.build_semvec(Kdev_for_semvec, U.i32(inp.sent_off), S, sv)
     torch.cuda.synchronize()
-    sv_np = sv.cpu().numpy()[:, :, :S]
+    sv_np = U.np_of(sv)[:, :, :S]
     n_ties = 0
     for l in (layers if layers is not None else range(wl.n_layers)):
         _say("chain", wl.name, "seed", seed, "budget", budget, "layer", l, "host_pool", pool_in_host)
@@ -132,9 +132,14 @@ def _chain_case(U, oracle32, wl, seed, budget, pool_in_host=False, layers=None):
         sc_ref_same_sv = oracle32.score(q, sv_np[l])
         assert np.all(np.abs(g["score"] - sc_ref_same_sv) <= U.score_tolerance(sc_ref_same_sv))
         # ... and end to end from the oracle's semantic vectors
-        sv_ref = oracle32.semvec(K[None], inp.sent_off)[0]
+        sv_ref = oracle32.semvec(K[None], inp.sent_off, sv_dtype=sv_dtype)[0]
         sc_ref = oracle32.score(q, sv_ref)
-        assert np.all(np.abs(g["score"] - sc_ref) <= 2 * U.score_tolerance(sc_ref))
+        if sv_dtype == "f32":
+            assert np.all(np.abs(g["score"] - sc_ref) <= 2 * U.score_tolerance(sc_ref))
+        else:                               # the two bf16 tables round fp32 means that differ in summation order
+            assert U.bf16_table_close(sv_np[l], sv_ref)
+            one = inp.lengths == 1
+            assert np.array_equal(sv_np[l][:, one], sv_ref[:, one])
         # (3) selection: the oracle's rule on the GPU's scores, bit for bit
         sel, n_sel, tok_idx, n_tok = oracle32.select(g["score"], inp.sent_off, inp.lengths, budget)
         assert np.array_equal(g["n_sel"], n_sel) and np.array_equal(g["n_tok"], n_tok)
@@ -145,7 +150,7 @@ def _chain_case(U, oracle32, wl, seed, budget, pool_in_host=False, layers=None):
         # end-to-end selection may differ only through documented ties
         sel_e, n_sel_e, tok_idx_e, n_tok_e = oracle32.select(sc_ref, inp.sent_off, inp.lengths, budget)
         for h in range(wl.n_kv_heads):
-            if n_sel_e[h] != n_sel[h] or not np.array_equal(sel_e[h, :n_sel_e[h]], sel[h, :n_sel[h]]):
+            if sv_dtype == "f32" and (n_sel_e[h] != n_sel[h] or not np.array_equal(sel_e[h, :n_sel_e[h]], sel[h, :n_sel[h]])):
                 ok, a, b, gap = U.documented_tie(sc_ref[h], g["score"][h], upto=int(max(n_sel_e[h], n_sel[h])) + 1)
                 _say(f"  documented tie: layer {l} head {h} buckets {a},{b} relative gap {gap:.3e}")
                 assert ok, (l, h, a, b, gap)
@@ -294,16 +299,16 @@ def test_attend_large_logits_do_not_overflow(U, oracle32):
 
 # ----------------------------------------------------------------------------- fused step
 
-def _fused_case(U, oracle32, wl, seed, layers):
+def _fused_case(U, oracle32, wl, seed, layers, sv_dtype="f32"):
     inp = gen.ragged_inputs(wl, seed=seed, device=U.DEV, resident_layers=len(layers))
     B, H, Hq, D = wl.batch, wl.n_kv_heads, wl.n_q_heads, wl.head_dim
     T_total, S_total = int(inp.cu_tok[-1]), int(inp.cu_sent[-1])
     max_budget = int(inp.budget.max())
-    ctx = U.make_ctx(wl.scaled(n_layers=len(layers)), T_total, S_total, max_budget, batch=B)
+    ctx = U.make_ctx(wl.scaled(n_layers=len(layers)), T_total, S_total, max_budget, batch=B, sv_dtype=sv_dtype)
     Kd, Vd, qd = inp.K.to(U.DEV), inp.V.to(U.DEV), inp.q.to(U.DEV)
     # semantic vectors of the concatenated stream: bucket boundaries are the concatenation of the sequences'
     glob_off = gen.offsets_of(inp.sent_len)
-    sv = torch.zeros(len(layers), H, S_total, D, dtype=torch.float32, device=U.DEV)
+    sv = torch.zeros(len(layers), H, S_total, D, dtype=U.sv_torch_dtype(sv_dtype), device=U.DEV)
     ctx.build_semvec(Kd, U.i32(glob_off), S_total, sv)
     out = torch.full((B, Hq, D), 7.0, device=U.DEV)
     lse = torch.full((B, Hq), 7.0, device=U.DEV)
@@ -316,7 +321,7 @@ def _fused_case(U, oracle32, wl, seed, layers):
         ctx.decode_step(li, B, qd[li], qd[li], Kd, Vd, T_total, sv, S_total, d["cu_tok"], d["cu_sent"], d["sent_off"],
                         d["sent_len"], d["budget"], out, lse, tok_idx, n_tok)
         torch.cuda.synchronize()
-        sv_l = sv[li].cpu().numpy()
+        sv_l = U.np_of(sv[li])
         o, ls, ti, nt = out.cpu().numpy(), lse.cpu().numpy(), tok_idx.cpu().numpy(), n_tok.cpu().numpy()
         for b in range(B):
             t0, t1, s0, s1 = inp.cu_tok[b], inp.cu_tok[b + 1], inp.cu_sent[b], inp.cu_sent[b + 1]
@@ -502,3 +507,20 @@ def test_equal_size_chunk_mode(U, oracle32):
     wl = gen.CFG1.scaled(n_layers=1, n_tokens=4096 + 7, len_dist=("fixed", 16))
     _chain_case(U, oracle32, wl, seed=23, budget=512)
     _fused_case(U, oracle32, wl.scaled(batch=1, t_range=(4103, 4103), budgets=(512,)), seed=23, layers=[0])
+
+
+# ----------------------------------------------------------------------------- bf16 table of mean key vectors
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_bf16_semvec_table_chain(U, oracle32, dtype):
+    """Mixed-precision sentence vectors (semvec_dtype = bf16): table within one bf16 ulp of the oracle's, scores from
+    the GPU's own table to the usual tolerance, selection bit-exact on those scores, through the 4-call chain."""
+    wl = gen.CFG1.scaled(n_layers=2, n_tokens=9000, dtype=dtype)
+    _chain_case(U, oracle32, wl, seed=31, budget=700, sv_dtype="bf16")
+
+
+@pytest.mark.parametrize("Hq,B", [(32, 1), (64, 9), (8, 3)])
+def test_bf16_semvec_table_fused(U, oracle32, Hq, B):
+    """The fused decode step (single sequence, small batch, batch path) on a bf16 table, every group size class."""
+    wl = gen.CFG4.scaled(n_layers=1, n_q_heads=Hq, batch=B, t_range=(300, 3500), budgets=(600,))
+    _fused_case(U, oracle32, wl, seed=33, layers=[0], sv_dtype="bf16")
