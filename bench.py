@@ -338,6 +338,23 @@ def run_ragged(args, wl):
     bl["total"] += (B - 1) * wl.n_q_heads * D * (wl.elt_bytes * 2 + 4)          # q and out of the other sequences
     us_per_layer = ms_per_step * 1e3 / L
     gbps = bl["total"] / (us_per_layer * 1e-6) / 1e9
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        orc = oracle.get("f32")
+        K0, V0, sv0, q0 = gen.to_numpy(inp.K[0]), gen.to_numpy(inp.V[0]), gen.to_numpy(semvec[0]), gen.to_numpy(qsets[0, 0])
+        done, t0 = 0, time.perf_counter()
+        while time.perf_counter() - t0 < args.cpu_seconds:
+            b = done % B
+            a0, a1, s0, s1 = int(inp.cu_tok[b]), int(inp.cu_tok[b + 1]), int(inp.cu_sent[b]), int(inp.cu_sent[b + 1])
+            orc.decode_step(q0[b], q0[b], np.ascontiguousarray(K0[:, a0:a1]), np.ascontiguousarray(V0[:, a0:a1]),
+                            np.ascontiguousarray(sv0[:, s0:s1]), inp.sent_off[s0 + b: s1 + b + 1], inp.sent_len[s0:s1],
+                            int(inp.budget[b]))
+            done += 1
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(bl["total"] / B * done / dt / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "us_per_layer": round(dt / done * B * 1e6, 1),
+               "sample": "%d sequence-steps of layer 0 (sequences in turn), score+select+gather+attend, single thread, fp32" % done}
     return {
         "metric": "decode-step achieved HBM GB/s (score+select+gather+attn), ragged batch",
         "value": round(gbps, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -354,9 +371,11 @@ def run_ragged(args, wl):
         "mean_tokens_selected_per_head": round(n_tok_layer / (B * H), 1),
         "prefill": {"semvec_ms": round(t_sv.ms, 3),
                     "semvec_GBps": round((R * H * T_total * D * wl.elt_bytes + R * H * S_total * D * sv_bytes) / (t_sv.ms * 1e-3) / 1e9, 1)},
-        "roofline": dict(bound="hbm", kernel="score_kernel + attend_kernel (fused step)", achieved=round(gbps, 1),
-                         peak=HBM_PEAK_GBPS, unit="GB/s", frac=round(gbps / HBM_PEAK_GBPS, 4), traffic=None),
-        "cpu_baseline": None, "input_gen_s": round(gen_s, 1),
+        "roofline": dict(bound="hbm", kernel="score_kernel + select_kernel + attend_stream_kernel (batch step)", achieved=round(gbps, 1),
+                         peak=HBM_PEAK_GBPS, unit="GB/s", frac=round(gbps / HBM_PEAK_GBPS, 4),
+                         traffic=None if sv16 else measured_traffic(wl.name, "decode_step"), bytes_per_launch=int(bl["total"]),
+                         us_per_launch=round(us_per_layer, 3)),
+        "cpu_baseline": cpu, "input_gen_s": round(gen_s, 1),
     }
 
 
