@@ -34,7 +34,7 @@ def test_strerror_covers_every_status():
 
 
 @pytest.mark.parametrize("field,value", [("head_dim", 64), ("n_q_heads", 30), ("kv_dtype", 7), ("max_budget", 0),
-                                         ("n_kv_heads", 0), ("max_batch", 0), ("n_q_heads", 8 * 16)])
+                                         ("n_kv_heads", 0), ("max_batch", 0), ("n_q_heads", 8 * 16), ("semvec_dtype", 2)])
 def test_create_rejects_bad_descriptors_before_touching_the_gpu(field, value):
     kw = dict(n_layers=1, n_q_heads=32, n_kv_heads=8, max_tokens=64, max_sentences=8, max_budget=16)
     kw[field] = value
@@ -50,6 +50,13 @@ def test_null_context_and_null_out_pointer_are_invalid_arguments():
     assert lib.skv_attend(None, None, None, None, None, 0, None, None) == skv.SKV_EINVAL
     assert lib.skv_set_stream(None, None) == skv.SKV_EINVAL
     assert lib.skv_workspace_bytes(None) == 0
+    assert lib.skv_query_update(None, 1, None, None, None, 8, None, None, None) == skv.SKV_EINVAL
+    assert lib.skv_build_semvec_layers(None, None, 0, None, 0, None) == skv.SKV_EINVAL
+    assert lib.skv_token_importance_work_bytes(None, 100, 8) == -1
+    assert lib.skv_token_importance(None, None, None, 100, 8, None, None, 0) == skv.SKV_EINVAL
+    assert lib.skv_retain(None, None, 1, 1, None, 1, None, None, None, None) == skv.SKV_EINVAL
+    assert lib.skv_compact_pool(None, None, None, 1, None, 1, None, None, None) == skv.SKV_EINVAL
+    assert lib.skv_merge_lse(None, 1, None, None, None, None, None, None) == skv.SKV_EINVAL
     lib.skv_destroy(None)      # no-op
 
 
