@@ -648,7 +648,7 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
     constexpr int kOut = G * kHeadDim;                        // outputs of the block
     constexpr int kCol2 = kOut / 2;                           // float pairs over the G heads
     constexpr int kGroups = kBlockThreads / kCol2;            // split groups of the merge: 16, 8, 4, 2 for G = 1, 2, 4, 8
-    static_assert(kIter >= 1 && kGroups >= 1 && (MODE != kFused || CHUNK == kWave), "block shape");
+    static_assert(kIter >= 1 && kGroups >= 1 && CHUNK % kWave == 0, "block shape");
 
     __shared__ float sm_logit[G][CHUNK];
     // Wave partial sums of P.V (wave ww, head g, dim d at sm_red_flat[ww * kRedStride + g * 128 + d]); later the
@@ -659,7 +659,7 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
     static_assert(!kMfma || G * kHeadDim <= kRedStride, "a wave's partial sums fit in its value tile");
     __shared__ __attribute__((aligned(16))) float sm_red_flat[kRedFloats];
     __shared__ int sm_last;
-    __shared__ int32_t sm_row[kWave];
+    __shared__ int32_t sm_row[CHUNK];
 
     const int bh = blockIdx.y, b = bh / a.Hkv, h = bh % a.Hkv, split = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -676,13 +676,16 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
         __shared__ SelectShared sel_sh;
         const int32_t budget = min(sq.budget, a.idx_stride);
         if (split > 0 && j0 >= budget) return;                    // n <= budget: nothing for this split
-        if (tid < kWave) sm_row[tid] = -1;
+        if (tid < CHUNK) sm_row[tid] = -1;
         int32_t nsel, ntok;
-        // Each selected bucket that reaches into this block's 64 positions marks where it starts there
-        // and which pool row that is; one wave then fills the positions in between.
+        // Each selected bucket that reaches into this block's positions marks, in every 64-position piece it touches,
+        // where it starts there and which pool row that is; one wave per piece then fills the positions in between.
         auto mark = [&](int32_t, int32_t o, int32_t ln, int32_t, int32_t tok_pos) {
-            const int32_t lo = max(tok_pos, j0);
-            if (lo < min(tok_pos + ln, j0 + CHUNK)) sm_row[lo - j0] = o + (lo - tok_pos);
+#pragma unroll
+            for (int pc = 0; pc < CHUNK / kWave; ++pc) {
+                const int32_t lo = max(tok_pos, j0 + pc * kWave);
+                if (lo < min(tok_pos + ln, j0 + (pc + 1) * kWave)) sm_row[lo - j0] = o + (lo - tok_pos);
+            }
         };
         const float* sc = a.score + (int64_t)h * a.v.S_total + sq.sent_base;
         const int32_t* len = a.sent_len + sq.sent_base;
@@ -692,8 +695,8 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
         n = ntok;
         if (split == 0 && tid == 0 && a.n_tok_out) a.n_tok_out[bh] = n;
         __syncthreads();                                          // bucket starts are marked
-        if (w == 0) {
-            const int32_t v = sm_row[lane];
+        if (w < CHUNK / kWave) {
+            const int32_t v = sm_row[w * kWave + lane];
             int32_t hp = v >= 0 ? lane : -1;                      // position of the last bucket start at or before this lane
 #pragma unroll
             for (int o = 1; o < 64; o <<= 1) {
@@ -702,8 +705,9 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
             }
             const int32_t base = __shfl(v, max(hp, 0));
             const int32_t row = hp >= 0 ? base + (lane - hp) : -1;
-            sm_row[lane] = row;
-            if (a.tok_idx_out && j0 + lane < n) a.tok_idx_out[(int64_t)bh * a.idx_stride + j0 + lane] = row;
+            sm_row[w * kWave + lane] = row;
+            const int32_t pos = j0 + w * kWave + lane;
+            if (a.tok_idx_out && pos < n) a.tok_idx_out[(int64_t)bh * a.idx_stride + pos] = row;
         }
         __syncthreads();                                          // sm_row complete
     } else {
@@ -1363,6 +1367,13 @@ hipError_t launch_select_attend(Ctx* c, const void* q, const void* K_layer, cons
     AttArgs a = att_common(c, q, K_layer, V_layer, v, out, lse);
     a.score = score; a.sent_off = sent_off; a.sent_len = sent_len;
     a.tok_idx_out = tok_idx_out; a.n_tok_out = n_tok_out; a.idx_stride = c->d.max_budget;
+    // Every split block of a head repeats the selection; with thousands of buckets per sequence that repetition
+    // (bucket loads from L2, histogram passes) outweighs the shorter K/V phase of 64-token blocks.
+    if (v.S_total / (v.B > 0 ? v.B : 1) > kMidChunkMinSentences) {
+        const int n_splits = (c->d.max_budget + kAttChunkMid - 1) / kAttChunkMid;
+        return c->d.kv_dtype == SKV_BF16 ? launch_attend_g<2, kFused, kAttChunkMid>(c, a, n_splits)
+                                         : launch_attend_g<4, kFused, kAttChunkMid>(c, a, n_splits);
+    }
     return c->d.kv_dtype == SKV_BF16 ? launch_attend_g<2, kFused, kAttChunk>(c, a, c->max_splits)
                                      : launch_attend_g<4, kFused, kAttChunk>(c, a, c->max_splits);
 }

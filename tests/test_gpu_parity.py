@@ -524,3 +524,15 @@ def test_bf16_semvec_table_fused(U, oracle32, Hq, B):
     """The fused decode step (single sequence, small batch, batch path) on a bf16 table, every group size class."""
     wl = gen.CFG4.scaled(n_layers=1, n_q_heads=Hq, batch=B, t_range=(300, 3500), budgets=(600,))
     _fused_case(U, oracle32, wl, seed=33, layers=[0], sv_dtype="bf16")
+
+
+@pytest.mark.parametrize("dtype,B", [("bf16", 1), ("f32", 1), ("bf16", 3)])
+def test_fused_many_buckets_per_sequence(U, oracle32, dtype, B):
+    """More than 2048 buckets per sequence: the fused step runs 128-token split blocks (two 64-position pieces per block,
+    buckets spanning both pieces) and the selection with up to 6 buckets per thread in registers."""
+    wl = gen.CFG1.scaled(n_layers=1, batch=B, t_range=(5800, 6400), budgets=(700,), len_dist=("uniform", 1, 3), dtype=dtype)
+    _fused_case(U, oracle32, wl, seed=41, layers=[0])
+    wl = gen.CFG1.scaled(n_layers=1, batch=B, t_range=(9000, 9100), budgets=(130,), len_dist=("uniform", 1, 200), dtype=dtype)
+    _fused_case(U, oracle32, wl, seed=42, layers=[0])          # few, long buckets: S small, 64-token blocks; long spans
+    wl = gen.CFG1.scaled(n_layers=1, batch=B, t_range=(40000, 40100), budgets=(1000,), len_dist=("uniform", 1, 30), dtype=dtype)
+    _fused_case(U, oracle32, wl, seed=43, layers=[0])          # S > 2048 with buckets that span the 64-position pieces
