@@ -28,7 +28,7 @@ constexpr int kGatherThreads = 256;
 
 constexpr int kAttChunk = 64;         // tokens per split-K block, single-sequence step (one wave-width of logits)
 constexpr int kAttChunkMid = 128;     // tokens per split-K block of the single-sequence step when a sequence has many buckets
-constexpr int kMidChunkMinSentences = 2048;
+constexpr int kMidChunkMinSentences = 1024;
 constexpr int kAttChunkWide = 256;    // tokens per split-K block when many (sequence, head) pairs fill the GPU
 constexpr int kWideChunkMinHeads = 64;   // (sequences x KV heads) from which the batch path is used
 

@@ -528,7 +528,7 @@ def test_bf16_semvec_table_fused(U, oracle32, Hq, B):
 
 @pytest.mark.parametrize("dtype,B", [("bf16", 1), ("f32", 1), ("bf16", 3)])
 def test_fused_many_buckets_per_sequence(U, oracle32, dtype, B):
-    """More than 2048 buckets per sequence: the fused step runs 128-token split blocks (two 64-position pieces per block,
+    """More than 1024 buckets per sequence: the fused step runs 128-token split blocks (two 64-position pieces per block,
     buckets spanning both pieces) and the selection with up to 6 buckets per thread in registers."""
     wl = gen.CFG1.scaled(n_layers=1, batch=B, t_range=(5800, 6400), budgets=(700,), len_dist=("uniform", 1, 3), dtype=dtype)
     _fused_case(U, oracle32, wl, seed=41, layers=[0])
