@@ -998,7 +998,7 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
         const float* mlg = a.ml + ((qhead0 + g) * a.max_splits) * 2;
         const float* pg = a.part + ((qhead0 + g) * a.max_splits) * kHeadDim + (col % (kHeadDim / 2)) * 2;
         float M = -INFINITY, L = 0.f, o0 = 0.f, o1 = 0.f;
-        constexpr int kU = 8;
+        constexpr int kU = CHUNK >= 2 * kWave ? 4 : 8;       // loads in flight per thread: sized for a 2048-token budget
         for (int s0 = grp; s0 < nsplit; s0 += kGroups * kU) {
             unsigned long long pv[kU], mv[kU];
 #pragma unroll
