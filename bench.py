@@ -371,7 +371,7 @@ def run_ragged(args, wl):
         "mean_tokens_selected_per_head": round(n_tok_layer / (B * H), 1),
         "prefill": {"semvec_ms": round(t_sv.ms, 3),
                     "semvec_GBps": round((R * H * T_total * D * wl.elt_bytes + R * H * S_total * D * sv_bytes) / (t_sv.ms * 1e-3) / 1e9, 1)},
-        "roofline": dict(bound="hbm", kernel="score_kernel + select_kernel + attend_stream_kernel (batch step)", achieved=round(gbps, 1),
+        "roofline": dict(bound="hbm", kernel="score_kernel + select_attend_stream_kernel (batch step)", achieved=round(gbps, 1),
                          peak=HBM_PEAK_GBPS, unit="GB/s", frac=round(gbps / HBM_PEAK_GBPS, 4),
                          traffic=None if sv16 else measured_traffic(wl.name, "decode_step"), bytes_per_launch=int(bl["total"]),
                          us_per_launch=round(us_per_layer, 3)),
@@ -585,6 +585,7 @@ def main():
     ap.add_argument("--window", type=int, default=32, help="cfg3-retain: observation-window tokens")
     ap.add_argument("--keep", type=int, default=4096, help="cfg3-retain: tokens retained per layer (floor(r tau))")
     ap.add_argument("--resident-layers", type=int, default=4, help="cfg4: layers of the pool kept in HBM")
+    ap.add_argument("--batch", type=int, default=0, help="cfg4: number of sequences (default: the workload's 16)")
     ap.add_argument("--budget", type=int, default=0, help="token budget (default: the workload's largest)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--semvec-dtype", default="f32", choices=["f32", "bf16"],
@@ -607,6 +608,8 @@ def main():
         sys.exit(2)
     retain = args.workload == "cfg3-retain"
     wl = gen.CONFIGS["cfg3" if retain else args.workload]
+    if args.batch > 0 and args.workload == "cfg4":
+        wl = wl.scaled(batch=args.batch)
     if args.host_pool_layers < 0:
         args.host_pool_layers = 2 if args.workload == "cfg2" else 0
     if retain:

@@ -318,6 +318,9 @@ int skv_decode_step(skv_ctx* ctx, int32_t layer, int32_t B, const void* q_score,
     const char* Kl = (const char*)K_pool + pool_off;
     const char* Vl = (const char*)V_pool + pool_off;
     if (B * c.d.n_kv_heads >= skv::kWideChunkMinHeads) {
+        if (c.d.kv_dtype == SKV_BF16 && T_total < (1 << 24))
+            return hip_status(skv::launch_select_attend_stream(&c, q_attn, Kl, Vl, c.f_score, sent_off, sent_len, v, out, lse,
+                                                               tok_idx_out, n_tok_out));
         // batch path: the selection runs once per (sequence, head); attention reads the pool through tok_idx
         int32_t* tok_idx = tok_idx_out ? tok_idx_out : c.f_tok_idx;
         int32_t* n_tok = n_tok_out ? n_tok_out : c.f_n_tok;

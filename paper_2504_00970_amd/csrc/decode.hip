@@ -1050,36 +1050,42 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// Streaming form of the bf16 attention for batches (rows through tok_idx).  Measured on the 1024-thread kernel
-// above with 16 sequences x 8 heads: all blocks start together, load together (memory saturated for 5 us) and then
-// compute together (memory idle for 7 us), twice.  Here a block is 4 waves, a wave owns 64 consecutive retrieved
-// tokens and walks them in four 16-token MFMA tiles -- the next tile's K and V rows are requested as soon as the
-// current ones have been consumed (K by the logit MFMAs, V by its copy to LDS) -- carrying a running (max,
-// normaliser, output) per head as in flash decoding; all blocks of the launch are resident at once (16 waves per
-// CU, each with 8 KB in flight).
+// Streaming form of the bf16 attention for batches.  Measured on the 1024-thread kernel above with 16 sequences
+// x 8 heads: all blocks start together, load together (memory saturated for 5 us) and then compute together
+// (memory idle for 7 us), twice.  Here a wave owns 64 consecutive retrieved tokens and walks them in four 16-token
+// MFMA tiles -- the next tile's K and V rows are requested as soon as the current ones have been consumed (K by the
+// logit MFMAs, V by its copy to LDS) -- carrying a running (max, normaliser, output) per head as in flash decoding;
+// all blocks of the launch are resident at once (16 waves per CU, each with 8 KB in flight).
 // Tile arithmetic is that of the kernel above: S^T = K Q^T with K rows as A fragments, P rounded to bf16 with the
 // normaliser summing the rounded weights, V through a wave-private LDS tile into B fragments.
+// A block is 16 waves = 1024 retrieved tokens of one (sequence, KV head).  It first runs the selection itself from the
+// scores (as the single-sequence kernel does, redundantly with the head's other block) and keeps the pool rows of
+// its positions in registers: no selection launch, no tok_idx round trip, two partials per 2048-token budget.
+// Measured against select_kernel + a 4-wave form of this kernel that read tok_idx (16 sequences x 8 heads, budget
+// 2048): 8.7 + 37.1 us -> 39 us per layer; equal or better from 8 to 48 sequences.
 // ------------------------------------------------------------------------------------------------
-constexpr int kStreamWaves = 4;
-constexpr int kStreamThreads = kStreamWaves * kWave;
 constexpr int kStreamTiles = 4;                                   // 16-token tiles per wave
-static_assert(kStreamWaves * kStreamTiles * 16 == kAttChunkWide, "a streaming block covers one wide chunk");
+constexpr int kStreamWaves = kBlockWaves;                         // the block-level selection needs kBlockThreads threads
+constexpr int kStreamChunk = kStreamWaves * kStreamTiles * 16;    // 1024 tokens per block, one position per thread
+static_assert(kStreamChunk == kBlockThreads, "one retrieved position per thread");
 
 template <int G>
-__global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void attend_stream_kernel(AttArgs a) {
-    constexpr int CHUNK = kAttChunkWide;
+__global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void select_attend_stream_kernel(AttArgs a) {
+    constexpr int NW = kStreamWaves;
+    constexpr int kThreads = kBlockThreads;
+    constexpr int CHUNK = kStreamChunk;
     constexpr int kRowBytes = kHeadDim * 2;
     constexpr int kVPitch = 2 * kHeadDim + 16;                    // bytes per value row in LDS
     constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
     constexpr int kOut = G * kHeadDim, kCol2 = kOut / 2;
-    constexpr int kColsPerThread = (kCol2 + kStreamThreads - 1) / kStreamThreads;
+    constexpr int kColsPerThread = (kCol2 + kThreads - 1) / kThreads;
     typedef short bf16x4 __attribute__((ext_vector_type(4)));
     typedef float f32x4 __attribute__((ext_vector_type(4)));
     static_assert(G * kHeadDim * 4 <= 16 * kVPitch, "a wave's partial sums fit in its value tile");
 
-    __shared__ __attribute__((aligned(16))) char sm_v[kStreamWaves][16 * kVPitch];   // value tile, later the wave's partial sums
+    __shared__ __attribute__((aligned(16))) char sm_v[NW][16 * kVPitch];             // value tile, later the wave's partial sums
     __shared__ __attribute__((aligned(16))) unsigned short sm_q[16][kHeadDim];       // the group's queries, rows >= G zero
-    __shared__ float sm_wmax[kStreamWaves][16], sm_wsum[kStreamWaves][16];
+    __shared__ float sm_wmax[NW][16], sm_wsum[NW][16];
     __shared__ int sm_last;
 
     const int bh = blockIdx.y, b = bh / a.Hkv, h = bh % a.Hkv, split = blockIdx.x;
@@ -1091,10 +1097,61 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
     const int32_t j0 = split * CHUNK;
     const int slot = split * (CHUNK / kWave);
     SKV_T(0);
-    const int32_t n = min(a.n_tok[bh], a.idx_stride);
+
+    auto load_queries = [&]() {   // queries of the group -> LDS (16 bytes per thread: 16 rows x 256 bytes)
+        if (tid < 256) {
+            const int row = tid >> 4, piece = tid & 15;
+            uint4 t = make_uint4(0, 0, 0, 0);
+            if (row < G) t = *reinterpret_cast<const uint4*>(a.q + ((qhead0 + row) * kHeadDim) * 2 + 16 * piece);
+            *reinterpret_cast<uint4*>(&sm_q[row][8 * piece]) = t;
+        }
+    };
+
+    int32_t n;                    // retrieved tokens of this (sequence, head)
+    int32_t xi;                   // pool row of this thread's position
+    {
+        __shared__ SelectShared sel_sh;
+        __shared__ int32_t sm_row[CHUNK];
+        const int32_t budget = min(sq.budget, a.idx_stride);
+        if (split > 0 && j0 >= budget) return;                    // n <= budget: nothing for this split
+        load_queries();
+        sm_row[tid] = -1;
+        // A selected bucket that reaches into this block's positions marks, in every 64-position piece it touches,
+        // where it starts there and which pool row that is; each wave then fills the positions of its own piece.
+        auto mark = [&](int32_t, int32_t o, int32_t ln, int32_t, int32_t tok_pos) {
+            const int32_t hi = min(tok_pos + ln, j0 + CHUNK);
+            int32_t lo = max(tok_pos, j0);
+            while (lo < hi) {
+                sm_row[lo - j0] = o + (lo - tok_pos);
+                lo = j0 + (((lo - j0) >> 6) + 1) * kWave;
+            }
+        };
+        const float* sc = a.score + (int64_t)h * a.v.S_total + sq.sent_base;
+        const int32_t* len = a.sent_len + sq.sent_base;
+        const int32_t* off = a.sent_off + sq.sent_base + (a.v.cu_sent ? b : 0);
+        int32_t nsel, ntok;
+        if (sq.n_sent <= 2 * kBlockThreads) select_block<2, false>(sc, len, off, sq.n_sent, budget, sel_sh, mark, &nsel, &ntok);
+        else select_block<kSelKreg, false>(sc, len, off, sq.n_sent, budget, sel_sh, mark, &nsel, &ntok);
+        n = ntok;
+        if (split == 0 && tid == 0 && a.n_tok_out) a.n_tok_out[bh] = n;
+        __syncthreads();                                          // bucket starts are marked, queries are in LDS
+        {
+            const int32_t v = sm_row[tid];
+            int32_t hp = v >= 0 ? lane : -1;                      // position of the last bucket start at or before this lane
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int32_t t = __shfl_up(hp, o);
+                if (lane >= o) hp = max(hp, t);
+            }
+            const int32_t base = __shfl(v, max(hp, 0));
+            xi = hp >= 0 ? base + (lane - hp) : -1;
+            const int32_t pos = j0 + tid;
+            if (a.tok_idx_out && pos < n) a.tok_idx_out[(int64_t)bh * a.idx_stride + pos] = xi;
+        }
+    }
     if (n <= 0) {
         if (split == 0) {
-            for (int i = tid; i < kOut; i += kStreamThreads) a.out[qhead0 * kHeadDim + i] = 0.f;
+            for (int i = tid; i < kOut; i += kThreads) a.out[qhead0 * kHeadDim + i] = 0.f;
             if (a.lse && tid < G) a.lse[qhead0 + tid] = -INFINITY;
         }
         return;
@@ -1105,16 +1162,10 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
 
     // this lane's token of the wave's 64 (clamped; validity travels as a ballot)
     const int jw = kWave * w + lane;
-    const int32_t xi = a.tok_idx[(int64_t)bh * a.idx_stride + j0 + min(jw, cnt - 1)];
     const bool lv_lane = jw < cnt && xi >= 0 && xi < sq.n_tok_ctx;
     const int32_t row_lane = min(max(xi, 0), max(sq.n_tok_ctx - 1, 0));
-    {   // queries of the group -> LDS (16 bytes per thread: 16 rows x 256 bytes)
-        const int row = tid >> 4, piece = tid & 15;
-        uint4 t = make_uint4(0, 0, 0, 0);
-        if (row < G) t = *reinterpret_cast<const uint4*>(a.q + ((qhead0 + row) * kHeadDim) * 2 + 16 * piece);
-        *reinterpret_cast<uint4*>(&sm_q[row][8 * piece]) = t;
-    }
     const unsigned long long vmask = __ballot(lv_lane);
+    const bool active = vmask != 0ull;                            // wave-uniform: a wave past the end streams nothing
     const char* Kh = a.Kb + ((int64_t)h * a.v.T_total + sq.tok_base) * kRowBytes;
     const char* Vh = a.Vb + ((int64_t)h * a.v.T_total + sq.tok_base) * kRowBytes;
     const float scale = kLog2e * rsqrtf((float)kHeadDim);
@@ -1132,8 +1183,7 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
             v[ii] = *reinterpret_cast<const uint4*>(Vh + offV);
         }
     };
-    issue(0, kA, vR);
-    __syncthreads();                                              // sm_q is complete
+    if (active) issue(0, kA, vR);
     SKV_T(5);
 
     float m_run = -INFINITY, l_run = 0.f;                         // per head t16; l_run covers this lane's tokens only
@@ -1143,83 +1193,85 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
     char* vt_b = sm_v[w];
     const unsigned short* vt = reinterpret_cast<const unsigned short*>(vt_b);
 
+    if (active) {
 #pragma unroll
-    for (int i = 0; i < kStreamTiles; ++i) {
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < kStreamTiles; ++i) {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int s2 = 0; s2 < 4; ++s2) {
-            const uint4 qq = *reinterpret_cast<const uint4*>(&sm_q[t16][32 * s2 + 8 * qd]);
-            acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4, make_uint2(kA[s2].x, kA[s2].y)),
-                                                            __builtin_bit_cast(bf16x4, make_uint2(qq.x, qq.y)), acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4, make_uint2(kA[s2].z, kA[s2].w)),
-                                                            __builtin_bit_cast(bf16x4, make_uint2(qq.z, qq.w)), acc, 0, 0, 0);
+            for (int s2 = 0; s2 < 4; ++s2) {
+                const uint4 qq = *reinterpret_cast<const uint4*>(&sm_q[t16][32 * s2 + 8 * qd]);
+                acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4, make_uint2(kA[s2].x, kA[s2].y)),
+                                                                __builtin_bit_cast(bf16x4, make_uint2(qq.x, qq.y)), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4, make_uint2(kA[s2].z, kA[s2].w)),
+                                                                __builtin_bit_cast(bf16x4, make_uint2(qq.z, qq.w)), acc, 0, 0, 0);
+            }
+            const unsigned int tm = (unsigned int)(vmask >> (16 * i)) & 0xffffu;   // bit t: token t of the tile is real
+            // the tile's value rows go to the wave's LDS tile (rows of masked tokens as zeros) ...
+#pragma unroll
+            for (int ii = 0; ii < 4; ++ii) {
+                const bool lr = (tm >> (4 * ii + qd)) & 1u;
+                *reinterpret_cast<uint4*>(vt_b + (4 * ii + qd) * kVPitch + 16 * t16) = lr ? vR[ii] : make_uint4(0, 0, 0, 0);
+            }
+            // ... which frees the row registers for the next tile: its loads fly during this tile's softmax and P.V
+            if (i + 1 < kStreamTiles) issue(i + 1, kA, vR);
+            float sj[4], mt = -INFINITY;
+            bool lv[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                lv[j] = (tm >> (4 * qd + j)) & 1u;
+                sj[j] = lv[j] ? acc[j] * scale : -INFINITY;
+                mt = fmaxf(mt, sj[j]);
+            }
+            mt = fmaxf(mt, __shfl_xor(mt, 16));
+            mt = fmaxf(mt, __shfl_xor(mt, 32));
+            const float m_new = fmaxf(m_run, mt);
+            const float alpha = (m_new > -INFINITY) ? exp2f(m_run - m_new) : 1.f;   // m_run == -inf gives 0
+            unsigned short pb[4];
+            float lw = 0.f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float p = lv[j] ? exp2f(sj[j] - m_new) : 0.f;
+                uint32_t u = __float_as_uint(p);
+                u += 0x7fffu + ((u >> 16) & 1u);                      // round to nearest even bf16
+                pb[j] = (unsigned short)(u >> 16);
+                lw += __uint_as_float((uint32_t)pb[j] << 16);         // the normaliser sums the rounded weights
+            }
+            l_run = l_run * alpha + lw;
+            m_run = m_new;
+            // running outputs: row 4qd+j of o is head 4qd+j, whose factor sits in lane 4qd+j
+            float ar[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) ar[j] = __shfl(alpha, 4 * qd + j);
+#pragma unroll
+            for (int dt = 0; dt < kHeadDim / 16; ++dt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) o[dt][j] *= ar[j];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");    // the tile is private to the wave: order only
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const bf16x4 pa = {(short)pb[0], (short)pb[1], (short)pb[2], (short)pb[3]};
+#pragma unroll
+            for (int dt = 0; dt < kHeadDim / 16; ++dt) {
+                bf16x4 vb;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) vb[j] = (short)vt[(4 * qd + j) * (kVPitch / 2) + 16 * dt + t16];
+                o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, vb, o[dt], 0, 0, 0);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");    // reads of this tile precede the next tile's writes
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         }
-        const unsigned int tm = (unsigned int)(vmask >> (16 * i)) & 0xffffu;   // bit t: token t of the tile is real
-        // the tile's value rows go to the wave's LDS tile (rows of masked tokens as zeros) ...
-#pragma unroll
-        for (int ii = 0; ii < 4; ++ii) {
-            const bool lr = (tm >> (4 * ii + qd)) & 1u;
-            *reinterpret_cast<uint4*>(vt_b + (4 * ii + qd) * kVPitch + 16 * t16) = lr ? vR[ii] : make_uint4(0, 0, 0, 0);
-        }
-        // ... which frees the row registers for the next tile: its loads fly during this tile's softmax and P.V
-        if (i + 1 < kStreamTiles) issue(i + 1, kA, vR);
-        float sj[4], mt = -INFINITY;
-        bool lv[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            lv[j] = (tm >> (4 * qd + j)) & 1u;
-            sj[j] = lv[j] ? acc[j] * scale : -INFINITY;
-            mt = fmaxf(mt, sj[j]);
-        }
-        mt = fmaxf(mt, __shfl_xor(mt, 16));
-        mt = fmaxf(mt, __shfl_xor(mt, 32));
-        const float m_new = fmaxf(m_run, mt);
-        const float alpha = (m_new > -INFINITY) ? exp2f(m_run - m_new) : 1.f;   // m_run == -inf gives 0
-        unsigned short pb[4];
-        float lw = 0.f;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const float p = lv[j] ? exp2f(sj[j] - m_new) : 0.f;
-            uint32_t u = __float_as_uint(p);
-            u += 0x7fffu + ((u >> 16) & 1u);                      // round to nearest even bf16
-            pb[j] = (unsigned short)(u >> 16);
-            lw += __uint_as_float((uint32_t)pb[j] << 16);         // the normaliser sums the rounded weights
-        }
-        l_run = l_run * alpha + lw;
-        m_run = m_new;
-        // running outputs: row 4qd+j of o is head 4qd+j, whose factor sits in lane 4qd+j
-        float ar[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) ar[j] = __shfl(alpha, 4 * qd + j);
-#pragma unroll
-        for (int dt = 0; dt < kHeadDim / 16; ++dt)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) o[dt][j] *= ar[j];
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");    // the tile is private to the wave: order only
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        const bf16x4 pa = {(short)pb[0], (short)pb[1], (short)pb[2], (short)pb[3]};
-#pragma unroll
-        for (int dt = 0; dt < kHeadDim / 16; ++dt) {
-            bf16x4 vb;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) vb[j] = (short)vt[(4 * qd + j) * (kVPitch / 2) + 16 * dt + t16];
-            o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, vb, o[dt], 0, 0, 0);
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");    // reads of this tile precede the next tile's writes
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
     SKV_T(6);
 
-    // ---- the block's four waves combine: common max per head, partial sums through the value tiles ----------
+    // ---- the block's waves combine: common max per head, partial sums through the value tiles ------------------
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
     if (qd == 0) sm_wmax[w][t16] = m_run;
     __syncthreads();
     float mb = -INFINITY;
 #pragma unroll
-    for (int ww = 0; ww < kStreamWaves; ++ww) mb = fmaxf(mb, sm_wmax[ww][t16]);
+    for (int ww = 0; ww < NW; ++ww) mb = fmaxf(mb, sm_wmax[ww][t16]);
     const float cw = (m_run > -INFINITY) ? exp2f(m_run - mb) : 0.f;
     if (qd == 0) sm_wsum[w][t16] = l_run * cw;
     {
@@ -1237,16 +1289,16 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
     if (tid < G) {
         float lb = 0.f, mh = -INFINITY;
 #pragma unroll
-        for (int ww = 0; ww < kStreamWaves; ++ww) { lb += sm_wsum[ww][tid]; mh = fmaxf(mh, sm_wmax[ww][tid]); }
+        for (int ww = 0; ww < NW; ++ww) { lb += sm_wsum[ww][tid]; mh = fmaxf(mh, sm_wmax[ww][tid]); }
         float* dst = a.ml + (((qhead0 + tid) * a.max_splits) + slot) * 2;
         st_agent(dst, mh);
         st_agent(dst + 1, lb);
     }
-    for (int i = tid; i < kOut; i += kStreamThreads) {
+    for (int i = tid; i < kOut; i += kThreads) {
         const int g = i / kHeadDim, d = i % kHeadDim;
         float sum = 0.f;
 #pragma unroll
-        for (int ww = 0; ww < kStreamWaves; ++ww) sum += reinterpret_cast<const float*>(sm_v[ww])[i];
+        for (int ww = 0; ww < NW; ++ww) sum += reinterpret_cast<const float*>(sm_v[ww])[i];
         st_agent(a.part + (((qhead0 + g) * a.max_splits) + slot) * kHeadDim + d, sum);
     }
     SKV_T(7);
@@ -1262,13 +1314,13 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
     if (!sm_last) return;
 #pragma unroll
     for (int c = 0; c < kColsPerThread; ++c) {
-        const int col = tid + c * kStreamThreads;
+        const int col = tid + c * kThreads;
         if (col >= kCol2) break;
         const int g = col / (kHeadDim / 2);
         const float* mlg = a.ml + ((qhead0 + g) * a.max_splits) * 2;
         const float* pg = a.part + ((qhead0 + g) * a.max_splits) * kHeadDim + (col % (kHeadDim / 2)) * 2;
         float M = -INFINITY, L = 0.f, o0 = 0.f, o1 = 0.f;
-        constexpr int kU = 8;
+        constexpr int kU = 2;                                     // loads in flight per thread: sized for a 2048-token budget
         for (int s0 = 0; s0 < nsplit; s0 += kU) {
             unsigned long long pv[kU], mv[kU];
 #pragma unroll
@@ -1299,13 +1351,13 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
     SKV_T(9);
 }
 
-static hipError_t launch_attend_stream(Ctx* c, const AttArgs& a, int32_t n_splits) {
-    const dim3 grid(n_splits, a.v.B * c->d.n_kv_heads), block(kStreamThreads);
+static hipError_t launch_select_attend_stream_g(Ctx* c, const AttArgs& a, int32_t n_splits) {
+    const dim3 grid(n_splits, a.v.B * c->d.n_kv_heads), block(kBlockThreads);
     switch (c->G) {
-        case 1: hipLaunchKernelGGL(attend_stream_kernel<1>, grid, block, 0, c->stream, a); break;
-        case 2: hipLaunchKernelGGL(attend_stream_kernel<2>, grid, block, 0, c->stream, a); break;
-        case 4: hipLaunchKernelGGL(attend_stream_kernel<4>, grid, block, 0, c->stream, a); break;
-        case 8: hipLaunchKernelGGL(attend_stream_kernel<8>, grid, block, 0, c->stream, a); break;
+        case 1: hipLaunchKernelGGL(select_attend_stream_kernel<1>, grid, block, 0, c->stream, a); break;
+        case 2: hipLaunchKernelGGL(select_attend_stream_kernel<2>, grid, block, 0, c->stream, a); break;
+        case 4: hipLaunchKernelGGL(select_attend_stream_kernel<4>, grid, block, 0, c->stream, a); break;
+        case 8: hipLaunchKernelGGL(select_attend_stream_kernel<8>, grid, block, 0, c->stream, a); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -1355,10 +1407,22 @@ hipError_t launch_attend_indirect(Ctx* c, const void* q, const void* K_layer, co
     AttArgs a = att_common(c, q, K_layer, V_layer, v, out, lse);
     a.n_tok = n_tok; a.tok_idx = tok_idx; a.idx_stride = c->d.max_budget;
     const int n_splits = (c->d.max_budget + kAttChunkWide - 1) / kAttChunkWide;
-    if (c->d.kv_dtype != SKV_BF16) return launch_attend_g<4, kIndirect, kAttChunkWide>(c, a, n_splits);
-    // the streaming kernel addresses rows with 32-bit byte offsets inside a (head, sequence) slab
-    if (v.T_total < (1 << 24)) return launch_attend_stream(c, a, n_splits);
-    return launch_attend_g<2, kIndirect, kAttChunkWide>(c, a, n_splits);
+    return c->d.kv_dtype == SKV_BF16 ? launch_attend_g<2, kIndirect, kAttChunkWide>(c, a, n_splits)
+                                     : launch_attend_g<4, kIndirect, kAttChunkWide>(c, a, n_splits);
+}
+
+// Batch form of the fused step (bf16 pools below 2^24 tokens, addressed with 32-bit byte offsets inside a
+// (head, sequence) slab): 1024-token blocks that select, then stream.
+hipError_t launch_select_attend_stream(Ctx* c, const void* q, const void* K_layer, const void* V_layer, const float* score,
+                                       const int32_t* sent_off, const int32_t* sent_len, const SeqView& v, float* out,
+                                       float* lse, int32_t* tok_idx_out, int32_t* n_tok_out) {
+    if (c->d.kv_dtype != SKV_BF16 || v.T_total >= (1 << 24)) return hipErrorInvalidValue;
+    AttArgs a = att_common(c, q, K_layer, V_layer, v, out, lse);
+    a.score = score; a.sent_off = sent_off; a.sent_len = sent_len;
+    a.tok_idx_out = tok_idx_out; a.n_tok_out = n_tok_out; a.idx_stride = c->d.max_budget;
+    int n_splits = (c->d.max_budget + kStreamChunk - 1) / kStreamChunk;
+    if (n_splits < 1) n_splits = 1;       // block 0 still writes the empty-selection result
+    return launch_select_attend_stream_g(c, a, n_splits);
 }
 
 hipError_t launch_select_attend(Ctx* c, const void* q, const void* K_layer, const void* V_layer, const float* score,

@@ -97,6 +97,11 @@ hipError_t launch_select_attend(Ctx* c, const void* q, const void* K_layer, cons
                                 const int32_t* sent_off, const int32_t* sent_len, const SeqView& v, float* out,
                                 float* lse, int32_t* tok_idx_out, int32_t* n_tok_out);
 
+// The same for batches with bf16 pools of fewer than 2^24 tokens: 1024-token blocks, streaming attention.
+hipError_t launch_select_attend_stream(Ctx* c, const void* q, const void* K_layer, const void* V_layer, const float* score,
+                                       const int32_t* sent_off, const int32_t* sent_len, const SeqView& v, float* out,
+                                       float* lse, int32_t* tok_idx_out, int32_t* n_tok_out);
+
 hipError_t launch_merge_lse(Ctx* c, const float* out_a, const float* lse_a, const float* out_b, const float* lse_b,
                             int32_t n_heads, float* out, float* lse);
 

@@ -362,12 +362,21 @@ def test_fused_ragged_batch_70b_heads(U, oracle32):
     _fused_case(U, oracle32, wl, seed=4, layers=[0, 1])
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("Hq", [8, 16, 32, 64])
-def test_fused_batch_path_many_heads(U, oracle32, Hq):
-    """Eight or more sequences x 8 KV heads take the batch path (one selection per head, 256-token blocks; the
-    streaming MFMA kernel for bf16), for every group size."""
-    wl = gen.CFG4.scaled(n_layers=1, n_q_heads=Hq, batch=9, t_range=(200, 3000), budgets=(700,))
+def test_fused_batch_path_many_heads(U, oracle32, Hq, dtype):
+    """Eight or more sequences x 8 KV heads take the batch path, for every group size: bf16 pools run the selection
+    inside 1024-token streaming MFMA blocks, fp32 pools run select_kernel and 256-token blocks through tok_idx."""
+    wl = gen.CFG4.scaled(n_layers=1, n_q_heads=Hq, batch=9, t_range=(200, 3000), budgets=(700,), dtype=dtype)
     _fused_case(U, oracle32, wl, seed=6, layers=[0])
+
+
+@pytest.mark.parametrize("budget", [1024, 1025, 1500, 2048])
+def test_fused_batch_path_two_blocks_per_head(U, oracle32, budget):
+    """Budgets around the 1024-token block of the bf16 batch kernel: a full block, one token in the second block, a
+    second block whose last waves have nothing to stream, two full blocks; contexts shorter than the budget too."""
+    wl = gen.CFG4.scaled(n_layers=1, n_q_heads=32, batch=8, t_range=(900, 5000), budgets=(budget,))
+    _fused_case(U, oracle32, wl, seed=8, layers=[0])
 
 
 @pytest.mark.parametrize("dtype,budget", [("f32", 700), ("bf16", 2), ("bf16", 256), ("bf16", 257), ("bf16", 5000)])
