@@ -1392,14 +1392,18 @@ hipError_t launch_attend(Ctx* c, const void* q, const void* K_sel, const void* V
                          const int32_t* n_tok, int32_t budget, const SeqView& v, float* out, float* lse) {
     AttArgs a = att_common(c, q, K_sel, V_sel, v, out, lse);
     a.n_tok = n_tok; a.row_stride = row_stride;
-    const int chunk = wide_chunks(c, v) ? kAttChunkWide : kAttChunk;
+    // Few (sequence, head) pairs: 128-token blocks.  The merging block's uncached reads of the partials cost about
+    // 0.1 us per split, more than a 64-token block saves on its K/V rows (budget 2048: 11.0 us with 64-token blocks,
+    // 9.2 with 128, 10.8 with 256; from a budget of 4096 on 256-token blocks are ahead).
+    const bool wide = wide_chunks(c, v) || budget >= 4096;
+    const int chunk = wide ? kAttChunkWide : kAttChunkMid;
     int n_splits = (budget + chunk - 1) / chunk;
     if (n_splits < 1) n_splits = 1;       // block 0 still writes the empty-selection result
-    if (wide_chunks(c, v))
+    if (wide)
         return c->d.kv_dtype == SKV_BF16 ? launch_attend_g<2, kDirect, kAttChunkWide>(c, a, n_splits)
                                          : launch_attend_g<4, kDirect, kAttChunkWide>(c, a, n_splits);
-    return c->d.kv_dtype == SKV_BF16 ? launch_attend_g<2, kDirect, kAttChunk>(c, a, n_splits)
-                                     : launch_attend_g<4, kDirect, kAttChunk>(c, a, n_splits);
+    return c->d.kv_dtype == SKV_BF16 ? launch_attend_g<2, kDirect, kAttChunkMid>(c, a, n_splits)
+                                     : launch_attend_g<4, kDirect, kAttChunkMid>(c, a, n_splits);
 }
 
 hipError_t launch_attend_indirect(Ctx* c, const void* q, const void* K_layer, const void* V_layer, const int32_t* tok_idx,
