@@ -202,8 +202,8 @@ int skv_attend(skv_ctx* ctx, const void* q_attn, const void* K_sel, const void* 
  * skv_gather + skv_attend run per sequence.
  * q_score, q_attn  dev [B][Hq][D] kv_dtype (may alias)
  * K_pool, V_pool   dev [L][Hkv][T_total][D]        semvec dev [L][Hkv][S_total][D]
- * cu_tok   dev [B+1]  token offset of each sequence in the pool (cu_tok[B] == T_total)
- * cu_sent  dev [B+1]  bucket offset of each sequence (cu_sent[B] == S_total)
+ * cu_tok   dev [B+1]  token offset of each sequence in the pool (cu_tok[0] == 0, cu_tok[B] == T_total)
+ * cu_sent  dev [B+1]  bucket offset of each sequence (cu_sent[0] == 0, cu_sent[B] == S_total)
  * sent_off dev [S_total + B]  per sequence b, S_b + 1 positions local to the sequence, stored at
  *                             sent_off + cu_sent[b] + b;   sent_len dev [S_total]
  * budget   dev [B]   per-sequence token budget, each <= max_budget

@@ -1109,9 +1109,10 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(4
 
     int32_t n;                    // retrieved tokens of this (sequence, head)
     int32_t xi;                   // pool row of this thread's position
+    __shared__ int32_t sm_row[CHUNK];                            // bucket-start marks, later the pool row of every position
+    __shared__ int sm_next_tile;
     {
         __shared__ SelectShared sel_sh;
-        __shared__ int32_t sm_row[CHUNK];
         const int32_t budget = min(sq.budget, a.idx_stride);
         if (split > 0 && j0 >= budget) return;                    // n <= budget: nothing for this split
         load_queries();
@@ -1160,30 +1161,37 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(4
     if (split >= nsplit) return;
     const int32_t cnt = min(CHUNK, n - j0);
 
-    // this lane's token of the wave's 64 (clamped; validity travels as a ballot)
-    const int jw = kWave * w + lane;
-    const bool lv_lane = jw < cnt && xi >= 0 && xi < sq.n_tok_ctx;
-    const int32_t row_lane = min(max(xi, 0), max(sq.n_tok_ctx - 1, 0));
-    const unsigned long long vmask = __ballot(lv_lane);
-    const bool active = vmask != 0ull;                            // wave-uniform: a wave past the end streams nothing
+    // The block's positions are walked in 16-token tiles handed out dynamically: a wave starts with tile w and takes the
+    // next free one from an LDS counter whenever it finishes one, so the waves that memory serves first do more tiles
+    // and all 16 keep loads in flight until the block's last tile (with four fixed tiles per wave the slowest wave ran
+    // about 5 us behind the first).  Rows of unreal positions are stored as -1.
+    sm_row[tid] = (tid < cnt && xi >= 0 && xi < sq.n_tok_ctx) ? xi : -1;
+    if (tid == 0) sm_next_tile = NW;
+    const int ntiles = (cnt + 15) / 16;
     const char* Kh = a.Kb + ((int64_t)h * a.v.T_total + sq.tok_base) * kRowBytes;
     const char* Vh = a.Vb + ((int64_t)h * a.v.T_total + sq.tok_base) * kRowBytes;
     const float scale = kLog2e * rsqrtf((float)kHeadDim);
+    __syncthreads();                                              // rows and the tile counter are in LDS
     SKV_T(4);
 
     uint4 kA[4], vR[4];
-    auto issue = [&](int i, uint4* k, uint4* v) {
+    // rows of a tile: lanes with the same t16 hold the row of the tile's token t16 (-1: not real)
+    auto rows_of = [&](int tile) { return sm_row[16 * tile + t16]; };
+    auto issue = [&](int32_t rowt, uint4* k, uint4* v) {
         // 32-bit byte offsets from the (head, sequence) base: the host only uses this kernel below 2^24 tokens
-        const uint32_t offK = (uint32_t)__shfl(row_lane, 16 * i + t16) * kRowBytes + 16u * qd;
+        const int32_t rc = max(rowt, 0);
+        const uint32_t offK = (uint32_t)rc * kRowBytes + 16u * qd;
 #pragma unroll
         for (int s2 = 0; s2 < 4; ++s2) k[s2] = *reinterpret_cast<const uint4*>(Kh + (offK + 64u * s2));
 #pragma unroll
         for (int ii = 0; ii < 4; ++ii) {
-            const uint32_t offV = (uint32_t)__shfl(row_lane, 16 * i + 4 * ii + qd) * kRowBytes + 16u * t16;
+            const uint32_t offV = (uint32_t)__shfl(rc, 4 * ii + qd) * kRowBytes + 16u * t16;
             v[ii] = *reinterpret_cast<const uint4*>(Vh + offV);
         }
     };
-    if (active) issue(0, kA, vR);
+    int tile = w;                                                 // wave-uniform
+    int32_t row_cur = tile < ntiles ? rows_of(tile) : -1;
+    if (tile < ntiles) issue(row_cur, kA, vR);
     SKV_T(5);
 
     float m_run = -INFINITY, l_run = 0.f;                         // per head t16; l_run covers this lane's tokens only
@@ -1193,74 +1201,77 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(4
     char* vt_b = sm_v[w];
     const unsigned short* vt = reinterpret_cast<const unsigned short*>(vt_b);
 
-    if (active) {
+    while (tile < ntiles) {
+        // the wave's next tile, asked for early so that its rows are known when this tile's registers come free
+        int nxt = 0;
+        if (lane == 0) nxt = atomicAdd(&sm_next_tile, 1);
+        nxt = __builtin_amdgcn_readfirstlane(nxt);
+        const unsigned int tm = (unsigned int)__ballot(row_cur >= 0) & 0xffffu;   // bit t: token t of the tile is real
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int i = 0; i < kStreamTiles; ++i) {
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int s2 = 0; s2 < 4; ++s2) {
-                const uint4 qq = *reinterpret_cast<const uint4*>(&sm_q[t16][32 * s2 + 8 * qd]);
-                acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4, make_uint2(kA[s2].x, kA[s2].y)),
-                                                                __builtin_bit_cast(bf16x4, make_uint2(qq.x, qq.y)), acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4, make_uint2(kA[s2].z, kA[s2].w)),
-                                                                __builtin_bit_cast(bf16x4, make_uint2(qq.z, qq.w)), acc, 0, 0, 0);
-            }
-            const unsigned int tm = (unsigned int)(vmask >> (16 * i)) & 0xffffu;   // bit t: token t of the tile is real
-            // the tile's value rows go to the wave's LDS tile (rows of masked tokens as zeros) ...
-#pragma unroll
-            for (int ii = 0; ii < 4; ++ii) {
-                const bool lr = (tm >> (4 * ii + qd)) & 1u;
-                *reinterpret_cast<uint4*>(vt_b + (4 * ii + qd) * kVPitch + 16 * t16) = lr ? vR[ii] : make_uint4(0, 0, 0, 0);
-            }
-            // ... which frees the row registers for the next tile: its loads fly during this tile's softmax and P.V
-            if (i + 1 < kStreamTiles) issue(i + 1, kA, vR);
-            float sj[4], mt = -INFINITY;
-            bool lv[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                lv[j] = (tm >> (4 * qd + j)) & 1u;
-                sj[j] = lv[j] ? acc[j] * scale : -INFINITY;
-                mt = fmaxf(mt, sj[j]);
-            }
-            mt = fmaxf(mt, __shfl_xor(mt, 16));
-            mt = fmaxf(mt, __shfl_xor(mt, 32));
-            const float m_new = fmaxf(m_run, mt);
-            const float alpha = (m_new > -INFINITY) ? exp2f(m_run - m_new) : 1.f;   // m_run == -inf gives 0
-            unsigned short pb[4];
-            float lw = 0.f;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float p = lv[j] ? exp2f(sj[j] - m_new) : 0.f;
-                uint32_t u = __float_as_uint(p);
-                u += 0x7fffu + ((u >> 16) & 1u);                      // round to nearest even bf16
-                pb[j] = (unsigned short)(u >> 16);
-                lw += __uint_as_float((uint32_t)pb[j] << 16);         // the normaliser sums the rounded weights
-            }
-            l_run = l_run * alpha + lw;
-            m_run = m_new;
-            // running outputs: row 4qd+j of o is head 4qd+j, whose factor sits in lane 4qd+j
-            float ar[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) ar[j] = __shfl(alpha, 4 * qd + j);
-#pragma unroll
-            for (int dt = 0; dt < kHeadDim / 16; ++dt)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) o[dt][j] *= ar[j];
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");    // the tile is private to the wave: order only
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            const bf16x4 pa = {(short)pb[0], (short)pb[1], (short)pb[2], (short)pb[3]};
-#pragma unroll
-            for (int dt = 0; dt < kHeadDim / 16; ++dt) {
-                bf16x4 vb;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) vb[j] = (short)vt[(4 * qd + j) * (kVPitch / 2) + 16 * dt + t16];
-                o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, vb, o[dt], 0, 0, 0);
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");    // reads of this tile precede the next tile's writes
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        for (int s2 = 0; s2 < 4; ++s2) {
+            const uint4 qq = *reinterpret_cast<const uint4*>(&sm_q[t16][32 * s2 + 8 * qd]);
+            acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4, make_uint2(kA[s2].x, kA[s2].y)),
+                                                            __builtin_bit_cast(bf16x4, make_uint2(qq.x, qq.y)), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4, make_uint2(kA[s2].z, kA[s2].w)),
+                                                            __builtin_bit_cast(bf16x4, make_uint2(qq.z, qq.w)), acc, 0, 0, 0);
         }
+        // the tile's value rows go to the wave's LDS tile (rows of masked tokens as zeros) ...
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii) {
+            const bool lr = (tm >> (4 * ii + qd)) & 1u;
+            *reinterpret_cast<uint4*>(vt_b + (4 * ii + qd) * kVPitch + 16 * t16) = lr ? vR[ii] : make_uint4(0, 0, 0, 0);
+        }
+        // ... which frees the row registers for the next tile: its loads fly during this tile's softmax and P.V
+        row_cur = nxt < ntiles ? rows_of(nxt) : -1;
+        if (nxt < ntiles) issue(row_cur, kA, vR);
+        tile = nxt;
+        float sj[4], mt = -INFINITY;
+        bool lv[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            lv[j] = (tm >> (4 * qd + j)) & 1u;
+            sj[j] = lv[j] ? acc[j] * scale : -INFINITY;
+            mt = fmaxf(mt, sj[j]);
+        }
+        mt = fmaxf(mt, __shfl_xor(mt, 16));
+        mt = fmaxf(mt, __shfl_xor(mt, 32));
+        const float m_new = fmaxf(m_run, mt);
+        const float alpha = (m_new > -INFINITY) ? exp2f(m_run - m_new) : 1.f;   // m_run == -inf gives 0
+        unsigned short pb[4];
+        float lw = 0.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float p = lv[j] ? exp2f(sj[j] - m_new) : 0.f;
+            uint32_t u = __float_as_uint(p);
+            u += 0x7fffu + ((u >> 16) & 1u);                      // round to nearest even bf16
+            pb[j] = (unsigned short)(u >> 16);
+            lw += __uint_as_float((uint32_t)pb[j] << 16);         // the normaliser sums the rounded weights
+        }
+        l_run = l_run * alpha + lw;
+        m_run = m_new;
+        // running outputs: row 4qd+j of o is head 4qd+j, whose factor sits in lane 4qd+j
+        float ar[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) ar[j] = __shfl(alpha, 4 * qd + j);
+#pragma unroll
+        for (int dt = 0; dt < kHeadDim / 16; ++dt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) o[dt][j] *= ar[j];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");    // the tile is private to the wave: order only
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const bf16x4 pa = {(short)pb[0], (short)pb[1], (short)pb[2], (short)pb[3]};
+#pragma unroll
+        for (int dt = 0; dt < kHeadDim / 16; ++dt) {
+            bf16x4 vb;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) vb[j] = (short)vt[(4 * qd + j) * (kVPitch / 2) + 16 * dt + t16];
+            o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, vb, o[dt], 0, 0, 0);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");    // reads of this tile precede the next tile's writes
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
     SKV_T(6);
 

@@ -347,7 +347,12 @@ def _fused_case(U, oracle32, wl, seed, layers, sv_dtype="f32"):
         ctx.decode_step(li, B, qd[li], qd[li], Kd, Vd, T_total, sv, S_total, d["cu_tok"], d["cu_sent"], d["sent_off"],
                         d["sent_len"], d["budget"], out2, None, None, None)
         torch.cuda.synchronize()
-        assert torch.equal(out, out2)
+        if B * H >= 64 and wl.dtype == "bf16":
+            # the bf16 batch kernel hands its 16-token tiles to whichever wave is free: the summation order, and with
+            # it the last bits of the output, differ from call to call
+            assert (out - out2).abs().max().item() <= ATT_TOL[wl.dtype] / 4
+        else:
+            assert torch.equal(out, out2)
 
 
 def test_fused_single_sequence_matches_oracle(U, oracle32):
