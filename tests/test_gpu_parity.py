@@ -299,8 +299,8 @@ def test_attend_large_logits_do_not_overflow(U, oracle32):
 
 # ----------------------------------------------------------------------------- fused step
 
-def _fused_case(U, oracle32, wl, seed, layers, sv_dtype="f32"):
-    inp = gen.ragged_inputs(wl, seed=seed, device=U.DEV, resident_layers=len(layers))
+def _fused_case(U, oracle32, wl, seed, layers, sv_dtype="f32", seq_tokens=None, budgets=None):
+    inp = gen.ragged_inputs(wl, seed=seed, device=U.DEV, resident_layers=len(layers), seq_tokens=seq_tokens, budgets=budgets)
     B, H, Hq, D = wl.batch, wl.n_kv_heads, wl.n_q_heads, wl.head_dim
     T_total, S_total = int(inp.cu_tok[-1]), int(inp.cu_sent[-1])
     max_budget = int(inp.budget.max())
@@ -382,6 +382,17 @@ def test_fused_batch_path_two_blocks_per_head(U, oracle32, budget):
     second block whose last waves have nothing to stream, two full blocks; contexts shorter than the budget too."""
     wl = gen.CFG4.scaled(n_layers=1, n_q_heads=32, batch=8, t_range=(900, 5000), budgets=(budget,))
     _fused_case(U, oracle32, wl, seed=8, layers=[0])
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("B", [3, 8])
+def test_fused_batch_with_empty_and_tiny_sequences(U, oracle32, dtype, B):
+    """Sequences without tokens, with one token and with one bucket next to ordinary ones, budgets from 0 to more than the
+    context, on the small-batch path (B = 3) and the batch path (B = 8)."""
+    toks = [0, 1, 1500, 0, 37, 2300, 5, 0][:B]
+    buds = [64, 64, 700, 0, 1000, 0, 3, 9][:B]
+    wl = gen.CFG4.scaled(n_layers=1, n_q_heads=32, batch=B, budgets=(1000,), dtype=dtype)
+    _fused_case(U, oracle32, wl, seed=12, layers=[0], seq_tokens=toks, budgets=buds)
 
 
 @pytest.mark.parametrize("dtype,budget", [("f32", 700), ("bf16", 2), ("bf16", 256), ("bf16", 257), ("bf16", 5000)])

@@ -252,12 +252,18 @@ class RaggedInputs:
     budget: np.ndarray              # int32 [B]
 
 
-def ragged_inputs(wl: Workload, seed: int = 0, device="cpu", resident_layers: Optional[int] = None) -> RaggedInputs:
-    """Ragged batch: B sequences concatenated along the token axis and the sentence axis."""
+def ragged_inputs(wl: Workload, seed: int = 0, device="cpu", resident_layers: Optional[int] = None,
+                  seq_tokens=None, budgets=None) -> RaggedInputs:
+    """Ragged batch: B sequences concatenated along the token axis and the sentence axis.  `seq_tokens` fixes the
+    context lengths (zero allowed: a sequence without tokens or buckets), `budgets` the per-sequence budgets."""
     rng = _rng(seed, 300)
     B = wl.batch
     lo, hi = wl.t_range
-    seq_tokens = rng.integers(lo, hi + 1, size=B).astype(np.int32)
+    if seq_tokens is None:
+        seq_tokens = rng.integers(lo, hi + 1, size=B).astype(np.int32)
+    else:
+        seq_tokens = np.asarray(seq_tokens, dtype=np.int32)
+        assert seq_tokens.shape == (B,) and seq_tokens.min() >= 0
     lens = [sentence_lengths(wl.len_dist, int(seq_tokens[b]), seed, stream=1 + b) for b in range(B)]
     cu_tok = np.zeros(B + 1, dtype=np.int32)
     cu_tok[1:] = np.cumsum(seq_tokens.astype(np.int64))
@@ -273,7 +279,8 @@ def ragged_inputs(wl: Workload, seed: int = 0, device="cpu", resident_layers: Op
     for l in range(Lr):
         kv_layer(all_lengths, wl.n_kv_heads, wl.head_dim, wl.torch_dtype, seed, l, device, out_k=K[l], out_v=V[l])
     q = queries(Lr * B, wl.n_q_heads, wl.head_dim, wl.torch_dtype, seed, device).view(Lr, B, wl.n_q_heads, wl.head_dim)
-    budget = np.full(B, wl.budgets[0], dtype=np.int32)
+    budget = np.full(B, wl.budgets[0], dtype=np.int32) if budgets is None else np.asarray(budgets, dtype=np.int32)
+    assert budget.shape == (B,)
     return RaggedInputs(wl, seq_tokens, lens, cu_tok, cu_sent, sent_off, sent_len, K, V, q, budget)
 
 
