@@ -96,6 +96,33 @@ hipError_t launch_query_update(Ctx* c, int32_t B, const void* q_t, const int32_t
     return hipGetLastError();
 }
 
+// Stores that other blocks of the same launch read (possibly on another XCD, each with its own L2): device-scope
+// relaxed atomic accesses go through to the level all XCDs share, so no L2 write-back / invalidate is needed around
+// the arrival counters that publish them.
+__device__ __forceinline__ void st_agent(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_agent(int32_t* p, int32_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_agent(unsigned int* p, unsigned int v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_agent(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int32_t ld_agent(const int32_t* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned int ld_agent(const unsigned int* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long ld_agent64(const float* p) {       // two consecutive floats
+    return __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float lo_f(unsigned long long v) { return __uint_as_float((uint32_t)v); }
+__device__ __forceinline__ float hi_f(unsigned long long v) { return __uint_as_float((uint32_t)(v >> 32)); }
+
 // ------------------------------------------------------------------------------------------------
 // Scores.  score[h][s] = sum_g q[hG+g] . semvec[h][s]  =  (sum_g q[hG+g]) . semvec[h][s].
 // A semantic vector is 512 bytes = 32 lanes x float4; a wave covers 2 buckets per load instruction
@@ -103,28 +130,19 @@ hipError_t launch_query_update(Ctx* c, int32_t B, const void* q_t, const int32_t
 // buckets per head: 4 and 32 were both slower).  The group-summed query lives in registers.
 // Blocks are aligned to sequences: block x -> (sequence b, local block) by walking cu_sent.
 // ------------------------------------------------------------------------------------------------
-template <int EB, int G, int RPWV>
-__global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_kernel(const char* __restrict__ q,
-                                                                            const float* __restrict__ semvec, SeqView v,
-                                                                            int32_t Hq, float* __restrict__ score) {
-    constexpr int kRowsPerBlock = RPWV * kScoreWavesPerBlock;
-    int blk = blockIdx.x, b = 0;
-    Seq sq{};
-    for (; b < v.B; ++b) {
-        sq = seq_of(v, b);
-        const int nb = (sq.n_sent + kRowsPerBlock - 1) / kRowsPerBlock;
-        if (blk < nb) break;
-        blk -= nb;
-    }
-    if (b >= v.B) return;
-    const int h = blockIdx.y;
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int c = lane & 31, half = lane >> 5;
 
+// One wave: the RPWV buckets [row_w, row_w + RPWV) of a sequence.  q_grp = the first query of the head's group,
+// sv_seq / out_seq = the (head, sequence) slices of the table and of the scores.  AGENT: scores are stored so that
+// other blocks of the same launch can read them.
+template <int EB, int G, int RPWV, bool AGENT>
+__device__ __forceinline__ void score_wave_f32(const char* __restrict__ q_grp, const float* __restrict__ sv_seq,
+                                               int32_t n_sent, int32_t row_w, float* __restrict__ out_seq) {
+    const int lane = threadIdx.x & 63;
+    const int c = lane & 31, half = lane >> 5;
     float qs[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-        const char* qrow = q + ((int64_t)(b * Hq + h * G + g) * kHeadDim + c * 4) * EB;
+        const char* qrow = q_grp + ((int64_t)g * kHeadDim + c * 4) * EB;
         if (EB == 4) {
             const float4 t = *reinterpret_cast<const float4*>(qrow);
             qs[0] += t.x; qs[1] += t.y; qs[2] += t.z; qs[3] += t.w;
@@ -134,16 +152,15 @@ __global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_kernel(cons
             qs[2] += __uint_as_float(t.y << 16); qs[3] += __uint_as_float(t.y & 0xffff0000u);
         }
     }
-
     constexpr int kIter = RPWV / 2;
-    const int32_t row0 = blk * kRowsPerBlock + w * RPWV + half;
-    const float* base = semvec + ((int64_t)h * v.S_total + sq.sent_base) * kHeadDim + c * 4;
+    const int32_t row0 = row_w + half;
+    const float* base = sv_seq + c * 4;
     // Addresses are clamped into the sequence instead of predicating the loads, so that all of a
     // lane's loads are issued back to back; rows past the end are computed and dropped.
     float4 x[kIter];
 #pragma unroll
     for (int i = 0; i < kIter; ++i) {
-        const int32_t s = min(row0 + 2 * i, sq.n_sent - 1);
+        const int32_t s = min(row0 + 2 * i, n_sent - 1);
         x[i] = *reinterpret_cast<const float4*>(base + (int64_t)s * kHeadDim);
     }
     float p[kIter];
@@ -158,41 +175,28 @@ __global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_kernel(cons
         p[i] += __shfl_xor(p[i], 16);
     }
     if (c == 0) {
-        float* out = score + (int64_t)h * v.S_total + sq.sent_base;
 #pragma unroll
         for (int i = 0; i < kIter; ++i) {
             const int32_t s = row0 + 2 * i;
-            if (s < sq.n_sent) out[s] = p[i];
+            if (s < n_sent) {
+                if (AGENT) st_agent(out_seq + s, p[i]);
+                else out_seq[s] = p[i];
+            }
         }
     }
 }
 
-// The same scores from a bf16 table: a vector is 256 bytes = 16 lanes x 16 bytes (8 dims per lane), a wave load covers
-// 4 buckets, 16 buckets per wave keep 4 loads in flight; the sum over a bucket's 16 lanes stays inside a DPP row.
-constexpr int kScoreRowsPerWave16 = 16;
-
-template <int EB, int G>
-__global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_sv16_kernel(const char* __restrict__ q,
-                                                                                 const char* __restrict__ semvec, SeqView v,
-                                                                                 int32_t Hq, float* __restrict__ score) {
-    constexpr int kRowsPerBlock = kScoreRowsPerWave16 * kScoreWavesPerBlock;
-    int blk = blockIdx.x, b = 0;
-    Seq sq{};
-    for (; b < v.B; ++b) {
-        sq = seq_of(v, b);
-        const int nb = (sq.n_sent + kRowsPerBlock - 1) / kRowsPerBlock;
-        if (blk < nb) break;
-        blk -= nb;
-    }
-    if (b >= v.B) return;
-    const int h = blockIdx.y;
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+// The same from a bf16 table: a vector is 256 bytes = 16 lanes x 16 bytes (8 dims per lane), a wave load covers
+// 4 buckets, RPWV / 4 loads in flight; the sum over a bucket's 16 lanes stays inside a DPP row.
+template <int EB, int G, int RPWV, bool AGENT>
+__device__ __forceinline__ void score_wave_bf16(const char* __restrict__ q_grp, const char* __restrict__ sv_seq,
+                                                int32_t n_sent, int32_t row_w, float* __restrict__ out_seq) {
+    const int lane = threadIdx.x & 63;
     const int c = lane & 15, sub = lane >> 4;
-
     float qs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-        const char* qrow = q + ((int64_t)(b * Hq + h * G + g) * kHeadDim + c * 8) * EB;
+        const char* qrow = q_grp + ((int64_t)g * kHeadDim + c * 8) * EB;
         if (EB == 4) {
             const float4 t0 = *reinterpret_cast<const float4*>(qrow), t1 = *reinterpret_cast<const float4*>(qrow + 16);
             qs[0] += t0.x; qs[1] += t0.y; qs[2] += t0.z; qs[3] += t0.w;
@@ -204,13 +208,13 @@ __global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_sv16_kernel
             for (int i = 0; i < 8; ++i) qs[i] += f[i];
         }
     }
-    constexpr int kIter = kScoreRowsPerWave16 / 4;
-    const int32_t row0 = blk * kRowsPerBlock + w * kScoreRowsPerWave16 + sub;
-    const char* base = semvec + (((int64_t)h * v.S_total + sq.sent_base) * kHeadDim + c * 8) * 2;
+    constexpr int kIter = RPWV / 4;
+    const int32_t row0 = row_w + sub;
+    const char* base = sv_seq + c * 16;
     uint4 x[kIter];
 #pragma unroll
     for (int i = 0; i < kIter; ++i) {                       // clamped addresses: all loads issued back to back
-        const int32_t s = min(row0 + 4 * i, sq.n_sent - 1);
+        const int32_t s = min(row0 + 4 * i, n_sent - 1);
         x[i] = *reinterpret_cast<const uint4*>(base + (int64_t)s * (kHeadDim * 2));
     }
     float p[kIter];
@@ -230,13 +234,61 @@ __global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_sv16_kernel
         p[i] = dpp_add<0x128>(p[i]);
     }
     if (c == 0) {
-        float* out = score + (int64_t)h * v.S_total + sq.sent_base;
 #pragma unroll
         for (int i = 0; i < kIter; ++i) {
             const int32_t s = row0 + 4 * i;
-            if (s < sq.n_sent) out[s] = p[i];
+            if (s < n_sent) {
+                if (AGENT) st_agent(out_seq + s, p[i]);
+                else out_seq[s] = p[i];
+            }
         }
     }
+}
+
+// Block x of a grid row -> (sequence b, local block) by walking cu_sent; false past the last sequence.
+__device__ __forceinline__ bool locate_score_block(const SeqView& v, int rows_per_block, int x, int* b_out, int* blk_out,
+                                                   Seq* sq_out) {
+    int blk = x, b = 0;
+    Seq sq{};
+    for (; b < v.B; ++b) {
+        sq = seq_of(v, b);
+        const int nb = (sq.n_sent + rows_per_block - 1) / rows_per_block;
+        if (blk < nb) break;
+        blk -= nb;
+    }
+    *b_out = b; *blk_out = blk; *sq_out = sq;
+    return b < v.B;
+}
+
+template <int EB, int G, int RPWV>
+__global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_kernel(const char* __restrict__ q,
+                                                                            const float* __restrict__ semvec, SeqView v,
+                                                                            int32_t Hq, float* __restrict__ score) {
+    constexpr int kRowsPerBlock = RPWV * kScoreWavesPerBlock;
+    int blk, b;
+    Seq sq;
+    if (!locate_score_block(v, kRowsPerBlock, blockIdx.x, &b, &blk, &sq)) return;
+    const int h = blockIdx.y, w = threadIdx.x >> 6;
+    const int64_t hs = (int64_t)h * v.S_total + sq.sent_base;
+    score_wave_f32<EB, G, RPWV, false>(q + ((int64_t)(b * Hq + h * G) * kHeadDim) * EB, semvec + hs * kHeadDim, sq.n_sent,
+                                       blk * kRowsPerBlock + w * RPWV, score + hs);
+}
+
+constexpr int kScoreRowsPerWave16 = 16;
+
+template <int EB, int G>
+__global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_sv16_kernel(const char* __restrict__ q,
+                                                                                 const char* __restrict__ semvec, SeqView v,
+                                                                                 int32_t Hq, float* __restrict__ score) {
+    constexpr int kRowsPerBlock = kScoreRowsPerWave16 * kScoreWavesPerBlock;
+    int blk, b;
+    Seq sq;
+    if (!locate_score_block(v, kRowsPerBlock, blockIdx.x, &b, &blk, &sq)) return;
+    const int h = blockIdx.y, w = threadIdx.x >> 6;
+    const int64_t hs = (int64_t)h * v.S_total + sq.sent_base;
+    score_wave_bf16<EB, G, kScoreRowsPerWave16, false>(q + ((int64_t)(b * Hq + h * G) * kHeadDim) * EB,
+                                                       semvec + hs * kHeadDim * 2, sq.n_sent,
+                                                       blk * kRowsPerBlock + w * kScoreRowsPerWave16, score + hs);
 }
 
 template <int EB, int RPWV>
@@ -312,7 +364,7 @@ struct SelectShared {
 // sel_pos / tok_pos being the number of selected buckets / tokens with lower ids (sel_pos is only
 // computed when COUNT is set, else 0).  Every thread of the block must call this; *n_sel_out /
 // *n_tok_out are block-uniform.
-template <int KREG, bool COUNT, typename Emit>
+template <int KREG, bool COUNT, bool AGENT, typename Emit>
 __device__ __forceinline__ void select_block(const float* __restrict__ sc, const int32_t* __restrict__ len,
                                              const int32_t* __restrict__ off, int32_t S, int32_t budget,
                                              SelectShared& sh, Emit emit, int32_t* n_sel_out, int32_t* n_tok_out) {
@@ -322,6 +374,8 @@ __device__ __forceinline__ void select_block(const float* __restrict__ sc, const
     if (S <= 0 || budget <= 0) return;
     const int kpt = (S + kBlockThreads - 1) / kBlockThreads;
     const int32_t s0 = tid * kpt;
+    // AGENT: the scores were written by other blocks of the same launch
+    auto ldsc = [&](int32_t i) -> float { return AGENT ? ld_agent(sc + i) : sc[i]; };
 
     uint32_t rkey[KREG];
     int32_t rlen[KREG], roff[KREG];
@@ -330,7 +384,7 @@ __device__ __forceinline__ void select_block(const float* __restrict__ sc, const
         rkey[i] = 0; rlen[i] = 0; roff[i] = 0;
         if (i < kpt) {                                     // block-uniform; addresses clamped, loads unconditional
             const int32_t sidx = min(s0 + i, S - 1);
-            rkey[i] = __float_as_uint(sc[sidx]);
+            rkey[i] = __float_as_uint(ldsc(sidx));
             rlen[i] = len[sidx];
             roff[i] = off[sidx];
         }
@@ -367,7 +421,7 @@ __device__ __forceinline__ void select_block(const float* __restrict__ sc, const
         }
         for (int i = KREG; i < kpt; ++i) {
             if (s0 + i < S && len[s0 + i] > 0) {               // a bucket without tokens takes part in nothing
-                const uint32_t k = score_key(sc[s0 + i]);
+                const uint32_t k = score_key(ldsc(s0 + i));
                 if (pass == 0 || (k >> shift) == prefix)
                     atomicAdd(&H[(k >> nshift) & (nbins - 1)], (1ull << 32) | (unsigned long long)(uint32_t)len[s0 + i]);
             }
@@ -405,7 +459,7 @@ __device__ __forceinline__ void select_block(const float* __restrict__ sc, const
         for (int i = 0; i < KREG; ++i)
             if (i < kpt && rlen[i] > 0) fn(i, s0 + i, rkey[i], rlen[i], roff[i]);
         for (int i = KREG; i < kpt; ++i)
-            if (s0 + i < S && len[s0 + i] > 0) fn(i, s0 + i, score_key(sc[s0 + i]), len[s0 + i], off[s0 + i]);
+            if (s0 + i < S && len[s0 + i] > 0) fn(i, s0 + i, score_key(ldsc(s0 + i)), len[s0 + i], off[s0 + i]);
     };
     uint32_t tie_run = 0;          // length of tied buckets with lower ids (starts at the thread's base)
     if (ties) {
@@ -479,8 +533,8 @@ __global__ __launch_bounds__(kBlockThreads) void select_kernel(const float* __re
             for (int32_t t = 0; t < ln && tok_pos + t < idx_stride; ++t) my_idx[tok_pos + t] = o + t;
         }
     };
-    if (sq.n_sent <= 2 * kBlockThreads) select_block<2, true>(sc, len, off, sq.n_sent, budget, sh, emit, &nsel, &ntok);
-    else select_block<kSelKreg, true>(sc, len, off, sq.n_sent, budget, sh, emit, &nsel, &ntok);
+    if (sq.n_sent <= 2 * kBlockThreads) select_block<2, true, false>(sc, len, off, sq.n_sent, budget, sh, emit, &nsel, &ntok);
+    else select_block<kSelKreg, true, false>(sc, len, off, sq.n_sent, budget, sh, emit, &nsel, &ntok);
     if (threadIdx.x == 0) { n_sel[bh] = min(nsel, max_sel); n_tok[bh] = ntok; }
     __syncthreads();
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -575,17 +629,7 @@ hipError_t launch_gather(Ctx* c, const void* K_layer, const void* V_layer, int32
 //      partials with one round of independent loads and an online-softmax merge.
 // ------------------------------------------------------------------------------------------------
 
-// Split-K partials travel between blocks (possibly on different XCDs, each with its own L2) inside one
-// kernel.  They are written and read with device-scope relaxed atomic accesses, which go through to the
-// level all XCDs share, so no L2 write-back / invalidate is needed around the arrival counter.
-__device__ __forceinline__ void st_agent(float* p, float v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ unsigned long long ld_agent64(const float* p) {       // two consecutive floats
-    return __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float lo_f(unsigned long long v) { return __uint_as_float((uint32_t)v); }
-__device__ __forceinline__ float hi_f(unsigned long long v) { return __uint_as_float((uint32_t)(v >> 32)); }
+// Split-K partials travel between blocks inside one kernel through st_agent / ld_agent64 (see above).
 
 // sum over the RPW rows of a wave (lane bits below log2 RPW); every lane gets the total
 template <int RPW>
@@ -690,8 +734,8 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
         const float* sc = a.score + (int64_t)h * a.v.S_total + sq.sent_base;
         const int32_t* len = a.sent_len + sq.sent_base;
         const int32_t* off = a.sent_off + sq.sent_base + (a.v.cu_sent ? b : 0);
-        if (sq.n_sent <= 2 * kBlockThreads) select_block<2, false>(sc, len, off, sq.n_sent, budget, sel_sh, mark, &nsel, &ntok);
-        else select_block<kSelKreg, false>(sc, len, off, sq.n_sent, budget, sel_sh, mark, &nsel, &ntok);
+        if (sq.n_sent <= 2 * kBlockThreads) select_block<2, false, false>(sc, len, off, sq.n_sent, budget, sel_sh, mark, &nsel, &ntok);
+        else select_block<kSelKreg, false, false>(sc, len, off, sq.n_sent, budget, sel_sh, mark, &nsel, &ntok);
         n = ntok;
         if (split == 0 && tid == 0 && a.n_tok_out) a.n_tok_out[bh] = n;
         __syncthreads();                                          // bucket starts are marked
@@ -1069,87 +1113,51 @@ constexpr int kStreamWaves = kBlockWaves;                         // the block-l
 constexpr int kStreamChunk = kStreamWaves * kStreamTiles * 16;    // 1024 tokens per block, one position per thread
 static_assert(kStreamChunk == kBlockThreads, "one retrieved position per thread");
 
+constexpr int kStreamVPitch = 2 * kHeadDim + 16;                  // bytes per value row in LDS; +16 spreads row groups over banks
+
+struct StreamShared {
+    __attribute__((aligned(16))) char v[kStreamWaves][16 * kStreamVPitch];   // value tile, later the wave's partial sums
+    __attribute__((aligned(16))) unsigned short q[16][kHeadDim];             // the group's queries, rows >= G zero
+    float wmax[kStreamWaves][16], wsum[kStreamWaves][16];
+    int32_t row[kStreamChunk];                                               // pool row of every position of the block (-1: none)
+    int next_tile;
+    int last;
+};
+
+// queries of the group -> LDS (16 bytes per thread: 16 rows x 256 bytes); a barrier must follow before they are read
 template <int G>
-__global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void select_attend_stream_kernel(AttArgs a) {
+__device__ __forceinline__ void stream_load_queries(const AttArgs& a, StreamShared& ss, int64_t qhead0) {
+    const int tid = threadIdx.x;
+    if (tid < 256) {
+        const int row = tid >> 4, piece = tid & 15;
+        uint4 t = make_uint4(0, 0, 0, 0);
+        if (row < G) t = *reinterpret_cast<const uint4*>(a.q + ((qhead0 + row) * kHeadDim) * 2 + 16 * piece);
+        *reinterpret_cast<uint4*>(&ss.q[row][8 * piece]) = t;
+    }
+}
+
+// Attention of one 1024-position block once the selection is known: n = retrieved tokens of the (sequence, head),
+// xi = pool row of position split * 1024 + tid (anything for positions >= n).  The queries are on their way to ss.q.
+// Every thread of the block calls this.
+template <int G>
+__device__ __forceinline__ void stream_attend(const AttArgs& a, StreamShared& ss, int bh, int b, int h, int split, const Seq& sq,
+                                              int32_t n, int32_t xi) {
     constexpr int NW = kStreamWaves;
     constexpr int kThreads = kBlockThreads;
     constexpr int CHUNK = kStreamChunk;
     constexpr int kRowBytes = kHeadDim * 2;
-    constexpr int kVPitch = 2 * kHeadDim + 16;                    // bytes per value row in LDS
+    constexpr int kVPitch = kStreamVPitch;
     constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
     constexpr int kOut = G * kHeadDim, kCol2 = kOut / 2;
     constexpr int kColsPerThread = (kCol2 + kThreads - 1) / kThreads;
     typedef short bf16x4 __attribute__((ext_vector_type(4)));
     typedef float f32x4 __attribute__((ext_vector_type(4)));
     static_assert(G * kHeadDim * 4 <= 16 * kVPitch, "a wave's partial sums fit in its value tile");
-
-    __shared__ __attribute__((aligned(16))) char sm_v[NW][16 * kVPitch];             // value tile, later the wave's partial sums
-    __shared__ __attribute__((aligned(16))) unsigned short sm_q[16][kHeadDim];       // the group's queries, rows >= G zero
-    __shared__ float sm_wmax[NW][16], sm_wsum[NW][16];
-    __shared__ int sm_last;
-
-    const int bh = blockIdx.y, b = bh / a.Hkv, h = bh % a.Hkv, split = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int t16 = lane & 15, qd = lane >> 4;
-    const int Hq = a.Hkv * G;
-    const int64_t qhead0 = (int64_t)b * Hq + (int64_t)h * G;
-    const Seq sq = seq_of(a.v, b);
+    const int64_t qhead0 = (int64_t)b * (a.Hkv * G) + (int64_t)h * G;
     const int32_t j0 = split * CHUNK;
     const int slot = split * (CHUNK / kWave);
-    SKV_T(0);
-
-    auto load_queries = [&]() {   // queries of the group -> LDS (16 bytes per thread: 16 rows x 256 bytes)
-        if (tid < 256) {
-            const int row = tid >> 4, piece = tid & 15;
-            uint4 t = make_uint4(0, 0, 0, 0);
-            if (row < G) t = *reinterpret_cast<const uint4*>(a.q + ((qhead0 + row) * kHeadDim) * 2 + 16 * piece);
-            *reinterpret_cast<uint4*>(&sm_q[row][8 * piece]) = t;
-        }
-    };
-
-    int32_t n;                    // retrieved tokens of this (sequence, head)
-    int32_t xi;                   // pool row of this thread's position
-    __shared__ int32_t sm_row[CHUNK];                            // bucket-start marks, later the pool row of every position
-    __shared__ int sm_next_tile;
-    {
-        __shared__ SelectShared sel_sh;
-        const int32_t budget = min(sq.budget, a.idx_stride);
-        if (split > 0 && j0 >= budget) return;                    // n <= budget: nothing for this split
-        load_queries();
-        sm_row[tid] = -1;
-        // A selected bucket that reaches into this block's positions marks, in every 64-position piece it touches,
-        // where it starts there and which pool row that is; each wave then fills the positions of its own piece.
-        auto mark = [&](int32_t, int32_t o, int32_t ln, int32_t, int32_t tok_pos) {
-            const int32_t hi = min(tok_pos + ln, j0 + CHUNK);
-            int32_t lo = max(tok_pos, j0);
-            while (lo < hi) {
-                sm_row[lo - j0] = o + (lo - tok_pos);
-                lo = j0 + (((lo - j0) >> 6) + 1) * kWave;
-            }
-        };
-        const float* sc = a.score + (int64_t)h * a.v.S_total + sq.sent_base;
-        const int32_t* len = a.sent_len + sq.sent_base;
-        const int32_t* off = a.sent_off + sq.sent_base + (a.v.cu_sent ? b : 0);
-        int32_t nsel, ntok;
-        if (sq.n_sent <= 2 * kBlockThreads) select_block<2, false>(sc, len, off, sq.n_sent, budget, sel_sh, mark, &nsel, &ntok);
-        else select_block<kSelKreg, false>(sc, len, off, sq.n_sent, budget, sel_sh, mark, &nsel, &ntok);
-        n = ntok;
-        if (split == 0 && tid == 0 && a.n_tok_out) a.n_tok_out[bh] = n;
-        __syncthreads();                                          // bucket starts are marked, queries are in LDS
-        {
-            const int32_t v = sm_row[tid];
-            int32_t hp = v >= 0 ? lane : -1;                      // position of the last bucket start at or before this lane
-#pragma unroll
-            for (int o = 1; o < 64; o <<= 1) {
-                const int32_t t = __shfl_up(hp, o);
-                if (lane >= o) hp = max(hp, t);
-            }
-            const int32_t base = __shfl(v, max(hp, 0));
-            xi = hp >= 0 ? base + (lane - hp) : -1;
-            const int32_t pos = j0 + tid;
-            if (a.tok_idx_out && pos < n) a.tok_idx_out[(int64_t)bh * a.idx_stride + pos] = xi;
-        }
-    }
     if (n <= 0) {
         if (split == 0) {
             for (int i = tid; i < kOut; i += kThreads) a.out[qhead0 * kHeadDim + i] = 0.f;
@@ -1165,8 +1173,8 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(4
     // next free one from an LDS counter whenever it finishes one, so the waves that memory serves first do more tiles
     // and all 16 keep loads in flight until the block's last tile (with four fixed tiles per wave the slowest wave ran
     // about 5 us behind the first).  Rows of unreal positions are stored as -1.
-    sm_row[tid] = (tid < cnt && xi >= 0 && xi < sq.n_tok_ctx) ? xi : -1;
-    if (tid == 0) sm_next_tile = NW;
+    ss.row[tid] = (tid < cnt && xi >= 0 && xi < sq.n_tok_ctx) ? xi : -1;
+    if (tid == 0) ss.next_tile = NW;
     const int ntiles = (cnt + 15) / 16;
     const char* Kh = a.Kb + ((int64_t)h * a.v.T_total + sq.tok_base) * kRowBytes;
     const char* Vh = a.Vb + ((int64_t)h * a.v.T_total + sq.tok_base) * kRowBytes;
@@ -1176,7 +1184,7 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(4
 
     uint4 kA[4], vR[4];
     // rows of a tile: lanes with the same t16 hold the row of the tile's token t16 (-1: not real)
-    auto rows_of = [&](int tile) { return sm_row[16 * tile + t16]; };
+    auto rows_of = [&](int tile) { return ss.row[16 * tile + t16]; };
     auto issue = [&](int32_t rowt, uint4* k, uint4* v) {
         // 32-bit byte offsets from the (head, sequence) base: the host only uses this kernel below 2^24 tokens
         const int32_t rc = max(rowt, 0);
@@ -1198,19 +1206,19 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(4
     f32x4 o[kHeadDim / 16];
 #pragma unroll
     for (int dt = 0; dt < kHeadDim / 16; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    char* vt_b = sm_v[w];
+    char* vt_b = ss.v[w];
     const unsigned short* vt = reinterpret_cast<const unsigned short*>(vt_b);
 
     while (tile < ntiles) {
         // the wave's next tile, asked for early so that its rows are known when this tile's registers come free
         int nxt = 0;
-        if (lane == 0) nxt = atomicAdd(&sm_next_tile, 1);
+        if (lane == 0) nxt = atomicAdd(&ss.next_tile, 1);
         nxt = __builtin_amdgcn_readfirstlane(nxt);
         const unsigned int tm = (unsigned int)__ballot(row_cur >= 0) & 0xffffu;   // bit t: token t of the tile is real
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s2 = 0; s2 < 4; ++s2) {
-            const uint4 qq = *reinterpret_cast<const uint4*>(&sm_q[t16][32 * s2 + 8 * qd]);
+            const uint4 qq = *reinterpret_cast<const uint4*>(&ss.q[t16][32 * s2 + 8 * qd]);
             acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4, make_uint2(kA[s2].x, kA[s2].y)),
                                                             __builtin_bit_cast(bf16x4, make_uint2(qq.x, qq.y)), acc, 0, 0, 0);
             acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4, make_uint2(kA[s2].z, kA[s2].w)),
@@ -1278,13 +1286,13 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(4
     // ---- the block's waves combine: common max per head, partial sums through the value tiles ------------------
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
-    if (qd == 0) sm_wmax[w][t16] = m_run;
+    if (qd == 0) ss.wmax[w][t16] = m_run;
     __syncthreads();
     float mb = -INFINITY;
 #pragma unroll
-    for (int ww = 0; ww < NW; ++ww) mb = fmaxf(mb, sm_wmax[ww][t16]);
+    for (int ww = 0; ww < NW; ++ww) mb = fmaxf(mb, ss.wmax[ww][t16]);
     const float cw = (m_run > -INFINITY) ? exp2f(m_run - mb) : 0.f;
-    if (qd == 0) sm_wsum[w][t16] = l_run * cw;
+    if (qd == 0) ss.wsum[w][t16] = l_run * cw;
     {
         float cr[4];
 #pragma unroll
@@ -1300,7 +1308,7 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(4
     if (tid < G) {
         float lb = 0.f, mh = -INFINITY;
 #pragma unroll
-        for (int ww = 0; ww < NW; ++ww) { lb += sm_wsum[ww][tid]; mh = fmaxf(mh, sm_wmax[ww][tid]); }
+        for (int ww = 0; ww < NW; ++ww) { lb += ss.wsum[ww][tid]; mh = fmaxf(mh, ss.wmax[ww][tid]); }
         float* dst = a.ml + (((qhead0 + tid) * a.max_splits) + slot) * 2;
         st_agent(dst, mh);
         st_agent(dst + 1, lb);
@@ -1309,7 +1317,7 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(4
         const int g = i / kHeadDim, d = i % kHeadDim;
         float sum = 0.f;
 #pragma unroll
-        for (int ww = 0; ww < NW; ++ww) sum += reinterpret_cast<const float*>(sm_v[ww])[i];
+        for (int ww = 0; ww < NW; ++ww) sum += reinterpret_cast<const float*>(ss.v[ww])[i];
         st_agent(a.part + (((qhead0 + g) * a.max_splits) + slot) * kHeadDim + d, sum);
     }
     SKV_T(7);
@@ -1318,11 +1326,11 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(4
     __syncthreads();
     if (tid == 0) {
         const unsigned int old = __hip_atomic_fetch_add(&a.counter[bh], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        sm_last = (old == (unsigned int)(nsplit - 1));
+        ss.last = (old == (unsigned int)(nsplit - 1));
     }
     __syncthreads();
     SKV_T(8);
-    if (!sm_last) return;
+    if (!ss.last) return;
 #pragma unroll
     for (int c = 0; c < kColsPerThread; ++c) {
         const int col = tid + c * kThreads;
@@ -1360,6 +1368,60 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(4
     }
     if (tid == 0) __hip_atomic_store(&a.counter[bh], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next call
     SKV_T(9);
+}
+
+template <int G>
+__global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void select_attend_stream_kernel(AttArgs a) {
+    constexpr int CHUNK = kStreamChunk;
+    __shared__ StreamShared ss;
+    const int bh = blockIdx.y, b = bh / a.Hkv, h = bh % a.Hkv, split = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const Seq sq = seq_of(a.v, b);
+    const int32_t j0 = split * CHUNK;
+    SKV_T(0);
+
+    int32_t n;                    // retrieved tokens of this (sequence, head)
+    int32_t xi;                   // pool row of this thread's position
+    {
+        __shared__ SelectShared sel_sh;
+        const int32_t budget = min(sq.budget, a.idx_stride);
+        if (split > 0 && j0 >= budget) return;                    // n <= budget: nothing for this split
+        stream_load_queries<G>(a, ss, (int64_t)b * (a.Hkv * G) + (int64_t)h * G);
+        ss.row[tid] = -1;                                         // bucket-start marks first, the rows of all positions later
+        // A selected bucket that reaches into this block's positions marks, in every 64-position piece it touches,
+        // where it starts there and which pool row that is; each wave then fills the positions of its own piece.
+        auto mark = [&](int32_t, int32_t o, int32_t ln, int32_t, int32_t tok_pos) {
+            const int32_t hi = min(tok_pos + ln, j0 + CHUNK);
+            int32_t lo = max(tok_pos, j0);
+            while (lo < hi) {
+                ss.row[lo - j0] = o + (lo - tok_pos);
+                lo = j0 + (((lo - j0) >> 6) + 1) * kWave;
+            }
+        };
+        const float* sc = a.score + (int64_t)h * a.v.S_total + sq.sent_base;
+        const int32_t* len = a.sent_len + sq.sent_base;
+        const int32_t* off = a.sent_off + sq.sent_base + (a.v.cu_sent ? b : 0);
+        int32_t nsel, ntok;
+        if (sq.n_sent <= 2 * kBlockThreads) select_block<2, false, false>(sc, len, off, sq.n_sent, budget, sel_sh, mark, &nsel, &ntok);
+        else select_block<kSelKreg, false, false>(sc, len, off, sq.n_sent, budget, sel_sh, mark, &nsel, &ntok);
+        n = ntok;
+        if (split == 0 && tid == 0 && a.n_tok_out) a.n_tok_out[bh] = n;
+        __syncthreads();                                          // bucket starts are marked, queries are in LDS
+        {
+            const int32_t v = ss.row[tid];
+            int32_t hp = v >= 0 ? lane : -1;                      // position of the last bucket start at or before this lane
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int32_t t = __shfl_up(hp, o);
+                if (lane >= o) hp = max(hp, t);
+            }
+            const int32_t base = __shfl(v, max(hp, 0));
+            xi = hp >= 0 ? base + (lane - hp) : -1;
+            const int32_t pos = j0 + tid;
+            if (a.tok_idx_out && pos < n) a.tok_idx_out[(int64_t)bh * a.idx_stride + pos] = xi;
+        }
+    }
+    stream_attend<G>(a, ss, bh, b, h, split, sq, n, xi);
 }
 
 static hipError_t launch_select_attend_stream_g(Ctx* c, const AttArgs& a, int32_t n_splits) {
