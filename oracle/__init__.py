@@ -19,7 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "sentencekv_oracle.c")
 _BUILD = os.path.join(_HERE, "_build")
 
-F32, BF16 = 0, 1
+F32, BF16, FP8 = 0, 1, 2
 
 
 def lib_path(real: str) -> str:
@@ -56,7 +56,9 @@ def _dtype_of(a: np.ndarray) -> int:
         return F32
     if a.dtype == np.uint16:
         return BF16
-    raise TypeError(f"oracle inputs are float32 or bf16-as-uint16, got {a.dtype}")
+    if a.dtype == np.uint8:
+        return FP8
+    raise TypeError(f"oracle inputs are float32, bf16-as-uint16 or E4M3-as-uint8, got {a.dtype}")
 
 
 class Oracle:
@@ -75,6 +77,10 @@ class Oracle:
         L.skvo_semvec_to.restype = None
         L.skvo_score_from.argtypes = [_vp, _ci, _i, _i, _i, _vp, _ci, _i, _f32p]
         L.skvo_score_from.restype = None
+        L.skvo_e4m3_encode.argtypes = [_f32p, ctypes.c_int64, _vp]
+        L.skvo_e4m3_encode.restype = None
+        L.skvo_e4m3_decode.argtypes = [_vp, ctypes.c_int64, _f32p]
+        L.skvo_e4m3_decode.restype = None
         L.skvo_score.argtypes = [_vp, _ci, _i, _i, _i, _f32p, _i, _f32p]
         L.skvo_score.restype = None
         L.skvo_select.argtypes = [_f32p, _i32p, _i32p, _i, _i, _i, _i32p, _i, _i32p, _i32p, _i, _i32p]
@@ -113,14 +119,28 @@ class Oracle:
         return seg_id, off[: S + 1].copy(), ln[:S].copy(), S
 
     def semvec(self, K: np.ndarray, sent_off: np.ndarray, sv_dtype: str = "f32") -> np.ndarray:
-        """K [L][Hkv][T][D] (float32 or bf16 bits) -> semvec [L][Hkv][S][D], float32 or (sv_dtype="bf16") bf16 bits."""
+        """K [L][Hkv][T][D] (float32 or bf16 bits) -> semvec [L][Hkv][S][D]: float32, bf16 bits (sv_dtype="bf16") or
+        E4M3 codes (sv_dtype="fp8")."""
         K = np.ascontiguousarray(K)
         L, H, T, D = K.shape
         sent_off = np.ascontiguousarray(sent_off, dtype=np.int32)
         S = sent_off.shape[0] - 1
-        out = np.zeros((L, H, S, D), dtype=np.float32 if sv_dtype == "f32" else np.uint16)
+        out = np.zeros((L, H, S, D), dtype={"f32": np.float32, "bf16": np.uint16, "fp8": np.uint8}[sv_dtype])
         self.lib.skvo_semvec_to(K.ctypes.data_as(_vp), _dtype_of(K), L, H, T, D, _ptr(sent_off, _i32p), S, _dtype_of(out),
                                 out.ctypes.data_as(_vp))
+        return out
+
+    def e4m3_encode(self, x: np.ndarray) -> np.ndarray:
+        """float32 -> E4M3 codes (nearest, ties to even, saturating at 448)."""
+        x = np.ascontiguousarray(x, dtype=np.float32)
+        out = np.zeros(x.shape, dtype=np.uint8)
+        self.lib.skvo_e4m3_encode(_ptr(x, _f32p), ctypes.c_int64(x.size), out.ctypes.data_as(_vp))
+        return out
+
+    def e4m3_decode(self, code: np.ndarray) -> np.ndarray:
+        code = np.ascontiguousarray(code, dtype=np.uint8)
+        out = np.zeros(code.shape, dtype=np.float32)
+        self.lib.skvo_e4m3_decode(code.ctypes.data_as(_vp), ctypes.c_int64(code.size), _ptr(out, _f32p))
         return out
 
     def token_importance(self, q_obs: np.ndarray, K: np.ndarray) -> np.ndarray:
@@ -154,7 +174,7 @@ class Oracle:
         return QueryCache(self, per, cap)
 
     def score(self, q: np.ndarray, semvec: np.ndarray) -> np.ndarray:
-        """q [Hq][D], semvec [Hkv][S][D] float32 or bf16 bits -> score float32 [Hkv][S]."""
+        """q [Hq][D], semvec [Hkv][S][D] float32, bf16 bits or E4M3 codes -> score float32 [Hkv][S]."""
         q = np.ascontiguousarray(q)
         semvec = np.ascontiguousarray(semvec)
         Hq, D = q.shape

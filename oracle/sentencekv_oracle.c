@@ -66,18 +66,57 @@
 #endif
 typedef SKVO_REAL real;
 
-enum { SKVO_F32 = 0, SKVO_BF16 = 1 };
+enum { SKVO_F32 = 0, SKVO_BF16 = 1, SKVO_FP8 = 2 };   /* FP8 = the 8-bit E4M3 format of the OCP specification */
+
+/* E4M3 (1 sign, 4 exponent bits with bias 7, 3 fraction bits; no infinities, 0x7f / 0xff are NaN, largest finite value
+ * 448): the value of a code, written out from the format's definition. */
+static float from_e4m3(uint8_t code) {
+    int e = (code >> 3) & 15, m = code & 7;
+    float mag;
+    if (e == 0) mag = (float)m * 0.001953125f;                       /* subnormal: m * 2^-9 */
+    else {
+        mag = 1.0f + (float)m * 0.125f;
+        for (int i = 7; i < e; ++i) mag *= 2.0f;                     /* 2^(e-7), exact */
+        for (int i = e; i < 7; ++i) mag *= 0.5f;
+    }
+    return (code & 0x80) ? -mag : mag;
+}
+
+/* nearest E4M3 value to a finite float, ties to the even code, magnitudes beyond the format saturate at 448 */
+static uint8_t to_e4m3(float f) {
+    uint8_t sign = f < 0.0f || (f == 0.0f && 1.0f / f < 0.0f) ? 0x80 : 0x00;
+    float a = f < 0.0f ? -f : f;
+    uint8_t lo = 0, best = 0;
+    /* the codes 0x00..0x7e are increasing in value: find the last one not above a (bisection), then compare with its
+     * successor */
+    int first = 0, last = 0x7e;
+    while (first < last) {
+        int mid = (first + last + 1) / 2;
+        if (from_e4m3((uint8_t)mid) <= a) first = mid; else last = mid - 1;
+    }
+    lo = (uint8_t)first;
+    if (lo == 0x7e) best = lo;                                       /* at or beyond 448 */
+    else {
+        float below = from_e4m3(lo), above = from_e4m3((uint8_t)(lo + 1));
+        float d0 = a - below, d1 = above - a;                        /* exact: neighbouring values, a between them */
+        if (d0 < d1) best = lo;
+        else if (d0 > d1) best = (uint8_t)(lo + 1);
+        else best = (lo & 1) ? (uint8_t)(lo + 1) : lo;
+    }
+    return (uint8_t)(sign | best);
+}
 
 /* exact widening of one stored element to REAL */
 static real load_elt(const void* base, int dtype, int64_t i) {
     if (dtype == SKVO_F32) return (real)((const float*)base)[i];
+    if (dtype == SKVO_FP8) return (real)from_e4m3(((const uint8_t*)base)[i]);
     uint32_t bits = ((uint32_t)((const uint16_t*)base)[i]) << 16;
     float f;
     memcpy(&f, &bits, sizeof f);
     return (real)f;
 }
 
-static size_t elt_size(int dtype) { return dtype == SKVO_F32 ? 4u : 2u; }
+static size_t elt_size(int dtype) { return dtype == SKVO_F32 ? 4u : dtype == SKVO_FP8 ? 1u : 2u; }
 
 static int is_terminator(const uint32_t* bitmap, int32_t vocab, int32_t id) {
     if (id < 0 || id >= vocab) return 0;
@@ -121,8 +160,12 @@ int skvo_segment(const int32_t* tok, int32_t T, const uint32_t* bitmap, int32_t 
     return seg <= cap_sent ? 0 : -1;
 }
 
+/* The two conversions on arrays, for the tests that pin them. */
+void skvo_e4m3_encode(const float* x, int64_t n, uint8_t* code) { for (int64_t i = 0; i < n; ++i) code[i] = to_e4m3(x[i]); }
+void skvo_e4m3_decode(const uint8_t* code, int64_t n, float* x) { for (int64_t i = 0; i < n; ++i) x[i] = from_e4m3(code[i]); }
+
 /* Eq. 1: semvec[l][h][s][:] = (1/|S_s|) sum_{x in S_s} k_{x,h}, S_s = the tokens of bucket s in the pool.
- * sv_dtype selects the storage of the table: float, or bf16 (the float mean rounded once, to nearest even: the
+ * sv_dtype selects the storage of the table: float, or bf16 or E4M3 (the float mean rounded once, to nearest even: the
  * mixed-precision sentence vectors the paper names as future work). */
 void skvo_semvec_to(const void* K, int dtype, int32_t L, int32_t Hkv, int32_t T, int32_t D,
                     const int32_t* sent_off, int32_t S, int sv_dtype, void* semvec) {
@@ -141,6 +184,7 @@ void skvo_semvec_to(const void* K, int dtype, int32_t L, int32_t Hkv, int32_t T,
                 for (int32_t d = 0; d < D; ++d) {
                     float mean = e > b ? (float)(acc[d] / n) : 0.0f;   /* no retained token: no bucket */
                     if (sv_dtype == SKVO_F32) ((float*)semvec)[o + d] = mean;
+                    else if (sv_dtype == SKVO_FP8) ((uint8_t*)semvec)[o + d] = to_e4m3(mean);
                     else ((uint16_t*)semvec)[o + d] = to_bf16(mean);
                 }
             }

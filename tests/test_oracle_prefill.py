@@ -173,3 +173,73 @@ def test_bf16_semvec_is_the_float_mean_rounded_once(oracle32):
     ref = oracle32.score(gen.to_numpy(q), sv32[0])
     d = np.abs(got - ref).max()
     assert 0 < d <= 2.0 ** -7 * np.abs(qd).sum(axis=1).max() * np.abs(sv32).max()
+
+
+# ----------------------------------------------------------------------------- E4M3 mean key vectors
+
+def _torch_e4m3(x: np.ndarray) -> np.ndarray:
+    """torch's float32 -> float8_e4m3fn conversion as codes (nearest, ties to even; NaN beyond the format)."""
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+
+
+def test_e4m3_codes_decode_to_the_format_definition(oracle32):
+    """All 256 codes against the written-out definition (-1)^s 2^(e-7) (1 + m/8), subnormals m 2^-9, and against torch."""
+    import torch
+    codes = np.arange(256, dtype=np.uint8)
+    got = oracle32.e4m3_decode(codes)
+    for c in range(256):
+        if (c & 0x7f) == 0x7f:
+            continue                                                    # the two NaN codes never occur in a table
+        s, e, m = c >> 7, (c >> 3) & 15, c & 7
+        want = (m * 2.0 ** -9) if e == 0 else 2.0 ** (e - 7) * (1 + m / 8)
+        assert got[c] == (-want if s else want), c
+    fin = (codes & 0x7f) != 0x7f
+    assert np.array_equal(got[fin], torch.from_numpy(codes).view(torch.float8_e4m3fn).float().numpy()[fin])
+    assert got[0x7e] == 448.0 and got[0x01] == 2.0 ** -9
+
+
+def test_e4m3_rounding_matches_torch_in_range_and_saturates(oracle32):
+    rng = np.random.default_rng(5)
+    # values over the whole range, every midpoint between neighbouring codes (ties), and values next to the midpoints
+    vals = oracle32.e4m3_decode(np.arange(0x7f, dtype=np.uint8)).astype(np.float64)
+    mids = (vals[:-1] + vals[1:]) / 2
+    x = np.concatenate([rng.normal(0, 1, 20000), rng.normal(0, 60, 20000), rng.uniform(-2.0 ** -6, 2.0 ** -6, 5000), vals, mids,
+                        np.nextafter(mids.astype(np.float32), np.float32(0)), np.nextafter(mids.astype(np.float32), np.float32(1e9)),
+                        [0.0, -0.0, 448.0, 463.9, 464.0]]).astype(np.float32)
+    x = np.concatenate([x, -x])
+    x = x[np.abs(x) <= 464.0]                                           # torch turns what lies beyond into NaN
+    assert np.array_equal(oracle32.e4m3_encode(x), _torch_e4m3(x))
+    # the rule for what does not fit: the largest finite value, sign kept (hand-written cases)
+    big = np.array([464.5, 480.0, 1e4, 3e38, -464.5, -1e30], dtype=np.float32)
+    assert oracle32.e4m3_encode(big).tolist() == [0x7e, 0x7e, 0x7e, 0x7e, 0xfe, 0xfe]
+    # ties go to the even code: 17 -> 16, 19 -> 20, 2^-10 -> 0, 1.5 * 2^-9 -> 2 * 2^-9
+    assert oracle32.e4m3_decode(oracle32.e4m3_encode(np.array([17, 19, 2.0 ** -10, 1.5 * 2.0 ** -9], dtype=np.float32))).tolist() == \
+        [16.0, 20.0, 0.0, 2.0 ** -8]
+    # monotone, idempotent on the format's own values
+    xs = np.sort(x)
+    assert np.all(np.diff(oracle32.e4m3_decode(oracle32.e4m3_encode(xs))) >= 0)
+    assert np.array_equal(oracle32.e4m3_encode(vals.astype(np.float32)), np.arange(0x7f, dtype=np.uint8))
+
+
+def test_e4m3_semvec_is_the_float_mean_rounded_once(oracle32):
+    """The stored code is torch's float32 -> float8_e4m3fn conversion of the oracle's own float mean; scores from the table
+    equal a float64 dot product with the decoded values; the rounding is visible in the scores."""
+    import torch
+    lens = np.array([3, 1, 40, 7, 25, 12, 2], dtype=np.int32)
+    off = gen.offsets_of(lens)
+    g = torch.Generator().manual_seed(37)
+    K = torch.randn(2, 2, int(lens.sum()), 128, generator=g).to(torch.bfloat16)
+    sv32 = oracle32.semvec(gen.to_numpy(K), off)
+    sv8 = oracle32.semvec(gen.to_numpy(K), off, sv_dtype="fp8")
+    assert sv8.dtype == np.uint8 and sv8.shape == sv32.shape
+    assert np.array_equal(sv8, _torch_e4m3(sv32))
+    q = torch.randn(8, 128, generator=g).to(torch.bfloat16)
+    got = oracle32.score(gen.to_numpy(q), sv8[0])
+    wide = torch.from_numpy(sv8[0]).view(torch.float8_e4m3fn).double().numpy()
+    qd = q.double().numpy()
+    want = np.stack([wide[h] @ qd[4 * h:4 * h + 4].sum(axis=0) for h in range(2)])
+    assert np.abs(got - want).max() <= 1e-5 * np.abs(want).max()
+    ref = oracle32.score(gen.to_numpy(q), sv32[0])
+    d = np.abs(got - ref).max()
+    assert 0 < d <= 2.0 ** -4 * np.abs(qd).sum(axis=1).max() * np.abs(sv32).max()
