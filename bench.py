@@ -32,6 +32,10 @@ HBM_PEAK_GBPS = 8000.0                      # MI355X datasheet HBM3E bandwidth
 N_QUERY_SETS = 16                           # distinct query sets rotated across steps
 
 
+SV_TABLE = {"f32": (4, torch.float32, skv.SKV_F32), "bf16": (2, torch.bfloat16, skv.SKV_BF16),
+            "fp8": (1, torch.uint8, skv.SKV_FP8_E4M3)}       # bytes per element, torch storage, library code
+
+
 def i32(a, dev):
     return torch.as_tensor(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
 
@@ -99,11 +103,11 @@ def run_single_sequence(args, wl, budget):
     gen_s = time.time() - t0
 
     S_cap = len(lengths) + 8
-    sv16 = args.semvec_dtype == "bf16"
-    sv_bytes = 2 if sv16 else 4
+    sv_bytes, sv_torch, sv_code = SV_TABLE[args.semvec_dtype]
+    sv16 = args.semvec_dtype != "f32"                        # a reduced table: no committed traffic counters
     ctx = skv.Context(skv.Desc(n_layers=L, n_q_heads=Hq, n_kv_heads=H, kv_dtype=skv.dtype_code(wl.torch_dtype),
                                max_tokens=T, max_sentences=S_cap, max_budget=budget, max_batch=1,
-                               semvec_dtype=skv.SKV_BF16 if sv16 else skv.SKV_F32))
+                               semvec_dtype=sv_code))
 
     # ---- prefill: segmentation + semantic vectors (HIP path), timed once -----------------------------
     d_tok, d_bm = i32(tok, dev), torch.as_tensor(bitmap.view(np.int32)).to(dev)
@@ -113,7 +117,7 @@ def run_single_sequence(args, wl, budget):
     n_sent = torch.empty(4, dtype=torch.int32, device=dev)
     S = ctx.segment(d_tok, d_bm, wl.vocab, seg_id, sent_off, sent_len, n_sent)
     assert S == len(lengths), (S, len(lengths))
-    semvec = torch.empty(L, H, S, D, dtype=torch.bfloat16 if sv16 else torch.float32, device=dev)
+    semvec = torch.empty(L, H, S, D, dtype=sv_torch, device=dev)
     ctx.build_semvec(inp.K, sent_off, S, semvec)
     torch.cuda.synchronize()
     with Timer() as t_seg:
@@ -289,13 +293,13 @@ def run_ragged(args, wl):
     qsets = gen.queries(N_QUERY_SETS * R * B, Hq, D, wl.torch_dtype, args.seed + 1, dev).view(N_QUERY_SETS, R, B, Hq, D)
     torch.cuda.synchronize()
     gen_s = time.time() - t0
-    sv16 = args.semvec_dtype == "bf16"
-    sv_bytes = 2 if sv16 else 4
+    sv_bytes, sv_torch, sv_code = SV_TABLE[args.semvec_dtype]
+    sv16 = args.semvec_dtype != "f32"                        # a reduced table: no committed traffic counters
     ctx = skv.Context(skv.Desc(n_layers=R, n_q_heads=Hq, n_kv_heads=H, kv_dtype=skv.dtype_code(wl.torch_dtype),
                                max_tokens=T_total, max_sentences=S_total, max_budget=budget, max_batch=B,
-                               semvec_dtype=skv.SKV_BF16 if sv16 else skv.SKV_F32))
+                               semvec_dtype=sv_code))
     glob_off = i32(gen.offsets_of(inp.sent_len), dev)
-    semvec = torch.empty(R, H, S_total, D, dtype=torch.bfloat16 if sv16 else torch.float32, device=dev)
+    semvec = torch.empty(R, H, S_total, D, dtype=sv_torch, device=dev)
     ctx.build_semvec(inp.K, glob_off, S_total, semvec)
     torch.cuda.synchronize()
     with Timer() as t_sv:
@@ -588,7 +592,7 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="cfg4: number of sequences (default: the workload's 16)")
     ap.add_argument("--budget", type=int, default=0, help="token budget (default: the workload's largest)")
     ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--semvec-dtype", default="f32", choices=["f32", "bf16"],
+    ap.add_argument("--semvec-dtype", default="f32", choices=["f32", "bf16", "fp8"],
                     help="storage of the mean key vectors (decode workloads); bf16 = the fp32 mean rounded once")
     ap.add_argument("--launch", default="graph", choices=["graph", "direct"],
                     help="graph: the step's launches replayed as one HIP graph; direct: one host call per layer")

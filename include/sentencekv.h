@@ -42,7 +42,7 @@ typedef enum {
     SKV_ENOMEM = -4      /* workspace allocation failed */
 } skv_status;
 
-typedef enum { SKV_F32 = 0, SKV_BF16 = 1 } skv_dtype;
+typedef enum { SKV_F32 = 0, SKV_BF16 = 1, SKV_FP8_E4M3 = 2 /* semantic-vector table only */ } skv_dtype;
 
 typedef struct {
     int32_t n_layers;       /* L: leading dimension of the K/V pools and of the semantic-vector table */
@@ -54,9 +54,10 @@ typedef struct {
     int32_t max_sentences;  /* largest S (S_total for a ragged batch) any call will pass */
     int32_t max_budget;     /* largest per-sequence token budget tau any call will pass */
     int32_t max_batch;      /* largest number of sequences in one skv_decode_step (>= 1) */
-    int32_t semvec_dtype;   /* skv_dtype of the semantic-vector table: SKV_F32, or SKV_BF16 = the fp32 mean rounded once to
-                               nearest even (the mixed-precision sentence vectors of the paper's "Future Work"; halves the
-                               bytes the scoring step reads) */
+    int32_t semvec_dtype;   /* skv_dtype of the semantic-vector table: SKV_F32, or SKV_BF16 / SKV_FP8_E4M3 = the fp32 mean
+                               rounded once to nearest even (the mixed-precision sentence vectors of the paper's "Future
+                               Work"; a half / a quarter of the bytes the scoring step reads).  E4M3 is the 8-bit format of
+                               the OCP specification (bias 7, no infinities, largest value 448); larger means saturate */
 } skv_desc;
 
 typedef struct skv_ctx skv_ctx;   /* opaque */

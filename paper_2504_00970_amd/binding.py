@@ -15,7 +15,7 @@ import torch
 
 from . import _build
 
-SKV_F32, SKV_BF16 = 0, 1
+SKV_F32, SKV_BF16, SKV_FP8_E4M3 = 0, 1, 2
 SKV_OK, SKV_EINVAL, SKV_ECAPACITY, SKV_EHIP, SKV_ENOMEM = 0, -1, -2, -3, -4
 
 

@@ -18,7 +18,7 @@ int check_desc(const skv_desc* d) {
     if (d->n_layers < 1 || d->n_q_heads < 1 || d->n_kv_heads < 1) return SKV_EINVAL;
     if (d->head_dim != skv::kHeadDim) return SKV_EINVAL;
     if (d->kv_dtype != SKV_F32 && d->kv_dtype != SKV_BF16) return SKV_EINVAL;
-    if (d->semvec_dtype != SKV_F32 && d->semvec_dtype != SKV_BF16) return SKV_EINVAL;
+    if (d->semvec_dtype != SKV_F32 && d->semvec_dtype != SKV_BF16 && d->semvec_dtype != SKV_FP8_E4M3) return SKV_EINVAL;
     if (d->n_q_heads % d->n_kv_heads != 0) return SKV_EINVAL;
     const int G = d->n_q_heads / d->n_kv_heads;
     if (G != 1 && G != 2 && G != 4 && G != 8) return SKV_EINVAL;
@@ -42,7 +42,7 @@ int check_ctx(const skv_ctx* ctx) {
 
 inline int64_t layer_elems(const Ctx& c, int64_t rows) { return (int64_t)c.d.n_kv_heads * rows * skv::kHeadDim; }
 inline int elt_bytes(const Ctx& c) { return c.d.kv_dtype == SKV_BF16 ? 2 : 4; }
-inline int sv_bytes(const Ctx& c) { return c.d.semvec_dtype == SKV_BF16 ? 2 : 4; }
+inline int sv_bytes(const Ctx& c) { return c.d.semvec_dtype == SKV_BF16 ? 2 : c.d.semvec_dtype == SKV_FP8_E4M3 ? 1 : 4; }
 
 }  // namespace
 

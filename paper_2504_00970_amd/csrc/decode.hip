@@ -291,14 +291,101 @@ __global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_sv16_kernel
                                                        blk * kRowsPerBlock + w * kScoreRowsPerWave16, score + hs);
 }
 
+// The same from an E4M3 table: a vector is 128 bytes = 8 lanes x 16 bytes (16 dims per lane), a wave load covers 8 buckets,
+// 32 buckets per wave keep 4 loads in flight; the sum over a bucket's 8 lanes is two quad exchanges and a rotation by 4.
+constexpr int kScoreRowsPerWave8 = 32;
+
+template <int EB, int G>
+__global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_sv8_kernel(const char* __restrict__ q,
+                                                                                const char* __restrict__ semvec, SeqView v,
+                                                                                int32_t Hq, float* __restrict__ score) {
+    constexpr int kRowsPerBlock = kScoreRowsPerWave8 * kScoreWavesPerBlock;
+    int blk, b;
+    Seq sq;
+    if (!locate_score_block(v, kRowsPerBlock, blockIdx.x, &b, &blk, &sq)) return;
+    const int h = blockIdx.y;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int c = lane & 7, sub = lane >> 3;
+
+    float qs[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) qs[i] = 0.f;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const char* qrow = q + ((int64_t)(b * Hq + h * G + g) * kHeadDim + c * 16) * EB;
+        if (EB == 4) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float4 t = *reinterpret_cast<const float4*>(qrow + 16 * k);
+                qs[4 * k] += t.x; qs[4 * k + 1] += t.y; qs[4 * k + 2] += t.z; qs[4 * k + 3] += t.w;
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                float f[8];
+                Row<2>::unpack(*reinterpret_cast<const uint4*>(qrow + 16 * k), f);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) qs[8 * k + i] += f[i];
+            }
+        }
+    }
+    constexpr int kIter = kScoreRowsPerWave8 / 8;
+    const int32_t row0 = blk * kRowsPerBlock + w * kScoreRowsPerWave8 + sub;
+    const char* base = semvec + ((int64_t)h * v.S_total + sq.sent_base) * kHeadDim + c * 16;
+    uint4 x[kIter];
+#pragma unroll
+    for (int i = 0; i < kIter; ++i) {                       // clamped addresses: all loads issued back to back
+        const int32_t s = min(row0 + 8 * i, sq.n_sent - 1);
+        x[i] = *reinterpret_cast<const uint4*>(base + (int64_t)s * kHeadDim);
+    }
+    float p[kIter];
+#pragma unroll
+    for (int i = 0; i < kIter; ++i) {
+        const uint32_t wd[4] = {x[i].x, x[i].y, x[i].z, x[i].w};
+        p[i] = 0.f;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            // v_cvt_pk_f32_fp8: two codes of a dword -> two floats; gfx950 reads them as E4M3 of the OCP specification
+            // (a parity test scores a table holding every code against the format's written-out definition)
+            typedef float f32x2 __attribute__((ext_vector_type(2)));
+            const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)wd[k], false), hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)wd[k], true);
+            p[i] += lo[0] * qs[4 * k] + lo[1] * qs[4 * k + 1] + hi[0] * qs[4 * k + 2] + hi[1] * qs[4 * k + 3];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < kIter; ++i) {                       // sum over the 8 lanes of a bucket
+        p[i] = dpp_add<0xB1>(p[i]);
+        p[i] = dpp_add<0x4E>(p[i]);
+        p[i] = dpp_add<0x124>(p[i]);                        // row_ror 4: lanes 4..7 of each group of 8 now hold the group's sum
+    }
+    if (c == 4) {
+        float* out = score + (int64_t)h * v.S_total + sq.sent_base;
+#pragma unroll
+        for (int i = 0; i < kIter; ++i) {
+            const int32_t s = row0 + 8 * i;
+            if (s < sq.n_sent) out[s] = p[i];
+        }
+    }
+}
+
 template <int EB, int RPWV>
 static hipError_t launch_score_g(Ctx* c, const void* q, const void* semvec_layer, const SeqView& v, float* score) {
-    const bool sv16 = c->d.semvec_dtype == SKV_BF16;
-    const int rows_per_block = (sv16 ? kScoreRowsPerWave16 : RPWV) * kScoreWavesPerBlock;
+    const bool sv16 = c->d.semvec_dtype == SKV_BF16, sv8 = c->d.semvec_dtype == SKV_FP8_E4M3;
+    const int rows_per_block = (sv8 ? kScoreRowsPerWave8 : sv16 ? kScoreRowsPerWave16 : RPWV) * kScoreWavesPerBlock;
     const int blocks = (v.S_total + rows_per_block - 1) / rows_per_block + v.B;   // bound on sum_b ceil(S_b/R)
     const dim3 grid(blocks, c->d.n_kv_heads), block(kScoreWavesPerBlock * kWave);
     const char* qp = (const char*)q;
     const char* sv = (const char*)semvec_layer;
+    if (sv8) {
+        switch (c->G) {
+            case 1: hipLaunchKernelGGL((score_sv8_kernel<EB, 1>), grid, block, 0, c->stream, qp, sv, v, c->d.n_q_heads, score); break;
+            case 2: hipLaunchKernelGGL((score_sv8_kernel<EB, 2>), grid, block, 0, c->stream, qp, sv, v, c->d.n_q_heads, score); break;
+            case 4: hipLaunchKernelGGL((score_sv8_kernel<EB, 4>), grid, block, 0, c->stream, qp, sv, v, c->d.n_q_heads, score); break;
+            case 8: hipLaunchKernelGGL((score_sv8_kernel<EB, 8>), grid, block, 0, c->stream, qp, sv, v, c->d.n_q_heads, score); break;
+            default: return hipErrorInvalidValue;
+        }
+        return hipGetLastError();
+    }
     if (sv16) {
         switch (c->G) {
             case 1: hipLaunchKernelGGL((score_sv16_kernel<EB, 1>), grid, block, 0, c->stream, qp, sv, v, c->d.n_q_heads, score); break;

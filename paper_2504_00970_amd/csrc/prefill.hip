@@ -159,7 +159,21 @@ hipError_t launch_segment(Ctx* c, const int32_t* tok, int32_t T, const uint32_t*
 // consecutive rows fully coalesced.  Four such loads are kept in flight per lane.
 // ------------------------------------------------------------------------------------------------
 
-template <int EB, int SVB>     // SVB: bytes per stored element of the table (4 = fp32, 2 = bf16, rounded to nearest even)
+// Nearest E4M3 code (8-bit float of the OCP specification: bias 7, no infinities, largest value 448) of a finite float,
+// ties to the even code, magnitudes that do not fit saturate at 448.
+__device__ __forceinline__ uint32_t f32_to_e4m3(float f) {
+    const uint32_t u = __float_as_uint(f), sign = (u >> 24) & 0x80u, a = u & 0x7fffffffu;
+    uint32_t code;
+    if (a < 0x3c800000u) {                                   // below 2^-6, the smallest normal: multiples of 2^-9
+        code = (uint32_t)__builtin_rintf(__uint_as_float(a) * 512.0f);         // round half to even; 8 is 2^-6 itself
+    } else {
+        const uint32_t r = a + 0x7ffffu + ((a >> 20) & 1u);  // 23 -> 3 fraction bits, round half to even
+        code = min((r >> 20) - (120u << 3), 0x7eu);          // exponent bias 127 -> 7; 0x7e = 448
+    }
+    return sign | code;
+}
+
+template <int EB, int SVB>     // SVB: bytes per stored element of the table (4 = fp32, 2 = bf16, 1 = E4M3; rounded to nearest even)
 __global__ __launch_bounds__(kSemvecWavesPerBlock * kWave) void semvec_kernel(const char* __restrict__ K, int32_t T,
                                                                               const int32_t* __restrict__ sent_off_all,
                                                                               int32_t off_layer_stride, int32_t Hkv,
@@ -209,6 +223,9 @@ __global__ __launch_bounds__(kSemvecWavesPerBlock * kWave) void semvec_kernel(co
             const float m[4] = {acc[i] / n, acc[i + 1] / n, acc[i + 2] / n, acc[i + 3] / n};
             if (SVB == 4) {
                 *reinterpret_cast<float4*>(semvec + (o + i) * 4) = make_float4(m[0], m[1], m[2], m[3]);
+            } else if (SVB == 1) {
+                *reinterpret_cast<uint32_t*>(semvec + (o + i)) = f32_to_e4m3(m[0]) | (f32_to_e4m3(m[1]) << 8) |
+                                                                 (f32_to_e4m3(m[2]) << 16) | (f32_to_e4m3(m[3]) << 24);
             } else {
                 uint32_t rb[4];
 #pragma unroll
@@ -228,6 +245,9 @@ static void launch_semvec_eb(Ctx* c, dim3 grid, dim3 block, const void* K_pool, 
                              int32_t off_layer_stride, int32_t S, void* semvec) {
     if (c->d.semvec_dtype == SKV_BF16)
         hipLaunchKernelGGL((semvec_kernel<EB, 2>), grid, block, 0, c->stream, (const char*)K_pool, T, sent_off, off_layer_stride,
+                           c->d.n_kv_heads, S, (char*)semvec);
+    else if (c->d.semvec_dtype == SKV_FP8_E4M3)
+        hipLaunchKernelGGL((semvec_kernel<EB, 1>), grid, block, 0, c->stream, (const char*)K_pool, T, sent_off, off_layer_stride,
                            c->d.n_kv_heads, S, (char*)semvec);
     else
         hipLaunchKernelGGL((semvec_kernel<EB, 4>), grid, block, 0, c->stream, (const char*)K_pool, T, sent_off, off_layer_stride,

@@ -26,11 +26,11 @@ def make_ctx(wl: gen.Workload, T, S, budget, batch=1, sv_dtype="f32"):
     return skv.Context(skv.Desc(n_layers=wl.n_layers, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
                                 kv_dtype=skv.dtype_code(wl.torch_dtype), max_tokens=max(T, 1),
                                 max_sentences=max(S, 1), max_budget=max(budget, 1), max_batch=batch,
-                                semvec_dtype=skv.SKV_BF16 if sv_dtype == "bf16" else skv.SKV_F32))
+                                semvec_dtype={"f32": skv.SKV_F32, "bf16": skv.SKV_BF16, "fp8": skv.SKV_FP8_E4M3}[sv_dtype]))
 
 
 def sv_torch_dtype(sv_dtype):
-    return torch.bfloat16 if sv_dtype == "bf16" else torch.float32
+    return {"f32": torch.float32, "bf16": torch.bfloat16, "fp8": torch.uint8}[sv_dtype]
 
 
 def bf16_table_close(got_bits: np.ndarray, ref_bits: np.ndarray) -> bool:
@@ -38,6 +38,16 @@ def bf16_table_close(got_bits: np.ndarray, ref_bits: np.ndarray) -> bool:
     g, r = got_bits.astype(np.int32), ref_bits.astype(np.int32)
     same = float((g == r).mean())
     return bool(np.abs(g - r).max() <= 1 and same >= 0.995)
+
+
+def e4m3_table_close(got: np.ndarray, ref: np.ndarray, decode) -> bool:
+    """Two E4M3 tables that round fp32 means differing in summation order: equal almost everywhere, and where they differ
+    the two values are neighbours of the format (one step of 2^(e-10) at their magnitude, 2^-9 below 2^-6)."""
+    g, r = decode(got).astype(np.float64), decode(ref).astype(np.float64)
+    mag = np.maximum(np.abs(g), np.abs(r))
+    step = np.where(mag < 2.0 ** -6, 2.0 ** -9, 2.0 ** (np.floor(np.log2(np.maximum(mag, 2.0 ** -6))) - 3))
+    same = float((got == ref).mean())
+    return bool(np.all(np.abs(g - r) <= step) and same >= 0.99)
 
 
 def np_of(t: torch.Tensor) -> np.ndarray:

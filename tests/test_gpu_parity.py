@@ -136,8 +136,11 @@ def _chain_case(U, oracle32, wl, seed, budget, pool_in_host=False, layers=None, 
         sc_ref = oracle32.score(q, sv_ref)
         if sv_dtype == "f32":
             assert np.all(np.abs(g["score"] - sc_ref) <= 2 * U.score_tolerance(sc_ref))
-        else:                               # the two bf16 tables round fp32 means that differ in summation order
-            assert U.bf16_table_close(sv_np[l], sv_ref)
+        else:                               # the two reduced tables round fp32 means that differ in summation order
+            if sv_dtype == "bf16":
+                assert U.bf16_table_close(sv_np[l], sv_ref)
+            else:
+                assert U.e4m3_table_close(sv_np[l], sv_ref, oracle32.e4m3_decode)
             one = inp.lengths == 1
             assert np.array_equal(sv_np[l][:, one], sv_ref[:, one])
         # (3) selection: the oracle's rule on the GPU's scores, bit for bit
@@ -536,19 +539,40 @@ def test_equal_size_chunk_mode(U, oracle32):
 
 # ----------------------------------------------------------------------------- bf16 table of mean key vectors
 
+@pytest.mark.parametrize("sv_dtype", ["bf16", "fp8"])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-def test_bf16_semvec_table_chain(U, oracle32, dtype):
-    """Mixed-precision sentence vectors (semvec_dtype = bf16): table within one bf16 ulp of the oracle's, scores from
+def test_reduced_semvec_table_chain(U, oracle32, dtype, sv_dtype):
+    """Mixed-precision sentence vectors (semvec_dtype = bf16 or E4M3): table within one step of the oracle's, scores from
     the GPU's own table to the usual tolerance, selection bit-exact on those scores, through the 4-call chain."""
     wl = gen.CFG1.scaled(n_layers=2, n_tokens=9000, dtype=dtype)
-    _chain_case(U, oracle32, wl, seed=31, budget=700, sv_dtype="bf16")
+    _chain_case(U, oracle32, wl, seed=31, budget=700, sv_dtype=sv_dtype)
 
 
-@pytest.mark.parametrize("Hq,B", [(32, 1), (64, 9), (8, 3)])
-def test_bf16_semvec_table_fused(U, oracle32, Hq, B):
-    """The fused decode step (single sequence, small batch, batch path) on a bf16 table, every group size class."""
+@pytest.mark.parametrize("sv_dtype", ["bf16", "fp8"])
+@pytest.mark.parametrize("Hq,B", [(32, 1), (64, 9), (8, 3), (16, 2)])
+def test_reduced_semvec_table_fused(U, oracle32, Hq, B, sv_dtype):
+    """The fused decode step (single sequence, small batch, batch path) on a reduced table, every group size."""
     wl = gen.CFG4.scaled(n_layers=1, n_q_heads=Hq, batch=B, t_range=(300, 3500), budgets=(600,))
-    _fused_case(U, oracle32, wl, seed=33, layers=[0], sv_dtype="bf16")
+    _fused_case(U, oracle32, wl, seed=33, layers=[0], sv_dtype=sv_dtype)
+
+
+def test_e4m3_table_every_code_scores_like_the_oracle(U, oracle32):
+    """A hand-filled E4M3 table holding every finite code (both signs, subnormals, 448) scored by the GPU and by the oracle:
+    pins the kernel's decoding of the format, for bf16 and fp32 queries."""
+    H, S, D = 2, 37, 128
+    codes = np.array([c for c in range(256) if (c & 0x7f) != 0x7f], dtype=np.uint8)
+    rng = np.random.default_rng(3)
+    table = codes[rng.integers(0, len(codes), size=(1, H, S, D))]
+    table[0, 0].reshape(-1)[:len(codes)] = codes                          # every code at least once, in order
+    for dtype in ("bf16", "f32"):
+        wl = gen.CFG1.scaled(n_layers=1, n_q_heads=8, n_kv_heads=H, n_tokens=64, dtype=dtype)
+        ctx = U.make_ctx(wl, 64, S, 8, sv_dtype="fp8")
+        q = gen.queries(1, 8, D, wl.torch_dtype, 5, U.DEV)[0]
+        score = torch.zeros(H, S, device=U.DEV)
+        ctx.score(0, q, torch.from_numpy(table).to(U.DEV), S, score)
+        torch.cuda.synchronize()
+        ref = oracle32.score(gen.to_numpy(q), table[0])
+        assert np.all(np.abs(score.cpu().numpy() - ref) <= U.score_tolerance(ref))
 
 
 @pytest.mark.parametrize("dtype,B", [("bf16", 1), ("f32", 1), ("bf16", 3)])
