@@ -24,6 +24,7 @@ int check_desc(const skv_desc* d) {
     if (G != 1 && G != 2 && G != 4 && G != 8) return SKV_EINVAL;
     if (d->max_tokens < 1 || d->max_sentences < 1 || d->max_budget < 1 || d->max_batch < 1) return SKV_EINVAL;
     if (d->max_batch > 4096) return SKV_EINVAL;
+    if ((int64_t)d->max_batch * d->n_kv_heads > 65535) return SKV_EINVAL;    // (sequence, head) pairs are a grid dimension
     return SKV_OK;
 }
 

@@ -34,7 +34,7 @@ def test_strerror_covers_every_status():
 
 
 @pytest.mark.parametrize("field,value", [("head_dim", 64), ("n_q_heads", 30), ("kv_dtype", 7), ("max_budget", 0),
-                                         ("n_kv_heads", 0), ("max_batch", 0), ("n_q_heads", 8 * 16), ("semvec_dtype", 3), ("kv_dtype", 2)])
+                                         ("n_kv_heads", 0), ("max_batch", 0), ("n_q_heads", 8 * 16), ("semvec_dtype", 3), ("kv_dtype", 2), ("max_batch", 4097)])
 def test_create_rejects_bad_descriptors_before_touching_the_gpu(field, value):
     kw = dict(n_layers=1, n_q_heads=32, n_kv_heads=8, max_tokens=64, max_sentences=8, max_budget=16)
     kw[field] = value
