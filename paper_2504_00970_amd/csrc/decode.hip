@@ -804,7 +804,8 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
     static_assert(kIter >= 1 && kGroups >= 1 && CHUNK % kWave == 0, "block shape");
 
     __shared__ float sm_logit[G][CHUNK];
-    // Wave partial sums of P.V (wave ww, head g, dim d at sm_red_flat[ww * kRedStride + g * 128 + d]); later the
+    // Wave partial sums of P.V (wave ww, head g, dim d at sm_red_flat[ww * kRedStride + g * 128 + d], on the MFMA path at
+    // [ww * kRedStride + d * G + g]); later the
     // merge scratch.  On the MFMA path each wave's partial sums reuse its own value tile.
     constexpr int kVPitch = 2 * kHeadDim + 16;                // bytes per value row in LDS; +16 spreads row groups over banks
     constexpr int kRedStride = kMfma ? 16 * kVPitch / 4 : G * kHeadDim;
@@ -823,6 +824,18 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
     const int32_t j0 = split * CHUNK;
     const int slot = split * (CHUNK / kWave);                     // partial slot (slots are counted in 64-token units)
     SKV_T(0);
+
+    // bf16: the query fragments of the tile waves are requested first of all; they are in registers long before the
+    // key rows arrive, so the logits wait for the keys only (lane (t16, qd): head t16, dims 32 s + 8 qd .. + 7)
+    uint4 qB[kMfma ? 4 : 1];
+    if constexpr (kMfma) {
+        if (w < kTiles) {
+            const int t16 = lane & 15, qd = lane >> 4;
+#pragma unroll
+            for (int s2 = 0; s2 < 4; ++s2)
+                qB[s2] = *reinterpret_cast<const uint4*>(a.q + ((qhead0 + min(t16, G - 1)) * kHeadDim) * EB + 64 * s2 + 16 * qd);
+        }
+    }
 
     int32_t n;                                                    // retrieved tokens of this (sequence, head)
     if (MODE == kFused) {
@@ -918,7 +931,7 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
                 liveK = liveK && x >= 0 && x < sq.n_tok_ctx;
                 rowK = min(max(x, 0), max(sq.n_tok_ctx - 1, 0));
             }
-            uint4 kA[4], vR[4], qB[4];
+            uint4 kA[4], vR[4];
 #pragma unroll
             for (int s2 = 0; s2 < 4; ++s2) kA[s2] = *reinterpret_cast<const uint4*>(Kh + (int64_t)rowK * kRowBytes + 64 * s2 + 16 * qd);
 #pragma unroll
@@ -926,9 +939,6 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
                 const int32_t rowV = __shfl(rowK, 4 * i + qd);     // lane 4i+qd (< 16) holds the row of token 4i+qd
                 vR[i] = *reinterpret_cast<const uint4*>(Vh + (int64_t)rowV * kRowBytes + 16 * t16);
             }
-#pragma unroll
-            for (int s2 = 0; s2 < 4; ++s2)
-                qB[s2] = *reinterpret_cast<const uint4*>(a.q + ((qhead0 + min(t16, G - 1)) * kHeadDim) * EB + 64 * s2 + 16 * qd);
             const unsigned long long vm = __ballot(liveK);        // bit t (t < 16): token t of the tile is real
             SKV_T(5);
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -988,13 +998,18 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
                 const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
                 o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, vb, zero, 0, 0, 0);
             }
-            // the value tile has been consumed: its space takes the wave's partial sums
+            // the value tile has been consumed: its space takes the wave's partial sums, head fastest (dim d, head g at
+            // red[d * G + g]), so that a lane stores its heads of one dim with a single instruction
             float* red = sm_red_flat + w * kRedStride;
+            if (4 * qd < G) {
 #pragma unroll
-            for (int dt = 0; dt < kHeadDim / 16; ++dt)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (4 * qd + j < G) red[(4 * qd + j) * kHeadDim + 16 * dt + t16] = o[dt][j];
+                for (int dt = 0; dt < kHeadDim / 16; ++dt) {
+                    float* dst = red + (16 * dt + t16) * G + 4 * qd;
+                    if constexpr (G >= 4) *reinterpret_cast<float4*>(dst) = make_float4(o[dt][0], o[dt][1], o[dt][2], o[dt][3]);
+                    else if constexpr (G == 2) *reinterpret_cast<float2*>(dst) = make_float2(o[dt][0], o[dt][1]);
+                    else dst[0] = o[dt][0];
+                }
+            }
         }
         __syncthreads();
         if (tid < G) {                                            // block max and normaliser of head tid
@@ -1124,9 +1139,10 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
     __syncthreads();
     for (int i = tid; i < kOut; i += kBlockThreads) {
         const int g = i / kHeadDim, d = i % kHeadDim;
-        float o = sm_red_flat[i];
+        const int src = kMfma ? d * G + g : i;                     // the MFMA path leaves its sums head fastest
+        float o = sm_red_flat[src];
 #pragma unroll
-        for (int ww = 1; ww < kRedWaves; ++ww) o += sm_red_flat[ww * kRedStride + i];
+        for (int ww = 1; ww < kRedWaves; ++ww) o += sm_red_flat[ww * kRedStride + src];
         st_agent(a.part + (((qhead0 + g) * a.max_splits) + slot) * kHeadDim + d, o);
     }
     SKV_T(7);
