@@ -863,12 +863,8 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
         __syncthreads();                                          // bucket starts are marked
         if (w < CHUNK / kWave) {
             const int32_t v = sm_row[w * kWave + lane];
-            int32_t hp = v >= 0 ? lane : -1;                      // position of the last bucket start at or before this lane
-#pragma unroll
-            for (int o = 1; o < 64; o <<= 1) {
-                const int32_t t = __shfl_up(hp, o);
-                if (lane >= o) hp = max(hp, t);
-            }
+            // position of the last bucket start at or before this lane (-1: none): running maximum of lane + 1 over the starts
+            const int32_t hp = (int32_t)wave_scan_max_u32(v >= 0 ? (uint32_t)lane + 1u : 0u) - 1;
             const int32_t base = __shfl(v, max(hp, 0));
             const int32_t row = hp >= 0 ? base + (lane - hp) : -1;
             sm_row[w * kWave + lane] = row;
@@ -1534,12 +1530,8 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(4
         __syncthreads();                                          // bucket starts are marked, queries are in LDS
         {
             const int32_t v = ss.row[tid];
-            int32_t hp = v >= 0 ? lane : -1;                      // position of the last bucket start at or before this lane
-#pragma unroll
-            for (int o = 1; o < 64; o <<= 1) {
-                const int32_t t = __shfl_up(hp, o);
-                if (lane >= o) hp = max(hp, t);
-            }
+            // position of the last bucket start at or before this lane (-1: none): running maximum of lane + 1 over the starts
+            const int32_t hp = (int32_t)wave_scan_max_u32(v >= 0 ? (uint32_t)lane + 1u : 0u) - 1;
             const int32_t base = __shfl(v, max(hp, 0));
             xi = hp >= 0 ? base + (lane - hp) : -1;
             const int32_t pos = j0 + tid;

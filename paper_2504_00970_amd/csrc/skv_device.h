@@ -38,6 +38,21 @@ __device__ __forceinline__ uint32_t wave_scan_u32(uint32_t v) {
     v = dpp_add_u32<0x143, 0xc>(v);
     return v;
 }
+// v and (v moved by a DPP pattern), the larger of the two; lanes without a source, or rows masked out, keep v
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_max_u32(uint32_t v) {
+    return max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, true));
+}
+// inclusive running maximum over the 64 lanes of a wave (same DPP steps as the prefix sum)
+__device__ __forceinline__ uint32_t wave_scan_max_u32(uint32_t v) {
+    v = dpp_max_u32<0x111, 0xf>(v);
+    v = dpp_max_u32<0x112, 0xf>(v);
+    v = dpp_max_u32<0x114, 0xf>(v);
+    v = dpp_max_u32<0x118, 0xf>(v);
+    v = dpp_max_u32<0x142, 0xa>(v);
+    v = dpp_max_u32<0x143, 0xc>(v);
+    return v;
+}
 // Inclusive scan over the block's threads (thread order); one barrier.  A `slot` is used once per call
 // of the selection.
 __device__ __forceinline__ uint32_t block_scan_u32(uint32_t val, uint32_t* slot, uint32_t* total) {
