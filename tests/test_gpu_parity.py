@@ -585,3 +585,47 @@ def test_fused_many_buckets_per_sequence(U, oracle32, dtype, B):
     _fused_case(U, oracle32, wl, seed=42, layers=[0])          # few, long buckets: S small, 64-token blocks; long spans
     wl = gen.CFG1.scaled(n_layers=1, batch=B, t_range=(40000, 40100), budgets=(1000,), len_dist=("uniform", 1, 30), dtype=dtype)
     _fused_case(U, oracle32, wl, seed=43, layers=[0])          # S > 2048 with buckets that span the 64-position pieces
+
+
+# ----------------------------------------------------------------------------- seeded sweeps over shapes
+
+_LEN_DISTS = [("uniform", 1, 3), ("uniform", 8, 40), ("lognormal", 20, 0.7, 3, 120), ("uniform", 1, 300)]
+
+
+@pytest.mark.parametrize("sweep_seed", [1, 7])
+def test_fused_step_seeded_shape_sweep(U, oracle32, sweep_seed):
+    """The fused step over a seeded sample of (batch, group size, pool type, table type, budget, context range, bucket
+    length distribution): every launch path (64/128-token blocks, 1024-token streaming blocks, the fp32 batch path) with
+    shapes no hand-written case has."""
+    rng = np.random.default_rng(sweep_seed)
+    for it in range(14):
+        B = int(rng.choice([1, 2, 3, 8, 9, 16, 20]))
+        Hq = int(rng.choice([8, 16, 32, 64]))
+        dtype = str(rng.choice(["bf16", "bf16", "f32"]))
+        sv = str(rng.choice(["f32", "bf16", "fp8"]))
+        budget = int(rng.choice([1, 17, 64, 200, 700, 1024, 1100, 2048, 3000]))
+        lo = int(rng.choice([1, 50, 400, 2000]))
+        hi = lo + int(rng.choice([0, 100, 3000, 9000]))
+        if B >= 16:
+            hi = min(hi, 3000)
+        ld = _LEN_DISTS[int(rng.integers(0, 4))]
+        wl = gen.CFG4.scaled(n_layers=1, n_q_heads=Hq, batch=B, t_range=(lo, hi), budgets=(budget,), dtype=dtype, len_dist=ld)
+        _say(f"sweep {sweep_seed}/{it}: B={B} Hq={Hq} {dtype} table={sv} budget={budget} T=[{lo},{hi}] len={ld}")
+        _fused_case(U, oracle32, wl, seed=100 * sweep_seed + it, layers=[0], sv_dtype=sv)
+
+
+@pytest.mark.parametrize("sweep_seed", [3, 11])
+def test_chain_seeded_shape_sweep(U, oracle32, sweep_seed):
+    """The 4-call chain over a seeded sample of head layouts, pool and table types, budgets around the block sizes of the
+    attention kernel (64, 128, 256 tokens) and contexts from one token up."""
+    rng = np.random.default_rng(sweep_seed)
+    for it in range(14):
+        Hq, Hkv = [(32, 8), (8, 8), (16, 8), (64, 8), (4, 1), (8, 2)][int(rng.integers(0, 6))]
+        dtype = str(rng.choice(["bf16", "bf16", "f32"]))
+        sv = str(rng.choice(["f32", "bf16", "fp8"]))
+        budget = int(rng.choice([1, 17, 64, 127, 128, 129, 700, 1024, 2048, 4096, 5000]))
+        Tn = int(rng.choice([1, 2, 63, 500, 3000, 9000, 20000]))
+        ld = _LEN_DISTS[int(rng.integers(0, 4))]
+        wl = gen.CFG1.scaled(n_layers=1, n_q_heads=Hq, n_kv_heads=Hkv, n_tokens=Tn, dtype=dtype, len_dist=ld)
+        _say(f"sweep {sweep_seed}/{it}: Hq={Hq}/{Hkv} {dtype} table={sv} budget={budget} T={Tn} len={ld}")
+        _chain_case(U, oracle32, wl, seed=200 * sweep_seed + it, budget=budget, sv_dtype=sv)
