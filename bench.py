@@ -134,10 +134,14 @@ def run_single_sequence(args, wl, budget):
 
     q_cur = torch.empty(L, Hq, D, dtype=wl.torch_dtype, device=dev)     # the step's queries (graph input)
 
+    # a model with few layers (cfg0 has one) is walked several times per step, so that a step is not all launch overhead
+    passes = max(1, 32 // L)
+
     def layers(record_into=None):
-        for l in range(L):
-            ctx.decode_step(l, 1, q_cur[l], q_cur[l], inp.K, inp.V, T, semvec, S, cu_tok, cu_sent, sent_off, sent_len,
-                            d_budget, out[l], None, None, None if record_into is None else record_into[l])
+        for _ in range(1 if record_into is not None else passes):
+            for l in range(L):
+                ctx.decode_step(l, 1, q_cur[l], q_cur[l], inp.K, inp.V, T, semvec, S, cu_tok, cu_sent, sent_off, sent_len,
+                                d_budget, out[l], None, None, None if record_into is None else record_into[l])
 
     for i in range(N_QUERY_SETS):            # records n_tok of every (query set, layer)
         q_cur.copy_(qsets[i])
@@ -168,7 +172,7 @@ def run_single_sequence(args, wl, budget):
     n_tok_layer = float(n_tok_all[used].sum(axis=2).mean()) if used else 0.0     # sum over heads, mean over layer-steps
     n_sel_layer = n_tok_layer / float(lengths.mean())
     bytes_layer = decode_bytes(wl, S, n_tok_layer, n_sel_layer, fused=True, sv_bytes=sv_bytes)
-    us_per_layer = ms_per_step * 1e3 / L
+    us_per_layer = ms_per_step * 1e3 / (L * passes)
     gbps = bytes_layer["total"] / (us_per_layer * 1e-6) / 1e9
 
     # ---- per-kernel live timing: each stage launched back-to-back over all layers ------------------------
@@ -191,8 +195,9 @@ def run_single_sequence(args, wl, budget):
     reps = max(2, min(20, args.steps))
     for name, fn in stages.items():
         def all_layers(fn=fn):
-            for l in range(L):
-                fn(l)
+            for _ in range(passes):
+                for l in range(L):
+                    fn(l)
         all_layers()
         g = capture(ctx, all_layers)
         g.replay()
@@ -200,7 +205,7 @@ def run_single_sequence(args, wl, budget):
         with Timer() as t:
             for _ in range(reps):
                 g.replay()
-        kern[name] = t.ms * 1e3 / (reps * L)
+        kern[name] = t.ms * 1e3 / (reps * L * passes)
     nt_chain = float(n_tok[:, :H].sum().item()) / L
     b_unf = decode_bytes(wl, S, nt_chain, nt_chain / float(lengths.mean()), fused=False, sv_bytes=sv_bytes)
     kernels = {k: dict(us=round(v, 3), bytes=int(b_unf[k]), GBps=round(b_unf[k] / (v * 1e-6) / 1e9, 1))
@@ -218,12 +223,12 @@ def run_single_sequence(args, wl, budget):
         "value": round(gbps, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
-        "config": {"workload": wl.name, "layers": L, "q_heads": Hq, "kv_heads": H, "head_dim": D, "context": T,
+        "config": {"workload": wl.name, "layers": L, "layer_passes_per_step": passes, "q_heads": Hq, "kv_heads": H, "head_dim": D, "context": T,
                    "sentences": S, "budget": budget, "batch": 1, "path": "skv_decode_step (score+select+attend from pool)",
                    "kv_pool": "hbm", "launch": args.launch, "semvec_dtype": args.semvec_dtype},
         "us_per_layer": round(us_per_layer, 3),
-        "us_per_layer_direct_launch": round(ms_direct * 1e3 / L, 3),
-        "us_per_layer_hip_graph": round(ms_graph * 1e3 / L, 3),
+        "us_per_layer_direct_launch": round(ms_direct * 1e3 / (L * passes), 3),
+        "us_per_layer_hip_graph": round(ms_graph * 1e3 / (L * passes), 3),
         "bytes_per_layer": int(bytes_layer["total"]),
         "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4),
         "mean_tokens_selected_per_head": round(n_tok_layer / H, 1),
