@@ -120,6 +120,13 @@ __device__ __forceinline__ unsigned int ld_agent(const unsigned int* p) {
 __device__ __forceinline__ unsigned long long ld_agent64(const float* p) {       // two consecutive floats
     return __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// Barrier behind which another thread of the block publishes what this block has stored (an arrival counter).  The
+// workgroup barrier by itself does not wait for a wave's outstanding global stores (the waves of a block share their CU's
+// cache, so the compiler leaves the store counter alone at workgroup scope): each wave waits for its own first.
+__device__ __forceinline__ void block_sync_after_stores() {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+}
 __device__ __forceinline__ float lo_f(unsigned long long v) { return __uint_as_float((uint32_t)v); }
 __device__ __forceinline__ float hi_f(unsigned long long v) { return __uint_as_float((uint32_t)(v >> 32)); }
 
@@ -1144,9 +1151,9 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
     SKV_T(7);
 
     // ---- 5. last arrival combines ------------------------------------------------------------------
-    // The barrier (with its wait for outstanding stores) puts the block's write-through partial stores
-    // before thread 0's device-scope increment; whoever reads nsplit - 1 knows every partial is there.
-    __syncthreads();
+    // Every wave waits for its own write-through partial stores, then the barrier: only after both does thread 0
+    // issue the device-scope increment, so whoever reads nsplit - 1 knows every partial is there.
+    block_sync_after_stores();
     if (tid == 0) {
         const unsigned int old = __hip_atomic_fetch_add(&a.counter[bh], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         sm_last = (old == (unsigned int)(nsplit - 1));
@@ -1444,7 +1451,7 @@ __device__ __forceinline__ void stream_attend(const AttArgs& a, StreamShared& ss
     SKV_T(7);
 
     // ---- last arrival combines (same protocol as attend_kernel) ------------------------------------------------
-    __syncthreads();
+    block_sync_after_stores();
     if (tid == 0) {
         const unsigned int old = __hip_atomic_fetch_add(&a.counter[bh], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         ss.last = (old == (unsigned int)(nsplit - 1));

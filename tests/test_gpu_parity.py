@@ -629,3 +629,54 @@ def test_chain_seeded_shape_sweep(U, oracle32, sweep_seed):
         wl = gen.CFG1.scaled(n_layers=1, n_q_heads=Hq, n_kv_heads=Hkv, n_tokens=Tn, dtype=dtype, len_dist=ld)
         _say(f"sweep {sweep_seed}/{it}: Hq={Hq}/{Hkv} {dtype} table={sv} budget={budget} T={Tn} len={ld}")
         _chain_case(U, oracle32, wl, seed=200 * sweep_seed + it, budget=budget, sv_dtype=sv)
+
+
+# ----------------------------------------------------------------------------- repeated launches
+
+@pytest.mark.parametrize("case", ["single", "small_batch", "batch_bf16", "batch_f32"])
+def test_repeated_launches_reproduce_their_results(U, oracle32, case):
+    """The split-K partials and the arrival counter travel between blocks inside one launch: many back-to-back launches
+    (nothing but the launches themselves between two checks) must keep reproducing the first result of the same inputs --
+    bit for bit where the summation order is fixed, within the attention tolerance for the bf16 batch kernel, whose waves
+    take their tiles in arrival order.  (A missing wait for the partial stores before the arrival showed up as wrong outputs
+    about once in 1600 launches of the full-size batch.)"""
+    wl, iters, exact = {
+        "single": (gen.CFG1.scaled(n_layers=1, batch=1, t_range=(32768, 32768), budgets=(2048,)), 1500, True),
+        "small_batch": (gen.CFG4.scaled(n_layers=1, batch=3, t_range=(3000, 9000), budgets=(1024,)), 1500, True),
+        "batch_bf16": (gen.CFG4.scaled(n_layers=1, t_range=(8192, 32768)), 3000, False),
+        "batch_f32": (gen.CFG4.scaled(n_layers=1, dtype="f32", batch=8, t_range=(3000, 9000)), 800, True),
+    }[case]
+    inp = gen.ragged_inputs(wl, seed=0, device=U.DEV, resident_layers=1)
+    B, H, Hq, D = wl.batch, wl.n_kv_heads, wl.n_q_heads, wl.head_dim
+    T_total, S_total = int(inp.cu_tok[-1]), int(inp.cu_sent[-1])
+    budget = int(inp.budget.max())
+    ctx = U.make_ctx(wl, T_total, S_total, budget, batch=B)
+    sv = torch.zeros(1, H, S_total, D, device=U.DEV)
+    ctx.build_semvec(inp.K, U.i32(gen.offsets_of(inp.sent_len)), S_total, sv)
+    d = [U.i32(x) for x in (inp.cu_tok, inp.cu_sent, inp.sent_off, inp.sent_len, inp.budget)]
+    NQ = 4
+    q = gen.queries(NQ * B, Hq, D, wl.torch_dtype, 1, U.DEV).view(NQ, B, Hq, D)
+    out = torch.empty(B, Hq, D, device=U.DEV)
+    lse = torch.empty(B, Hq, device=U.DEV)
+    nt = U.empty_i32(B, H, fill=-1)
+
+    def step(k):
+        ctx.decode_step(0, B, q[k], q[k], inp.K, inp.V, T_total, sv, S_total, *d, out, lse, None, nt)
+
+    ref = []
+    for k in range(NQ):
+        step(k)
+        torch.cuda.synchronize()
+        ref.append((out.clone(), lse.clone(), nt.clone()))
+    _say("repeated launches:", case, "B", B, "tokens", T_total, "iters", iters)
+    for it in range(iters):
+        step(it % NQ)
+        if it % 8 == 7 or it == iters - 1:
+            torch.cuda.synchronize()
+            o, l, n = ref[it % NQ]
+            assert torch.equal(nt, n), it
+            if exact:
+                assert torch.equal(out, o) and torch.equal(lse, l), it
+            else:
+                assert float((out - o).abs().max()) <= ATT_TOL[wl.dtype] / 4, it
+                assert float((lse - l).abs().max()) <= ATT_TOL[wl.dtype] / 4, it
