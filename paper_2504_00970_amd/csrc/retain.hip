@@ -426,6 +426,28 @@ __global__ __launch_bounds__(kBlockThreads) void retain_kernel(const float* __re
     const int kpt = (Tp + kBlockThreads - 1) / kBlockThreads;
     const int32_t i0 = tid * kpt, i1 = min(i0 + kpt, Tp);
 
+    // Up to kRetainKreg tokens per thread (prompts up to 32K) keep their keys in registers: one batch of loads on
+    // clamped addresses instead of a dependent load per token in each of the six sweeps below.
+    constexpr int kRetainKreg = 32;
+    const bool in_regs = kpt <= kRetainKreg;                           // block-uniform
+    uint32_t rk[kRetainKreg];
+    if (in_regs) {
+#pragma unroll
+        for (int j = 0; j < kRetainKreg; ++j) rk[j] = __float_as_uint(alpha[min(i0 + j, Tp - 1)]);
+#pragma unroll
+        for (int j = 0; j < kRetainKreg; ++j) rk[j] = score_key(__uint_as_float(rk[j]));
+    }
+    // fn(i, key) for every token the thread owns, in position order
+    auto for_keys = [&](auto&& fn) {
+        if (in_regs) {
+#pragma unroll
+            for (int j = 0; j < kRetainKreg; ++j)
+                if (i0 + j < i1) fn(i0 + j, rk[j]);
+        } else {
+            for (int32_t i = i0; i < i1; ++i) fn(i, score_key(alpha[i]));
+        }
+    };
+
     // ---- key of the need-th largest importance ---------------------------------------------------------
     uint32_t prefix = 0;
     int shift = 32;
@@ -436,10 +458,9 @@ __global__ __launch_bounds__(kBlockThreads) void retain_kernel(const float* __re
         for (int i = tid; i < 2048; i += kBlockThreads) sh.hist[i] = 0;
         if (tid == 0) sh.res[pass][0] = -1;
         __syncthreads();
-        for (int32_t i = i0; i < i1; ++i) {
-            const uint32_t key = score_key(alpha[i]);
+        for_keys([&](int32_t, uint32_t key) {
             if (pass == 0 || (key >> shift) == prefix) atomicAdd(&sh.hist[(key >> nshift) & (nbins - 1)], 1u);
-        }
+        });
         __syncthreads();
         // thread order == descending digit order: thread t owns digits nbins-1-2t and nbins-2-2t
         const int d1 = nbins - 1 - 2 * tid;
@@ -460,27 +481,25 @@ __global__ __launch_bounds__(kBlockThreads) void retain_kernel(const float* __re
 
     // ---- compaction in position order ------------------------------------------------------------------
     uint32_t my_eq = 0;
-    for (int32_t i = i0; i < i1; ++i) my_eq += score_key(alpha[i]) == prefix ? 1u : 0u;
+    for_keys([&](int32_t, uint32_t key) { my_eq += key == prefix ? 1u : 0u; });
     uint32_t tot;
     uint32_t eq_before = block_scan_u32(my_eq, sh.wave_tot[3], &tot) - my_eq;
     uint32_t my_cnt = 0;
     {
         uint32_t e = eq_before;
-        for (int32_t i = i0; i < i1; ++i) {
-            const uint32_t key = score_key(alpha[i]);
+        for_keys([&](int32_t, uint32_t key) {
             if (key > prefix) my_cnt += 1;
             else if (key == prefix) { if (e < take_equal) my_cnt += 1; e += 1; }
-        }
+        });
     }
     uint32_t pos = block_scan_u32(my_cnt, sh.wave_tot[4], &tot) - my_cnt;
     {
         uint32_t e = eq_before;
-        for (int32_t i = i0; i < i1; ++i) {
-            const uint32_t key = score_key(alpha[i]);
+        for_keys([&](int32_t i, uint32_t key) {
             bool kept = key > prefix;
             if (key == prefix) { kept = e < take_equal; e += 1; }
             if (kept) keep[pos++] = i;
-        }
+        });
     }
     __syncthreads();                                                   // keep[0 .. need) is written (block-visible)
 
