@@ -274,7 +274,7 @@ int skv_gather(skv_ctx* ctx, int32_t layer, const void* K_pool, const void* V_po
         Vd = vd;
     }
     const int64_t off = (int64_t)layer * layer_elems(ctx->c, T) * elt_bytes(ctx->c);
-    return hip_status(skv::launch_gather(&ctx->c, (const char*)Kd + off, (const char*)Vd + off, T, tok_idx, n_tok, budget,
+    return hip_status(skv::launch_gather(&ctx->c, (const char*)Kd + off, (const char*)Vd + off, T, pool_in_host != 0, tok_idx, n_tok, budget,
                                          K_sel, V_sel));
 }
 

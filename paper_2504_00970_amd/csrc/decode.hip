@@ -670,22 +670,27 @@ hipError_t launch_select(Ctx* c, const float* score, const int32_t* sent_off, co
 }
 
 // ------------------------------------------------------------------------------------------------
-// Gather.  One 16-byte lane chunk per thread per row; a block copies kGatherRowsPerBlock rows of K
-// (blockIdx.z == 0) or V (blockIdx.z == 1) of one KV head with all its loads issued before its stores.
-// The pool pointer may be device-mapped pinned host memory: the same loads then cross PCIe.
+// Gather.  One 16-byte lane chunk per thread per row; a block copies RPB rows of K (blockIdx.z == 0) or V
+// (blockIdx.z == 1) of one KV head with all its loads issued before its stores.  The pool pointer may be
+// device-mapped pinned host memory: the same loads then cross PCIe.  RPB = 32 for a pool in HBM (16.7 MB per layer
+// at a 2048-token budget: 6.3 us against 7.1 with 64 rows and 8.9 with 128), 64 for a host pool (53 GB/s over PCIe
+// against 52 with 32 rows and 47 with 16).
 // ------------------------------------------------------------------------------------------------
-template <int EB>
+constexpr int kGatherRowsHbm = 32, kGatherRowsHost = kGatherRowsPerBlock;
+
+template <int EB, int RPB>
 __global__ __launch_bounds__(kGatherThreads) void gather_kernel(const char* __restrict__ Kl, const char* __restrict__ Vl,
                                                                 int32_t T, const int32_t* __restrict__ tok_idx,
                                                                 const int32_t* __restrict__ n_tok, int32_t budget,
                                                                 char* __restrict__ Ks, char* __restrict__ Vs) {
     using R = Row<EB>;
     constexpr int kRowsPerIter = kGatherThreads / R::LPR;
-    constexpr int kIter = kGatherRowsPerBlock / kRowsPerIter;
+    constexpr int kIter = RPB / kRowsPerIter;
     constexpr int kRowBytes = kHeadDim * EB;
+    static_assert(kIter >= 1 && RPB % kRowsPerIter == 0, "block shape of the gather");
     const int h = blockIdx.y;
     const int32_t n = min(n_tok[h], budget);
-    const int32_t j0 = blockIdx.x * kGatherRowsPerBlock;
+    const int32_t j0 = blockIdx.x * RPB;
     if (j0 >= n) return;
     const char* src = (blockIdx.z == 0 ? Kl : Vl) + (int64_t)h * T * kRowBytes;
     char* dst = (blockIdx.z == 0 ? Ks : Vs) + (int64_t)h * budget * kRowBytes;
@@ -712,17 +717,23 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(const char* __re
     }
 }
 
-hipError_t launch_gather(Ctx* c, const void* K_layer, const void* V_layer, int32_t T, const int32_t* tok_idx,
+template <int EB, int RPB>
+static hipError_t launch_gather_g(Ctx* c, const void* K_layer, const void* V_layer, int32_t T, const int32_t* tok_idx,
+                                  const int32_t* n_tok, int32_t budget, void* K_sel, void* V_sel) {
+    const dim3 grid((budget + RPB - 1) / RPB, c->d.n_kv_heads, 2), block(kGatherThreads);
+    hipLaunchKernelGGL((gather_kernel<EB, RPB>), grid, block, 0, c->stream, (const char*)K_layer, (const char*)V_layer, T, tok_idx,
+                       n_tok, budget, (char*)K_sel, (char*)V_sel);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather(Ctx* c, const void* K_layer, const void* V_layer, int32_t T, bool host_pool, const int32_t* tok_idx,
                          const int32_t* n_tok, int32_t budget, void* K_sel, void* V_sel) {
     if (budget == 0) return hipSuccess;
-    const dim3 grid((budget + kGatherRowsPerBlock - 1) / kGatherRowsPerBlock, c->d.n_kv_heads, 2), block(kGatherThreads);
     if (c->d.kv_dtype == SKV_BF16)
-        hipLaunchKernelGGL(gather_kernel<2>, grid, block, 0, c->stream, (const char*)K_layer, (const char*)V_layer, T,
-                           tok_idx, n_tok, budget, (char*)K_sel, (char*)V_sel);
-    else
-        hipLaunchKernelGGL(gather_kernel<4>, grid, block, 0, c->stream, (const char*)K_layer, (const char*)V_layer, T,
-                           tok_idx, n_tok, budget, (char*)K_sel, (char*)V_sel);
-    return hipGetLastError();
+        return host_pool ? launch_gather_g<2, kGatherRowsHost>(c, K_layer, V_layer, T, tok_idx, n_tok, budget, K_sel, V_sel)
+                         : launch_gather_g<2, kGatherRowsHbm>(c, K_layer, V_layer, T, tok_idx, n_tok, budget, K_sel, V_sel);
+    return host_pool ? launch_gather_g<4, kGatherRowsHost>(c, K_layer, V_layer, T, tok_idx, n_tok, budget, K_sel, V_sel)
+                     : launch_gather_g<4, kGatherRowsHbm>(c, K_layer, V_layer, T, tok_idx, n_tok, budget, K_sel, V_sel);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -84,7 +84,7 @@ hipError_t launch_score(Ctx* c, const void* q, const void* semvec_layer, const S
 hipError_t launch_select(Ctx* c, const float* score, const int32_t* sent_off, const int32_t* sent_len,
                          const SeqView& v, int32_t* sel_sent, int32_t* n_sel, int32_t* tok_idx, int32_t idx_stride,
                          int32_t* n_tok);
-hipError_t launch_gather(Ctx* c, const void* K_layer, const void* V_layer, int32_t T, const int32_t* tok_idx,
+hipError_t launch_gather(Ctx* c, const void* K_layer, const void* V_layer, int32_t T, bool host_pool, const int32_t* tok_idx,
                          const int32_t* n_tok, int32_t budget, void* K_sel, void* V_sel);
 // Attention over K_sel/V_sel [B*Hkv][row_stride][D] with n_tok [B*Hkv] from memory.
 hipError_t launch_attend(Ctx* c, const void* q, const void* K_sel, const void* V_sel, int32_t row_stride,
