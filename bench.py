@@ -594,7 +594,7 @@ def main():
     ap.add_argument("--window", type=int, default=32, help="cfg3-retain: observation-window tokens")
     ap.add_argument("--keep", type=int, default=4096, help="cfg3-retain: tokens retained per layer (floor(r tau))")
     ap.add_argument("--resident-layers", type=int, default=4, help="cfg4: layers of the pool kept in HBM")
-    ap.add_argument("--batch", type=int, default=0, help="cfg4: number of sequences (default: the workload's 16)")
+    ap.add_argument("--batch", type=int, default=0, help="cfg4: number of sequences (default 16); cfg1, cfg2: that many sequences of the workload's context in one batch")
     ap.add_argument("--budget", type=int, default=0, help="token budget (default: the workload's largest)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--semvec-dtype", default="f32", choices=["f32", "bf16", "fp8"],
@@ -619,6 +619,10 @@ def main():
     wl = gen.CONFIGS["cfg3" if retain else args.workload]
     if args.batch > 0 and args.workload == "cfg4":
         wl = wl.scaled(batch=args.batch)
+    elif args.batch > 1 and args.workload in ("cfg1", "cfg2"):
+        # The same decode step for `batch` sequences of the workload's context, each with its own sentence structure.
+        wl = wl.scaled(name="%s_x%d" % (wl.name, args.batch), batch=args.batch, t_range=(wl.n_tokens, wl.n_tokens),
+                       budgets=(args.budget or max(wl.budgets),))
     if args.host_pool_layers < 0:
         args.host_pool_layers = 2 if args.workload == "cfg2" else 0
     if retain:

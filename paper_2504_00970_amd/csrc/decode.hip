@@ -252,74 +252,19 @@ __device__ __forceinline__ void score_wave_bf16(const char* __restrict__ q_grp, 
     }
 }
 
-// Block x of a grid row -> (sequence b, local block) by walking cu_sent; false past the last sequence.
-__device__ __forceinline__ bool locate_score_block(const SeqView& v, int rows_per_block, int x, int* b_out, int* blk_out,
-                                                   Seq* sq_out) {
-    int blk = x, b = 0;
-    Seq sq{};
-    for (; b < v.B; ++b) {
-        sq = seq_of(v, b);
-        const int nb = (sq.n_sent + rows_per_block - 1) / rows_per_block;
-        if (blk < nb) break;
-        blk -= nb;
-    }
-    *b_out = b; *blk_out = blk; *sq_out = sq;
-    return b < v.B;
-}
-
-template <int EB, int G, int RPWV>
-__global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_kernel(const char* __restrict__ q,
-                                                                            const float* __restrict__ semvec, SeqView v,
-                                                                            int32_t Hq, float* __restrict__ score) {
-    constexpr int kRowsPerBlock = RPWV * kScoreWavesPerBlock;
-    int blk, b;
-    Seq sq;
-    if (!locate_score_block(v, kRowsPerBlock, blockIdx.x, &b, &blk, &sq)) return;
-    const int h = blockIdx.y, w = threadIdx.x >> 6;
-    const int64_t hs = (int64_t)h * v.S_total + sq.sent_base;
-    score_wave_f32<EB, G, RPWV, false>(q + ((int64_t)(b * Hq + h * G) * kHeadDim) * EB, semvec + hs * kHeadDim, sq.n_sent,
-                                       blk * kRowsPerBlock + w * RPWV, score + hs);
-}
-
-constexpr int kScoreRowsPerWave16 = 16;
-
-template <int EB, int G>
-__global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_sv16_kernel(const char* __restrict__ q,
-                                                                                 const char* __restrict__ semvec, SeqView v,
-                                                                                 int32_t Hq, float* __restrict__ score) {
-    constexpr int kRowsPerBlock = kScoreRowsPerWave16 * kScoreWavesPerBlock;
-    int blk, b;
-    Seq sq;
-    if (!locate_score_block(v, kRowsPerBlock, blockIdx.x, &b, &blk, &sq)) return;
-    const int h = blockIdx.y, w = threadIdx.x >> 6;
-    const int64_t hs = (int64_t)h * v.S_total + sq.sent_base;
-    score_wave_bf16<EB, G, kScoreRowsPerWave16, false>(q + ((int64_t)(b * Hq + h * G) * kHeadDim) * EB,
-                                                       semvec + hs * kHeadDim * 2, sq.n_sent,
-                                                       blk * kRowsPerBlock + w * kScoreRowsPerWave16, score + hs);
-}
-
 // The same from an E4M3 table: a vector is 128 bytes = 8 lanes x 16 bytes (16 dims per lane), a wave load covers 8 buckets,
-// 32 buckets per wave keep 4 loads in flight; the sum over a bucket's 8 lanes is two quad exchanges and a rotation by 4.
-constexpr int kScoreRowsPerWave8 = 32;
-
-template <int EB, int G>
-__global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_sv8_kernel(const char* __restrict__ q,
-                                                                                const char* __restrict__ semvec, SeqView v,
-                                                                                int32_t Hq, float* __restrict__ score) {
-    constexpr int kRowsPerBlock = kScoreRowsPerWave8 * kScoreWavesPerBlock;
-    int blk, b;
-    Seq sq;
-    if (!locate_score_block(v, kRowsPerBlock, blockIdx.x, &b, &blk, &sq)) return;
-    const int h = blockIdx.y;
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+// RPWV / 8 loads in flight; the sum over a bucket's 8 lanes is two quad exchanges and a rotation by 4.
+template <int EB, int G, int RPWV, bool AGENT>
+__device__ __forceinline__ void score_wave_e4m3(const char* __restrict__ q_grp, const char* __restrict__ sv_seq,
+                                                int32_t n_sent, int32_t row_w, float* __restrict__ out_seq) {
+    const int lane = threadIdx.x & 63;
     const int c = lane & 7, sub = lane >> 3;
-
     float qs[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) qs[i] = 0.f;
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-        const char* qrow = q + ((int64_t)(b * Hq + h * G + g) * kHeadDim + c * 16) * EB;
+        const char* qrow = q_grp + ((int64_t)g * kHeadDim + c * 16) * EB;
         if (EB == 4) {
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -336,13 +281,13 @@ __global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_sv8_kernel(
             }
         }
     }
-    constexpr int kIter = kScoreRowsPerWave8 / 8;
-    const int32_t row0 = blk * kRowsPerBlock + w * kScoreRowsPerWave8 + sub;
-    const char* base = semvec + ((int64_t)h * v.S_total + sq.sent_base) * kHeadDim + c * 16;
+    constexpr int kIter = RPWV / 8;
+    const int32_t row0 = row_w + sub;
+    const char* base = sv_seq + c * 16;
     uint4 x[kIter];
 #pragma unroll
     for (int i = 0; i < kIter; ++i) {                       // clamped addresses: all loads issued back to back
-        const int32_t s = min(row0 + 8 * i, sq.n_sent - 1);
+        const int32_t s = min(row0 + 8 * i, n_sent - 1);
         x[i] = *reinterpret_cast<const uint4*>(base + (int64_t)s * kHeadDim);
     }
     float p[kIter];
@@ -366,49 +311,120 @@ __global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_sv8_kernel(
         p[i] = dpp_add<0x124>(p[i]);                        // row_ror 4: lanes 4..7 of each group of 8 now hold the group's sum
     }
     if (c == 4) {
-        float* out = score + (int64_t)h * v.S_total + sq.sent_base;
 #pragma unroll
         for (int i = 0; i < kIter; ++i) {
             const int32_t s = row0 + 8 * i;
-            if (s < sq.n_sent) out[s] = p[i];
+            if (s < n_sent) {
+                if (AGENT) st_agent(out_seq + s, p[i]);
+                else out_seq[s] = p[i];
+            }
         }
     }
 }
 
-template <int EB, int RPWV>
-static hipError_t launch_score_g(Ctx* c, const void* q, const void* semvec_layer, const SeqView& v, float* score) {
+constexpr int kScoreRowsPerWave16 = 16;
+constexpr int kScoreRowsPerWave8 = 32;
+enum { kTableF32 = 4, kTableBf16 = 2, kTableE4m3 = 1 };       // bytes per element of the mean-key table
+
+// Scores of one layer: grid (blocks over the S_total buckets of the concatenated batch, KV heads).  A wave owns RPWV
+// consecutive buckets of that axis, wherever the sequence boundaries fall, and scores them in runs that belong to one
+// sequence, each run with that sequence's queries: one run unless a boundary falls inside the wave's buckets; a sequence
+// without buckets has no run.  The sequence of the wave's first bucket r0 is the last b with cu_sent[b] <= r0: bisection
+// of cu_sent down to eight candidates (dependent scalar loads), then eight consecutive boundaries in one scalar load,
+// which also gives the end of the first run; log2(B / 8) + 1 round trips, whatever the batch size.
+
+template <int EB, int G, int SVB, int RPWV>
+__global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_kernel(const char* __restrict__ q,
+                                                                            const char* __restrict__ semvec, SeqView v,
+                                                                            int32_t Hq, float* __restrict__ score) {
+    // every argument is demanded here, so the kernel-argument loads go out together; left alone, the compiler loads
+    // each one before its first use, a dependent round trip per branch below
+    asm volatile("" ::"s"(q), "s"(semvec), "s"(v.cu_sent), "s"(v.S_total), "s"(v.B), "s"(Hq), "s"(score));
+    const int h = blockIdx.y;
+    const int32_t r0 = (blockIdx.x * kScoreWavesPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6)) * RPWV;
+    if (r0 >= v.S_total) return;
+    const int32_t r1 = min(r0 + RPWV, v.S_total);
+    auto run = [&](int b, int32_t first, int32_t n) {      // buckets [first, first + n) of the batch axis, sequence b
+        const char* qg = q + ((int64_t)(b * Hq + h * G) * kHeadDim) * EB;
+        const int64_t row = (int64_t)h * v.S_total + first;
+        if (SVB == kTableF32)
+            score_wave_f32<EB, G, RPWV, false>(qg, reinterpret_cast<const float*>(semvec) + row * kHeadDim, n, 0, score + row);
+        else if (SVB == kTableBf16)
+            score_wave_bf16<EB, G, RPWV, false>(qg, semvec + row * kHeadDim * 2, n, 0, score + row);
+        else
+            score_wave_e4m3<EB, G, RPWV, false>(qg, semvec + row * kHeadDim, n, 0, score + row);
+    };
+    if (!v.cu_sent) {                                      // one sequence
+        run(0, r0, r1 - r0);
+        return;
+    }
+    // cu_sent is read through the constant address space: the loads stay scalar whatever else the kernel contains
+    // (the kernel never writes the array)
+    typedef const int32_t __attribute__((address_space(4))) * ConstI32;
+    const ConstI32 cu = (ConstI32)(uintptr_t)v.cu_sent;
+    int b = 0, hi = v.B;                                   // cu[b] <= r0 < cu[hi]
+    int32_t end;
+    if (v.B >= 8) {
+        while (hi - b > 8) {
+            const int mid = (b + hi) >> 1;
+            if (cu[mid] <= r0) b = mid; else hi = mid;
+        }
+        const int start = min(b + 1, v.B - 7);             // boundaries start .. start + 7 include hi
+        int32_t w[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) w[j] = cu[start + j];
+        int below = 0;
+        end = w[7];
+#pragma unroll
+        for (int j = 7; j >= 0; --j) {
+            below += w[j] <= r0;
+            if (w[j] > r0) end = w[j];
+        }
+        b = start - 1 + below;
+    } else {
+        while (hi - b > 1) {
+            const int mid = (b + hi) >> 1;
+            if (cu[mid] <= r0) b = mid; else hi = mid;
+        }
+        end = cu[b + 1];
+    }
+    int32_t cur = r0;
+    for (;;) {
+        end = min(end, r1);
+        if (end > cur) {
+            run(b, cur, end - cur);
+            cur = end;
+        }
+        if (cur >= r1 || ++b >= v.B) break;
+        end = cu[b + 1];
+    }
+}
+
+template <int EB, int G>
+static void launch_score_t(Ctx* c, const char* q, const char* sv, const SeqView& v, float* score) {
     const bool sv16 = c->d.semvec_dtype == SKV_BF16, sv8 = c->d.semvec_dtype == SKV_FP8_E4M3;
-    const int rows_per_block = (sv8 ? kScoreRowsPerWave8 : sv16 ? kScoreRowsPerWave16 : RPWV) * kScoreWavesPerBlock;
-    const int blocks = (v.S_total + rows_per_block - 1) / rows_per_block + v.B;   // bound on sum_b ceil(S_b/R)
-    const dim3 grid(blocks, c->d.n_kv_heads), block(kScoreWavesPerBlock * kWave);
+    const int rows_per_block = (sv8 ? kScoreRowsPerWave8 : sv16 ? kScoreRowsPerWave16 : kScoreRowsPerWave) * kScoreWavesPerBlock;
+    const dim3 grid((v.S_total + rows_per_block - 1) / rows_per_block, c->d.n_kv_heads), block(kScoreWavesPerBlock * kWave);
+    if (sv8)
+        hipLaunchKernelGGL((score_kernel<EB, G, kTableE4m3, kScoreRowsPerWave8>), grid, block, 0, c->stream, q, sv, v,
+                           c->d.n_q_heads, score);
+    else if (sv16)
+        hipLaunchKernelGGL((score_kernel<EB, G, kTableBf16, kScoreRowsPerWave16>), grid, block, 0, c->stream, q, sv, v,
+                           c->d.n_q_heads, score);
+    else
+        hipLaunchKernelGGL((score_kernel<EB, G, kTableF32, kScoreRowsPerWave>), grid, block, 0, c->stream, q, sv, v,
+                           c->d.n_q_heads, score);
+}
+
+template <int EB>
+static hipError_t launch_score_g(Ctx* c, const void* q, const void* semvec_layer, const SeqView& v, float* score) {
     const char* qp = (const char*)q;
     const char* sv = (const char*)semvec_layer;
-    if (sv8) {
-        switch (c->G) {
-            case 1: hipLaunchKernelGGL((score_sv8_kernel<EB, 1>), grid, block, 0, c->stream, qp, sv, v, c->d.n_q_heads, score); break;
-            case 2: hipLaunchKernelGGL((score_sv8_kernel<EB, 2>), grid, block, 0, c->stream, qp, sv, v, c->d.n_q_heads, score); break;
-            case 4: hipLaunchKernelGGL((score_sv8_kernel<EB, 4>), grid, block, 0, c->stream, qp, sv, v, c->d.n_q_heads, score); break;
-            case 8: hipLaunchKernelGGL((score_sv8_kernel<EB, 8>), grid, block, 0, c->stream, qp, sv, v, c->d.n_q_heads, score); break;
-            default: return hipErrorInvalidValue;
-        }
-        return hipGetLastError();
-    }
-    if (sv16) {
-        switch (c->G) {
-            case 1: hipLaunchKernelGGL((score_sv16_kernel<EB, 1>), grid, block, 0, c->stream, qp, sv, v, c->d.n_q_heads, score); break;
-            case 2: hipLaunchKernelGGL((score_sv16_kernel<EB, 2>), grid, block, 0, c->stream, qp, sv, v, c->d.n_q_heads, score); break;
-            case 4: hipLaunchKernelGGL((score_sv16_kernel<EB, 4>), grid, block, 0, c->stream, qp, sv, v, c->d.n_q_heads, score); break;
-            case 8: hipLaunchKernelGGL((score_sv16_kernel<EB, 8>), grid, block, 0, c->stream, qp, sv, v, c->d.n_q_heads, score); break;
-            default: return hipErrorInvalidValue;
-        }
-        return hipGetLastError();
-    }
-    const float* svf = (const float*)semvec_layer;
     switch (c->G) {
-        case 1: hipLaunchKernelGGL((score_kernel<EB, 1, RPWV>), grid, block, 0, c->stream, qp, svf, v, c->d.n_q_heads, score); break;
-        case 2: hipLaunchKernelGGL((score_kernel<EB, 2, RPWV>), grid, block, 0, c->stream, qp, svf, v, c->d.n_q_heads, score); break;
-        case 4: hipLaunchKernelGGL((score_kernel<EB, 4, RPWV>), grid, block, 0, c->stream, qp, svf, v, c->d.n_q_heads, score); break;
-        case 8: hipLaunchKernelGGL((score_kernel<EB, 8, RPWV>), grid, block, 0, c->stream, qp, svf, v, c->d.n_q_heads, score); break;
+        case 1: launch_score_t<EB, 1>(c, qp, sv, v, score); break;
+        case 2: launch_score_t<EB, 2>(c, qp, sv, v, score); break;
+        case 4: launch_score_t<EB, 4>(c, qp, sv, v, score); break;
+        case 8: launch_score_t<EB, 8>(c, qp, sv, v, score); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -416,8 +432,8 @@ static hipError_t launch_score_g(Ctx* c, const void* q, const void* semvec_layer
 
 hipError_t launch_score(Ctx* c, const void* q, const void* semvec_layer, const SeqView& v, float* score) {
     if (v.S_total == 0) return hipSuccess;
-    return c->d.kv_dtype == SKV_BF16 ? launch_score_g<2, kScoreRowsPerWave>(c, q, semvec_layer, v, score)
-                                     : launch_score_g<4, kScoreRowsPerWave>(c, q, semvec_layer, v, score);
+    return c->d.kv_dtype == SKV_BF16 ? launch_score_g<2>(c, q, semvec_layer, v, score)
+                                     : launch_score_g<4>(c, q, semvec_layer, v, score);
 }
 
 // ------------------------------------------------------------------------------------------------

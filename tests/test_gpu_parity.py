@@ -398,6 +398,23 @@ def test_fused_batch_with_empty_and_tiny_sequences(U, oracle32, dtype, B):
     _fused_case(U, oracle32, wl, seed=12, layers=[0], seq_tokens=toks, budgets=buds)
 
 
+@pytest.mark.parametrize("sv_dtype", ["f32", "bf16", "fp8"])
+@pytest.mark.parametrize("B", [2, 7, 8, 9, 21, 70])
+def test_fused_batch_sequence_boundaries_inside_a_wave(U, oracle32, B, sv_dtype):
+    """The score kernel's waves own 8, 16 or 32 consecutive buckets of the concatenated batch (fp32, bf16, E4M3 table)
+    and look up the sequences they fall in.  Sequences of a handful of tokens, some without tokens, put several
+    boundaries inside one wave; a long sequence in between spans many waves; batch sizes lie on both sides of the
+    lookup's eight-entry step."""
+    rng = np.random.default_rng(100 + B)
+    toks = rng.integers(0, 90, size=B)
+    toks[rng.integers(0, B, size=max(1, B // 5))] = 0
+    toks[B // 2] = 2100
+    toks[-1] = int(rng.integers(1, 30))
+    buds = rng.integers(0, 400, size=B)
+    wl = gen.CFG4.scaled(n_layers=1, n_q_heads=32, batch=B, budgets=(400,), dtype="bf16")
+    _fused_case(U, oracle32, wl, seed=40 + B, layers=[0], sv_dtype=sv_dtype, seq_tokens=toks.tolist(), budgets=buds.tolist())
+
+
 @pytest.mark.parametrize("dtype,budget", [("f32", 700), ("bf16", 2), ("bf16", 256), ("bf16", 257), ("bf16", 5000)])
 def test_fused_batch_path_edges(U, oracle32, dtype, budget):
     """Batch path with fp32 inputs (the VALU kernel), a budget no bucket fits (empty selections), budgets at and
