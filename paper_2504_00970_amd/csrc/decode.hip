@@ -17,23 +17,32 @@ struct Seq {
     int32_t budget;
 };
 
+// Read of an int32 array that no kernel of this library writes (the caller's cu_tok, cu_sent, budgets, n_tok), through
+// the constant address space: with a wave-uniform index it is a scalar load whatever else the kernel contains (loads of
+// a plain global pointer turn into vector loads once the compiler cannot prove that the kernel leaves the memory alone,
+// which an inline asm statement is enough to cause).
+__device__ __forceinline__ int32_t ld_const(const int32_t* p, int64_t i) {
+    typedef const int32_t __attribute__((address_space(4))) * ConstI32;
+    return ((ConstI32)(uintptr_t)p)[i];
+}
+
 __device__ __forceinline__ Seq seq_of(const SeqView& v, int b) {
     Seq s;
     if (v.cu_sent) {
-        s.sent_base = v.cu_sent[b];
-        s.n_sent = v.cu_sent[b + 1] - s.sent_base;
+        s.sent_base = ld_const(v.cu_sent, b);
+        s.n_sent = ld_const(v.cu_sent, b + 1) - s.sent_base;
     } else {
         s.sent_base = 0;
         s.n_sent = v.S_total;
     }
     if (v.cu_tok) {
-        s.tok_base = v.cu_tok[b];
-        s.n_tok_ctx = v.cu_tok[b + 1] - s.tok_base;
+        s.tok_base = ld_const(v.cu_tok, b);
+        s.n_tok_ctx = ld_const(v.cu_tok, b + 1) - s.tok_base;
     } else {
         s.tok_base = 0;
         s.n_tok_ctx = v.T_total;
     }
-    s.budget = v.budget_arr ? v.budget_arr[b] : v.budget;
+    s.budget = v.budget_arr ? ld_const(v.budget_arr, b) : v.budget;
     return s;
 }
 
@@ -358,21 +367,18 @@ __global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_kernel(cons
         run(0, r0, r1 - r0);
         return;
     }
-    // cu_sent is read through the constant address space: the loads stay scalar whatever else the kernel contains
-    // (the kernel never writes the array)
-    typedef const int32_t __attribute__((address_space(4))) * ConstI32;
-    const ConstI32 cu = (ConstI32)(uintptr_t)v.cu_sent;
-    int b = 0, hi = v.B;                                   // cu[b] <= r0 < cu[hi]
+    auto cu = [&](int i) { return ld_const(v.cu_sent, i); };
+    int b = 0, hi = v.B;                                   // cu(b) <= r0 < cu(hi)
     int32_t end;
     if (v.B >= 8) {
         while (hi - b > 8) {
             const int mid = (b + hi) >> 1;
-            if (cu[mid] <= r0) b = mid; else hi = mid;
+            if (cu(mid) <= r0) b = mid; else hi = mid;
         }
         const int start = min(b + 1, v.B - 7);             // boundaries start .. start + 7 include hi
         int32_t w[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) w[j] = cu[start + j];
+        for (int j = 0; j < 8; ++j) w[j] = cu(start + j);
         int below = 0;
         end = w[7];
 #pragma unroll
@@ -384,9 +390,9 @@ __global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_kernel(cons
     } else {
         while (hi - b > 1) {
             const int mid = (b + hi) >> 1;
-            if (cu[mid] <= r0) b = mid; else hi = mid;
+            if (cu(mid) <= r0) b = mid; else hi = mid;
         }
-        end = cu[b + 1];
+        end = cu(b + 1);
     }
     int32_t cur = r0;
     for (;;) {
@@ -396,7 +402,7 @@ __global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_kernel(cons
             cur = end;
         }
         if (cur >= r1 || ++b >= v.B) break;
-        end = cu[b + 1];
+        end = cu(b + 1);
     }
 }
 
@@ -817,6 +823,16 @@ struct AttArgs {
 
 enum { kDirect = 0, kFused = 1, kIndirect = 2 };
 
+// Every argument is demanded at this point, so the kernel-argument loads go out in one batch at the top of the kernel;
+// left alone, the compiler loads each argument before its first use: one dependent round trip per branch, and a
+// scalar-cache miss for each new 64-byte line of the argument block.
+__device__ __forceinline__ void demand_args(const AttArgs& a) {
+    asm volatile("" ::"s"(a.q), "s"(a.Kb), "s"(a.Vb), "s"(a.n_tok), "s"(a.tok_idx), "s"(a.row_stride), "s"(a.score),
+                 "s"(a.sent_off), "s"(a.sent_len), "s"(a.tok_idx_out), "s"(a.n_tok_out), "s"(a.idx_stride), "s"(a.v.cu_tok),
+                 "s"(a.v.cu_sent), "s"(a.v.budget_arr), "s"(a.v.T_total), "s"(a.v.S_total), "s"(a.v.budget), "s"(a.v.B),
+                 "s"(a.Hkv), "s"(a.max_splits), "s"(a.part), "s"(a.ml), "s"(a.counter), "s"(a.out), "s"(a.lse));
+}
+
 // CHUNK = retrieved tokens per block: 64 for the latency-bound single-sequence step (most blocks in
 // flight), 256 for batches (fewer partials and arrivals per head, more loads in flight per block).
 template <int EB, int G, int MODE, int CHUNK>
@@ -854,6 +870,7 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
     const int r = lane % R::RPW, cc = lane / R::RPW;
     const int Hq = a.Hkv * G;
     const int64_t qhead0 = (int64_t)b * Hq + (int64_t)h * G;      // first query head of the group
+    demand_args(a);
     const Seq sq = seq_of(a.v, b);
     const int32_t j0 = split * CHUNK;
     const int slot = split * (CHUNK / kWave);                     // partial slot (slots are counted in 64-token units)
@@ -907,7 +924,7 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
         }
         __syncthreads();                                          // sm_row complete
     } else {
-        n = min(a.n_tok[bh], MODE == kDirect ? a.row_stride : a.idx_stride);
+        n = min(ld_const(a.n_tok, bh), MODE == kDirect ? a.row_stride : a.idx_stride);
     }
     if (n <= 0) {
         if (split == 0) {
@@ -1531,6 +1548,7 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(4
     __shared__ StreamShared ss;
     const int bh = blockIdx.y, b = bh / a.Hkv, h = bh % a.Hkv, split = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63;
+    demand_args(a);
     const Seq sq = seq_of(a.v, b);
     const int32_t j0 = split * CHUNK;
     SKV_T(0);
