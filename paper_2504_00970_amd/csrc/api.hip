@@ -321,8 +321,11 @@ int skv_decode_step(skv_ctx* ctx, int32_t layer, int32_t B, const void* q_score,
     if (e != hipSuccess) return hip_status(e);
     const char* Kl = (const char*)K_pool + pool_off;
     const char* Vl = (const char*)V_pool + pool_off;
-    if (B * c.d.n_kv_heads >= skv::kWideChunkMinHeads) {
-        if (c.d.kv_dtype == SKV_BF16 && T_total < (1 << 24))
+    const int pairs = B * c.d.n_kv_heads;
+    const bool can_stream = c.d.kv_dtype == SKV_BF16 && T_total < (1 << 24);
+    const int wide_blocks = pairs * ((c.d.max_budget + skv::kAttChunkWide - 1) / skv::kAttChunkWide);
+    if (can_stream ? pairs > skv::kLatencyPairs && wide_blocks > skv::kComputeUnits : pairs >= skv::kWideChunkMinHeads) {
+        if (can_stream)
             return hip_status(skv::launch_select_attend_stream(&c, q_attn, Kl, Vl, c.f_score, sent_off, sent_len, v, out, lse,
                                                                tok_idx_out, n_tok_out));
         // batch path: the selection runs once per (sequence, head); attention reads the pool through tok_idx

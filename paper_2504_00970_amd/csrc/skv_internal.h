@@ -30,7 +30,12 @@ constexpr int kAttChunk = 64;         // tokens per split-K block, single-sequen
 constexpr int kAttChunkMid = 128;     // tokens per split-K block of the single-sequence step when a sequence has many buckets
 constexpr int kMidChunkMinSentences = 1024;
 constexpr int kAttChunkWide = 256;    // tokens per split-K block when many (sequence, head) pairs fill the GPU
-constexpr int kWideChunkMinHeads = 64;   // (sequences x KV heads) from which the batch path is used
+constexpr int kWideChunkMinHeads = 64;   // (sequences x KV heads) from which the fp32 batch path is used
+constexpr int kComputeUnits = 256;       // MI355X
+// bf16 decode step, by the number of (sequence, KV head) pairs: up to kLatencyPairs the 64/128-token fused blocks;
+// above, 256-token fused blocks while they all fit the chip at once (one block per compute unit), else the streaming
+// kernel's 1024-token blocks
+constexpr int kLatencyPairs = 16;
 
 struct Ctx {
     skv_desc d;

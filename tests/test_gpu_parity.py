@@ -302,11 +302,18 @@ def test_attend_large_logits_do_not_overflow(U, oracle32):
 
 # ----------------------------------------------------------------------------- fused step
 
-def _fused_case(U, oracle32, wl, seed, layers, sv_dtype="f32", seq_tokens=None, budgets=None):
+STREAM_CAPACITY = 9000      # descriptor max_budget that sends a bf16 batch of 8 or more (sequence, head) pairs to the streaming kernel
+
+
+def _fused_case(U, oracle32, wl, seed, layers, sv_dtype="f32", seq_tokens=None, budgets=None, capacity=0):
+    """One skv_decode_step per layer against the oracle, sequence by sequence.  `capacity` raises the context's
+    max_budget above the budgets in use: the library sizes its grids by it, and a bf16 batch whose 256-token blocks
+    (pairs x ceil(max_budget / 256)) outnumber the compute units takes the streaming kernel instead of the fused one,
+    so the same inputs reach both kernels."""
     inp = gen.ragged_inputs(wl, seed=seed, device=U.DEV, resident_layers=len(layers), seq_tokens=seq_tokens, budgets=budgets)
     B, H, Hq, D = wl.batch, wl.n_kv_heads, wl.n_q_heads, wl.head_dim
     T_total, S_total = int(inp.cu_tok[-1]), int(inp.cu_sent[-1])
-    max_budget = int(inp.budget.max())
+    max_budget = max(int(inp.budget.max()), capacity)
     ctx = U.make_ctx(wl.scaled(n_layers=len(layers)), T_total, S_total, max_budget, batch=B, sv_dtype=sv_dtype)
     Kd, Vd, qd = inp.K.to(U.DEV), inp.V.to(U.DEV), inp.q.to(U.DEV)
     # semantic vectors of the concatenated stream: bucket boundaries are the concatenation of the sequences'
@@ -350,9 +357,10 @@ def _fused_case(U, oracle32, wl, seed, layers, sv_dtype="f32", seq_tokens=None, 
         ctx.decode_step(li, B, qd[li], qd[li], Kd, Vd, T_total, sv, S_total, d["cu_tok"], d["cu_sent"], d["sent_off"],
                         d["sent_len"], d["budget"], out2, None, None, None)
         torch.cuda.synchronize()
-        if B * H >= 64 and wl.dtype == "bf16":
-            # the bf16 batch kernel hands its 16-token tiles to whichever wave is free: the summation order, and with
-            # it the last bits of the output, differ from call to call
+        if B * H > 16 and wl.dtype == "bf16":
+            # the streaming batch kernel (bf16, more than 16 pairs, more 256-token blocks than compute units) hands its
+            # 16-token tiles to whichever wave is free: the summation order, and with it the last bits of the output,
+            # differ from call to call
             assert (out - out2).abs().max().item() <= ATT_TOL[wl.dtype] / 4
         else:
             assert torch.equal(out, out2)
@@ -370,32 +378,41 @@ def test_fused_ragged_batch_70b_heads(U, oracle32):
     _fused_case(U, oracle32, wl, seed=4, layers=[0, 1])
 
 
+@pytest.mark.parametrize("capacity", [0, STREAM_CAPACITY])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("Hq", [8, 16, 32, 64])
-def test_fused_batch_path_many_heads(U, oracle32, Hq, dtype):
-    """Eight or more sequences x 8 KV heads take the batch path, for every group size: bf16 pools run the selection
-    inside 1024-token streaming MFMA blocks, fp32 pools run select_kernel and 256-token blocks through tok_idx."""
+def test_fused_batch_path_many_heads(U, oracle32, Hq, dtype, capacity):
+    """Nine sequences x 8 KV heads, for every group size: bf16 pools run the selection inside 256-token fused MFMA blocks
+    or, with the large capacity, inside 1024-token streaming MFMA blocks; fp32 pools run select_kernel and 256-token
+    blocks through tok_idx."""
     wl = gen.CFG4.scaled(n_layers=1, n_q_heads=Hq, batch=9, t_range=(200, 3000), budgets=(700,), dtype=dtype)
-    _fused_case(U, oracle32, wl, seed=6, layers=[0])
+    _fused_case(U, oracle32, wl, seed=6, layers=[0], capacity=capacity)
 
 
+@pytest.mark.parametrize("capacity", [0, STREAM_CAPACITY])
 @pytest.mark.parametrize("budget", [1024, 1025, 1500, 2048])
-def test_fused_batch_path_two_blocks_per_head(U, oracle32, budget):
-    """Budgets around the 1024-token block of the bf16 batch kernel: a full block, one token in the second block, a
-    second block whose last waves have nothing to stream, two full blocks; contexts shorter than the budget too."""
+def test_fused_batch_path_two_blocks_per_head(U, oracle32, budget, capacity):
+    """Budgets around the 1024-token block of the bf16 streaming kernel: a full block, one token in the second block, a
+    second block whose last waves have nothing to stream, two full blocks; contexts shorter than the budget too.
+    (Without the capacity a budget of 1024 runs 256-token fused blocks, the others the streaming kernel.)"""
     wl = gen.CFG4.scaled(n_layers=1, n_q_heads=32, batch=8, t_range=(900, 5000), budgets=(budget,))
-    _fused_case(U, oracle32, wl, seed=8, layers=[0])
+    _fused_case(U, oracle32, wl, seed=8, layers=[0], capacity=capacity)
 
 
+@pytest.mark.parametrize("capacity", [0, STREAM_CAPACITY])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-@pytest.mark.parametrize("B", [3, 8])
-def test_fused_batch_with_empty_and_tiny_sequences(U, oracle32, dtype, B):
+@pytest.mark.parametrize("B", [2, 3, 8])
+def test_fused_batch_with_empty_and_tiny_sequences(U, oracle32, dtype, B, capacity):
     """Sequences without tokens, with one token and with one bucket next to ordinary ones, budgets from 0 to more than the
-    context, on the small-batch path (B = 3) and the batch path (B = 8)."""
+    context, on the small-batch path (B = 2: 64/128-token blocks; B = 3: 256-token blocks) and on the batch paths
+    (B = 8: 256-token fused blocks, or the streaming kernel with the large capacity; fp32: selection kernel + indirect
+    attention)."""
     toks = [0, 1, 1500, 0, 37, 2300, 5, 0][:B]
     buds = [64, 64, 700, 0, 1000, 0, 3, 9][:B]
+    if B == 2:
+        toks, buds = [1500, 0], [700, 64]
     wl = gen.CFG4.scaled(n_layers=1, n_q_heads=32, batch=B, budgets=(1000,), dtype=dtype)
-    _fused_case(U, oracle32, wl, seed=12, layers=[0], seq_tokens=toks, budgets=buds)
+    _fused_case(U, oracle32, wl, seed=12, layers=[0], seq_tokens=toks, budgets=buds, capacity=capacity)
 
 
 @pytest.mark.parametrize("sv_dtype", ["f32", "bf16", "fp8"])
@@ -415,12 +432,14 @@ def test_fused_batch_sequence_boundaries_inside_a_wave(U, oracle32, B, sv_dtype)
     _fused_case(U, oracle32, wl, seed=40 + B, layers=[0], sv_dtype=sv_dtype, seq_tokens=toks.tolist(), budgets=buds.tolist())
 
 
+@pytest.mark.parametrize("capacity", [0, STREAM_CAPACITY])
 @pytest.mark.parametrize("dtype,budget", [("f32", 700), ("bf16", 2), ("bf16", 256), ("bf16", 257), ("bf16", 5000)])
-def test_fused_batch_path_edges(U, oracle32, dtype, budget):
-    """Batch path with fp32 inputs (the VALU kernel), a budget no bucket fits (empty selections), budgets at and
-    just past one 256-token block, and a budget above every context length (all tokens retrieved)."""
+def test_fused_batch_path_edges(U, oracle32, dtype, budget, capacity):
+    """Batch paths (fp32: the VALU kernel through tok_idx; bf16: 256-token fused blocks, and the streaming kernel with the
+    large capacity or the 5000-token budget) with a budget no bucket fits (empty selections), budgets at and just past
+    one 256-token block, and a budget above every context length (all tokens retrieved)."""
     wl = gen.CFG4.scaled(n_layers=1, n_q_heads=32, batch=8, t_range=(150, 2500), budgets=(budget,), dtype=dtype)
-    _fused_case(U, oracle32, wl, seed=9, layers=[0])
+    _fused_case(U, oracle32, wl, seed=9, layers=[0], capacity=capacity)
 
 
 def test_attend_batch_path_direct_rows(U, oracle32):
