@@ -1308,15 +1308,14 @@ __device__ __forceinline__ void stream_load_queries(const AttArgs& a, StreamShar
     }
 }
 
-// Attention of one 1024-position block once the selection is known: n = retrieved tokens of the (sequence, head),
-// xi = pool row of position split * 1024 + tid (anything for positions >= n).  The queries are on their way to ss.q.
+// Attention of one block of CHUNK (1024 or 512) positions once the selection is known: n = retrieved tokens of the
+// (sequence, head), xi = pool row of position split * CHUNK + tid (anything for positions >= n or threads >= CHUNK).  The queries are on their way to ss.q.
 // Every thread of the block calls this.
-template <int G>
+template <int G, int CHUNK>
 __device__ __forceinline__ void stream_attend(const AttArgs& a, StreamShared& ss, int bh, int b, int h, int split, const Seq& sq,
                                               int32_t n, int32_t xi) {
     constexpr int NW = kStreamWaves;
     constexpr int kThreads = kBlockThreads;
-    constexpr int CHUNK = kStreamChunk;
     constexpr int kRowBytes = kHeadDim * 2;
     constexpr int kVPitch = kStreamVPitch;
     constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
@@ -1542,9 +1541,9 @@ __device__ __forceinline__ void stream_attend(const AttArgs& a, StreamShared& ss
     SKV_T(9);
 }
 
-template <int G>
+template <int G, int CHUNK>
 __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void select_attend_stream_kernel(AttArgs a) {
-    constexpr int CHUNK = kStreamChunk;
+    static_assert(CHUNK % kWave == 0 && CHUNK <= kStreamChunk, "at most one retrieved position per thread");
     __shared__ StreamShared ss;
     const int bh = blockIdx.y, b = bh / a.Hkv, h = bh % a.Hkv, split = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -1587,19 +1586,22 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(4
             const int32_t base = __shfl(v, max(hp, 0));
             xi = hp >= 0 ? base + (lane - hp) : -1;
             const int32_t pos = j0 + tid;
-            if (a.tok_idx_out && pos < n) a.tok_idx_out[(int64_t)bh * a.idx_stride + pos] = xi;
+            if (a.tok_idx_out && tid < CHUNK && pos < n) a.tok_idx_out[(int64_t)bh * a.idx_stride + pos] = xi;
         }
     }
-    stream_attend<G>(a, ss, bh, b, h, split, sq, n, xi);
+    stream_attend<G, CHUNK>(a, ss, bh, b, h, split, sq, n, xi);
 }
 
-static hipError_t launch_select_attend_stream_g(Ctx* c, const AttArgs& a, int32_t n_splits) {
+template <int CHUNK>
+static hipError_t launch_select_attend_stream_g(Ctx* c, const AttArgs& a) {
+    int n_splits = (c->d.max_budget + CHUNK - 1) / CHUNK;
+    if (n_splits < 1) n_splits = 1;       // block 0 still writes the empty-selection result
     const dim3 grid(n_splits, a.v.B * c->d.n_kv_heads), block(kBlockThreads);
     switch (c->G) {
-        case 1: hipLaunchKernelGGL(select_attend_stream_kernel<1>, grid, block, 0, c->stream, a); break;
-        case 2: hipLaunchKernelGGL(select_attend_stream_kernel<2>, grid, block, 0, c->stream, a); break;
-        case 4: hipLaunchKernelGGL(select_attend_stream_kernel<4>, grid, block, 0, c->stream, a); break;
-        case 8: hipLaunchKernelGGL(select_attend_stream_kernel<8>, grid, block, 0, c->stream, a); break;
+        case 1: hipLaunchKernelGGL((select_attend_stream_kernel<1, CHUNK>), grid, block, 0, c->stream, a); break;
+        case 2: hipLaunchKernelGGL((select_attend_stream_kernel<2, CHUNK>), grid, block, 0, c->stream, a); break;
+        case 4: hipLaunchKernelGGL((select_attend_stream_kernel<4, CHUNK>), grid, block, 0, c->stream, a); break;
+        case 8: hipLaunchKernelGGL((select_attend_stream_kernel<8, CHUNK>), grid, block, 0, c->stream, a); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -1666,9 +1668,12 @@ hipError_t launch_select_attend_stream(Ctx* c, const void* q, const void* K_laye
     AttArgs a = att_common(c, q, K_layer, V_layer, v, out, lse);
     a.score = score; a.sent_off = sent_off; a.sent_len = sent_len;
     a.tok_idx_out = tok_idx_out; a.n_tok_out = n_tok_out; a.idx_stride = c->d.max_budget;
-    int n_splits = (c->d.max_budget + kStreamChunk - 1) / kStreamChunk;
-    if (n_splits < 1) n_splits = 1;       // block 0 still writes the empty-selection result
-    return launch_select_attend_stream_g(c, a, n_splits);
+    // While 512-token blocks still run in one round (one block per compute unit) they are ahead: two tiles per wave
+    // instead of four and twice the compute units busy (8 sequences x 8 heads, budget 2048: 36.7 -> 33.0 us per layer);
+    // in two rounds they lose (16 sequences: 50.8 -> 58.1).
+    const int blocks = v.B * c->d.n_kv_heads * ((c->d.max_budget + kStreamChunk - 1) / kStreamChunk);
+    if (2 * blocks <= kComputeUnits) return launch_select_attend_stream_g<kStreamChunk / 2>(c, a);
+    return launch_select_attend_stream_g<kStreamChunk>(c, a);
 }
 
 hipError_t launch_select_attend(Ctx* c, const void* q, const void* K_layer, const void* V_layer, const float* score,

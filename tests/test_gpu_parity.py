@@ -302,7 +302,11 @@ def test_attend_large_logits_do_not_overflow(U, oracle32):
 
 # ----------------------------------------------------------------------------- fused step
 
-STREAM_CAPACITY = 9000      # descriptor max_budget that sends a bf16 batch of 8 or more (sequence, head) pairs to the streaming kernel
+# Descriptor max_budget values that steer a bf16 batch of 8 sequences x 8 KV heads: the library picks the attention kernel
+# from block counts, pairs x ceil(max_budget / 256) <= 256 compute units: 256-token fused blocks; else the streaming
+# kernel, in 512-token blocks while pairs x ceil(max_budget / 1024) <= 128, else in 1024-token blocks.
+STREAM_CAPACITY = 9000      # 1024-token streaming blocks
+HALF_CAPACITY = 1500        # 512-token streaming blocks (for 64 pairs; 72 pairs need 1024)
 
 
 def _fused_case(U, oracle32, wl, seed, layers, sv_dtype="f32", seq_tokens=None, budgets=None, capacity=0):
@@ -378,28 +382,28 @@ def test_fused_ragged_batch_70b_heads(U, oracle32):
     _fused_case(U, oracle32, wl, seed=4, layers=[0, 1])
 
 
-@pytest.mark.parametrize("capacity", [0, STREAM_CAPACITY])
+@pytest.mark.parametrize("capacity", [0, 1024, STREAM_CAPACITY])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("Hq", [8, 16, 32, 64])
 def test_fused_batch_path_many_heads(U, oracle32, Hq, dtype, capacity):
     """Nine sequences x 8 KV heads, for every group size: bf16 pools run the selection inside 256-token fused MFMA blocks
-    or, with the large capacity, inside 1024-token streaming MFMA blocks; fp32 pools run select_kernel and 256-token
-    blocks through tok_idx."""
+    or, with the larger capacities, inside 512-token and 1024-token streaming MFMA blocks; fp32 pools run select_kernel
+    and 256-token blocks through tok_idx."""
     wl = gen.CFG4.scaled(n_layers=1, n_q_heads=Hq, batch=9, t_range=(200, 3000), budgets=(700,), dtype=dtype)
     _fused_case(U, oracle32, wl, seed=6, layers=[0], capacity=capacity)
 
 
-@pytest.mark.parametrize("capacity", [0, STREAM_CAPACITY])
-@pytest.mark.parametrize("budget", [1024, 1025, 1500, 2048])
+@pytest.mark.parametrize("capacity", [0, HALF_CAPACITY, STREAM_CAPACITY])
+@pytest.mark.parametrize("budget", [512, 513, 1024, 1025, 1500, 2048])
 def test_fused_batch_path_two_blocks_per_head(U, oracle32, budget, capacity):
-    """Budgets around the 1024-token block of the bf16 streaming kernel: a full block, one token in the second block, a
-    second block whose last waves have nothing to stream, two full blocks; contexts shorter than the budget too.
-    (Without the capacity a budget of 1024 runs 256-token fused blocks, the others the streaming kernel.)"""
+    """Budgets around the 512- and 1024-token blocks of the bf16 streaming kernel: a full block, one token in the next
+    block, a block whose last waves have nothing to stream, two full blocks; contexts shorter than the budget too.
+    (Without a capacity budgets up to 1024 run 256-token fused blocks, the others 512-token streaming blocks.)"""
     wl = gen.CFG4.scaled(n_layers=1, n_q_heads=32, batch=8, t_range=(900, 5000), budgets=(budget,))
     _fused_case(U, oracle32, wl, seed=8, layers=[0], capacity=capacity)
 
 
-@pytest.mark.parametrize("capacity", [0, STREAM_CAPACITY])
+@pytest.mark.parametrize("capacity", [0, HALF_CAPACITY, STREAM_CAPACITY])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("B", [2, 3, 8])
 def test_fused_batch_with_empty_and_tiny_sequences(U, oracle32, dtype, B, capacity):
@@ -432,7 +436,7 @@ def test_fused_batch_sequence_boundaries_inside_a_wave(U, oracle32, B, sv_dtype)
     _fused_case(U, oracle32, wl, seed=40 + B, layers=[0], sv_dtype=sv_dtype, seq_tokens=toks.tolist(), budgets=buds.tolist())
 
 
-@pytest.mark.parametrize("capacity", [0, STREAM_CAPACITY])
+@pytest.mark.parametrize("capacity", [0, HALF_CAPACITY, STREAM_CAPACITY])
 @pytest.mark.parametrize("dtype,budget", [("f32", 700), ("bf16", 2), ("bf16", 256), ("bf16", 257), ("bf16", 5000)])
 def test_fused_batch_path_edges(U, oracle32, dtype, budget, capacity):
     """Batch paths (fp32: the VALU kernel through tok_idx; bf16: 256-token fused blocks, and the streaming kernel with the
