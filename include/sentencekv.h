@@ -201,9 +201,9 @@ int skv_attend(skv_ctx* ctx, const void* q_attn, const void* K_sel, const void* 
  * batch of B sequences concatenated along the token axis and the bucket axis.  The retrieved tokens
  * are read straight from the HBM pool (no K_sel/V_sel copy).  Results equal skv_score + skv_select +
  * skv_gather + skv_attend run per sequence: the selection bit for bit, out / lse up to the order of the
- * floating-point sums.  For bf16 batches of more than 16 (sequence, KV head) pairs that order can depend on how the
- * hardware schedules a block's waves (the streaming kernel, chosen when the 256-token blocks of the whole batch
- * outnumber the compute units), so the last bits of out / lse can differ between two identical calls.
+ * floating-point sums.  For bf16 pools that order can depend on how the hardware schedules a block's waves (the
+ * streaming kernel, chosen when the 256-token blocks of the whole call, B * Hkv * ceil(max_budget / 256), outnumber
+ * the compute units), so the last bits of out / lse can differ between two identical calls.
  * q_score, q_attn  dev [B][Hq][D] kv_dtype (may alias)
  * K_pool, V_pool   dev [L][Hkv][T_total][D]        semvec dev [L][Hkv][S_total][D]
  * cu_tok   dev [B+1]  token offset of each sequence in the pool (cu_tok[0] == 0, cu_tok[B] == T_total)

@@ -324,7 +324,7 @@ int skv_decode_step(skv_ctx* ctx, int32_t layer, int32_t B, const void* q_score,
     const int pairs = B * c.d.n_kv_heads;
     const bool can_stream = c.d.kv_dtype == SKV_BF16 && T_total < (1 << 24);
     const int wide_blocks = pairs * ((c.d.max_budget + skv::kAttChunkWide - 1) / skv::kAttChunkWide);
-    if (can_stream ? pairs > skv::kLatencyPairs && wide_blocks > skv::kComputeUnits : pairs >= skv::kWideChunkMinHeads) {
+    if (can_stream ? wide_blocks > skv::kComputeUnits : pairs >= skv::kWideChunkMinHeads) {
         if (can_stream)
             return hip_status(skv::launch_select_attend_stream(&c, q_attn, Kl, Vl, c.f_score, sent_off, sent_len, v, out, lse,
                                                                tok_idx_out, n_tok_out));

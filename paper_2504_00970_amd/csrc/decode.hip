@@ -1684,13 +1684,18 @@ hipError_t launch_select_attend(Ctx* c, const void* q, const void* K_layer, cons
     a.tok_idx_out = tok_idx_out; a.n_tok_out = n_tok_out; a.idx_stride = c->d.max_budget;
     // Every split block of a head repeats the selection; with thousands of buckets per sequence that repetition
     // (bucket loads from L2, histogram passes) outweighs the shorter K/V phase of 64-token blocks.
-    // bf16 with more pairs than fill the chip in 128-token blocks (one block per compute unit fits): 256-token blocks, one
-    // round of blocks instead of two (4 sequences of 32K, 8 heads, budget 2048: 25.9 -> 17 us)
-    if (c->d.kv_dtype == SKV_BF16 && v.B * c->d.n_kv_heads > kLatencyPairs) {
+    // bf16: one block per compute unit fits (value tiles + selection histograms in LDS), so the block size is the
+    // smallest whose blocks all run at once; a second round of blocks costs more than the larger blocks' longer K/V phase
+    // (4 sequences of 32K, 8 heads, budget 2048: 25.9 us in 128-token blocks, 17 in 256-token blocks).
+    const int pairs = v.B * c->d.n_kv_heads;
+    auto blocks = [&](int chunk) { return pairs * ((c->d.max_budget + chunk - 1) / chunk); };
+    if (c->d.kv_dtype == SKV_BF16 && blocks(kAttChunkMid) > kComputeUnits) {
         const int n_splits = (c->d.max_budget + kAttChunkWide - 1) / kAttChunkWide;
         return launch_attend_g<2, kFused, kAttChunkWide>(c, a, n_splits);
     }
-    if (v.S_total / (v.B > 0 ? v.B : 1) > kMidChunkMinSentences) {
+    // Every split block of a head repeats the selection; with thousands of buckets per sequence that repetition
+    // (bucket loads from L2, histogram passes) outweighs the shorter K/V phase of 64-token blocks.
+    if (v.S_total / (v.B > 0 ? v.B : 1) > kMidChunkMinSentences || (c->d.kv_dtype == SKV_BF16 && blocks(kAttChunk) > kComputeUnits)) {
         const int n_splits = (c->d.max_budget + kAttChunkMid - 1) / kAttChunkMid;
         return c->d.kv_dtype == SKV_BF16 ? launch_attend_g<2, kFused, kAttChunkMid>(c, a, n_splits)
                                          : launch_attend_g<4, kFused, kAttChunkMid>(c, a, n_splits);

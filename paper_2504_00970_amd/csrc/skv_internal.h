@@ -32,10 +32,9 @@ constexpr int kMidChunkMinSentences = 1024;
 constexpr int kAttChunkWide = 256;    // tokens per split-K block when many (sequence, head) pairs fill the GPU
 constexpr int kWideChunkMinHeads = 64;   // (sequences x KV heads) from which the fp32 batch path is used
 constexpr int kComputeUnits = 256;       // MI355X
-// bf16 decode step, by the number of (sequence, KV head) pairs: up to kLatencyPairs the 64/128-token fused blocks;
-// above, 256-token fused blocks while they all fit the chip at once (one block per compute unit), else the streaming
-// kernel's 1024-token blocks
-constexpr int kLatencyPairs = 16;
+// bf16 decode step: the fused kernel's block size (64, 128, 256 tokens) is the smallest whose blocks, (sequence, KV head)
+// pairs x ceil(max_budget / size), all fit the chip at once (one block per compute unit); if even the 256-token blocks do
+// not, the streaming kernel's 512- or 1024-token blocks
 
 struct Ctx {
     skv_desc d;

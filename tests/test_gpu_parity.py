@@ -361,8 +361,8 @@ def _fused_case(U, oracle32, wl, seed, layers, sv_dtype="f32", seq_tokens=None, 
         ctx.decode_step(li, B, qd[li], qd[li], Kd, Vd, T_total, sv, S_total, d["cu_tok"], d["cu_sent"], d["sent_off"],
                         d["sent_len"], d["budget"], out2, None, None, None)
         torch.cuda.synchronize()
-        if B * H > 16 and wl.dtype == "bf16":
-            # the streaming batch kernel (bf16, more than 16 pairs, more 256-token blocks than compute units) hands its
+        if wl.dtype == "bf16" and B * H * math.ceil(max_budget / 256) > 256:
+            # the streaming kernel (bf16, more 256-token blocks than compute units) hands its
             # 16-token tiles to whichever wave is free: the summation order, and with it the last bits of the output,
             # differ from call to call
             assert (out - out2).abs().max().item() <= ATT_TOL[wl.dtype] / 4
@@ -370,11 +370,23 @@ def _fused_case(U, oracle32, wl, seed, layers, sv_dtype="f32", seq_tokens=None, 
             assert torch.equal(out, out2)
 
 
-def test_fused_single_sequence_matches_oracle(U, oracle32):
+@pytest.mark.parametrize("capacity", [0, 5000, STREAM_CAPACITY, 20000])
+def test_fused_single_sequence_matches_oracle(U, oracle32, capacity):
+    """One sequence through every bf16 block size: 128-token fused blocks, 256-token fused blocks (capacity 5000: 8 heads x
+    40 blocks of 128 tokens no longer fit the chip at once), 512- and 1024-token streaming blocks (capacities 9000 and
+    20000: 8 x 36 > 256 blocks of 256 tokens); fp32 keeps its 64-token blocks."""
     wl = gen.CFG1.scaled(n_layers=2, batch=1, t_range=(6000, 6000), budgets=(1024,))
-    _fused_case(U, oracle32, wl, seed=2, layers=[0, 1])
+    _fused_case(U, oracle32, wl, seed=2, layers=[0, 1], capacity=capacity)
     wl = gen.CFG0.scaled(n_layers=1, batch=1, t_range=(4096, 4096), budgets=(512,))
-    _fused_case(U, oracle32, wl, seed=3, layers=[0])
+    _fused_case(U, oracle32, wl, seed=3, layers=[0], capacity=capacity)
+
+
+@pytest.mark.parametrize("budget", [3000, 6000])
+def test_fused_single_sequence_large_budget(U, oracle32, budget):
+    """Budgets of thousands of tokens for one sequence: 256-token fused blocks (3000: 8 x 24 blocks of 128 tokens still
+    fit; 6000 does not) with every block full of retrieved tokens."""
+    wl = gen.CFG1.scaled(n_layers=1, batch=1, t_range=(9000, 9000), budgets=(budget,))
+    _fused_case(U, oracle32, wl, seed=5, layers=[0])
 
 
 def test_fused_ragged_batch_70b_heads(U, oracle32):
