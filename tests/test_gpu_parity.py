@@ -500,6 +500,10 @@ def test_full_size_cfg2_128k_sampled_layers(U, oracle32):
     torch.cuda.empty_cache()
     wl = gen.CFG2.scaled(n_layers=2, batch=1, t_range=(131072, 131072), budgets=(2048,))
     _fused_case(U, oracle32, wl, seed=1, layers=[0, 1])
+    # the same sequence through the streaming kernel (a context sized for budgets up to 20000 takes 1024-token blocks)
+    _fused_case(U, oracle32, wl.scaled(n_layers=1), seed=1, layers=[0], capacity=20000)
+    # and with a budget of 8192 tokens: 256-token fused blocks, each full of retrieved tokens
+    _fused_case(U, oracle32, wl.scaled(n_layers=1, budgets=(8192,)), seed=1, layers=[0])
 
 
 def test_full_size_cfg3_prefill(U, oracle32):
