@@ -74,6 +74,9 @@ int skv_create(skv_ctx** out, const skv_desc* desc, void* hip_stream) {
     c.d = *desc;
     c.stream = static_cast<hipStream_t>(hip_stream);
     c.device = dev;
+    c.n_cu = skv::kComputeUnits;
+    int n_cu = 0;
+    if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n_cu > 0) c.n_cu = n_cu;
     c.G = desc->n_q_heads / desc->n_kv_heads;
     c.max_sel = desc->max_sentences < desc->max_budget ? desc->max_sentences : desc->max_budget;
     c.max_splits = (desc->max_budget + skv::kAttChunk - 1) / skv::kAttChunk;
@@ -324,7 +327,7 @@ int skv_decode_step(skv_ctx* ctx, int32_t layer, int32_t B, const void* q_score,
     const int pairs = B * c.d.n_kv_heads;
     const bool can_stream = c.d.kv_dtype == SKV_BF16 && T_total < (1 << 24);
     const int wide_blocks = pairs * ((c.d.max_budget + skv::kAttChunkWide - 1) / skv::kAttChunkWide);
-    if (can_stream ? wide_blocks > skv::kComputeUnits : pairs >= skv::kWideChunkMinHeads) {
+    if (can_stream ? wide_blocks > c.n_cu : pairs >= skv::kWideChunkMinHeads) {
         if (can_stream)
             return hip_status(skv::launch_select_attend_stream(&c, q_attn, Kl, Vl, c.f_score, sent_off, sent_len, v, out, lse,
                                                                tok_idx_out, n_tok_out));

@@ -1672,7 +1672,7 @@ hipError_t launch_select_attend_stream(Ctx* c, const void* q, const void* K_laye
     // instead of four and twice the compute units busy (8 sequences x 8 heads, budget 2048: 36.7 -> 33.0 us per layer);
     // in two rounds they lose (16 sequences: 50.8 -> 58.1).
     const int blocks = v.B * c->d.n_kv_heads * ((c->d.max_budget + kStreamChunk - 1) / kStreamChunk);
-    if (2 * blocks <= kComputeUnits) return launch_select_attend_stream_g<kStreamChunk / 2>(c, a);
+    if (2 * blocks <= c->n_cu) return launch_select_attend_stream_g<kStreamChunk / 2>(c, a);
     return launch_select_attend_stream_g<kStreamChunk>(c, a);
 }
 
@@ -1689,13 +1689,13 @@ hipError_t launch_select_attend(Ctx* c, const void* q, const void* K_layer, cons
     // (4 sequences of 32K, 8 heads, budget 2048: 25.9 us in 128-token blocks, 17 in 256-token blocks).
     const int pairs = v.B * c->d.n_kv_heads;
     auto blocks = [&](int chunk) { return pairs * ((c->d.max_budget + chunk - 1) / chunk); };
-    if (c->d.kv_dtype == SKV_BF16 && blocks(kAttChunkMid) > kComputeUnits) {
+    if (c->d.kv_dtype == SKV_BF16 && blocks(kAttChunkMid) > c->n_cu) {
         const int n_splits = (c->d.max_budget + kAttChunkWide - 1) / kAttChunkWide;
         return launch_attend_g<2, kFused, kAttChunkWide>(c, a, n_splits);
     }
     // Every split block of a head repeats the selection; with thousands of buckets per sequence that repetition
     // (bucket loads from L2, histogram passes) outweighs the shorter K/V phase of 64-token blocks.
-    if (v.S_total / (v.B > 0 ? v.B : 1) > kMidChunkMinSentences || (c->d.kv_dtype == SKV_BF16 && blocks(kAttChunk) > kComputeUnits)) {
+    if (v.S_total / (v.B > 0 ? v.B : 1) > kMidChunkMinSentences || (c->d.kv_dtype == SKV_BF16 && blocks(kAttChunk) > c->n_cu)) {
         const int n_splits = (c->d.max_budget + kAttChunkMid - 1) / kAttChunkMid;
         return c->d.kv_dtype == SKV_BF16 ? launch_attend_g<2, kFused, kAttChunkMid>(c, a, n_splits)
                                          : launch_attend_g<4, kFused, kAttChunkMid>(c, a, n_splits);

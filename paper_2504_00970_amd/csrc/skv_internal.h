@@ -31,7 +31,7 @@ constexpr int kAttChunkMid = 128;     // tokens per split-K block of the single-
 constexpr int kMidChunkMinSentences = 1024;
 constexpr int kAttChunkWide = 256;    // tokens per split-K block when many (sequence, head) pairs fill the GPU
 constexpr int kWideChunkMinHeads = 64;   // (sequences x KV heads) from which the fp32 batch path is used
-constexpr int kComputeUnits = 256;       // MI355X
+constexpr int kComputeUnits = 256;       // MI355X; the context takes the device's own count when it can be read
 // bf16 decode step: the fused kernel's block size (64, 128, 256 tokens) is the smallest whose blocks, (sequence, KV head)
 // pairs x ceil(max_budget / size), all fit the chip at once (one block per compute unit); if even the 256-token blocks do
 // not, the streaming kernel's 512- or 1024-token blocks
@@ -40,6 +40,7 @@ struct Ctx {
     skv_desc d;
     hipStream_t stream;
     int device;
+    int n_cu;               // compute units of the device
     int G;
     int max_sel;            // min(max_sentences, max_budget)
     int max_splits;         // ceil(max_budget / kAttChunk)
