@@ -595,9 +595,9 @@ def main():
     ap.add_argument("--keep", type=int, default=4096, help="cfg3-retain: tokens retained per layer (floor(r tau))")
     ap.add_argument("--resident-layers", type=int, default=4, help="cfg4: layers of the pool kept in HBM")
     ap.add_argument("--batch", type=int, default=0, help="cfg4: number of sequences (default 16); cfg1, cfg2: that many sequences of the workload's context in one batch")
-    ap.add_argument("--batched-sequences", type=int, default=16,
-                    help="cfg1 without --batch: also time the step for this many sequences in one batch and report it "
-                         "under \"batched\" (0: skip)")
+    ap.add_argument("--batched-sequences", default="16,64",
+                    help="cfg1 without --batch: also time the step for these many sequences in one batch (comma-separated) "
+                         "and report them under \"batched\" (0: skip)")
     ap.add_argument("--budget", type=int, default=0, help="token budget (default: the workload's largest)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--semvec-dtype", default="f32", choices=["f32", "bf16", "fp8"],
@@ -636,19 +636,21 @@ def main():
         res = run_ragged(args, wl)
     else:
         res = run_single_sequence(args, wl, args.budget or max(wl.budgets))
-        if args.workload == "cfg1" and args.batched_sequences > 1:
+        sizes = [int(x) for x in args.batched_sequences.split(",") if x.strip()] if args.workload == "cfg1" else []
+        for Bs in [b for b in sizes if b > 1]:
             # the same step for a batch of sequences of the same context, each with its own buckets: what the kernels reach
-            # once a launch has enough work (a reported extra, not `value`)
+            # once a launch has enough work (reported extras, never `value`)
             import copy
             a2 = copy.copy(args)
             a2.steps, a2.warmup, a2.no_cpu_baseline = min(args.steps, 10), min(args.warmup, 2), True
-            Bs = args.batched_sequences
             wb = wl.scaled(name="%s_x%d" % (wl.name, Bs), batch=Bs, t_range=(wl.n_tokens, wl.n_tokens),
                            budgets=(args.budget or max(wl.budgets),))
             rb = run_ragged(a2, wb)
-            res["batched"] = {"workload": wb.name, "sequences": Bs, "us_per_layer": rb["us_per_layer"], "value": rb["value"],
-                              "unit": rb["unit"], "hbm_frac": rb["hbm_frac"], "bytes_per_layer": rb["bytes_per_layer"],
-                              "resident_layers": args.resident_layers, "steps": a2.steps}
+            res.setdefault("batched", []).append(
+                {"workload": wb.name, "sequences": Bs, "us_per_layer": rb["us_per_layer"], "value": rb["value"],
+                 "unit": rb["unit"], "hbm_frac": rb["hbm_frac"], "bytes_per_layer": rb["bytes_per_layer"],
+                 "resident_layers": args.resident_layers, "steps": a2.steps})
+            torch.cuda.empty_cache()
     res["host"] = {"nproc": os.cpu_count()}
     print(json.dumps(res), flush=True)
 
