@@ -448,6 +448,17 @@ def test_fused_batch_sequence_boundaries_inside_a_wave(U, oracle32, B, sv_dtype)
     _fused_case(U, oracle32, wl, seed=40 + B, layers=[0], sv_dtype=sv_dtype, seq_tokens=toks.tolist(), budgets=buds.tolist())
 
 
+def test_fused_batch_of_hundreds_of_short_sequences(U, oracle32):
+    """600 sequences of 0..60 tokens (4800 (sequence, head) pairs): the sequence lookup of the score kernel bisects seven
+    levels deep before its eight-entry step, most waves span several sequences, the attention grid has thousands of rows."""
+    B = 600
+    rng = np.random.default_rng(77)
+    toks = rng.integers(0, 61, size=B)
+    buds = rng.integers(0, 80, size=B)
+    wl = gen.CFG4.scaled(n_layers=1, n_q_heads=32, batch=B, budgets=(80,), dtype="bf16")
+    _fused_case(U, oracle32, wl, seed=77, layers=[0], seq_tokens=toks.tolist(), budgets=buds.tolist())
+
+
 @pytest.mark.parametrize("capacity", [0, HALF_CAPACITY, STREAM_CAPACITY])
 @pytest.mark.parametrize("dtype,budget", [("f32", 700), ("bf16", 2), ("bf16", 256), ("bf16", 257), ("bf16", 5000)])
 def test_fused_batch_path_edges(U, oracle32, dtype, budget, capacity):
