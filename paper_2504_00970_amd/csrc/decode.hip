@@ -1285,13 +1285,14 @@ constexpr int kStreamWaves = kBlockWaves;                         // the block-l
 constexpr int kStreamChunk = kStreamWaves * kStreamTiles * 16;    // 1024 tokens per block, one position per thread
 static_assert(kStreamChunk == kBlockThreads, "one retrieved position per thread");
 
+constexpr int kStreamMaxChunk = 2 * kStreamChunk;                 // the largest block: two positions per thread
 constexpr int kStreamVPitch = 2 * kHeadDim + 16;                  // bytes per value row in LDS; +16 spreads row groups over banks
 
 struct StreamShared {
     __attribute__((aligned(16))) char v[kStreamWaves][16 * kStreamVPitch];   // value tile, later the wave's partial sums
     __attribute__((aligned(16))) unsigned short q[16][kHeadDim];             // the group's queries, rows >= G zero
     float wmax[kStreamWaves][16], wsum[kStreamWaves][16];
-    int32_t row[kStreamChunk];                                               // pool row of every position of the block (-1: none)
+    int32_t row[kStreamMaxChunk];                                            // pool row of every position of the block (-1: none)
     int next_tile;
     int last;
 };
@@ -1308,12 +1309,13 @@ __device__ __forceinline__ void stream_load_queries(const AttArgs& a, StreamShar
     }
 }
 
-// Attention of one block of CHUNK (1024 or 512) positions once the selection is known: n = retrieved tokens of the
-// (sequence, head), xi = pool row of position split * CHUNK + tid (anything for positions >= n or threads >= CHUNK).  The queries are on their way to ss.q.
-// Every thread of the block calls this.
+// Attention of one block of CHUNK (512, 1024 or 2048) positions once the selection is known: n = retrieved tokens of the
+// (sequence, head); ss.row holds the pool row of position split * CHUNK + i at i (-1: no such token) for i < CHUNK.
+// The queries are on their way to ss.q.  Every thread of the block calls this.
 template <int G, int CHUNK>
 __device__ __forceinline__ void stream_attend(const AttArgs& a, StreamShared& ss, int bh, int b, int h, int split, const Seq& sq,
-                                              int32_t n, int32_t xi) {
+                                              int32_t n) {
+
     constexpr int NW = kStreamWaves;
     constexpr int kThreads = kBlockThreads;
     constexpr int kRowBytes = kHeadDim * 2;
@@ -1344,7 +1346,6 @@ __device__ __forceinline__ void stream_attend(const AttArgs& a, StreamShared& ss
     // next free one from an LDS counter whenever it finishes one, so the waves that memory serves first do more tiles
     // and all 16 keep loads in flight until the block's last tile (with four fixed tiles per wave the slowest wave ran
     // about 5 us behind the first).  Rows of unreal positions are stored as -1.
-    ss.row[tid] = (tid < cnt && xi >= 0 && xi < sq.n_tok_ctx) ? xi : -1;
     if (tid == 0) ss.next_tile = NW;
     const int ntiles = (cnt + 15) / 16;
     const char* Kh = a.Kb + ((int64_t)h * a.v.T_total + sq.tok_base) * kRowBytes;
@@ -1476,6 +1477,29 @@ __device__ __forceinline__ void stream_attend(const AttArgs& a, StreamShared& ss
                 if (4 * qd + j < G) red[(4 * qd + j) * kHeadDim + 16 * dt + t16] = o[dt][j] * cr[j];
     }
     __syncthreads();
+#ifndef SKV_NO_DIRECT
+    if (nsplit == 1) {
+        // the only block of this (sequence, head): its combined sums are the result, no partials, no arrival, no merge
+        for (int i = tid; i < kOut; i += kThreads) {
+            const int g = i / kHeadDim;
+            float sum = 0.f, lb = 0.f;
+#pragma unroll
+            for (int ww = 0; ww < NW; ++ww) {
+                sum += reinterpret_cast<const float*>(ss.v[ww])[i];
+                lb += ss.wsum[ww][g];
+            }
+            const bool empty = !(lb > 0.f);                       // every retrieved position was out of range
+            a.out[qhead0 * kHeadDim + i] = empty ? 0.f : sum / lb;
+            if (a.lse && (i % kHeadDim) == 0) {
+                float mh = -INFINITY;
+#pragma unroll
+                for (int ww = 0; ww < NW; ++ww) mh = fmaxf(mh, ss.wmax[ww][g]);
+                a.lse[qhead0 + g] = empty ? -INFINITY : (mh + log2f(lb)) * kLn2;
+            }
+        }
+        return;
+    }
+#endif
     if (tid < G) {
         float lb = 0.f, mh = -INFINITY;
 #pragma unroll
@@ -1543,7 +1567,7 @@ __device__ __forceinline__ void stream_attend(const AttArgs& a, StreamShared& ss
 
 template <int G, int CHUNK>
 __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void select_attend_stream_kernel(AttArgs a) {
-    static_assert(CHUNK % kWave == 0 && CHUNK <= kStreamChunk, "at most one retrieved position per thread");
+    static_assert(CHUNK % kWave == 0 && CHUNK <= kStreamMaxChunk, "the row table holds kStreamMaxChunk positions");
     __shared__ StreamShared ss;
     const int bh = blockIdx.y, b = bh / a.Hkv, h = bh % a.Hkv, split = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -1553,13 +1577,13 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(4
     SKV_T(0);
 
     int32_t n;                    // retrieved tokens of this (sequence, head)
-    int32_t xi;                   // pool row of this thread's position
     {
         __shared__ SelectShared sel_sh;
         const int32_t budget = min(sq.budget, a.idx_stride);
         if (split > 0 && j0 >= budget) return;                    // n <= budget: nothing for this split
         stream_load_queries<G>(a, ss, (int64_t)b * (a.Hkv * G) + (int64_t)h * G);
-        ss.row[tid] = -1;                                         // bucket-start marks first, the rows of all positions later
+        for (int p = tid; p < (CHUNK > kBlockThreads ? CHUNK : kBlockThreads); p += kBlockThreads)
+            ss.row[p] = -1;                                       // bucket-start marks first, the rows of all positions later
         // A selected bucket that reaches into this block's positions marks, in every 64-position piece it touches,
         // where it starts there and which pool row that is; each wave then fills the positions of its own piece.
         auto mark = [&](int32_t, int32_t o, int32_t ln, int32_t, int32_t tok_pos) {
@@ -1579,17 +1603,18 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(4
         n = ntok;
         if (split == 0 && tid == 0 && a.n_tok_out) a.n_tok_out[bh] = n;
         __syncthreads();                                          // bucket starts are marked, queries are in LDS
-        {
-            const int32_t v = ss.row[tid];
+        for (int pc = tid >> 6; pc < CHUNK / kWave; pc += kStreamWaves) {    // a wave fills 64-position pieces, in place
+            const int32_t v = ss.row[pc * kWave + lane];
             // position of the last bucket start at or before this lane (-1: none): running maximum of lane + 1 over the starts
             const int32_t hp = (int32_t)wave_scan_max_u32(v >= 0 ? (uint32_t)lane + 1u : 0u) - 1;
             const int32_t base = __shfl(v, max(hp, 0));
-            xi = hp >= 0 ? base + (lane - hp) : -1;
-            const int32_t pos = j0 + tid;
-            if (a.tok_idx_out && tid < CHUNK && pos < n) a.tok_idx_out[(int64_t)bh * a.idx_stride + pos] = xi;
+            const int32_t xi = hp >= 0 ? base + (lane - hp) : -1;
+            const int32_t pos = j0 + pc * kWave + lane;
+            if (a.tok_idx_out && pos < n) a.tok_idx_out[(int64_t)bh * a.idx_stride + pos] = xi;
+            ss.row[pc * kWave + lane] = (pos < n && xi >= 0 && xi < sq.n_tok_ctx) ? xi : -1;
         }
     }
-    stream_attend<G, CHUNK>(a, ss, bh, b, h, split, sq, n, xi);
+    stream_attend<G, CHUNK>(a, ss, bh, b, h, split, sq, n);
 }
 
 template <int CHUNK>
@@ -1668,11 +1693,17 @@ hipError_t launch_select_attend_stream(Ctx* c, const void* q, const void* K_laye
     AttArgs a = att_common(c, q, K_layer, V_layer, v, out, lse);
     a.score = score; a.sent_off = sent_off; a.sent_len = sent_len;
     a.tok_idx_out = tok_idx_out; a.n_tok_out = n_tok_out; a.idx_stride = c->d.max_budget;
-    // While 512-token blocks still run in one round (one block per compute unit) they are ahead: two tiles per wave
-    // instead of four and twice the compute units busy (8 sequences x 8 heads, budget 2048: 36.7 -> 33.0 us per layer);
-    // in two rounds they lose (16 sequences: 50.8 -> 58.1).
-    const int blocks = v.B * c->d.n_kv_heads * ((c->d.max_budget + kStreamChunk - 1) / kStreamChunk);
+    // Block size by rounds of blocks (one block per compute unit).  While 512-token blocks still run in one round they
+    // are ahead: two tiles per wave instead of four and twice the compute units busy (8 sequences x 8 heads, budget 2048:
+    // 36.7 -> 33.0 us per layer); in two rounds they lose (16 sequences: 50.8 -> 58.1).  With several rounds of 1024-token
+    // blocks, 2048-token blocks halve the selections and, up to a budget of 2048, need no merge: a round of them takes
+    // about 5/3 of a 1024-token round (32 sequences: 94.7 -> 87.0 us, 64: 180.2 -> 166.3; 48: 137.8 either way).
+    const int pairs = v.B * c->d.n_kv_heads;
+    const int blocks = pairs * ((c->d.max_budget + kStreamChunk - 1) / kStreamChunk);
     if (2 * blocks <= c->n_cu) return launch_select_attend_stream_g<kStreamChunk / 2>(c, a);
+    const int big_blocks = pairs * ((c->d.max_budget + kStreamMaxChunk - 1) / kStreamMaxChunk);
+    const int rounds = (blocks + c->n_cu - 1) / c->n_cu, big_rounds = (big_blocks + c->n_cu - 1) / c->n_cu;
+    if (5 * big_rounds < 3 * rounds) return launch_select_attend_stream_g<kStreamMaxChunk>(c, a);
     return launch_select_attend_stream_g<kStreamChunk>(c, a);
 }
 

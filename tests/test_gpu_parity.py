@@ -431,13 +431,15 @@ def test_fused_batch_with_empty_and_tiny_sequences(U, oracle32, dtype, B, capaci
     _fused_case(U, oracle32, wl, seed=12, layers=[0], seq_tokens=toks, budgets=buds, capacity=capacity)
 
 
+@pytest.mark.parametrize("capacity", [0, 2048])
 @pytest.mark.parametrize("sv_dtype", ["f32", "bf16", "fp8"])
 @pytest.mark.parametrize("B", [2, 7, 8, 9, 21, 70])
-def test_fused_batch_sequence_boundaries_inside_a_wave(U, oracle32, B, sv_dtype):
+def test_fused_batch_sequence_boundaries_inside_a_wave(U, oracle32, B, sv_dtype, capacity):
     """The score kernel's waves own 8, 16 or 32 consecutive buckets of the concatenated batch (fp32, bf16, E4M3 table)
     and look up the sequences they fall in.  Sequences of a handful of tokens, some without tokens, put several
     boundaries inside one wave; a long sequence in between spans many waves; batch sizes lie on both sides of the
-    lookup's eight-entry step."""
+    lookup's eight-entry step.  (With a capacity of 2048 the two largest batches take the streaming kernel's 2048-token
+    blocks, the others 512-token blocks or the fused kernel.)"""
     rng = np.random.default_rng(100 + B)
     toks = rng.integers(0, 90, size=B)
     toks[rng.integers(0, B, size=max(1, B // 5))] = 0
@@ -445,7 +447,19 @@ def test_fused_batch_sequence_boundaries_inside_a_wave(U, oracle32, B, sv_dtype)
     toks[-1] = int(rng.integers(1, 30))
     buds = rng.integers(0, 400, size=B)
     wl = gen.CFG4.scaled(n_layers=1, n_q_heads=32, batch=B, budgets=(400,), dtype="bf16")
-    _fused_case(U, oracle32, wl, seed=40 + B, layers=[0], sv_dtype=sv_dtype, seq_tokens=toks.tolist(), budgets=buds.tolist())
+    _fused_case(U, oracle32, wl, seed=40 + B, layers=[0], sv_dtype=sv_dtype, seq_tokens=toks.tolist(), budgets=buds.tolist(),
+                capacity=capacity)
+
+
+@pytest.mark.parametrize("Hq", [8, 32, 64])
+@pytest.mark.parametrize("budget", [1025, 1500, 2048, 2049, 3000])
+def test_fused_batch_2048_token_blocks(U, oracle32, budget, Hq):
+    """20 sequences x 8 KV heads with budgets above 1024: the 1024-token streaming blocks would need two rounds on 256
+    compute units, so the kernel runs 2048-token blocks (two positions per thread), each writing its result directly
+    while one block covers the budget, and through the split-K merge from 2049 tokens on; contexts shorter and longer
+    than the budget."""
+    wl = gen.CFG4.scaled(n_layers=1, n_q_heads=Hq, batch=20, t_range=(900, 4500), budgets=(budget,))
+    _fused_case(U, oracle32, wl, seed=31, layers=[0])
 
 
 def test_fused_batch_of_hundreds_of_short_sequences(U, oracle32):
@@ -457,6 +471,7 @@ def test_fused_batch_of_hundreds_of_short_sequences(U, oracle32):
     buds = rng.integers(0, 80, size=B)
     wl = gen.CFG4.scaled(n_layers=1, n_q_heads=32, batch=B, budgets=(80,), dtype="bf16")
     _fused_case(U, oracle32, wl, seed=77, layers=[0], seq_tokens=toks.tolist(), budgets=buds.tolist())
+    _fused_case(U, oracle32, wl, seed=78, layers=[0], seq_tokens=toks.tolist(), budgets=buds.tolist(), capacity=2048)   # 2048-token blocks
 
 
 @pytest.mark.parametrize("capacity", [0, HALF_CAPACITY, STREAM_CAPACITY])
