@@ -52,7 +52,8 @@ typedef struct {
     int32_t kv_dtype;       /* skv_dtype of K, V and the queries */
     int32_t max_tokens;     /* largest T (T_total for a ragged batch) any call will pass */
     int32_t max_sentences;  /* largest S (S_total for a ragged batch) any call will pass */
-    int32_t max_budget;     /* largest per-sequence token budget tau any call will pass */
+    int32_t max_budget;     /* largest per-sequence token budget tau any call will pass; skv_decode_step sizes its grid and
+                               picks its block size from this value, so keep it close to the budgets in use */
     int32_t max_batch;      /* largest number of sequences in one skv_decode_step (>= 1, <= 4096, max_batch * Hkv <= 65535) */
     int32_t semvec_dtype;   /* skv_dtype of the semantic-vector table: SKV_F32, or SKV_BF16 / SKV_FP8_E4M3 = the fp32 mean
                                rounded once to nearest even (the mixed-precision sentence vectors of the paper's "Future
