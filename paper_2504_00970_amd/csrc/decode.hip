@@ -1274,16 +1274,17 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
 // all blocks of the launch are resident at once (16 waves per CU, each with 8 KB in flight).
 // Tile arithmetic is that of the kernel above: S^T = K Q^T with K rows as A fragments, P rounded to bf16 with the
 // normaliser summing the rounded weights, V through a wave-private LDS tile into B fragments.
-// A block is 16 waves = 1024 retrieved tokens of one (sequence, KV head).  It first runs the selection itself from the
-// scores (as the single-sequence kernel does, redundantly with the head's other block) and keeps the pool rows of
-// its positions in registers: no selection launch, no tok_idx round trip, two partials per 2048-token budget.
+// A block is 16 waves and CHUNK = 1024 (or 512, or 2048) retrieved tokens of one (sequence, KV head).  It first runs the
+// selection itself from the scores (as the single-sequence kernel does, redundantly with the head's other blocks) and
+// keeps the pool rows of its positions in LDS: no selection launch, no tok_idx round trip, two partials per 2048-token
+// budget with 1024-token blocks, none when one block covers the budget.
 // Measured against select_kernel + a 4-wave form of this kernel that read tok_idx (16 sequences x 8 heads, budget
 // 2048): 8.7 + 37.1 us -> 39 us per layer; equal or better from 8 to 48 sequences.
 // ------------------------------------------------------------------------------------------------
 constexpr int kStreamTiles = 4;                                   // 16-token tiles per wave
 constexpr int kStreamWaves = kBlockWaves;                         // the block-level selection needs kBlockThreads threads
 constexpr int kStreamChunk = kStreamWaves * kStreamTiles * 16;    // 1024 tokens per block, one position per thread
-static_assert(kStreamChunk == kBlockThreads, "one retrieved position per thread");
+static_assert(kStreamChunk == kBlockThreads, "the usual block: one retrieved position per thread");
 
 constexpr int kStreamMaxChunk = 2 * kStreamChunk;                 // the largest block: two positions per thread
 constexpr int kStreamVPitch = 2 * kHeadDim + 16;                  // bytes per value row in LDS; +16 spreads row groups over banks
