@@ -68,6 +68,23 @@ def capture(ctx, fn):
     return g
 
 
+def step_spread(run_step, set_query, steps, layers_per_step):
+    """Per-step times of `steps` further steps (an event after every step): median, 10th and 90th percentile in us per
+    layer.  Run after the timed region, which is measured as a whole."""
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    evs[0].record()
+    for i in range(steps):
+        set_query(i)
+        run_step()
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    us = np.array([evs[i].elapsed_time(evs[i + 1]) for i in range(steps)]) * 1e3 / layers_per_step
+    if len(us) == 0:
+        return None
+    return {"median": round(float(np.median(us)), 3), "p10": round(float(np.percentile(us, 10)), 3),
+            "p90": round(float(np.percentile(us, 90)), 3), "steps": steps}
+
+
 def measured_traffic(workload, kernel):
     """HBM bytes per launch from the committed rocprofv3 counter runs (profiles/), or None."""
     try:
@@ -166,6 +183,8 @@ def run_single_sequence(args, wl, budget):
     graph = capture(ctx, layers)             # the same launches replayed as one HIP graph per decode step
     ms_graph = timed(graph.replay)
     ms_per_step = ms_graph if args.launch == "graph" else ms_direct
+    spread = step_spread(graph.replay if args.launch == "graph" else layers,
+                         lambda i: q_cur.copy_(qsets[i % N_QUERY_SETS]), args.steps, L * passes)
 
     n_tok_all = n_tok_rec.cpu().numpy().astype(np.int64)
     used = [i % N_QUERY_SETS for i in range(args.steps)]
@@ -229,6 +248,7 @@ def run_single_sequence(args, wl, budget):
         "us_per_layer": round(us_per_layer, 3),
         "us_per_layer_direct_launch": round(ms_direct * 1e3 / (L * passes), 3),
         "us_per_layer_hip_graph": round(ms_graph * 1e3 / (L * passes), 3),
+        "us_per_layer_per_step": spread,
         "bytes_per_layer": int(bytes_layer["total"]),
         "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4),
         "mean_tokens_selected_per_head": round(n_tok_layer / H, 1),
@@ -341,6 +361,8 @@ def run_ragged(args, wl):
     graph = capture(ctx, layers)
     ms_graph = timed(graph.replay)
     ms_per_step = ms_graph if args.launch == "graph" else ms_direct
+    spread = step_spread(graph.replay if args.launch == "graph" else layers,
+                         lambda i: q_cur.copy_(qsets[i % N_QUERY_SETS]), args.steps, L)
     n_tok_layer = float(n_tok_rec.sum().item()) / R
     mean_len = float(inp.sent_len.mean())
     bl = decode_bytes(wl, S_total, n_tok_layer, n_tok_layer / mean_len, fused=True, sv_bytes=sv_bytes)
@@ -376,6 +398,7 @@ def run_ragged(args, wl):
         "us_per_layer": round(us_per_layer, 3),
         "us_per_layer_direct_launch": round(ms_direct * 1e3 / L, 3),
         "us_per_layer_hip_graph": round(ms_graph * 1e3 / L, 3),
+        "us_per_layer_per_step": spread,
         "bytes_per_layer": int(bl["total"]), "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4),
         "mean_tokens_selected_per_head": round(n_tok_layer / (B * H), 1),
         "prefill": {"semvec_ms": round(t_sv.ms, 3),
