@@ -560,6 +560,15 @@ def test_full_size_cfg4_ragged_batch(U, oracle32):
     _fused_case(U, oracle32, gen.CFG4.scaled(n_layers=2), seed=0, layers=[0, 1])
 
 
+def test_full_size_cfg1_batched(U, oracle32):
+    """The batched extras of bench.py at their real shapes, one layer: 16 sequences of 32768 tokens (1024-token streaming
+    blocks) and 24 sequences (2048-token blocks, one per (sequence, head)), budget 2048, every sequence against the oracle."""
+    for B in (16, 24):
+        wl = gen.CFG1.scaled(n_layers=1, batch=B, t_range=(32768, 32768), budgets=(2048,))
+        _fused_case(U, oracle32, wl, seed=3, layers=[0])
+        torch.cuda.empty_cache()
+
+
 # ----------------------------------------------------------------------------- local window merge, equal chunks
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
