@@ -798,6 +798,16 @@ __device__ __forceinline__ float sum_chunks(float x) {
     return x;
 }
 
+// ds_read_b64_tr_b16 (gfx950): within each group of 16 lanes, lane i receives element i % 4 of the 8-byte pieces that
+// lanes i / 4, i / 4 + 4, i / 4 + 8 and i / 4 + 12 of the group point at, in that order.  With lane s of the group
+// pointing at dims 4 (s % 4) .. + 3 of row s / 4 of a row-major 4 x 16 block of bf16, lane i gets column i of the
+// block's four rows: the B fragment of a 16x16x16 MFMA whose k index runs over the rows (one read instead of four
+// 2-byte reads).
+typedef short bf16x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ bf16x4_t lds_read_tr16(const char* p) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((bf16x4_t __attribute__((address_space(3)))*)(p));
+}
+
 struct AttArgs {
     const char* q;            // [B][Hq][D]
     const char* Kb;           // kDirect: K_sel [B*Hkv][row_stride][D]; else the layer's pool [Hkv][T_total][D]
@@ -1035,13 +1045,12 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
             lw += __shfl_xor(lw, 32);
             if (qd == 0) sm_wsum[w][t16] = lw;
             const bf16x4 pa = {(short)pb[0], (short)pb[1], (short)pb[2], (short)pb[3]};
-            const unsigned short* vt = reinterpret_cast<const unsigned short*>(sm_v);
+            // B fragments by the LDS transpose read: this lane points at dims 4 (t16 % 4) .. + 3 of value row 4 qd + t16 / 4
+            const char* vtr = sm_v + (4 * qd + (t16 >> 2)) * kVPitch + 8 * (t16 & 3);
             f32x4 o[kHeadDim / 16];
 #pragma unroll
             for (int dt = 0; dt < kHeadDim / 16; ++dt) {
-                bf16x4 vb;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) vb[j] = (short)vt[(4 * qd + j) * (kVPitch / 2) + 16 * dt + t16];
+                const bf16x4 vb = lds_read_tr16(vtr + 32 * dt);
                 const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
                 o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, vb, zero, 0, 0, 0);
             }
@@ -1380,7 +1389,9 @@ __device__ __forceinline__ void stream_attend(const AttArgs& a, StreamShared& ss
 #pragma unroll
     for (int dt = 0; dt < kHeadDim / 16; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     char* vt_b = ss.v[w];
-    const unsigned short* vt = reinterpret_cast<const unsigned short*>(vt_b);
+    // B fragments of P.V by the LDS transpose read: this lane's address is the 4-dim piece (dims 4 (t16 % 4) .. + 3 of
+    // the 16-dim group) of value row 4 qd + t16 / 4
+    const char* vtr = vt_b + (4 * qd + (t16 >> 2)) * kVPitch + 8 * (t16 & 3);
 
     while (tile < ntiles) {
         // the wave's next tile, asked for early so that its rows are known when this tile's registers come free
@@ -1445,9 +1456,7 @@ __device__ __forceinline__ void stream_attend(const AttArgs& a, StreamShared& ss
         const bf16x4 pa = {(short)pb[0], (short)pb[1], (short)pb[2], (short)pb[3]};
 #pragma unroll
         for (int dt = 0; dt < kHeadDim / 16; ++dt) {
-            bf16x4 vb;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) vb[j] = (short)vt[(4 * qd + j) * (kVPitch / 2) + 16 * dt + t16];
+            const bf16x4 vb = lds_read_tr16(vtr + 32 * dt);
             o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, vb, o[dt], 0, 0, 0);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");    // reads of this tile precede the next tile's writes
