@@ -808,6 +808,13 @@ __device__ __forceinline__ bf16x4_t lds_read_tr16(const char* p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((bf16x4_t __attribute__((address_space(3)))*)(p));
 }
 
+// q.K^T step on 32 dims: v_mfma_f32_16x16x32_bf16 with a 16-byte row chunk (8 consecutive dims) per lane on both sides
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ f32x4_t mfma_qk32(const uint4& k, const uint4& q, f32x4_t c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, k), __builtin_bit_cast(bf16x8_t, q), c, 0, 0, 0);
+}
+
 struct AttArgs {
     const char* q;            // [B][Hq][D]
     const char* Kb;           // kDirect: K_sel [B*Hkv][row_stride][D]; else the layer's pool [Hkv][T_total][D]
@@ -960,11 +967,11 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
     }
     const float scale = kLog2e * rsqrtf((float)kHeadDim);
     if constexpr (kMfma) {
-        // ---- bf16: q.K^T and P.V on the matrix cores (v_mfma_f32_16x16x16_bf16) ------------------------------
+        // ---- bf16: q.K^T (v_mfma_f32_16x16x32_bf16) and P.V (v_mfma_f32_16x16x16_bf16) on the matrix cores ----
         // Wave w owns the 16 tokens [16w, 16w+16) of the chunk.  With t = lane % 16 and qd = lane / 16:
-        //  * S^T = K Q^T: A fragment = 4 consecutive dims of token t's key, B fragment = the same 4 dims of head t's
+        //  * S^T = K Q^T: A fragment = 8 consecutive dims of token t's key, B fragment = the same 8 dims of head t's
         //    query (heads >= G are zero).  The dimension order inside the contraction is free as long as A and B agree,
-        //    so one 16-byte load of a row (dims 32s+8qd .. +7) feeds two MFMA steps; four loads cover the row.
+        //    so one 16-byte load of a row (dims 32s+8qd .. +7) is one 32-deep MFMA step; four loads cover the row.
         //    The accumulator holds logit(token 4qd+j, head t), j = 0..3.
         //  * O = P V: that accumulator layout IS the A-fragment layout (head t, tokens 4qd+j); the B fragment
         //    V[token 4qd+j][16dt + t] is read from a wave-private LDS copy of the 16 value rows (padded pitch).
@@ -1003,10 +1010,7 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
             for (int s2 = 0; s2 < 4; ++s2) {
                 uint4 qq = qB[s2];
                 if (t16 >= G) qq = make_uint4(0, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4, make_uint2(kA[s2].x, kA[s2].y)),
-                                                                __builtin_bit_cast(bf16x4, make_uint2(qq.x, qq.y)), acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4, make_uint2(kA[s2].z, kA[s2].w)),
-                                                                __builtin_bit_cast(bf16x4, make_uint2(qq.z, qq.w)), acc, 0, 0, 0);
+                acc = mfma_qk32(kA[s2], qq, acc);
             }
             float mw = -INFINITY;
 #pragma unroll
@@ -1403,10 +1407,7 @@ __device__ __forceinline__ void stream_attend(const AttArgs& a, StreamShared& ss
 #pragma unroll
         for (int s2 = 0; s2 < 4; ++s2) {
             const uint4 qq = *reinterpret_cast<const uint4*>(&ss.q[t16][32 * s2 + 8 * qd]);
-            acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4, make_uint2(kA[s2].x, kA[s2].y)),
-                                                            __builtin_bit_cast(bf16x4, make_uint2(qq.x, qq.y)), acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4, make_uint2(kA[s2].z, kA[s2].w)),
-                                                            __builtin_bit_cast(bf16x4, make_uint2(qq.z, qq.w)), acc, 0, 0, 0);
+            acc = mfma_qk32(kA[s2], qq, acc);
         }
         // the tile's value rows go to the wave's LDS tile (rows of masked tokens as zeros) ...
 #pragma unroll
