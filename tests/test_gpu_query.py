@@ -91,6 +91,7 @@ def test_query_update_feeds_decode_step(U, oracle32):
     n_tok = U.empty_i32(max(H, 4), fill=-5)
     K, V = gen.to_numpy(inp.K[L]), gen.to_numpy(inp.V[L])
     sv_np = sv.cpu().numpy()[0]
+    n_ties = 0
     for t in range(4):
         print("query_update -> decode_step, token", t, flush=True)
         ctx.query_update(1, qs[t], U.i32([OTHER]), d_bm, VOCAB, q_sum, q_cnt, q_bar)
@@ -98,18 +99,16 @@ def test_query_update_feeds_decode_step(U, oracle32):
                         U.i32(inp.sent_off), U.i32(inp.lengths), U.i32([budget]), out, None, tok_idx, n_tok)
         torch.cuda.synchronize()
         _, qbar_ref = cache.step(U.np_of(qs[t]).reshape(-1), OTHER, _bitmap(), VOCAB)
-        ref = oracle32.decode_step(qbar_ref.reshape(Hq, D), U.np_of(qs[t]), K, V, sv_np, inp.sent_off, inp.lengths, budget)
+        assert np.array_equal(U.np_of(q_bar[0]).reshape(-1).view(qbar_ref.dtype), qbar_ref)
         g_n, g_idx = n_tok.cpu().numpy()[:H], tok_idx.cpu().numpy()
-        same = all(g_n[h] == ref["n_tok"][h] and np.array_equal(g_idx[h, :g_n[h]], ref["tok_idx"][h, :g_n[h]])
-                   for h in range(H))
-        if same:
-            tol = 1e-4 if wl.dtype == "f32" else 2e-2
-            assert np.abs(out.cpu().numpy() - ref["out"]).max() <= tol
-        else:                                                     # only a documented score tie may change the selection
-            sc = oracle32.score(qbar_ref.reshape(Hq, D), sv_np)
-            for h in range(H):
-                sel, n_sel, ti, nt = oracle32.select(sc[h:h + 1], inp.sent_off, inp.lengths, budget)
-                if nt[0] != g_n[h] or not np.array_equal(ti[0, :nt[0]], g_idx[h, :g_n[h]]):
-                    srt = np.sort(sc[h])[::-1]
-                    gaps = np.abs(np.diff(srt)) / max(np.abs(srt).max(), 1e-30)
-                    assert gaps.min() < 1e-5, (t, h)
+        # the GPU's mean query is bit-exact (checked above), so both sides rank with the same query; the selection gate
+        # is the usual one: oracle rule on the GPU's scores bit for bit, documented ties only against the oracle's scores
+        sc = oracle32.score(qbar_ref.reshape(Hq, D), sv_np)
+        sc_gpu = U.gpu_scores(ctx, L, q_bar[0], sv, S, H)
+        n_ties += U.check_selection(oracle32, sc, sc_gpu, inp.sent_off, inp.lengths, budget, g_idx, g_n, what=f"token {t}")
+        tok_g = np.where(g_idx < 0, 0, g_idx).astype(np.int32)
+        o_ref, _ = oracle32.attend(U.np_of(qs[t]), oracle32.gather(K, tok_g, g_n.astype(np.int32)),
+                                   oracle32.gather(V, tok_g, g_n.astype(np.int32)), g_n.astype(np.int32))
+        tol = 1e-4 if wl.dtype == "f32" else 2e-2
+        assert np.abs(out.cpu().numpy() - o_ref).max() <= tol
+    assert n_ties <= U.MAX_TIES_PER_TEST, n_ties

@@ -59,6 +59,44 @@ def test_token_importance_matches_oracle(U, oracle32, dtype, Hq, H, N, T):
         assert np.all(alpha[l] >= 0)
 
 
+FULL_IMP_CASES = [("bf16", 32, 8, 32, 32768), ("f32", 32, 8, 32, 32768), ("bf16", 8, 2, 32, 40100), ("f32", 4, 1, 32, 70001)]
+
+
+@pytest.mark.parametrize("dtype,Hq,H,N,T", FULL_IMP_CASES, ids=[f"{c[0]}-Hq{c[1]}-H{c[2]}-N{c[3]}-T{c[4]}" for c in FULL_IMP_CASES])
+def test_token_importance_and_retention_at_benchmark_size(U, oracle32, dtype, Hq, H, N, T):
+    """The size the retention benchmark times (32768 tokens, 32/8 heads, a 32-token window: 64 key chunks of 512 per
+    head) and prompts beyond it, where the per-row combine walks its chunks in several strides of 64 (40100 tokens: 79
+    chunks; 70001: 137) and most sweeps lie wholly before the window (no masking): one layer against the oracle, then
+    the k = 4096 best tokens by the oracle's rule on the GPU's own importance, bit for bit."""
+    _say("importance at size", dtype, Hq, H, N, T)
+    wl = gen.CFG3.scaled(n_layers=1, n_q_heads=Hq, n_kv_heads=H, n_tokens=T, dtype=dtype)
+    lens = gen.sentence_lengths(wl.len_dist, T, seed=5)
+    K = gen.kv_layer(lens, H, 128, wl.torch_dtype, 5, 0)[0][None].to(U.DEV)
+    q_obs = gen.queries(Hq, N, 128, wl.torch_dtype, seed=6, device=U.DEV).view(1, Hq, N, 128)
+    S = len(lens)
+    ctx = U.make_ctx(wl, T, S, 16)
+    alpha_dev = _gpu_importance(U, ctx, q_obs, K, T, N)
+    alpha = alpha_dev.cpu().numpy()
+    ref = oracle32.token_importance(U.np_of(q_obs[0]), U.np_of(K[0]))
+    err = np.abs(alpha[0] - ref)
+    assert np.all(err <= 2e-4 * ref + 1e-7 * ref.max()), float((err / (ref + 1e-30)).max())
+    assert np.all(alpha[0] >= 0)
+    k, Tp = 4096, T - N
+    seg = np.repeat(np.arange(S), lens).astype(np.int32)[:T]
+    keep, n_keep, off, ln = _gpu_retain(U, ctx, alpha_dev, k, seg, S)
+    want_keep, want_off, want_len = oracle32.retain(alpha[0], k, seg, S)
+    assert n_keep[0] == len(want_keep) == min(k, Tp)
+    assert np.array_equal(keep[0, :n_keep[0]], want_keep)
+    assert np.array_equal(off[0], want_off) and np.array_equal(ln[0], want_len)
+    # end to end against the oracle's own importance: the two sets may differ only in tokens at the cut
+    ref_keep, _, _ = oracle32.retain(ref, k, seg, S)
+    diff = np.setxor1d(want_keep, ref_keep)
+    if len(diff):
+        cut = np.sort(ref)[::-1][k - 1]
+        _say(f"  retained sets differ in {len(diff)} tokens at the cut")
+        assert np.all(np.abs(ref[diff] - cut) <= 5e-4 * cut), float(np.abs(ref[diff] - cut).max() / cut)
+
+
 def _gpu_retain(U, ctx, alpha_dev, k, seg_id, S):
     L, Tp = alpha_dev.shape
     keep = U.empty_i32(L, max(k, 1), fill=-9)
