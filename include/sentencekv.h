@@ -220,6 +220,29 @@ int skv_decode_step(skv_ctx* ctx, int32_t layer, int32_t B, const void* q_score,
                     const int32_t* cu_tok, const int32_t* cu_sent, const int32_t* sent_off, const int32_t* sent_len,
                     const int32_t* budget, float* out, float* lse, int32_t* tok_idx_out, int32_t* n_tok_out);
 
+/* skv_decode_step for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, results and errors as skv_decode_step, but no context: the
+ * descriptor and the stream are passed with every call, and the workspace (scores, split-K partials, arrival counters)
+ * is a static array of SKV_NOALLOC_SCRATCH_BYTES of device memory inside the library, which every GPU the library runs
+ * on holds until the process ends.  The call allocates and frees nothing (no hipMalloc / hipFree, no allocating library
+ * routine) and never blocks the host; it queues one small clearing kernel (the arrival counters) ahead of the kernels of
+ * skv_decode_step.  The address of the array is looked up once per device, at skv_create or at the first call here on
+ * that device (a symbol lookup: make that first call outside graph capture).
+ * desc        host; the maxima only need to cover this call (max_tokens is not used for sizing).  The workspace a
+ *             descriptor needs is about  max_batch * Hq * ceil(max_budget / 64) * 520  +  Hkv * max_sentences * 4
+ *             + max_batch * Hkv * (max_budget + min(max_sentences, max_budget)) * 4  bytes
+ *             (0.7 MB for 32/8 heads, 2048-token budget, 1332 buckets, one sequence).
+ * Errors: as skv_decode_step, plus SKV_EINVAL for a bad descriptor and SKV_ECAPACITY when the descriptor needs more
+ * than SKV_NOALLOC_SCRATCH_BYTES.
+ * All calls on one GPU share the one array, on whatever stream: calls that overlap in time on the same GPU race
+ * (order them on one stream or by events).  skv_decode_step with a context is unaffected. */
+#define SKV_NOALLOC_SCRATCH_BYTES (4 * 1024 * 1024)
+int skv_decode_step_noalloc(const skv_desc* desc, void* hip_stream, int32_t layer, int32_t B, const void* q_score,
+                            const void* q_attn, const void* K_pool, const void* V_pool, int32_t T_total, const void* semvec,
+                            int32_t S_total, const int32_t* cu_tok, const int32_t* cu_sent, const int32_t* sent_off,
+                            const int32_t* sent_len, const int32_t* budget, float* out, float* lse, int32_t* tok_idx_out,
+                            int32_t* n_tok_out);
+
 /* Eq. 3 over the union of two disjoint token sets from the two partial results (each side's `out` and `lse` as
  * written by skv_attend or skv_decode_step): out = (Z_a out_a + Z_b out_b) / (Z_a + Z_b), lse = log(Z_a + Z_b),
  * Z = exp(lse).  The paper's Eq. 3 sees the retrieved prompt tokens only; a caller that also keeps a contiguous

@@ -54,6 +54,8 @@ _SIGNATURES = {
     "skv_merge_lse": (_int, [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
     "skv_decode_step": (_int, [_vp, _i32, _i32, _vp, _vp, _vp, _vp, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp,
                                _vp, _vp, _vp]),
+    "skv_decode_step_noalloc": (_int, [ctypes.POINTER(_Desc), _vp, _i32, _i32, _vp, _vp, _vp, _vp, _i32, _vp, _i32, _vp, _vp,
+                                       _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
 }
 EXPORTS = tuple(_SIGNATURES)
 
@@ -211,3 +213,20 @@ class Context:
     def merge_lse(self, n_heads: int, out_a, lse_a, out_b, lse_b, out, lse=None) -> None:
         _check(_lib().skv_merge_lse(self._h, n_heads, _p(out_a), _p(lse_a), _p(out_b), _p(lse_b), _p(out), _p(lse)),
                "skv_merge_lse")
+
+
+NOALLOC_SCRATCH_BYTES = 4 * 1024 * 1024
+
+
+def decode_step_noalloc(desc: Desc, layer: int, B: int, q_score, q_attn, K_pool, V_pool, T_total: int, semvec, S_total: int,
+                        cu_tok, cu_sent, sent_off, sent_len, budget, out, lse=None, tok_idx_out=None, n_tok_out=None,
+                        stream: Optional[int] = None) -> None:
+    """skv_decode_step_noalloc: the decode step without a context, on the library's static device scratch."""
+    d = _Desc(desc.n_layers, desc.n_q_heads, desc.n_kv_heads, desc.head_dim, desc.kv_dtype, desc.max_tokens,
+              desc.max_sentences, desc.max_budget, desc.max_batch, desc.semvec_dtype)
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else 0
+    _check(_lib().skv_decode_step_noalloc(ctypes.byref(d), _vp(stream), layer, B, _p(q_score), _p(q_attn), _p(K_pool),
+                                          _p(V_pool), T_total, _p(semvec), S_total, _p(cu_tok), _p(cu_sent), _p(sent_off),
+                                          _p(sent_len), _p(budget), _p(out), _p(lse), _p(tok_idx_out), _p(n_tok_out)),
+           "skv_decode_step_noalloc")

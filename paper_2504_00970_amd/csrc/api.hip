@@ -1,5 +1,6 @@
 // C ABI of libsentencekv: context management, host-side argument checks, and the launch sequence of
 // every entry point declared in sentencekv.h.  All checks run before anything touches the GPU.
+#include <mutex>
 #include <new>
 
 #include "skv_internal.h"
@@ -45,6 +46,85 @@ inline int64_t layer_elems(const Ctx& c, int64_t rows) { return (int64_t)c.d.n_k
 inline int elt_bytes(const Ctx& c) { return c.d.kv_dtype == SKV_BF16 ? 2 : 4; }
 inline int sv_bytes(const Ctx& c) { return c.d.semvec_dtype == SKV_BF16 ? 2 : c.d.semvec_dtype == SKV_FP8_E4M3 ? 1 : 4; }
 
+
+// ---- workspace: one block of device memory, carved the same way whether skv_create allocated it or it is the static
+// scratch array of skv_decode_step_noalloc ---------------------------------------------------------------------------
+constexpr int kWsParts = 9;
+size_t workspace_layout(const skv_desc& d, int max_splits, int max_sel, size_t sz[kWsParts]) {
+    const size_t BH = (size_t)d.max_batch * d.n_kv_heads, BQ = (size_t)d.max_batch * d.n_q_heads;
+    const size_t n_seg = (size_t)(d.max_tokens + skv::kSegTokPerBlock - 1) / skv::kSegTokPerBlock;
+    sz[0] = round256(n_seg * sizeof(unsigned long long));                          // seg_part
+    sz[1] = round256(BQ * max_splits * skv::kHeadDim * sizeof(float));             // att_part
+    sz[2] = round256(BQ * max_splits * 2 * sizeof(float));                         // att_ml
+    sz[3] = round256(BH * sizeof(unsigned int));                                   // att_counter
+    sz[4] = round256((size_t)d.n_kv_heads * d.max_sentences * sizeof(float));      // f_score
+    sz[5] = round256(BH * max_sel * sizeof(int32_t));                              // f_sel_sent
+    sz[6] = round256(BH * sizeof(int32_t));                                        // f_n_sel
+    sz[7] = round256(BH * sizeof(int32_t));                                        // f_n_tok
+    sz[8] = round256(BH * d.max_budget * sizeof(int32_t));                         // f_tok_idx
+    size_t total = 0;
+    for (int i = 0; i < kWsParts; ++i) total += sz[i];
+    return total;
+}
+
+void carve_workspace(Ctx& c, char* base, const size_t sz[kWsParts]) {
+    char* p = base;
+    c.seg_part = reinterpret_cast<unsigned long long*>(p); p += sz[0];
+    c.att_part = reinterpret_cast<float*>(p); p += sz[1];
+    c.att_ml = reinterpret_cast<float*>(p); p += sz[2];
+    c.att_counter = reinterpret_cast<unsigned int*>(p); p += sz[3];
+    c.f_score = reinterpret_cast<float*>(p); p += sz[4];
+    c.f_sel_sent = reinterpret_cast<int32_t*>(p); p += sz[5];
+    c.f_n_sel = reinterpret_cast<int32_t*>(p); p += sz[6];
+    c.f_n_tok = reinterpret_cast<int32_t*>(p); p += sz[7];
+    c.f_tok_idx = reinterpret_cast<int32_t*>(p); p += sz[8];
+}
+
+void fill_context(Ctx& c, const skv_desc& d, hipStream_t stream, int dev) {
+    c.d = d;
+    c.stream = stream;
+    c.device = dev;
+    c.n_cu = skv::kComputeUnits;
+    int n_cu = 0;
+    if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n_cu > 0) c.n_cu = n_cu;
+    c.G = d.n_q_heads / d.n_kv_heads;
+    c.max_sel = d.max_sentences < d.max_budget ? d.max_sentences : d.max_budget;
+    c.max_splits = (d.max_budget + skv::kAttChunk - 1) / skv::kAttChunk;
+}
+
+// ---- static scratch of skv_decode_step_noalloc -----------------------------------------------------------------------
+// Device memory that exists from the moment the code object is loaded on a GPU until the process ends: nothing is
+// allocated for it at run time.  Every GPU holds its own copy at its own address; `scratch` below is only the host-side
+// handle of the symbol and must never be used as an address.  static_scratch() resolves the address once per device
+// (with that device current) and every use goes through the pointer it returns.
+constexpr size_t kStaticScratchBytes = (size_t)SKV_NOALLOC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+std::mutex g_scratch_mutex;
+char* g_scratch_ptr[kMaxDevices];      // per device; null until resolved
+
+// Device address of the scratch array on device `dev`, which must be the current device.  out may be null.
+int static_scratch(int dev, char** out) {
+    if (dev < 0 || dev >= kMaxDevices) return SKV_EINVAL;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return SKV_EHIP;
+        }
+        g_scratch_ptr[dev] = static_cast<char*>(p);
+    }
+    if (out) *out = g_scratch_ptr[dev];
+    return SKV_OK;
+}
+
+// Clears `n` 32-bit words (a kernel rather than a memset node: the call may be recorded into a HIP graph).
+__global__ void clear_words_kernel(uint32_t* __restrict__ p, int32_t n) {
+    const int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
 }  // namespace
 
 extern "C" {
@@ -53,7 +133,7 @@ const char* skv_strerror(int status) {
     switch (status) {
         case SKV_OK: return "ok";
         case SKV_EINVAL: return "invalid argument";
-        case SKV_ECAPACITY: return "size exceeds the capacity given at skv_create";
+        case SKV_ECAPACITY: return "size exceeds the capacity (the maxima given at skv_create, or the static scratch of skv_decode_step_noalloc)";
         case SKV_EHIP: return "HIP runtime error";
         case SKV_ENOMEM: return "out of device memory";
         default: return "unknown status";
@@ -71,46 +151,17 @@ int skv_create(skv_ctx** out, const skv_desc* desc, void* hip_stream) {
     skv_ctx* ctx = new (std::nothrow) skv_ctx();
     if (!ctx) return SKV_ENOMEM;
     Ctx& c = ctx->c;
-    c.d = *desc;
-    c.stream = static_cast<hipStream_t>(hip_stream);
-    c.device = dev;
-    c.n_cu = skv::kComputeUnits;
-    int n_cu = 0;
-    if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n_cu > 0) c.n_cu = n_cu;
-    c.G = desc->n_q_heads / desc->n_kv_heads;
-    c.max_sel = desc->max_sentences < desc->max_budget ? desc->max_sentences : desc->max_budget;
-    c.max_splits = (desc->max_budget + skv::kAttChunk - 1) / skv::kAttChunk;
+    fill_context(c, *desc, static_cast<hipStream_t>(hip_stream), dev);
 
-    const size_t BH = (size_t)desc->max_batch * desc->n_kv_heads, BQ = (size_t)desc->max_batch * desc->n_q_heads;
-    const size_t n_seg = (size_t)(desc->max_tokens + skv::kSegTokPerBlock - 1) / skv::kSegTokPerBlock;
-    const size_t sz[] = {
-        round256(n_seg * sizeof(unsigned long long)),                        // seg_part
-        round256(BQ * c.max_splits * skv::kHeadDim * sizeof(float)),         // att_part
-        round256(BQ * c.max_splits * 2 * sizeof(float)),                     // att_ml
-        round256(BH * sizeof(unsigned int)),                                 // att_counter
-        round256((size_t)desc->n_kv_heads * desc->max_sentences * sizeof(float)),  // f_score
-        round256(BH * c.max_sel * sizeof(int32_t)),                          // f_sel_sent
-        round256(BH * sizeof(int32_t)),                                      // f_n_sel
-        round256(BH * sizeof(int32_t)),                                      // f_n_tok
-        round256(BH * desc->max_budget * sizeof(int32_t)),                   // f_tok_idx
-    };
-    size_t total = 0;
-    for (size_t s : sz) total += s;
+    size_t sz[kWsParts];
+    const size_t total = workspace_layout(*desc, c.max_splits, c.max_sel, sz);
     hipError_t e = hipMalloc(reinterpret_cast<void**>(&c.ws), total);
     if (e != hipSuccess) { delete ctx; return hip_status(e); }
     e = hipMemset(c.ws, 0, total);
     if (e != hipSuccess) { (void)hipFree(c.ws); delete ctx; return hip_status(e); }
     c.ws_bytes = total;
-    char* p = c.ws;
-    c.seg_part = reinterpret_cast<unsigned long long*>(p); p += sz[0];
-    c.att_part = reinterpret_cast<float*>(p); p += sz[1];
-    c.att_ml = reinterpret_cast<float*>(p); p += sz[2];
-    c.att_counter = reinterpret_cast<unsigned int*>(p); p += sz[3];
-    c.f_score = reinterpret_cast<float*>(p); p += sz[4];
-    c.f_sel_sent = reinterpret_cast<int32_t*>(p); p += sz[5];
-    c.f_n_sel = reinterpret_cast<int32_t*>(p); p += sz[6];
-    c.f_n_tok = reinterpret_cast<int32_t*>(p); p += sz[7];
-    c.f_tok_idx = reinterpret_cast<int32_t*>(p); p += sz[8];
+    carve_workspace(c, c.ws, sz);
+    (void)static_scratch(dev, nullptr);     // set-up call with the device current: resolve the static scratch too (best effort)
     *out = ctx;
     return SKV_OK;
 }
@@ -295,12 +346,11 @@ int skv_attend(skv_ctx* ctx, const void* q_attn, const void* K_sel, const void* 
     return hip_status(skv::launch_attend(&ctx->c, q_attn, K_sel, V_sel, budget, n_tok, budget, v, out, lse));
 }
 
-int skv_decode_step(skv_ctx* ctx, int32_t layer, int32_t B, const void* q_score, const void* q_attn,
-                    const void* K_pool, const void* V_pool, int32_t T_total, const void* semvec, int32_t S_total,
-                    const int32_t* cu_tok, const int32_t* cu_sent, const int32_t* sent_off, const int32_t* sent_len,
-                    const int32_t* budget, float* out, float* lse, int32_t* tok_idx_out, int32_t* n_tok_out) {
-    if (!ctx) return SKV_EINVAL;
-    Ctx& c = ctx->c;
+// Host-side checks of skv_decode_step (nothing has touched the GPU yet).
+static int decode_step_check(const Ctx& c, int32_t layer, int32_t B, const void* q_score, const void* q_attn, const void* K_pool,
+                             const void* V_pool, int32_t T_total, const void* semvec, int32_t S_total, const int32_t* cu_tok,
+                             const int32_t* cu_sent, const int32_t* sent_off, const int32_t* sent_len, const int32_t* budget,
+                             float* out, float* lse, int32_t* tok_idx_out, int32_t* n_tok_out) {
     if (layer < 0 || layer >= c.d.n_layers || B < 1 || T_total < 0 || S_total < 0) return SKV_EINVAL;
     if (bad_ptr(q_score) || bad_ptr(q_attn) || bad_ptr(cu_tok) || bad_ptr(cu_sent) || bad_ptr(sent_off) ||
         bad_ptr(budget) || bad_ptr(out))
@@ -310,8 +360,14 @@ int skv_decode_step(skv_ctx* ctx, int32_t layer, int32_t B, const void* q_score,
     if ((lse && !aligned16(lse)) || (tok_idx_out && !aligned16(tok_idx_out)) || (n_tok_out && !aligned16(n_tok_out)))
         return SKV_EINVAL;
     if (B > c.d.max_batch || T_total > c.d.max_tokens || S_total > c.d.max_sentences) return SKV_ECAPACITY;
-    const int rc = check_ctx(ctx);
-    if (rc != SKV_OK) return rc;
+    return SKV_OK;
+}
+
+// Launch sequence of skv_decode_step on a checked argument set; `c` holds the workspace pointers to use.
+static int decode_step_launch(Ctx& c, int32_t layer, int32_t B, const void* q_score, const void* q_attn, const void* K_pool,
+                              const void* V_pool, int32_t T_total, const void* semvec, int32_t S_total, const int32_t* cu_tok,
+                              const int32_t* cu_sent, const int32_t* sent_off, const int32_t* sent_len, const int32_t* budget,
+                              float* out, float* lse, int32_t* tok_idx_out, int32_t* n_tok_out) {
 
     // A single sequence spans the whole pool (cu_tok = {0, T_total}, cu_sent = {0, S_total}): the kernels then take the
     // sizes from the arguments instead of loading them, one dependent memory round trip less per launch.
@@ -341,6 +397,58 @@ int skv_decode_step(skv_ctx* ctx, int32_t layer, int32_t B, const void* q_score,
     // latency path: every attention block derives the selection itself (no launch, no tok_idx round trip)
     e = skv::launch_select_attend(&c, q_attn, Kl, Vl, c.f_score, sent_off, sent_len, v, out, lse, tok_idx_out, n_tok_out);
     return hip_status(e);
+}
+
+int skv_decode_step(skv_ctx* ctx, int32_t layer, int32_t B, const void* q_score, const void* q_attn,
+                    const void* K_pool, const void* V_pool, int32_t T_total, const void* semvec, int32_t S_total,
+                    const int32_t* cu_tok, const int32_t* cu_sent, const int32_t* sent_off, const int32_t* sent_len,
+                    const int32_t* budget, float* out, float* lse, int32_t* tok_idx_out, int32_t* n_tok_out) {
+    if (!ctx) return SKV_EINVAL;
+    int rc = decode_step_check(ctx->c, layer, B, q_score, q_attn, K_pool, V_pool, T_total, semvec, S_total, cu_tok, cu_sent,
+                               sent_off, sent_len, budget, out, lse, tok_idx_out, n_tok_out);
+    if (rc != SKV_OK) return rc;
+    rc = check_ctx(ctx);
+    if (rc != SKV_OK) return rc;
+    return decode_step_launch(ctx->c, layer, B, q_score, q_attn, K_pool, V_pool, T_total, semvec, S_total, cu_tok, cu_sent,
+                              sent_off, sent_len, budget, out, lse, tok_idx_out, n_tok_out);
+}
+
+int skv_decode_step_noalloc(const skv_desc* desc, void* hip_stream, int32_t layer, int32_t B, const void* q_score,
+                            const void* q_attn, const void* K_pool, const void* V_pool, int32_t T_total, const void* semvec,
+                            int32_t S_total, const int32_t* cu_tok, const int32_t* cu_sent, const int32_t* sent_off,
+                            const int32_t* sent_len, const int32_t* budget, float* out, float* lse, int32_t* tok_idx_out,
+                            int32_t* n_tok_out) {
+    int rc = check_desc(desc);
+    if (rc != SKV_OK) return rc;
+    Ctx c{};
+    // sizes first: everything below is host arithmetic until the scratch address is needed
+    c.d = *desc;
+    c.G = desc->n_q_heads / desc->n_kv_heads;
+    c.max_sel = desc->max_sentences < desc->max_budget ? desc->max_sentences : desc->max_budget;
+    c.max_splits = (desc->max_budget + skv::kAttChunk - 1) / skv::kAttChunk;
+    rc = decode_step_check(c, layer, B, q_score, q_attn, K_pool, V_pool, T_total, semvec, S_total, cu_tok, cu_sent, sent_off,
+                           sent_len, budget, out, lse, tok_idx_out, n_tok_out);
+    if (rc != SKV_OK) return rc;
+    skv_desc d0 = *desc;
+    d0.max_tokens = 1;                                    // the prefill partials are not part of this call
+    size_t sz[kWsParts];
+    if (workspace_layout(d0, c.max_splits, c.max_sel, sz) > kStaticScratchBytes) return SKV_ECAPACITY;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return SKV_EHIP;
+    char* base = nullptr;
+    rc = static_scratch(dev, &base);
+    if (rc != SKV_OK) return rc;
+    fill_context(c, *desc, static_cast<hipStream_t>(hip_stream), dev);
+    carve_workspace(c, base, sz);
+    c.ws = base;
+    c.ws_bytes = kStaticScratchBytes;
+    // the arrival counters must start at zero; the array keeps whatever the last call on this GPU left there
+    const int32_t n_words = (int32_t)(sz[3] / sizeof(uint32_t));
+    hipLaunchKernelGGL(clear_words_kernel, dim3((n_words + 255) / 256), dim3(256), 0, c.stream,
+                       reinterpret_cast<uint32_t*>(c.att_counter), n_words);
+    if (hipGetLastError() != hipSuccess) return SKV_EHIP;
+    return decode_step_launch(c, layer, B, q_score, q_attn, K_pool, V_pool, T_total, semvec, S_total, cu_tok, cu_sent,
+                              sent_off, sent_len, budget, out, lse, tok_idx_out, n_tok_out);
 }
 
 int skv_merge_lse(skv_ctx* ctx, int32_t n_heads, const float* out_a, const float* lse_a, const float* out_b, const float* lse_b,
