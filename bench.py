@@ -574,6 +574,77 @@ def run_retention(args, wl):
     }
 
 
+STAMP_LABELS = {0: "kernel start", 12: "own share of the scores stored", 13: "all scores of the pair published",
+                1: "buckets in registers", 2: "cut known", 3: "selection compacted", 4: "pool rows of the block's positions",
+                5: "K/V loads issued", 6: "logits and value tile done", 7: "partial written", 8: "arrived at the pair's counter",
+                10: "partials loaded (merging block)", 11: "merged in LDS (merging block)", 9: "output written (merging block)"}
+
+
+def run_phase_stamps(args, wl, budget):
+    """Phase stamps of skv_decode_step's last kernel (profiling build, csrc/skv_stamps.h): one launch at a time, the
+    100 MHz clock of thread 0 of every block at the marked places, relative to the launch's first block start."""
+    import ctypes
+    from paper_2504_00970_amd import binding
+    lib = binding._lib()
+    lib.skv_stamps_read.argtypes, lib.skv_stamps_read.restype = [ctypes.c_void_p, ctypes.c_int], ctypes.c_int
+    dev = "cuda:0"
+    H, Hq, D = wl.n_kv_heads, wl.n_q_heads, wl.head_dim
+    B = max(wl.batch, 1)
+    R = min(wl.n_layers, args.resident_layers)
+    if wl.batch > 1:
+        inp = gen.ragged_inputs(wl, seed=args.seed, device=dev, resident_layers=R)
+    else:
+        w1 = wl.scaled(batch=1, t_range=(wl.n_tokens, wl.n_tokens), budgets=(budget,))
+        inp = gen.ragged_inputs(w1, seed=args.seed, device=dev, resident_layers=R)
+    T_total, S_total = int(inp.cu_tok[-1]), int(inp.cu_sent[-1])
+    budget = int(inp.budget.max())
+    sv_bytes, sv_torch, sv_code = SV_TABLE[args.semvec_dtype]
+    ctx = skv.Context(skv.Desc(n_layers=R, n_q_heads=Hq, n_kv_heads=H, kv_dtype=skv.dtype_code(wl.torch_dtype),
+                               max_tokens=T_total, max_sentences=S_total, max_budget=budget, max_batch=B, semvec_dtype=sv_code))
+    semvec = torch.empty(R, H, S_total, D, dtype=sv_torch, device=dev)
+    ctx.build_semvec(inp.K, i32(gen.offsets_of(inp.sent_len), dev), S_total, semvec)
+    d = [i32(x, dev) for x in (inp.cu_tok, inp.cu_sent, inp.sent_off, inp.sent_len, inp.budget)]
+    qsets = gen.queries(N_QUERY_SETS * R * B, Hq, D, wl.torch_dtype, args.seed + 1, dev).view(N_QUERY_SETS, R, B, Hq, D)
+    out = torch.empty(B, Hq, D, dtype=torch.float32, device=dev)
+    n_words = 4096 * 16
+    buf = np.zeros(n_words, dtype=np.uint64)
+
+    def read():
+        assert lib.skv_stamps_read(buf.ctypes.data, n_words) == 0
+        return buf.reshape(4096, 16).astype(np.int64)
+
+    def step(i):
+        r = i % R
+        q = qsets[i % N_QUERY_SETS, r]
+        ctx.decode_step(r, B, q, q, inp.K, inp.V, T_total, semvec, S_total, *d, out, None, None, None)
+
+    for i in range(args.warmup * R):
+        step(i)
+    read()
+    rel = {k: [] for k in STAMP_LABELS}
+    launches = max(args.steps, 1)
+    for i in range(launches):
+        for j in range(3):                 # the stamped launch follows two others back to back, as in a decode step
+            step(i * 3 + j)
+        st = read()                        # the table holds the last writer of every slot: with identical grids, the last launch
+        t0 = st[:, 0][st[:, 0] > 0].min()
+        for k in STAMP_LABELS:
+            col = st[:, k]
+            rel[k].append((col[col >= t0] - t0) / 100.0)
+    rows = []
+    for k, name in STAMP_LABELS.items():
+        x = np.concatenate(rel[k]) if rel[k] else np.zeros(0)
+        if len(x) == 0:
+            continue
+        rows.append({"slot": k, "phase": name, "blocks_per_launch": round(len(x) / launches, 1),
+                     "median_us": round(float(np.median(x)), 2), "p10_us": round(float(np.percentile(x, 10)), 2),
+                     "p90_us": round(float(np.percentile(x, 90)), 2), "max_us": round(float(x.max()), 2)})
+    rows.sort(key=lambda r: r["median_us"])
+    return {"phase_stamps": rows, "workload": wl.name, "batch": B, "budget": budget, "tokens_total": T_total,
+            "sentences_total": S_total, "launches": launches, "semvec_dtype": args.semvec_dtype,
+            "note": "us since the first block start of the launch; thread 0 of every block; kernel = the last launch of skv_decode_step"}
+
+
 def _ctx_name(T):
     return "%dk" % (T // 1024) if T % 1024 == 0 else str(T)
 
@@ -630,6 +701,9 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--cpu-layers", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--phase-stamps", action="store_true",
+                    help="decode workloads: load the profiling build (python -m paper_2504_00970_amd._build --stamps) and "
+                         "print where the blocks of the step's last kernel spend their time instead of the benchmark line")
     ap.add_argument("--host-pool-layers", type=int, default=-1,
                     help="layers of the K/V pool also kept in pinned host memory for the host-pool gather measurement "
                          "(default: 2 for cfg2, 0 otherwise)")
@@ -641,6 +715,12 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
+    if args.phase_stamps:
+        from paper_2504_00970_amd import _build
+        if not os.path.exists(_build.LIB_STAMPS):
+            print("no profiling build: run `python -m paper_2504_00970_amd._build --stamps` first", file=sys.stderr)
+            sys.exit(2)
+        _build.LIB = _build.LIB_STAMPS
     retain = args.workload == "cfg3-retain"
     wl = gen.CONFIGS["cfg3" if retain else args.workload]
     if args.batch > 0 and args.workload == "cfg4":
@@ -651,6 +731,10 @@ def main():
                        budgets=(args.budget or max(wl.budgets),))
     if args.host_pool_layers < 0:
         args.host_pool_layers = 2 if args.workload == "cfg2" else 0
+    if args.phase_stamps and not retain and args.workload != "cfg3":
+        res = run_phase_stamps(args, wl, args.budget or max(wl.budgets))
+        print(json.dumps(res), flush=True)
+        return
     if retain:
         res = run_retention(args, wl)
     elif args.workload == "cfg3":

@@ -72,6 +72,14 @@ int skv_set_stream(skv_ctx* ctx, void* hip_stream);
 const char* skv_strerror(int status);
 /* Bytes of device workspace the context holds (0 for a NULL context). */
 int64_t skv_workspace_bytes(const skv_ctx* ctx);
+/* skv_decode_step with few (sequence, head) pairs runs as ONE launch whose blocks wait, inside the kernel, for the bucket
+ * scores the other blocks of their pair compute (see skv_decode_step).  The wait is bounded: `polls` is the number of
+ * times a block looks at its pair's arrival counter before it gives up (about a microsecond each; default 200000;
+ * 0 makes every block that is not the last of its pair to arrive give up at once: the kernel still ends normally).
+ * A give-up turns the outputs of that call into NaN and makes every later skv_decode_step on the context return
+ * SKV_EHIP until this function is called again, which also clears the condition (it waits for the stream).
+ * Errors: SKV_EINVAL (NULL context, polls < 0). */
+int skv_set_wait_limit(skv_ctx* ctx, int32_t polls);
 
 /* ---------------------------------------------------------------------------------------------
  * (1) Prefill.  Sec. 4.1 first paragraph and Alg. 1 prefilling phase: the prompt is split into

@@ -9,8 +9,12 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libsentencekv.so")
+# profiling build (-DSKV_PHASE_STAMPS): the decode kernels record the wall clock at marked places, see csrc/skv_stamps.h;
+# built by `python -m paper_2504_00970_amd._build --stamps`, loaded by `bench.py --phase-stamps`
+LIB_STAMPS = os.path.join(HERE, "libsentencekv_stamps.so")
 SOURCES = ["api.hip", "prefill.hip", "decode.hip", "retain.hip"]
-HEADERS = [os.path.join(CSRC, "skv_internal.h"), os.path.join(CSRC, "skv_device.h"), os.path.join(INCLUDE, "sentencekv.h")]
+HEADERS = [os.path.join(CSRC, "skv_internal.h"), os.path.join(CSRC, "skv_device.h"), os.path.join(CSRC, "skv_stamps.h"),
+           os.path.join(INCLUDE, "sentencekv.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -28,15 +32,16 @@ def stale() -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build(force: bool = True, verbose: bool = False) -> str:
+def build(force: bool = True, verbose: bool = False, stamps: bool = False) -> str:
     """Compile the library: one hipcc process per source file, side by side, then one link.  With force=False an
-    up-to-date library is kept."""
-    if not force and not stale():
+    up-to-date library is kept.  stamps=True builds the profiling variant (LIB_STAMPS) instead."""
+    if not force and not stamps and not stale():
         return LIB
     hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
-    objdir = os.path.join(HERE, "_build")
+    objdir = os.path.join(HERE, "_build", "stamps" if stamps else "lib")
     os.makedirs(objdir, exist_ok=True)
-    compile_flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    compile_flags = [f for f in HIPCC_FLAGS if f != "-shared"] + (["-DSKV_PHASE_STAMPS"] if stamps else [])
+    lib = LIB_STAMPS if stamps else LIB
     jobs = []
     for src in SOURCES:
         obj = os.path.join(objdir, src + ".o")
@@ -51,15 +56,16 @@ def build(force: bool = True, verbose: bool = False) -> str:
             failed.append(f"{src}:\n{out}")
     if failed:
         raise RuntimeError("hipcc failed:\n" + "\n".join(failed))
-    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *[obj for _, obj, _ in jobs], "-o", LIB + ".tmp"]
+    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *[obj for _, obj, _ in jobs], "-o", lib + ".tmp"]
     if verbose:
         print(" ".join(link), flush=True)
     proc = subprocess.run(link, capture_output=True, text=True)
     if proc.returncode != 0:
         raise RuntimeError("link failed:\n" + proc.stdout + proc.stderr)
-    os.replace(LIB + ".tmp", LIB)
-    return LIB
+    os.replace(lib + ".tmp", lib)
+    return lib
 
 
 if __name__ == "__main__":
-    print(build(force=True, verbose=True))
+    import sys
+    print(build(force=True, verbose=True, stamps="--stamps" in sys.argv[1:]))

@@ -39,6 +39,7 @@ _SIGNATURES = {
     "skv_set_stream": (_int, [_vp, _vp]),
     "skv_strerror": (ctypes.c_char_p, [_int]),
     "skv_workspace_bytes": (_i64, [_vp]),
+    "skv_set_wait_limit": (_int, [_vp, _i32]),
     "skv_segment": (_int, [_vp, _vp, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _vp]),
     "skv_build_semvec": (_int, [_vp, _vp, _i32, _vp, _i32, _vp]),
     "skv_build_semvec_layers": (_int, [_vp, _vp, _i32, _vp, _i32, _vp]),
@@ -146,6 +147,9 @@ class Context:
 
     def workspace_bytes(self) -> int:
         return int(_lib().skv_workspace_bytes(self._h))
+
+    def set_wait_limit(self, polls: int) -> None:
+        _check(_lib().skv_set_wait_limit(self._h, polls), "skv_set_wait_limit")
 
     # ---- (1) prefill ----------------------------------------------------------------------------
     def segment(self, tok, term_bitmap, vocab: int, seg_id, sent_off, sent_len, n_sent_dev, sync: bool = True,

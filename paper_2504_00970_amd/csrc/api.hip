@@ -49,7 +49,7 @@ inline int sv_bytes(const Ctx& c) { return c.d.semvec_dtype == SKV_BF16 ? 2 : c.
 
 // ---- workspace: one block of device memory, carved the same way whether skv_create allocated it or it is the static
 // scratch array of skv_decode_step_noalloc ---------------------------------------------------------------------------
-constexpr int kWsParts = 9;
+constexpr int kWsParts = 11;
 size_t workspace_layout(const skv_desc& d, int max_splits, int max_sel, size_t sz[kWsParts]) {
     const size_t BH = (size_t)d.max_batch * d.n_kv_heads, BQ = (size_t)d.max_batch * d.n_q_heads;
     const size_t n_seg = (size_t)(d.max_tokens + skv::kSegTokPerBlock - 1) / skv::kSegTokPerBlock;
@@ -62,6 +62,8 @@ size_t workspace_layout(const skv_desc& d, int max_splits, int max_sel, size_t s
     sz[6] = round256(BH * sizeof(int32_t));                                        // f_n_sel
     sz[7] = round256(BH * sizeof(int32_t));                                        // f_n_tok
     sz[8] = round256(BH * d.max_budget * sizeof(int32_t));                         // f_tok_idx
+    sz[9] = round256(BH * skv::kStepCounterSlots * sizeof(unsigned int));          // step_counter
+    sz[10] = 256;                                                                  // err_dev
     size_t total = 0;
     for (int i = 0; i < kWsParts; ++i) total += sz[i];
     return total;
@@ -78,6 +80,8 @@ void carve_workspace(Ctx& c, char* base, const size_t sz[kWsParts]) {
     c.f_n_sel = reinterpret_cast<int32_t*>(p); p += sz[6];
     c.f_n_tok = reinterpret_cast<int32_t*>(p); p += sz[7];
     c.f_tok_idx = reinterpret_cast<int32_t*>(p); p += sz[8];
+    c.step_counter = reinterpret_cast<unsigned int*>(p); p += sz[9];
+    c.err_dev = reinterpret_cast<unsigned int*>(p); p += sz[10];
 }
 
 void fill_context(Ctx& c, const skv_desc& d, hipStream_t stream, int dev) {
@@ -90,6 +94,7 @@ void fill_context(Ctx& c, const skv_desc& d, hipStream_t stream, int dev) {
     c.G = d.n_q_heads / d.n_kv_heads;
     c.max_sel = d.max_sentences < d.max_budget ? d.max_sentences : d.max_budget;
     c.max_splits = (d.max_budget + skv::kAttChunk - 1) / skv::kAttChunk;
+    c.wait_limit = skv::kStepWaitLimit;
 }
 
 // ---- static scratch of skv_decode_step_noalloc -----------------------------------------------------------------------
@@ -120,7 +125,7 @@ int static_scratch(int dev, char** out) {
 }
 
 // Clears `n` 32-bit words (a kernel rather than a memset node: the call may be recorded into a HIP graph).
-__global__ void clear_words_kernel(uint32_t* __restrict__ p, int32_t n) {
+__global__ void clear_words_kernel(unsigned int* __restrict__ p, int32_t n) {
     const int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = 0u;
 }
@@ -161,6 +166,23 @@ int skv_create(skv_ctx** out, const skv_desc* desc, void* hip_stream) {
     if (e != hipSuccess) { (void)hipFree(c.ws); delete ctx; return hip_status(e); }
     c.ws_bytes = total;
     carve_workspace(c, c.ws, sz);
+    // a word of pinned host memory the kernels can reach: a block of the single-launch step that gives up waiting sets
+    // it, and the next skv_decode_step on this context reports it
+    void* eh = nullptr;
+    e = hipHostMalloc(&eh, sizeof(unsigned int), hipHostMallocMapped);
+    if (e == hipSuccess) {
+        void* ed = nullptr;
+        *static_cast<unsigned int*>(eh) = 0u;
+        if (hipHostGetDevicePointer(&ed, eh, 0) == hipSuccess) {
+            c.err_host = static_cast<unsigned int*>(eh);
+            c.err_host_dev = static_cast<unsigned int*>(ed);
+        } else {
+            (void)hipGetLastError();
+            (void)hipHostFree(eh);
+        }
+    } else {
+        (void)hipGetLastError();           // without the word errors are still visible as NaN outputs
+    }
     (void)static_scratch(dev, nullptr);     // set-up call with the device current: resolve the static scratch too (best effort)
     *out = ctx;
     return SKV_OK;
@@ -172,6 +194,7 @@ void skv_destroy(skv_ctx* ctx) {
         (void)hipStreamSynchronize(ctx->c.stream);
         (void)hipFree(ctx->c.ws);
     }
+    if (ctx->c.err_host) (void)hipHostFree(ctx->c.err_host);
     delete ctx;
 }
 
@@ -182,6 +205,19 @@ int skv_set_stream(skv_ctx* ctx, void* hip_stream) {
 }
 
 int64_t skv_workspace_bytes(const skv_ctx* ctx) { return ctx ? (int64_t)ctx->c.ws_bytes : 0; }
+
+int skv_set_wait_limit(skv_ctx* ctx, int32_t polls) {
+    if (!ctx || polls < 0) return SKV_EINVAL;
+    const int rc = check_ctx(ctx);
+    if (rc != SKV_OK) return rc;
+    Ctx& c = ctx->c;
+    c.wait_limit = polls;
+    // a reported give-up is cleared: the device word in stream order, the host word once the stream has drained
+    hipLaunchKernelGGL(clear_words_kernel, dim3(1), dim3(64), 0, c.stream, c.err_dev, 1);
+    if (hipGetLastError() != hipSuccess || hipStreamSynchronize(c.stream) != hipSuccess) return SKV_EHIP;
+    if (c.err_host) *c.err_host = 0u;
+    return SKV_OK;
+}
 
 int skv_segment(skv_ctx* ctx, const int32_t* tok, int32_t T, const uint32_t* term_bitmap, int32_t vocab,
                 int32_t* seg_id, int32_t* sent_off, int32_t* sent_len, int32_t* n_sent_dev, int32_t* n_sent_host) {
@@ -376,11 +412,19 @@ static int decode_step_launch(Ctx& c, int32_t layer, int32_t B, const void* q_sc
     const char* sv = (const char*)semvec + (int64_t)layer * layer_elems(c, S_total) * sv_bytes(c);
     const int64_t pool_off = (int64_t)layer * layer_elems(c, T_total) * elt_bytes(c);
 
-    hipError_t e = skv::launch_score(&c, q_score, sv, v, c.f_score);
-    if (e != hipSuccess) return hip_status(e);
     const char* Kl = (const char*)K_pool + pool_off;
     const char* Vl = (const char*)V_pool + pool_off;
     const int pairs = B * c.d.n_kv_heads;
+    hipError_t e;
+    // Few (sequence, head) pairs: the whole step in one launch, when the 128-token attention blocks of the call fit the
+    // chip at once (the shapes the two-launch latency path below would take in 64- or 128-token blocks).
+    if (pairs * ((c.d.max_budget + skv::kAttChunkMid - 1) / skv::kAttChunkMid) <= c.n_cu && S_total > 0) {
+        bool launched = false;
+        e = skv::launch_step(&c, q_score, q_attn, sv, Kl, Vl, sent_off, sent_len, v, out, lse, tok_idx_out, n_tok_out, &launched);
+        if (launched || e != hipSuccess) return hip_status(e);
+    }
+    e = skv::launch_score(&c, q_score, sv, v, c.f_score);
+    if (e != hipSuccess) return hip_status(e);
     const bool can_stream = c.d.kv_dtype == SKV_BF16 && T_total < (1 << 24);
     const int wide_blocks = pairs * ((c.d.max_budget + skv::kAttChunkWide - 1) / skv::kAttChunkWide);
     if (can_stream ? wide_blocks > c.n_cu : pairs >= skv::kWideChunkMinHeads) {
@@ -409,6 +453,7 @@ int skv_decode_step(skv_ctx* ctx, int32_t layer, int32_t B, const void* q_score,
     if (rc != SKV_OK) return rc;
     rc = check_ctx(ctx);
     if (rc != SKV_OK) return rc;
+    if (ctx->c.err_host && *static_cast<volatile unsigned int*>(ctx->c.err_host) != 0u) return SKV_EHIP;   // an earlier step gave up waiting
     return decode_step_launch(ctx->c, layer, B, q_score, q_attn, K_pool, V_pool, T_total, semvec, S_total, cu_tok, cu_sent,
                               sent_off, sent_len, budget, out, lse, tok_idx_out, n_tok_out);
 }
@@ -445,7 +490,13 @@ int skv_decode_step_noalloc(const skv_desc* desc, void* hip_stream, int32_t laye
     // the arrival counters must start at zero; the array keeps whatever the last call on this GPU left there
     const int32_t n_words = (int32_t)(sz[3] / sizeof(uint32_t));
     hipLaunchKernelGGL(clear_words_kernel, dim3((n_words + 255) / 256), dim3(256), 0, c.stream,
-                       reinterpret_cast<uint32_t*>(c.att_counter), n_words);
+                       c.att_counter, n_words);
+    if (hipGetLastError() != hipSuccess) return SKV_EHIP;
+    // the same for the ticket counters of the single-launch step (all zero is a valid state) and its error word,
+    // which are adjacent at the end of the layout
+    const int32_t n_tail = (int32_t)((sz[9] + sz[10]) / sizeof(uint32_t));
+    hipLaunchKernelGGL(clear_words_kernel, dim3((n_tail + 255) / 256), dim3(256), 0, c.stream,
+                       c.step_counter, n_tail);
     if (hipGetLastError() != hipSuccess) return SKV_EHIP;
     return decode_step_launch(c, layer, B, q_score, q_attn, K_pool, V_pool, T_total, semvec, S_total, cu_tok, cu_sent,
                               sent_off, sent_len, budget, out, lse, tok_idx_out, n_tok_out);

@@ -2,10 +2,24 @@
 // retrieval, K/V row gather, split-K attention with an online-softmax combine.  gfx950, wave64.
 #include "skv_internal.h"
 #include "skv_device.h"
+#include "skv_stamps.h"
 
-// Phase markers: no-ops unless a profiling build pre-defines SKV_T(k) to record a timestamp.
-#ifndef SKV_T
-#define SKV_T(k)
+#include <type_traits>
+
+#ifdef SKV_PHASE_STAMPS
+namespace skv {
+__device__ unsigned long long g_stamps[kStampBlocks * kStampSlots];
+}
+// Copies the stamp table (kStampBlocks x kStampSlots 64-bit ticks of the 100 MHz clock, zero where nothing was
+// recorded) to `host` and clears it on the device.  Profiling build only.
+extern "C" int skv_stamps_read(unsigned long long* host, int n_words) {
+    if (!host || n_words != skv::kStampBlocks * skv::kStampSlots) return -1;
+    if (hipDeviceSynchronize() != hipSuccess) return -3;
+    if (hipMemcpyFromSymbol(host, HIP_SYMBOL(skv::g_stamps), sizeof(unsigned long long) * n_words) != hipSuccess) return -3;
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(skv::g_stamps)) != hipSuccess) return -3;
+    return hipMemset(p, 0, sizeof(unsigned long long) * n_words) == hipSuccess ? 0 : -3;
+}
 #endif
 
 namespace skv {
@@ -836,9 +850,19 @@ struct AttArgs {
     unsigned int* counter;
     float* out;
     float* lse;
+    // kStep: the blocks of a (sequence, head) pair first score the pair's buckets between them
+    const char* q_score;      // [B][Hq][D]
+    const char* semvec;       // the layer's table [Hkv][S_total][D]
+    float* score_out;         // [Hkv][S_total]; `score` points at the same memory
+    int32_t sv_bytes;         // bytes per element of the table: 4, 2 or 1
+    int32_t lg_parts;         // log2 of the blocks per pair
+    unsigned int* step_counter;   // [pairs][kStepCounterSlots] ticket counters, one per power of two of blocks per pair
+    int32_t wait_limit;       // polls of the ticket counter before a block gives up
+    unsigned int* err_dev;    // set to 1 by a block that gave up; read by the merging blocks
+    unsigned int* err_host;   // the same word in pinned host memory (device address), nullable
 };
 
-enum { kDirect = 0, kFused = 1, kIndirect = 2 };
+enum { kDirect = 0, kFused = 1, kIndirect = 2, kStep = 3 };
 
 // Every argument is demanded at this point, so the kernel-argument loads go out in one batch at the top of the kernel;
 // left alone, the compiler loads each argument before its first use: one dependent round trip per branch, and a
@@ -848,6 +872,10 @@ __device__ __forceinline__ void demand_args(const AttArgs& a) {
                  "s"(a.sent_off), "s"(a.sent_len), "s"(a.tok_idx_out), "s"(a.n_tok_out), "s"(a.idx_stride), "s"(a.v.cu_tok),
                  "s"(a.v.cu_sent), "s"(a.v.budget_arr), "s"(a.v.T_total), "s"(a.v.S_total), "s"(a.v.budget), "s"(a.v.B),
                  "s"(a.Hkv), "s"(a.max_splits), "s"(a.part), "s"(a.ml), "s"(a.counter), "s"(a.out), "s"(a.lse));
+}
+__device__ __forceinline__ void demand_step_args(const AttArgs& a) {
+    asm volatile("" ::"s"(a.q_score), "s"(a.semvec), "s"(a.score_out), "s"(a.sv_bytes), "s"(a.lg_parts), "s"(a.step_counter),
+                 "s"(a.wait_limit), "s"(a.err_dev), "s"(a.err_host));
 }
 
 // CHUNK = retrieved tokens per block: 64 for the latency-bound single-sequence step (most blocks in
@@ -882,12 +910,19 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
     __shared__ int sm_last;
     __shared__ int32_t sm_row[CHUNK];
 
-    const int bh = blockIdx.y, b = bh / a.Hkv, h = bh % a.Hkv, split = blockIdx.x;
+    // kStep: a one-dimensional grid, pair fastest, so that the hardware's round-robin of consecutive blocks over the XCDs
+    // keeps the blocks of a pair together whenever the number of pairs is a multiple of the number of XCDs
+    constexpr bool kSel = MODE == kFused || MODE == kStep;        // the block runs the selection itself
+    const int n_pairs = a.v.B * a.Hkv;
+    const int bh = MODE == kStep ? (int)(blockIdx.x % (unsigned)n_pairs) : (int)blockIdx.y;
+    const int split = MODE == kStep ? (int)(blockIdx.x / (unsigned)n_pairs) : (int)blockIdx.x;
+    const int b = bh / a.Hkv, h = bh % a.Hkv;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int r = lane % R::RPW, cc = lane / R::RPW;
     const int Hq = a.Hkv * G;
     const int64_t qhead0 = (int64_t)b * Hq + (int64_t)h * G;      // first query head of the group
     demand_args(a);
+    if constexpr (MODE == kStep) demand_step_args(a);
     const Seq sq = seq_of(a.v, b);
     const int32_t j0 = split * CHUNK;
     const int slot = split * (CHUNK / kWave);                     // partial slot (slots are counted in 64-token units)
@@ -906,10 +941,74 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
     }
 
     int32_t n;                                                    // retrieved tokens of this (sequence, head)
-    if (MODE == kFused) {
+    if constexpr (kSel) {
         __shared__ SelectShared sel_sh;
         const int32_t budget = min(sq.budget, a.idx_stride);
-        if (split > 0 && j0 >= budget) return;                    // n <= budget: nothing for this split
+        if constexpr (MODE == kStep) {
+            // ---- 0. scores of this block's share of the pair's buckets, published to the pair's other blocks ---------
+            // Part `split` of the 2^lg_parts blocks of the pair owns the buckets [split * per, (split + 1) * per); wave
+            // w takes RPWV consecutive buckets at a time.  The arithmetic per bucket is that of score_kernel (same
+            // lanes, same order), so skv_score returns the very floats that are ranked here.
+            const int32_t S = sq.n_sent;
+            const int32_t per = (S + (1 << a.lg_parts) - 1) >> a.lg_parts;
+            const int32_t lo = split * per, hi = min(lo + per, S);
+            const char* qg = a.q_score + ((qhead0 * kHeadDim) * EB);
+            const int64_t row0 = (int64_t)h * a.v.S_total + sq.sent_base;
+            float* sc_out = a.score_out + row0;
+            auto score_rows = [&](auto rpwv_tag) {
+                constexpr int RPWV = decltype(rpwv_tag)::value;
+                for (int32_t rw = lo + w * RPWV; rw < hi; rw += kBlockWaves * RPWV) {
+                    if (a.sv_bytes == kTableF32)
+                        score_wave_f32<EB, G, RPWV, true>(qg, reinterpret_cast<const float*>(a.semvec) + row0 * kHeadDim, hi, rw, sc_out);
+                    else if (a.sv_bytes == kTableBf16)
+                        score_wave_bf16<EB, G, (RPWV < 4 ? 4 : RPWV), true>(qg, a.semvec + row0 * kHeadDim * 2, hi, rw, sc_out);
+                    else
+                        score_wave_e4m3<EB, G, (RPWV < 8 ? 8 : RPWV), true>(qg, a.semvec + row0 * kHeadDim, hi, rw, sc_out);
+                }
+            };
+            // few buckets per block: 4 per wave visit (two loads in flight per lane, all 16 waves busy from 64 buckets on);
+            // many: 16 per visit (eight loads in flight per lane)
+            if (per <= kBlockWaves * 4) score_rows(std::integral_constant<int, 4>{});
+            else score_rows(std::integral_constant<int, 16>{});
+            SKV_T(12);
+            // Every wave waits for its own write-through score stores, then the barrier; only then does thread 0 take
+            // its ticket.  The counter of (pair, lg_parts) only ever counts arrivals of launches with 2^lg_parts blocks
+            // per pair, so between launches it is a multiple of that number: the ticket's round ends at the next
+            // multiple, whatever the counter's absolute value (it wraps at 2^32, a multiple too).  Nothing is reset.
+            block_sync_after_stores();
+            if (split > 0 && j0 >= budget) {                      // no position of this block can hold a token (n <= budget)
+                if (tid == 0)
+                    __hip_atomic_fetch_add(&a.step_counter[bh * kStepCounterSlots + a.lg_parts], 1u, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
+                return;
+            }
+            if (tid == 0) {
+                unsigned int* ctr = &a.step_counter[bh * kStepCounterSlots + a.lg_parts];
+                const unsigned int parts = 1u << a.lg_parts;
+                const unsigned int old = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const unsigned int target = (old & ~(parts - 1u)) + parts;
+                // The wait ends: every block of the grid is resident (the host launches this kernel only when the grid
+                // fits the chip, one block per compute unit) and arrives without waiting for anyone.  It is bounded all
+                // the same: on expiry the error word is set, the block carries on with whatever scores it can see, and
+                // the pair's output is NaN.
+                int32_t polls = 0;
+                bool ok = true;
+                if (old + 1u != target) {
+                    while ((int32_t)(ld_agent(ctr) - target) < 0) {
+                        if (++polls > a.wait_limit) { ok = false; break; }
+                        __builtin_amdgcn_s_sleep(1);
+                    }
+                }
+                if (!ok) {
+                    st_agent(a.err_dev, 1u);
+                    if (a.err_host) st_agent(a.err_host, 1u);
+                }
+            }
+            __syncthreads();
+            SKV_T(13);
+        } else {
+            if (split > 0 && j0 >= budget) return;                // n <= budget: nothing for this split
+        }
         if (tid < CHUNK) sm_row[tid] = -1;
         int32_t nsel, ntok;
         // Each selected bucket that reaches into this block's positions marks, in every 64-position piece it touches,
@@ -924,8 +1023,9 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
         const float* sc = a.score + (int64_t)h * a.v.S_total + sq.sent_base;
         const int32_t* len = a.sent_len + sq.sent_base;
         const int32_t* off = a.sent_off + sq.sent_base + (a.v.cu_sent ? b : 0);
-        if (sq.n_sent <= 2 * kBlockThreads) select_block<2, false, false>(sc, len, off, sq.n_sent, budget, sel_sh, mark, &nsel, &ntok);
-        else select_block<kSelKreg, false, false>(sc, len, off, sq.n_sent, budget, sel_sh, mark, &nsel, &ntok);
+        constexpr bool kAgent = MODE == kStep;                    // the scores were written by other blocks of this launch
+        if (sq.n_sent <= 2 * kBlockThreads) select_block<2, false, kAgent>(sc, len, off, sq.n_sent, budget, sel_sh, mark, &nsel, &ntok);
+        else select_block<kSelKreg, false, kAgent>(sc, len, off, sq.n_sent, budget, sel_sh, mark, &nsel, &ntok);
         n = ntok;
         if (split == 0 && tid == 0 && a.n_tok_out) a.n_tok_out[bh] = n;
         __syncthreads();                                          // bucket starts are marked
@@ -991,7 +1091,7 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
             if (MODE == kDirect) {
                 rowK = jc;
             } else {
-                const int32_t x = MODE == kFused ? sm_row[jc] : a.tok_idx[(int64_t)bh * a.idx_stride + j0 + jc];
+                const int32_t x = kSel ? sm_row[jc] : a.tok_idx[(int64_t)bh * a.idx_stride + j0 + jc];
                 liveK = liveK && x >= 0 && x < sq.n_tok_ctx;
                 rowK = min(max(x, 0), max(sq.n_tok_ctx - 1, 0));
             }
@@ -1093,7 +1193,7 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
             if (MODE == kDirect) {
                 rowi[i] = jc;
             } else {
-                const int32_t x = MODE == kFused ? sm_row[jc] : a.tok_idx[(int64_t)bh * a.idx_stride + j0 + jc];
+                const int32_t x = kSel ? sm_row[jc] : a.tok_idx[(int64_t)bh * a.idx_stride + j0 + jc];
                 live[i] = live[i] && x >= 0 && x < sq.n_tok_ctx;
                 rowi[i] = min(max(x, 0), max(sq.n_tok_ctx - 1, 0));
             }
@@ -1269,7 +1369,10 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
             }
         }
         const bool empty = !(L > 0.f);                       // every retrieved position was out of range
-        const float inv = empty ? 0.f : 1.f / L;
+        float inv = empty ? 0.f : 1.f / L;
+        if constexpr (MODE == kStep) {
+            if (ld_agent(a.err_dev) != 0u) inv = __builtin_nanf("");      // a block of this launch gave up waiting for scores
+        }
         reinterpret_cast<float2*>(a.out + qhead0 * kHeadDim)[tid] = make_float2(o0 * inv, o1 * inv);
         if (a.lse && (tid % (kHeadDim / 2)) == 0)
             a.lse[qhead0 + tid / (kHeadDim / 2)] = empty ? -INFINITY : (M + log2f(L)) * kLn2;
@@ -1488,7 +1591,6 @@ __device__ __forceinline__ void stream_attend(const AttArgs& a, StreamShared& ss
                 if (4 * qd + j < G) red[(4 * qd + j) * kHeadDim + 16 * dt + t16] = o[dt][j] * cr[j];
     }
     __syncthreads();
-#ifndef SKV_NO_DIRECT
     if (nsplit == 1) {
         // the only block of this (sequence, head): its combined sums are the result, no partials, no arrival, no merge
         for (int i = tid; i < kOut; i += kThreads) {
@@ -1510,7 +1612,6 @@ __device__ __forceinline__ void stream_attend(const AttArgs& a, StreamShared& ss
         }
         return;
     }
-#endif
     if (tid < G) {
         float lb = 0.f, mh = -INFINITY;
 #pragma unroll
@@ -1744,6 +1845,45 @@ hipError_t launch_select_attend(Ctx* c, const void* q, const void* K_layer, cons
     }
     return c->d.kv_dtype == SKV_BF16 ? launch_attend_g<2, kFused, kAttChunk>(c, a, c->max_splits)
                                      : launch_attend_g<4, kFused, kAttChunk>(c, a, c->max_splits);
+}
+
+// Single-launch step.  Blocks per pair: the largest power of two that keeps pairs x blocks within the compute units (every
+// block must be resident for the per-pair wait to end: one 1024-thread block per compute unit).  All of them score; the
+// first ceil(max_budget / CHUNK) of them attend.
+template <int EB, int CHUNK>
+static hipError_t launch_step_g(Ctx* c, const AttArgs& a, int n_blocks) {
+    const dim3 grid(n_blocks), block(kBlockThreads);
+    switch (c->G) {
+        case 1: hipLaunchKernelGGL((attend_kernel<EB, 1, kStep, CHUNK>), grid, block, 0, c->stream, a); break;
+        case 2: hipLaunchKernelGGL((attend_kernel<EB, 2, kStep, CHUNK>), grid, block, 0, c->stream, a); break;
+        case 4: hipLaunchKernelGGL((attend_kernel<EB, 4, kStep, CHUNK>), grid, block, 0, c->stream, a); break;
+        case 8: hipLaunchKernelGGL((attend_kernel<EB, 8, kStep, CHUNK>), grid, block, 0, c->stream, a); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_step(Ctx* c, const void* q_score, const void* q_attn, const void* semvec_layer, const void* K_layer,
+                       const void* V_layer, const int32_t* sent_off, const int32_t* sent_len, const SeqView& v, float* out,
+                       float* lse, int32_t* tok_idx_out, int32_t* n_tok_out, bool* launched) {
+    *launched = false;
+    const int pairs = v.B * c->d.n_kv_heads;
+    if (pairs < 1 || pairs > c->n_cu || !c->step_counter) return hipSuccess;
+    int lg = 0;
+    while ((pairs << (lg + 1)) <= c->n_cu && lg + 1 < kStepCounterSlots) ++lg;
+    const int parts = 1 << lg;
+    const int chunk = kAttChunkMid;
+    if ((c->d.max_budget + chunk - 1) / chunk > parts) return hipSuccess;       // the attention blocks of a pair do not fit
+    AttArgs a = att_common(c, q_attn, K_layer, V_layer, v, out, lse);
+    a.score = c->f_score; a.score_out = c->f_score; a.sent_off = sent_off; a.sent_len = sent_len;
+    a.tok_idx_out = tok_idx_out; a.n_tok_out = n_tok_out; a.idx_stride = c->d.max_budget;
+    a.q_score = (const char*)q_score; a.semvec = (const char*)semvec_layer;
+    a.sv_bytes = c->d.semvec_dtype == SKV_BF16 ? kTableBf16 : c->d.semvec_dtype == SKV_FP8_E4M3 ? kTableE4m3 : kTableF32;
+    a.lg_parts = lg; a.step_counter = c->step_counter; a.wait_limit = c->wait_limit;
+    a.err_dev = c->err_dev; a.err_host = c->err_host_dev;
+    *launched = true;
+    return c->d.kv_dtype == SKV_BF16 ? launch_step_g<2, kAttChunkMid>(c, a, pairs * parts)
+                                     : launch_step_g<4, kAttChunkMid>(c, a, pairs * parts);
 }
 
 // ------------------------------------------------------------------------------------------------

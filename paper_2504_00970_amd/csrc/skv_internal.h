@@ -32,6 +32,8 @@ constexpr int kMidChunkMinSentences = 1024;
 constexpr int kAttChunkWide = 256;    // tokens per split-K block when many (sequence, head) pairs fill the GPU
 constexpr int kWideChunkMinHeads = 64;   // (sequences x KV heads) from which the fp32 batch path is used
 constexpr int kComputeUnits = 256;       // MI355X; the context takes the device's own count when it can be read
+constexpr int kStepCounterSlots = 16;    // ticket counters per (sequence, head) pair of the single-launch step: one per log2(blocks per pair)
+constexpr int kStepWaitLimit = 200000;   // default bound on the polls of a block waiting for its pair's scores (a poll is about a microsecond)
 // bf16 decode step: the fused kernel's block size (64, 128, 256 tokens) is the smallest whose blocks, (sequence, KV head)
 // pairs x ceil(max_budget / size), all fit the chip at once (one block per compute unit); if even the 256-token blocks do
 // not, the streaming kernel's 512- or 1024-token blocks
@@ -55,6 +57,11 @@ struct Ctx {
     int32_t* f_n_sel;       // [max_batch * Hkv]
     int32_t* f_n_tok;       // [max_batch * Hkv]
     int32_t* f_tok_idx;     // [max_batch * Hkv][max_budget]
+    unsigned int* step_counter;  // [max_batch * Hkv][kStepCounterSlots] ticket counters of the single-launch step; never reset
+    unsigned int* err_dev;       // [1] set by a block of the single-launch step that gave up waiting
+    unsigned int* err_host;      // the same flag in pinned host memory (host address; null: none)
+    unsigned int* err_host_dev;  // device address of err_host
+    int wait_limit;              // polls before a waiting block gives up
 };
 
 // Ragged-batch view handed to the decode kernels.  For single-sequence calls cu_tok / cu_sent /
@@ -101,6 +108,12 @@ hipError_t launch_attend_indirect(Ctx* c, const void* q, const void* K_layer, co
 hipError_t launch_select_attend(Ctx* c, const void* q, const void* K_layer, const void* V_layer, const float* score,
                                 const int32_t* sent_off, const int32_t* sent_len, const SeqView& v, float* out,
                                 float* lse, int32_t* tok_idx_out, int32_t* n_tok_out);
+
+// The whole step in one launch (scores by the blocks of each pair, a per-pair ticket barrier, selection, attention) when
+// its grid fits the chip at once; *launched is false (and nothing was launched) when the shapes do not allow it.
+hipError_t launch_step(Ctx* c, const void* q_score, const void* q_attn, const void* semvec_layer, const void* K_layer,
+                       const void* V_layer, const int32_t* sent_off, const int32_t* sent_len, const SeqView& v, float* out,
+                       float* lse, int32_t* tok_idx_out, int32_t* n_tok_out, bool* launched);
 
 // The same for batches with bf16 pools of fewer than 2^24 tokens: 1024-token blocks, streaming attention.
 hipError_t launch_select_attend_stream(Ctx* c, const void* q, const void* K_layer, const void* V_layer, const float* score,
