@@ -244,7 +244,7 @@ int skv_decode_step(skv_ctx* ctx, int32_t layer, int32_t B, const void* q_score,
  * than SKV_NOALLOC_SCRATCH_BYTES.
  * All calls on one GPU share the one array, on whatever stream: calls that overlap in time on the same GPU race
  * (order them on one stream or by events).  skv_decode_step with a context is unaffected. */
-#define SKV_NOALLOC_SCRATCH_BYTES (4 * 1024 * 1024)
+#define SKV_NOALLOC_SCRATCH_BYTES (8 * 1024 * 1024)
 int skv_decode_step_noalloc(const skv_desc* desc, void* hip_stream, int32_t layer, int32_t B, const void* q_score,
                             const void* q_attn, const void* K_pool, const void* V_pool, int32_t T_total, const void* semvec,
                             int32_t S_total, const int32_t* cu_tok, const int32_t* cu_sent, const int32_t* sent_off,

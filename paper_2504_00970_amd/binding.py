@@ -219,7 +219,7 @@ class Context:
                "skv_merge_lse")
 
 
-NOALLOC_SCRATCH_BYTES = 4 * 1024 * 1024
+NOALLOC_SCRATCH_BYTES = 8 * 1024 * 1024
 
 
 def decode_step_noalloc(desc: Desc, layer: int, B: int, q_score, q_attn, K_pool, V_pool, T_total: int, semvec, S_total: int,

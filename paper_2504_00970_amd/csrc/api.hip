@@ -49,39 +49,62 @@ inline int sv_bytes(const Ctx& c) { return c.d.semvec_dtype == SKV_BF16 ? 2 : c.
 
 // ---- workspace: one block of device memory, carved the same way whether skv_create allocated it or it is the static
 // scratch array of skv_decode_step_noalloc ---------------------------------------------------------------------------
-constexpr int kWsParts = 11;
-size_t workspace_layout(const skv_desc& d, int max_splits, int max_sel, size_t sz[kWsParts]) {
+constexpr int kWsParts = 14;
+// Fixed sizes of the tagged area (epochs, tagged scores, tagged partials) in the static scratch of
+// skv_decode_step_noalloc: that area must hold tagged words only, whatever descriptor a call brings (a word of some
+// other array could look like a valid tag), so it has the same extent for every descriptor.
+constexpr size_t kFixedEpochBytes = (size_t)skv::kStepMaxPairs * skv::kStepEpochStride * sizeof(unsigned int);
+constexpr size_t kFixedScoreWords = 128 * 1024;
+constexpr size_t kFixedPartBytes = (size_t)skv::kStepMaxBlocks * 8 * skv::kStepPartWords * sizeof(unsigned long long);
+
+// fixed_tagged: the static-scratch form.  *score_stride receives the words per pair of the tagged scores.
+size_t workspace_layout(const skv_desc& d, int max_splits, int max_sel, bool fixed_tagged, size_t sz[kWsParts], int32_t* score_stride) {
     const size_t BH = (size_t)d.max_batch * d.n_kv_heads, BQ = (size_t)d.max_batch * d.n_q_heads;
     const size_t n_seg = (size_t)(d.max_tokens + skv::kSegTokPerBlock - 1) / skv::kSegTokPerBlock;
-    sz[0] = round256(n_seg * sizeof(unsigned long long));                          // seg_part
-    sz[1] = round256(BQ * max_splits * skv::kHeadDim * sizeof(float));             // att_part
-    sz[2] = round256(BQ * max_splits * 2 * sizeof(float));                         // att_ml
-    sz[3] = round256(BH * sizeof(unsigned int));                                   // att_counter
-    sz[4] = round256((size_t)d.n_kv_heads * d.max_sentences * sizeof(float));      // f_score
-    sz[5] = round256(BH * max_sel * sizeof(int32_t));                              // f_sel_sent
-    sz[6] = round256(BH * sizeof(int32_t));                                        // f_n_sel
-    sz[7] = round256(BH * sizeof(int32_t));                                        // f_n_tok
-    sz[8] = round256(BH * d.max_budget * sizeof(int32_t));                         // f_tok_idx
-    sz[9] = round256(BH * skv::kStepCounterSlots * sizeof(unsigned int));          // step_counter
-    sz[10] = 256;                                                                  // err_dev
+    const size_t step_pairs = BH < (size_t)skv::kStepMaxPairs ? BH : (size_t)skv::kStepMaxPairs;
+    const int G = d.n_q_heads / d.n_kv_heads;
+    *score_stride = d.max_sentences;
+    sz[0] = kFixedEpochBytes;                                                      // step_epoch
+    if (fixed_tagged) {
+        sz[1] = kFixedScoreWords * sizeof(unsigned long long);                     // step_score
+        sz[2] = kFixedPartBytes;                                                   // step_part
+    } else {
+        sz[1] = round256(step_pairs * (size_t)d.max_sentences * sizeof(unsigned long long));
+        sz[2] = round256((size_t)skv::kStepMaxBlocks * G * skv::kStepPartWords * sizeof(unsigned long long));
+    }
+    sz[3] = round256(n_seg * sizeof(unsigned long long));                          // seg_part
+    sz[4] = round256(BQ * max_splits * skv::kHeadDim * sizeof(float));             // att_part
+    sz[5] = round256(BQ * max_splits * 2 * sizeof(float));                         // att_ml
+    sz[6] = round256(BH * sizeof(unsigned int));                                   // att_counter
+    sz[7] = round256((size_t)d.n_kv_heads * d.max_sentences * sizeof(float));      // f_score
+    sz[8] = round256(BH * max_sel * sizeof(int32_t));                              // f_sel_sent
+    sz[9] = round256(BH * sizeof(int32_t));                                        // f_n_sel
+    sz[10] = round256(BH * sizeof(int32_t));                                       // f_n_tok
+    sz[11] = round256(BH * d.max_budget * sizeof(int32_t));                        // f_tok_idx
+    sz[12] = 256;                                                                  // err_dev
+    sz[13] = 0;
     size_t total = 0;
     for (int i = 0; i < kWsParts; ++i) total += sz[i];
     return total;
 }
 
-void carve_workspace(Ctx& c, char* base, const size_t sz[kWsParts]) {
+void carve_workspace(Ctx& c, char* base, const size_t sz[kWsParts], int32_t score_stride) {
     char* p = base;
-    c.seg_part = reinterpret_cast<unsigned long long*>(p); p += sz[0];
-    c.att_part = reinterpret_cast<float*>(p); p += sz[1];
-    c.att_ml = reinterpret_cast<float*>(p); p += sz[2];
-    c.att_counter = reinterpret_cast<unsigned int*>(p); p += sz[3];
-    c.f_score = reinterpret_cast<float*>(p); p += sz[4];
-    c.f_sel_sent = reinterpret_cast<int32_t*>(p); p += sz[5];
-    c.f_n_sel = reinterpret_cast<int32_t*>(p); p += sz[6];
-    c.f_n_tok = reinterpret_cast<int32_t*>(p); p += sz[7];
-    c.f_tok_idx = reinterpret_cast<int32_t*>(p); p += sz[8];
-    c.step_counter = reinterpret_cast<unsigned int*>(p); p += sz[9];
-    c.err_dev = reinterpret_cast<unsigned int*>(p); p += sz[10];
+    c.step_epoch = reinterpret_cast<unsigned int*>(p); p += sz[0];
+    c.step_score = reinterpret_cast<unsigned long long*>(p); p += sz[1];
+    c.step_part = reinterpret_cast<unsigned long long*>(p); p += sz[2];
+    c.step_score_stride = score_stride;
+    c.step_score_words = (int64_t)(sz[1] / sizeof(unsigned long long));
+    c.seg_part = reinterpret_cast<unsigned long long*>(p); p += sz[3];
+    c.att_part = reinterpret_cast<float*>(p); p += sz[4];
+    c.att_ml = reinterpret_cast<float*>(p); p += sz[5];
+    c.att_counter = reinterpret_cast<unsigned int*>(p); p += sz[6];
+    c.f_score = reinterpret_cast<float*>(p); p += sz[7];
+    c.f_sel_sent = reinterpret_cast<int32_t*>(p); p += sz[8];
+    c.f_n_sel = reinterpret_cast<int32_t*>(p); p += sz[9];
+    c.f_n_tok = reinterpret_cast<int32_t*>(p); p += sz[10];
+    c.f_tok_idx = reinterpret_cast<int32_t*>(p); p += sz[11];
+    c.err_dev = reinterpret_cast<unsigned int*>(p); p += sz[12];
 }
 
 void fill_context(Ctx& c, const skv_desc& d, hipStream_t stream, int dev) {
@@ -95,6 +118,7 @@ void fill_context(Ctx& c, const skv_desc& d, hipStream_t stream, int dev) {
     c.max_sel = d.max_sentences < d.max_budget ? d.max_sentences : d.max_budget;
     c.max_splits = (d.max_budget + skv::kAttChunk - 1) / skv::kAttChunk;
     c.wait_limit = skv::kStepWaitLimit;
+    c.step_chunk = skv::kAttChunkMid;
 }
 
 // ---- static scratch of skv_decode_step_noalloc -----------------------------------------------------------------------
@@ -159,13 +183,14 @@ int skv_create(skv_ctx** out, const skv_desc* desc, void* hip_stream) {
     fill_context(c, *desc, static_cast<hipStream_t>(hip_stream), dev);
 
     size_t sz[kWsParts];
-    const size_t total = workspace_layout(*desc, c.max_splits, c.max_sel, sz);
+    int32_t score_stride = 0;
+    const size_t total = workspace_layout(*desc, c.max_splits, c.max_sel, false, sz, &score_stride);
     hipError_t e = hipMalloc(reinterpret_cast<void**>(&c.ws), total);
     if (e != hipSuccess) { delete ctx; return hip_status(e); }
     e = hipMemset(c.ws, 0, total);
     if (e != hipSuccess) { (void)hipFree(c.ws); delete ctx; return hip_status(e); }
     c.ws_bytes = total;
-    carve_workspace(c, c.ws, sz);
+    carve_workspace(c, c.ws, sz, score_stride);
     // a word of pinned host memory the kernels can reach: a block of the single-launch step that gives up waiting sets
     // it, and the next skv_decode_step on this context reports it
     void* eh = nullptr;
@@ -477,26 +502,24 @@ int skv_decode_step_noalloc(const skv_desc* desc, void* hip_stream, int32_t laye
     skv_desc d0 = *desc;
     d0.max_tokens = 1;                                    // the prefill partials are not part of this call
     size_t sz[kWsParts];
-    if (workspace_layout(d0, c.max_splits, c.max_sel, sz) > kStaticScratchBytes) return SKV_ECAPACITY;
+    int32_t score_stride = 0;
+    if (workspace_layout(d0, c.max_splits, c.max_sel, true, sz, &score_stride) > kStaticScratchBytes) return SKV_ECAPACITY;
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess) return SKV_EHIP;
     char* base = nullptr;
     rc = static_scratch(dev, &base);
     if (rc != SKV_OK) return rc;
     fill_context(c, *desc, static_cast<hipStream_t>(hip_stream), dev);
-    carve_workspace(c, base, sz);
+    carve_workspace(c, base, sz, score_stride);
     c.ws = base;
     c.ws_bytes = kStaticScratchBytes;
     // the arrival counters must start at zero; the array keeps whatever the last call on this GPU left there
-    const int32_t n_words = (int32_t)(sz[3] / sizeof(uint32_t));
-    hipLaunchKernelGGL(clear_words_kernel, dim3((n_words + 255) / 256), dim3(256), 0, c.stream,
-                       c.att_counter, n_words);
+    // (the tagged area at the start of the array -- epochs, tagged scores, tagged partials of the single-launch step --
+    // is never cleared: its words are only ever valid for the launch that wrote them)
+    const int32_t n_words = (int32_t)(sz[6] / sizeof(uint32_t));
+    hipLaunchKernelGGL(clear_words_kernel, dim3((n_words + 255) / 256), dim3(256), 0, c.stream, c.att_counter, n_words);
     if (hipGetLastError() != hipSuccess) return SKV_EHIP;
-    // the same for the ticket counters of the single-launch step (all zero is a valid state) and its error word,
-    // which are adjacent at the end of the layout
-    const int32_t n_tail = (int32_t)((sz[9] + sz[10]) / sizeof(uint32_t));
-    hipLaunchKernelGGL(clear_words_kernel, dim3((n_tail + 255) / 256), dim3(256), 0, c.stream,
-                       c.step_counter, n_tail);
+    hipLaunchKernelGGL(clear_words_kernel, dim3(1), dim3(64), 0, c.stream, c.err_dev, 1);
     if (hipGetLastError() != hipSuccess) return SKV_EHIP;
     return decode_step_launch(c, layer, B, q_score, q_attn, K_pool, V_pool, T_total, semvec, S_total, cu_tok, cu_sent,
                               sent_off, sent_len, budget, out, lse, tok_idx_out, n_tok_out);

@@ -143,6 +143,20 @@ __device__ __forceinline__ unsigned int ld_agent(const unsigned int* p) {
 __device__ __forceinline__ unsigned long long ld_agent64(const float* p) {       // two consecutive floats
     return __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// A float and the tag of the launch that produced it, in one 64-bit word written and read with single relaxed
+// device-scope atomic accesses.  A reader that finds the tag it expects holds the value that belongs to it: nothing has
+// to be ordered against any other location (per-location coherence of atomics is all that is used), so there is no
+// arrival counter, no wait for store acknowledgements and no cache maintenance between producer and consumer.
+__device__ __forceinline__ void st_tagged(unsigned long long* p, float v, uint32_t tag) {
+    __hip_atomic_store(p, ((unsigned long long)tag << 32) | (unsigned long long)__float_as_uint(v), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long ld_tagged(const unsigned long long* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t tag_of(unsigned long long w) { return (uint32_t)(w >> 32); }
+__device__ __forceinline__ float val_of(unsigned long long w) { return __uint_as_float((uint32_t)w); }
+
 // Barrier behind which another thread of the block publishes what this block has stored (an arrival counter).  The
 // workgroup barrier by itself does not wait for a wave's outstanding global stores (the waves of a block share their CU's
 // cache, so the compiler leaves the store counter alone at workgroup scope): each wave waits for its own first.
@@ -162,11 +176,17 @@ __device__ __forceinline__ float hi_f(unsigned long long v) { return __uint_as_f
 // ------------------------------------------------------------------------------------------------
 
 // One wave: the RPWV buckets [row_w, row_w + RPWV) of a sequence.  q_grp = the first query of the head's group,
-// sv_seq / out_seq = the (head, sequence) slices of the table and of the scores.  AGENT: scores are stored so that
-// other blocks of the same launch can read them.
-template <int EB, int G, int RPWV, bool AGENT>
+// sv_seq / out_seq = the (head, sequence) slices of the table and of the scores.  TAGGED: out_seq holds 64-bit (score, tag)
+// words that other blocks of the same launch read.
+template <bool TAGGED>
+__device__ __forceinline__ void store_score(void* __restrict__ out_seq, int32_t s, float v, uint32_t tag) {
+    if (TAGGED) st_tagged(static_cast<unsigned long long*>(out_seq) + s, v, tag);
+    else static_cast<float*>(out_seq)[s] = v;
+}
+
+template <int EB, int G, int RPWV, bool TAGGED>
 __device__ __forceinline__ void score_wave_f32(const char* __restrict__ q_grp, const float* __restrict__ sv_seq,
-                                               int32_t n_sent, int32_t row_w, float* __restrict__ out_seq) {
+                                               int32_t n_sent, int32_t row_w, void* __restrict__ out_seq, uint32_t tag = 0) {
     const int lane = threadIdx.x & 63;
     const int c = lane & 31, half = lane >> 5;
     float qs[4] = {0.f, 0.f, 0.f, 0.f};
@@ -208,19 +228,16 @@ __device__ __forceinline__ void score_wave_f32(const char* __restrict__ q_grp, c
 #pragma unroll
         for (int i = 0; i < kIter; ++i) {
             const int32_t s = row0 + 2 * i;
-            if (s < n_sent) {
-                if (AGENT) st_agent(out_seq + s, p[i]);
-                else out_seq[s] = p[i];
-            }
+            if (s < n_sent) store_score<TAGGED>(out_seq, s, p[i], tag);
         }
     }
 }
 
 // The same from a bf16 table: a vector is 256 bytes = 16 lanes x 16 bytes (8 dims per lane), a wave load covers
 // 4 buckets, RPWV / 4 loads in flight; the sum over a bucket's 16 lanes stays inside a DPP row.
-template <int EB, int G, int RPWV, bool AGENT>
+template <int EB, int G, int RPWV, bool TAGGED>
 __device__ __forceinline__ void score_wave_bf16(const char* __restrict__ q_grp, const char* __restrict__ sv_seq,
-                                                int32_t n_sent, int32_t row_w, float* __restrict__ out_seq) {
+                                                int32_t n_sent, int32_t row_w, void* __restrict__ out_seq, uint32_t tag = 0) {
     const int lane = threadIdx.x & 63;
     const int c = lane & 15, sub = lane >> 4;
     float qs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -267,19 +284,16 @@ __device__ __forceinline__ void score_wave_bf16(const char* __restrict__ q_grp, 
 #pragma unroll
         for (int i = 0; i < kIter; ++i) {
             const int32_t s = row0 + 4 * i;
-            if (s < n_sent) {
-                if (AGENT) st_agent(out_seq + s, p[i]);
-                else out_seq[s] = p[i];
-            }
+            if (s < n_sent) store_score<TAGGED>(out_seq, s, p[i], tag);
         }
     }
 }
 
 // The same from an E4M3 table: a vector is 128 bytes = 8 lanes x 16 bytes (16 dims per lane), a wave load covers 8 buckets,
 // RPWV / 8 loads in flight; the sum over a bucket's 8 lanes is two quad exchanges and a rotation by 4.
-template <int EB, int G, int RPWV, bool AGENT>
+template <int EB, int G, int RPWV, bool TAGGED>
 __device__ __forceinline__ void score_wave_e4m3(const char* __restrict__ q_grp, const char* __restrict__ sv_seq,
-                                                int32_t n_sent, int32_t row_w, float* __restrict__ out_seq) {
+                                                int32_t n_sent, int32_t row_w, void* __restrict__ out_seq, uint32_t tag = 0) {
     const int lane = threadIdx.x & 63;
     const int c = lane & 7, sub = lane >> 3;
     float qs[16];
@@ -337,10 +351,7 @@ __device__ __forceinline__ void score_wave_e4m3(const char* __restrict__ q_grp, 
 #pragma unroll
         for (int i = 0; i < kIter; ++i) {
             const int32_t s = row0 + 8 * i;
-            if (s < n_sent) {
-                if (AGENT) st_agent(out_seq + s, p[i]);
-                else out_seq[s] = p[i];
-            }
+            if (s < n_sent) store_score<TAGGED>(out_seq, s, p[i], tag);
         }
     }
 }
@@ -488,31 +499,38 @@ struct SelectShared {
     unsigned long long hist[3][kBins];                        // packed (count << 32 | total length) per digit
     uint32_t wave_tot[6][kBlockWaves];                        // one slot per block scan
     int32_t res[3][4];                                        // per pass: crossing digit (-1: none), carry, count
+    int32_t poll[3];                                          // tagged scores: [0] set by a thread whose wait ran out
 };
 
 // emit(s, off_s, len_s, sel_pos, tok_pos) is called by the owner thread of every selected bucket,
 // sel_pos / tok_pos being the number of selected buckets / tokens with lower ids (sel_pos is only
 // computed when COUNT is set, else 0).  Every thread of the block must call this; *n_sel_out /
 // *n_tok_out are block-uniform.
-template <int KREG, bool COUNT, bool AGENT, typename Emit>
+// TAGGED: `sc` points at 64-bit (score, tag) words that other blocks of the same launch are writing; every thread reads
+// its words again and again until they carry `tag` (at most wait_limit + 1 times: *ok_out tells whether they all
+// arrived; if not, the selection is made from whatever was read and is meaningless).
+template <int KREG, bool COUNT, bool TAGGED, typename Emit>
 __device__ __forceinline__ void select_block(const float* __restrict__ sc, const int32_t* __restrict__ len,
                                              const int32_t* __restrict__ off, int32_t S, int32_t budget,
-                                             SelectShared& sh, Emit emit, int32_t* n_sel_out, int32_t* n_tok_out) {
+                                             SelectShared& sh, Emit emit, int32_t* n_sel_out, int32_t* n_tok_out,
+                                             uint32_t tag = 0, int32_t wait_limit = 0, bool* ok_out = nullptr,
+                                             uint32_t* __restrict__ key_lds = nullptr /* TAGGED: KREG * kBlockThreads words */) {
     const int tid = threadIdx.x;
     *n_sel_out = 0;
     *n_tok_out = 0;
+    if (ok_out) *ok_out = true;
     if (S <= 0 || budget <= 0) return;
     const int kpt = (S + kBlockThreads - 1) / kBlockThreads;
     const int32_t s0 = tid * kpt;
-    // AGENT: the scores were written by other blocks of the same launch
-    auto ldsc = [&](int32_t i) -> float { return AGENT ? ld_agent(sc + i) : sc[i]; };
+    const unsigned long long* tw = reinterpret_cast<const unsigned long long*>(sc);
+    auto ldsc = [&](int32_t i) -> float { return TAGGED ? val_of(ld_tagged(tw + i)) : sc[i]; };
 
     uint32_t rkey[KREG];
     int32_t rlen[KREG], roff[KREG];
     static_assert(KREG % 2 == 0, "the register-held buckets are loaded in pairs");
 #pragma unroll
     for (int i = 0; i < KREG; ++i) { rkey[i] = 0; rlen[i] = 0; roff[i] = 0; }
-    if (KREG > 2 && S >= 2 && !AGENT) {
+    if (KREG > 2 && S >= 2) {
         // Many buckets per thread: they are consecutive, so two per load instruction (8 bytes at 4-byte alignment; with
         // two buckets per thread single loads measured slightly faster).  The pair is moved back so that it ends inside
         // the arrays; a slot past the end gets some in-range value and is dropped below.
@@ -521,7 +539,8 @@ __device__ __forceinline__ void select_block(const float* __restrict__ sc, const
         for (int j = 0; j < KREG / 2; ++j) {
             if (2 * j < kpt) {                             // block-uniform; loads unconditional
                 const int32_t idx = s0 + 2 * j, bse = min(idx, S - 2);
-                const Pair k = *reinterpret_cast<const Pair*>(sc + bse);
+                Pair k{0u, 0u};
+                if (!TAGGED) k = *reinterpret_cast<const Pair*>(sc + bse);
                 const Pair l = *reinterpret_cast<const Pair*>(len + bse);
                 const Pair o = *reinterpret_cast<const Pair*>(off + bse);
                 const bool tail = idx == S - 1;            // the pair was moved back by one: the last bucket sits in .y
@@ -535,7 +554,7 @@ __device__ __forceinline__ void select_block(const float* __restrict__ sc, const
         for (int i = 0; i < KREG; ++i) {
             if (i < kpt) {                                 // block-uniform; addresses clamped, loads unconditional
                 const int32_t sidx = min(s0 + i, S - 1);
-                rkey[i] = __float_as_uint(ldsc(sidx));
+                if (!TAGGED) rkey[i] = __float_as_uint(sc[sidx]);
                 rlen[i] = len[sidx];
                 roff[i] = off[sidx];
             }
@@ -546,9 +565,41 @@ __device__ __forceinline__ void select_block(const float* __restrict__ sc, const
         unsigned long long* h = &sh.hist[0][0];
 #pragma unroll
         for (int i = 0; i < 3 * kBins / kBlockThreads; ++i) h[i * kBlockThreads + tid] = 0;
-        if (tid < 3) sh.res[tid][0] = -1;
+        if (tid < 3) { sh.res[tid][0] = -1; sh.poll[tid] = 0; }
     }
     __syncthreads();
+    if (TAGGED) {
+        // Every thread reads its own words until all of them carry the tag (bounded), without talking to anyone; the
+        // block meets at one barrier afterwards.  A thread whose wait ran out raises the block's flag.
+        // The words are read with consecutive lanes on consecutive words (thread t: words t, t + 1024, ...: whole cache
+        // lines per wave instruction; a thread's own consecutive buckets would cost kpt times the memory requests), and
+        // the keys reach their owners through LDS.
+        bool mine = false;
+        uint32_t kk[KREG];
+        for (int32_t round = 0; !mine && round <= wait_limit; ++round) {
+            mine = true;
+#pragma unroll
+            for (int i = 0; i < KREG; ++i) {
+                if (i < kpt) {
+                    const int32_t sidx = min(i * kBlockThreads + tid, S - 1);
+                    const unsigned long long wd = ld_tagged(tw + sidx);
+                    kk[i] = (uint32_t)wd;
+                    mine = mine && tag_of(wd) == tag;
+                }
+            }
+            for (int i = KREG; i < kpt; ++i)               // buckets beyond the registers are re-read in every phase below
+                if (s0 + i < S) mine = mine && tag_of(ld_tagged(tw + s0 + i)) == tag;
+        }
+#pragma unroll
+        for (int i = 0; i < KREG; ++i)
+            if (i < kpt) key_lds[i * kBlockThreads + tid] = kk[i];
+        if (!mine) sh.poll[0] = 1;
+        __syncthreads();
+        if (sh.poll[0] != 0 && ok_out) *ok_out = false;
+#pragma unroll
+        for (int i = 0; i < KREG; ++i)
+            if (i < kpt) rkey[i] = key_lds[min(s0 + i, KREG * kBlockThreads - 1)];
+    }
 #pragma unroll
     for (int i = 0; i < KREG; ++i) {
         rkey[i] = score_key(__uint_as_float(rkey[i]));
@@ -829,6 +880,16 @@ __device__ __forceinline__ f32x4_t mfma_qk32(const uint4& k, const uint4& q, f32
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, k), __builtin_bit_cast(bf16x8_t, q), c, 0, 0, 0);
 }
 
+// Tag of a launch of the single-launch step for one pair: the pair's epoch after this launch (1 .. 2^26 - 1, never 0, so
+// zero-filled memory never looks valid) above the pair's number.  A word of memory carries a pair's current tag only if
+// a block of that pair wrote it in this launch: other pairs differ in the low bits, earlier launches in the epoch (which
+// repeats after 2^26 - 1 launches of the pair).
+__device__ __forceinline__ uint32_t step_tag(uint32_t epoch, int pair) {
+    uint32_t e = (epoch + 1u) & ((1u << (32 - kStepPairBits)) - 1u);
+    if (e == 0u) e = 1u;
+    return (e << kStepPairBits) | (uint32_t)pair;
+}
+
 struct AttArgs {
     const char* q;            // [B][Hq][D]
     const char* Kb;           // kDirect: K_sel [B*Hkv][row_stride][D]; else the layer's pool [Hkv][T_total][D]
@@ -853,12 +914,14 @@ struct AttArgs {
     // kStep: the blocks of a (sequence, head) pair first score the pair's buckets between them
     const char* q_score;      // [B][Hq][D]
     const char* semvec;       // the layer's table [Hkv][S_total][D]
-    float* score_out;         // [Hkv][S_total]; `score` points at the same memory
     int32_t sv_bytes;         // bytes per element of the table: 4, 2 or 1
     int32_t lg_parts;         // log2 of the blocks per pair
-    unsigned int* step_counter;   // [pairs][kStepCounterSlots] ticket counters, one per power of two of blocks per pair
-    int32_t wait_limit;       // polls of the ticket counter before a block gives up
-    unsigned int* err_dev;    // set to 1 by a block that gave up; read by the merging blocks
+    unsigned int* step_epoch; // [pairs][kStepEpochStride]: launches of the single-launch step each pair has been through
+    unsigned long long* step_score;   // [pairs][score_stride] (score, tag) words
+    int32_t score_stride;
+    unsigned long long* step_part;    // [blocks][G][kHeadDim + 2] (value, tag) words: a block's partial sums, then (max, normaliser)
+    int32_t wait_limit;       // rounds of polling before a block gives up
+    unsigned int* err_dev;    // set to 1 by a block that gave up
     unsigned int* err_host;   // the same word in pinned host memory (device address), nullable
 };
 
@@ -874,8 +937,8 @@ __device__ __forceinline__ void demand_args(const AttArgs& a) {
                  "s"(a.Hkv), "s"(a.max_splits), "s"(a.part), "s"(a.ml), "s"(a.counter), "s"(a.out), "s"(a.lse));
 }
 __device__ __forceinline__ void demand_step_args(const AttArgs& a) {
-    asm volatile("" ::"s"(a.q_score), "s"(a.semvec), "s"(a.score_out), "s"(a.sv_bytes), "s"(a.lg_parts), "s"(a.step_counter),
-                 "s"(a.wait_limit), "s"(a.err_dev), "s"(a.err_host));
+    asm volatile("" ::"s"(a.q_score), "s"(a.semvec), "s"(a.sv_bytes), "s"(a.lg_parts), "s"(a.step_epoch), "s"(a.step_score),
+                 "s"(a.score_stride), "s"(a.step_part), "s"(a.wait_limit), "s"(a.err_dev), "s"(a.err_host));
 }
 
 // CHUNK = retrieved tokens per block: 64 for the latency-bound single-sequence step (most blocks in
@@ -922,7 +985,14 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
     const int Hq = a.Hkv * G;
     const int64_t qhead0 = (int64_t)b * Hq + (int64_t)h * G;      // first query head of the group
     demand_args(a);
-    if constexpr (MODE == kStep) demand_step_args(a);
+    // kStep: the tag of this launch for this pair.  Every launch of the pair ends with its epoch advanced by one (block 0,
+    // after it has seen the partial of every attending block, each of which had seen every score of the pair: so every
+    // block whose tag matters has read the epoch by then), and the pair's number makes tags of different pairs differ.
+    uint32_t tag = 0;
+    if constexpr (MODE == kStep) {
+        demand_step_args(a);
+        tag = step_tag(ld_agent(a.step_epoch + bh * kStepEpochStride), bh);
+    }
     const Seq sq = seq_of(a.v, b);
     const int32_t j0 = split * CHUNK;
     const int slot = split * (CHUNK / kWave);                     // partial slot (slots are counted in 64-token units)
@@ -941,6 +1011,7 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
     }
 
     int32_t n;                                                    // retrieved tokens of this (sequence, head)
+    bool step_ok = true;                                          // kStep: every wait of this block ended in time
     if constexpr (kSel) {
         __shared__ SelectShared sel_sh;
         const int32_t budget = min(sq.budget, a.idx_stride);
@@ -948,22 +1019,23 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
             // ---- 0. scores of this block's share of the pair's buckets, published to the pair's other blocks ---------
             // Part `split` of the 2^lg_parts blocks of the pair owns the buckets [split * per, (split + 1) * per); wave
             // w takes RPWV consecutive buckets at a time.  The arithmetic per bucket is that of score_kernel (same
-            // lanes, same order), so skv_score returns the very floats that are ranked here.
+            // lanes, same order), so skv_score returns the very floats that are ranked here.  Each score is stored
+            // with the launch tag in one 64-bit word; the blocks that go on read the pair's words until all carry it.
             const int32_t S = sq.n_sent;
             const int32_t per = (S + (1 << a.lg_parts) - 1) >> a.lg_parts;
             const int32_t lo = split * per, hi = min(lo + per, S);
             const char* qg = a.q_score + ((qhead0 * kHeadDim) * EB);
             const int64_t row0 = (int64_t)h * a.v.S_total + sq.sent_base;
-            float* sc_out = a.score_out + row0;
+            unsigned long long* sc_out = a.step_score + (int64_t)bh * a.score_stride;
             auto score_rows = [&](auto rpwv_tag) {
                 constexpr int RPWV = decltype(rpwv_tag)::value;
                 for (int32_t rw = lo + w * RPWV; rw < hi; rw += kBlockWaves * RPWV) {
                     if (a.sv_bytes == kTableF32)
-                        score_wave_f32<EB, G, RPWV, true>(qg, reinterpret_cast<const float*>(a.semvec) + row0 * kHeadDim, hi, rw, sc_out);
+                        score_wave_f32<EB, G, RPWV, true>(qg, reinterpret_cast<const float*>(a.semvec) + row0 * kHeadDim, hi, rw, sc_out, tag);
                     else if (a.sv_bytes == kTableBf16)
-                        score_wave_bf16<EB, G, (RPWV < 4 ? 4 : RPWV), true>(qg, a.semvec + row0 * kHeadDim * 2, hi, rw, sc_out);
+                        score_wave_bf16<EB, G, (RPWV < 4 ? 4 : RPWV), true>(qg, a.semvec + row0 * kHeadDim * 2, hi, rw, sc_out, tag);
                     else
-                        score_wave_e4m3<EB, G, (RPWV < 8 ? 8 : RPWV), true>(qg, a.semvec + row0 * kHeadDim, hi, rw, sc_out);
+                        score_wave_e4m3<EB, G, (RPWV < 8 ? 8 : RPWV), true>(qg, a.semvec + row0 * kHeadDim, hi, rw, sc_out, tag);
                 }
             };
             // few buckets per block: 4 per wave visit (two loads in flight per lane, all 16 waves busy from 64 buckets on);
@@ -971,41 +1043,8 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
             if (per <= kBlockWaves * 4) score_rows(std::integral_constant<int, 4>{});
             else score_rows(std::integral_constant<int, 16>{});
             SKV_T(12);
-            // Every wave waits for its own write-through score stores, then the barrier; only then does thread 0 take
-            // its ticket.  The counter of (pair, lg_parts) only ever counts arrivals of launches with 2^lg_parts blocks
-            // per pair, so between launches it is a multiple of that number: the ticket's round ends at the next
-            // multiple, whatever the counter's absolute value (it wraps at 2^32, a multiple too).  Nothing is reset.
-            block_sync_after_stores();
-            if (split > 0 && j0 >= budget) {                      // no position of this block can hold a token (n <= budget)
-                if (tid == 0)
-                    __hip_atomic_fetch_add(&a.step_counter[bh * kStepCounterSlots + a.lg_parts], 1u, __ATOMIC_RELAXED,
-                                           __HIP_MEMORY_SCOPE_AGENT);
-                return;
-            }
-            if (tid == 0) {
-                unsigned int* ctr = &a.step_counter[bh * kStepCounterSlots + a.lg_parts];
-                const unsigned int parts = 1u << a.lg_parts;
-                const unsigned int old = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                const unsigned int target = (old & ~(parts - 1u)) + parts;
-                // The wait ends: every block of the grid is resident (the host launches this kernel only when the grid
-                // fits the chip, one block per compute unit) and arrives without waiting for anyone.  It is bounded all
-                // the same: on expiry the error word is set, the block carries on with whatever scores it can see, and
-                // the pair's output is NaN.
-                int32_t polls = 0;
-                bool ok = true;
-                if (old + 1u != target) {
-                    while ((int32_t)(ld_agent(ctr) - target) < 0) {
-                        if (++polls > a.wait_limit) { ok = false; break; }
-                        __builtin_amdgcn_s_sleep(1);
-                    }
-                }
-                if (!ok) {
-                    st_agent(a.err_dev, 1u);
-                    if (a.err_host) st_agent(a.err_host, 1u);
-                }
-            }
-            __syncthreads();
-            SKV_T(13);
+            // Blocks that neither attend (no position of theirs can hold a token: n <= budget) nor merge are done.
+            if (split >= G && j0 >= budget) return;
         } else {
             if (split > 0 && j0 >= budget) return;                // n <= budget: nothing for this split
         }
@@ -1023,9 +1062,18 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
         const float* sc = a.score + (int64_t)h * a.v.S_total + sq.sent_base;
         const int32_t* len = a.sent_len + sq.sent_base;
         const int32_t* off = a.sent_off + sq.sent_base + (a.v.cu_sent ? b : 0);
-        constexpr bool kAgent = MODE == kStep;                    // the scores were written by other blocks of this launch
-        if (sq.n_sent <= 2 * kBlockThreads) select_block<2, false, kAgent>(sc, len, off, sq.n_sent, budget, sel_sh, mark, &nsel, &ntok);
-        else select_block<kSelKreg, false, kAgent>(sc, len, off, sq.n_sent, budget, sel_sh, mark, &nsel, &ntok);
+        if constexpr (MODE == kStep) {                            // the scores are being written by the pair's blocks
+            const float* tsc = reinterpret_cast<const float*>(a.step_score + (int64_t)bh * a.score_stride);
+            __shared__ uint32_t sm_keys[kSelKreg * kBlockThreads];    // the pair's scores on their way to the owning threads
+            if (sq.n_sent <= 2 * kBlockThreads)
+                select_block<2, false, true>(tsc, len, off, sq.n_sent, budget, sel_sh, mark, &nsel, &ntok, tag, a.wait_limit, &step_ok, sm_keys);
+            else
+                select_block<kSelKreg, false, true>(tsc, len, off, sq.n_sent, budget, sel_sh, mark, &nsel, &ntok, tag, a.wait_limit, &step_ok, sm_keys);
+        } else if (sq.n_sent <= 2 * kBlockThreads) {
+            select_block<2, false, false>(sc, len, off, sq.n_sent, budget, sel_sh, mark, &nsel, &ntok);
+        } else {
+            select_block<kSelKreg, false, false>(sc, len, off, sq.n_sent, budget, sel_sh, mark, &nsel, &ntok);
+        }
         n = ntok;
         if (split == 0 && tid == 0 && a.n_tok_out) a.n_tok_out[bh] = n;
         __syncthreads();                                          // bucket starts are marked
@@ -1045,267 +1093,387 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
     }
     if (n <= 0) {
         if (split == 0) {
-            for (int i = tid; i < kOut; i += kBlockThreads) a.out[qhead0 * kHeadDim + i] = 0.f;
+            for (int i = tid; i < kOut; i += kBlockThreads) a.out[qhead0 * kHeadDim + i] = step_ok ? 0.f : __builtin_nanf("");
             if (a.lse && tid < G) a.lse[qhead0 + tid] = -INFINITY;
+            if constexpr (MODE == kStep) {
+                if (tid == 0) {
+                    st_agent(a.step_epoch + bh * kStepEpochStride, tag >> kStepPairBits);     // this launch of the pair is over
+                    if (!step_ok) { st_agent(a.err_dev, 1u); if (a.err_host) st_agent(a.err_host, 1u); }
+                }
+            }
         }
         return;
     }
     const int nsplit = (n + CHUNK - 1) / CHUNK;
-    if (split >= nsplit) return;
-    const int32_t cnt = min(CHUNK, n - j0);
-    SKV_T(4);
-
-    // ---- 1. issue every load of the chunk ------------------------------------------------------------
-    const char* Kh;
-    const char* Vh;
-    if (MODE == kDirect) {
-        Kh = a.Kb + ((int64_t)bh * a.row_stride + j0) * kRowBytes;
-        Vh = a.Vb + ((int64_t)bh * a.row_stride + j0) * kRowBytes;
-    } else {
-        Kh = a.Kb + ((int64_t)h * a.v.T_total + sq.tok_base) * kRowBytes;
-        Vh = a.Vb + ((int64_t)h * a.v.T_total + sq.tok_base) * kRowBytes;
+    // kStep: block g < G merges query head g of the group, whether or not it holds retrieved tokens itself
+    const bool has_work = split < nsplit;
+    if (!has_work && !(MODE == kStep && split < G)) return;
+    unsigned long long* my_part = nullptr;
+    uint32_t part_tag = 0;
+    if constexpr (MODE == kStep) {
+        my_part = a.step_part + (int64_t)blockIdx.x * G * kStepPartWords;
+        part_tag = step_ok ? tag : 0u;                            // a block that gave up publishes nothing valid
     }
-    const float scale = kLog2e * rsqrtf((float)kHeadDim);
-    if constexpr (kMfma) {
-        // ---- bf16: q.K^T (v_mfma_f32_16x16x32_bf16) and P.V (v_mfma_f32_16x16x16_bf16) on the matrix cores ----
-        // Wave w owns the 16 tokens [16w, 16w+16) of the chunk.  With t = lane % 16 and qd = lane / 16:
-        //  * S^T = K Q^T: A fragment = 8 consecutive dims of token t's key, B fragment = the same 8 dims of head t's
-        //    query (heads >= G are zero).  The dimension order inside the contraction is free as long as A and B agree,
-        //    so one 16-byte load of a row (dims 32s+8qd .. +7) is one 32-deep MFMA step; four loads cover the row.
-        //    The accumulator holds logit(token 4qd+j, head t), j = 0..3.
-        //  * O = P V: that accumulator layout IS the A-fragment layout (head t, tokens 4qd+j); the B fragment
-        //    V[token 4qd+j][16dt + t] is read from a wave-private LDS copy of the 16 value rows (padded pitch).
-        typedef short bf16x4 __attribute__((ext_vector_type(4)));
-        typedef float f32x4 __attribute__((ext_vector_type(4)));
-        char* sm_v = reinterpret_cast<char*>(sm_red_flat) + (size_t)w * 16 * kVPitch;       // this wave's value tile
-        __shared__ float sm_wmax[kTiles][16], sm_wsum[kTiles][16];
-        const int t16 = lane & 15, qd = lane >> 4;
-        const bool tile = w < kTiles;
-        float sj[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-        bool lv[4] = {false, false, false, false};
-        if (tile) {
-            const int jj = 16 * w + t16;
-            bool liveK = jj < cnt;
-            const int jc = min(jj, cnt - 1);
-            int32_t rowK;
-            if (MODE == kDirect) {
-                rowK = jc;
-            } else {
-                const int32_t x = kSel ? sm_row[jc] : a.tok_idx[(int64_t)bh * a.idx_stride + j0 + jc];
-                liveK = liveK && x >= 0 && x < sq.n_tok_ctx;
-                rowK = min(max(x, 0), max(sq.n_tok_ctx - 1, 0));
-            }
-            uint4 kA[4], vR[4];
-#pragma unroll
-            for (int s2 = 0; s2 < 4; ++s2) kA[s2] = *reinterpret_cast<const uint4*>(Kh + (int64_t)rowK * kRowBytes + 64 * s2 + 16 * qd);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int32_t rowV = __shfl(rowK, 4 * i + qd);     // lane 4i+qd (< 16) holds the row of token 4i+qd
-                vR[i] = *reinterpret_cast<const uint4*>(Vh + (int64_t)rowV * kRowBytes + 16 * t16);
-            }
-            const unsigned long long vm = __ballot(liveK);        // bit t (t < 16): token t of the tile is real
-            SKV_T(5);
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int s2 = 0; s2 < 4; ++s2) {
-                uint4 qq = qB[s2];
-                if (t16 >= G) qq = make_uint4(0, 0, 0, 0);
-                acc = mfma_qk32(kA[s2], qq, acc);
-            }
-            float mw = -INFINITY;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                lv[j] = (vm >> (4 * qd + j)) & 1ull;
-                sj[j] = lv[j] ? acc[j] * scale : -INFINITY;
-                mw = fmaxf(mw, sj[j]);
-            }
-            mw = fmaxf(mw, __shfl_xor(mw, 16));
-            mw = fmaxf(mw, __shfl_xor(mw, 32));
-            if (qd == 0) sm_wmax[w][t16] = mw;
-            // the tile's value rows go to LDS (rows of masked tokens as zeros)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const bool lr = (vm >> (4 * i + qd)) & 1ull;
-                *reinterpret_cast<uint4*>(sm_v + (4 * i + qd) * kVPitch + 16 * t16) = lr ? vR[i] : make_uint4(0, 0, 0, 0);
-            }
+    if (has_work) {
+        const int32_t cnt = min(CHUNK, n - j0);
+        SKV_T(4);
+
+        // ---- 1. issue every load of the chunk ------------------------------------------------------------
+        const char* Kh;
+        const char* Vh;
+        if (MODE == kDirect) {
+            Kh = a.Kb + ((int64_t)bh * a.row_stride + j0) * kRowBytes;
+            Vh = a.Vb + ((int64_t)bh * a.row_stride + j0) * kRowBytes;
+        } else {
+            Kh = a.Kb + ((int64_t)h * a.v.T_total + sq.tok_base) * kRowBytes;
+            Vh = a.Vb + ((int64_t)h * a.v.T_total + sq.tok_base) * kRowBytes;
         }
-        __syncthreads();
-        SKV_T(6);
-        if (tile) {
-            float mb = -INFINITY;
+        const float scale = kLog2e * rsqrtf((float)kHeadDim);
+        if constexpr (kMfma) {
+            // ---- bf16: q.K^T (v_mfma_f32_16x16x32_bf16) and P.V (v_mfma_f32_16x16x16_bf16) on the matrix cores ----
+            // Wave w owns the 16 tokens [16w, 16w+16) of the chunk.  With t = lane % 16 and qd = lane / 16:
+            //  * S^T = K Q^T: A fragment = 8 consecutive dims of token t's key, B fragment = the same 8 dims of head t's
+            //    query (heads >= G are zero).  The dimension order inside the contraction is free as long as A and B agree,
+            //    so one 16-byte load of a row (dims 32s+8qd .. +7) is one 32-deep MFMA step; four loads cover the row.
+            //    The accumulator holds logit(token 4qd+j, head t), j = 0..3.
+            //  * O = P V: that accumulator layout IS the A-fragment layout (head t, tokens 4qd+j); the B fragment
+            //    V[token 4qd+j][16dt + t] is read from a wave-private LDS copy of the 16 value rows (padded pitch).
+            typedef short bf16x4 __attribute__((ext_vector_type(4)));
+            typedef float f32x4 __attribute__((ext_vector_type(4)));
+            char* sm_v = reinterpret_cast<char*>(sm_red_flat) + (size_t)w * 16 * kVPitch;       // this wave's value tile
+            __shared__ float sm_wmax[kTiles][16], sm_wsum[kTiles][16];
+            const int t16 = lane & 15, qd = lane >> 4;
+            const bool tile = w < kTiles;
+            float sj[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+            bool lv[4] = {false, false, false, false};
+            if (tile) {
+                const int jj = 16 * w + t16;
+                bool liveK = jj < cnt;
+                const int jc = min(jj, cnt - 1);
+                int32_t rowK;
+                if (MODE == kDirect) {
+                    rowK = jc;
+                } else {
+                    const int32_t x = kSel ? sm_row[jc] : a.tok_idx[(int64_t)bh * a.idx_stride + j0 + jc];
+                    liveK = liveK && x >= 0 && x < sq.n_tok_ctx;
+                    rowK = min(max(x, 0), max(sq.n_tok_ctx - 1, 0));
+                }
+                uint4 kA[4], vR[4];
 #pragma unroll
-            for (int ww = 0; ww < kTiles; ++ww) mb = fmaxf(mb, sm_wmax[ww][t16]);
-            unsigned short pb[4];
-            float lw = 0.f;
+                for (int s2 = 0; s2 < 4; ++s2) kA[s2] = *reinterpret_cast<const uint4*>(Kh + (int64_t)rowK * kRowBytes + 64 * s2 + 16 * qd);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float p = (lv[j] && mb > -INFINITY) ? exp2f(sj[j] - mb) : 0.f;
-                uint32_t u = __float_as_uint(p);
-                u += 0x7fffu + ((u >> 16) & 1u);                  // round to nearest even bf16
-                pb[j] = (unsigned short)(u >> 16);
-                lw += __uint_as_float((uint32_t)pb[j] << 16);     // the normaliser sums the rounded weights
+                for (int i = 0; i < 4; ++i) {
+                    const int32_t rowV = __shfl(rowK, 4 * i + qd);     // lane 4i+qd (< 16) holds the row of token 4i+qd
+                    vR[i] = *reinterpret_cast<const uint4*>(Vh + (int64_t)rowV * kRowBytes + 16 * t16);
+                }
+                const unsigned long long vm = __ballot(liveK);        // bit t (t < 16): token t of the tile is real
+                SKV_T(5);
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int s2 = 0; s2 < 4; ++s2) {
+                    uint4 qq = qB[s2];
+                    if (t16 >= G) qq = make_uint4(0, 0, 0, 0);
+                    acc = mfma_qk32(kA[s2], qq, acc);
+                }
+                float mw = -INFINITY;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    lv[j] = (vm >> (4 * qd + j)) & 1ull;
+                    sj[j] = lv[j] ? acc[j] * scale : -INFINITY;
+                    mw = fmaxf(mw, sj[j]);
+                }
+                mw = fmaxf(mw, __shfl_xor(mw, 16));
+                mw = fmaxf(mw, __shfl_xor(mw, 32));
+                if (qd == 0) sm_wmax[w][t16] = mw;
+                // the tile's value rows go to LDS (rows of masked tokens as zeros)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const bool lr = (vm >> (4 * i + qd)) & 1ull;
+                    *reinterpret_cast<uint4*>(sm_v + (4 * i + qd) * kVPitch + 16 * t16) = lr ? vR[i] : make_uint4(0, 0, 0, 0);
+                }
             }
-            lw += __shfl_xor(lw, 16);
-            lw += __shfl_xor(lw, 32);
-            if (qd == 0) sm_wsum[w][t16] = lw;
-            const bf16x4 pa = {(short)pb[0], (short)pb[1], (short)pb[2], (short)pb[3]};
-            // B fragments by the LDS transpose read: this lane points at dims 4 (t16 % 4) .. + 3 of value row 4 qd + t16 / 4
-            const char* vtr = sm_v + (4 * qd + (t16 >> 2)) * kVPitch + 8 * (t16 & 3);
-            f32x4 o[kHeadDim / 16];
+            __syncthreads();
+            SKV_T(6);
+            if (tile) {
+                float mb = -INFINITY;
 #pragma unroll
-            for (int dt = 0; dt < kHeadDim / 16; ++dt) {
-                const bf16x4 vb = lds_read_tr16(vtr + 32 * dt);
-                const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-                o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, vb, zero, 0, 0, 0);
-            }
-            // the value tile has been consumed: its space takes the wave's partial sums, head fastest (dim d, head g at
-            // red[d * G + g]), so that a lane stores its heads of one dim with a single instruction
-            float* red = sm_red_flat + w * kRedStride;
-            if (4 * qd < G) {
+                for (int ww = 0; ww < kTiles; ++ww) mb = fmaxf(mb, sm_wmax[ww][t16]);
+                unsigned short pb[4];
+                float lw = 0.f;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float p = (lv[j] && mb > -INFINITY) ? exp2f(sj[j] - mb) : 0.f;
+                    uint32_t u = __float_as_uint(p);
+                    u += 0x7fffu + ((u >> 16) & 1u);                  // round to nearest even bf16
+                    pb[j] = (unsigned short)(u >> 16);
+                    lw += __uint_as_float((uint32_t)pb[j] << 16);     // the normaliser sums the rounded weights
+                }
+                lw += __shfl_xor(lw, 16);
+                lw += __shfl_xor(lw, 32);
+                if (qd == 0) sm_wsum[w][t16] = lw;
+                const bf16x4 pa = {(short)pb[0], (short)pb[1], (short)pb[2], (short)pb[3]};
+                // B fragments by the LDS transpose read: this lane points at dims 4 (t16 % 4) .. + 3 of value row 4 qd + t16 / 4
+                const char* vtr = sm_v + (4 * qd + (t16 >> 2)) * kVPitch + 8 * (t16 & 3);
+                f32x4 o[kHeadDim / 16];
 #pragma unroll
                 for (int dt = 0; dt < kHeadDim / 16; ++dt) {
-                    float* dst = red + (16 * dt + t16) * G + 4 * qd;
-                    if constexpr (G >= 4) *reinterpret_cast<float4*>(dst) = make_float4(o[dt][0], o[dt][1], o[dt][2], o[dt][3]);
-                    else if constexpr (G == 2) *reinterpret_cast<float2*>(dst) = make_float2(o[dt][0], o[dt][1]);
-                    else dst[0] = o[dt][0];
+                    const bf16x4 vb = lds_read_tr16(vtr + 32 * dt);
+                    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+                    o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, vb, zero, 0, 0, 0);
+                }
+                // the value tile has been consumed: its space takes the wave's partial sums, head fastest (dim d, head g at
+                // red[d * G + g]), so that a lane stores its heads of one dim with a single instruction
+                float* red = sm_red_flat + w * kRedStride;
+                if (4 * qd < G) {
+#pragma unroll
+                    for (int dt = 0; dt < kHeadDim / 16; ++dt) {
+                        float* dst = red + (16 * dt + t16) * G + 4 * qd;
+                        if constexpr (G >= 4) *reinterpret_cast<float4*>(dst) = make_float4(o[dt][0], o[dt][1], o[dt][2], o[dt][3]);
+                        else if constexpr (G == 2) *reinterpret_cast<float2*>(dst) = make_float2(o[dt][0], o[dt][1]);
+                        else dst[0] = o[dt][0];
+                    }
                 }
             }
-        }
-        __syncthreads();
-        if (tid < G) {                                            // block max and normaliser of head tid
-            float mb = -INFINITY, lb = 0.f;
+            __syncthreads();
+            if (tid < G) {                                            // block max and normaliser of head tid
+                float mb = -INFINITY, lb = 0.f;
 #pragma unroll
-            for (int ww = 0; ww < kTiles; ++ww) { mb = fmaxf(mb, sm_wmax[ww][tid]); lb += sm_wsum[ww][tid]; }
-            float* dst = a.ml + (((qhead0 + tid) * a.max_splits) + slot) * 2;
-            st_agent(dst, mb);
-            st_agent(dst + 1, lb);
-        }
-    } else {
-        // Rows past the chunk's end (and positions outside the sequence) are clamped to a valid row, loaded
-        // anyway and masked afterwards, so that all loads are in flight together.
-        int32_t rowi[kIter];
-        bool live[kIter];
-#pragma unroll
-        for (int i = 0; i < kIter; ++i) {
-            const int jj = i * kRowsPerIter + w * R::RPW + r;
-            live[i] = jj < cnt;
-            const int jc = min(jj, cnt - 1);
-            if (MODE == kDirect) {
-                rowi[i] = jc;
-            } else {
-                const int32_t x = kSel ? sm_row[jc] : a.tok_idx[(int64_t)bh * a.idx_stride + j0 + jc];
-                live[i] = live[i] && x >= 0 && x < sq.n_tok_ctx;
-                rowi[i] = min(max(x, 0), max(sq.n_tok_ctx - 1, 0));
-            }
-        }
-        uint4 kraw[kIter], vraw[kIter];
-#pragma unroll
-        for (int i = 0; i < kIter; ++i) {
-            kraw[i] = *reinterpret_cast<const uint4*>(Kh + (int64_t)rowi[i] * kRowBytes + cc * 16);
-            vraw[i] = *reinterpret_cast<const uint4*>(Vh + (int64_t)rowi[i] * kRowBytes + cc * 16);
-        }
-        SKV_T(5);
-
-        // ---- 2. logits ---------------------------------------------------------------------------------
-#pragma unroll
-        for (int hh = 0; hh < NH; ++hh) {
-            float qf[GH][R::EPL];
-#pragma unroll
-            for (int g = 0; g < GH; ++g) {
-                const uint4 t = *reinterpret_cast<const uint4*>(a.q + ((qhead0 + hh * GH + g) * kHeadDim) * EB + cc * 16);
-                R::unpack(t, qf[g]);
-            }
-#pragma unroll
-            for (int i = 0; i < kIter; ++i) {
-                float kf[R::EPL];
-                R::unpack(kraw[i], kf);
-#pragma unroll
-                for (int g = 0; g < GH; ++g) {
-                    float acc = 0.f;
-#pragma unroll
-                    for (int e = 0; e < R::EPL; ++e) acc += qf[g][e] * kf[e];
-                    acc = sum_chunks<R::RPW>(acc);
-                    if (cc == 0) sm_logit[hh * GH + g][i * kRowsPerIter + w * R::RPW + r] = live[i] ? acc * scale : -INFINITY;
+                for (int ww = 0; ww < kTiles; ++ww) { mb = fmaxf(mb, sm_wmax[ww][tid]); lb += sm_wsum[ww][tid]; }
+                if constexpr (MODE == kStep) {
+                    unsigned long long* dst = my_part + tid * kStepPartWords + kHeadDim;
+                    st_tagged(dst, mb, part_tag);
+                    st_tagged(dst + 1, lb, part_tag);
+                } else {
+                    float* dst = a.ml + (((qhead0 + tid) * a.max_splits) + slot) * 2;
+                    st_agent(dst, mb);
+                    st_agent(dst + 1, lb);
                 }
             }
-        }
-        __syncthreads();
-        SKV_T(6);
-
-        // ---- 3. softmax over the chunk, one wave per query head --------------------------------------------
-        if (w < G) {
-            const int g = w;
-            float x[kTPL];
-            float m = -INFINITY;
-#pragma unroll
-            for (int t = 0; t < kTPL; ++t) { x[t] = sm_logit[g][t * kWave + lane]; m = fmaxf(m, x[t]); }
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
-            float l = 0.f;
-#pragma unroll
-            for (int t = 0; t < kTPL; ++t) {
-                const float p = (m == -INFINITY) ? 0.f : exp2f(x[t] - m);
-                sm_logit[g][t * kWave + lane] = p;
-                l += p;
-            }
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) l += __shfl_xor(l, off);
-            if (lane == 0) {
-                float* dst = a.ml + (((qhead0 + g) * a.max_splits) + slot) * 2;
-                st_agent(dst, m);
-                st_agent(dst + 1, l);
-            }
-        }
-        __syncthreads();
-
-        // ---- 4. P.V -------------------------------------------------------------------------------------
-#pragma unroll
-        for (int hh = 0; hh < NH; ++hh) {
-            float acc[GH][R::EPL];
-#pragma unroll
-            for (int g = 0; g < GH; ++g)
-#pragma unroll
-                for (int e = 0; e < R::EPL; ++e) acc[g][e] = 0.f;
+        } else {
+            // Rows past the chunk's end (and positions outside the sequence) are clamped to a valid row, loaded
+            // anyway and masked afterwards, so that all loads are in flight together.
+            int32_t rowi[kIter];
+            bool live[kIter];
 #pragma unroll
             for (int i = 0; i < kIter; ++i) {
                 const int jj = i * kRowsPerIter + w * R::RPW + r;
-                float vf[R::EPL];
-                R::unpack(vraw[i], vf);
-                if (!live[i]) {                                      // masked rows hold a clamped (foreign) row
-#pragma unroll
-                    for (int e = 0; e < R::EPL; ++e) vf[e] = 0.f;
-                }
-#pragma unroll
-                for (int g = 0; g < GH; ++g) {
-                    const float p = sm_logit[hh * GH + g][jj];
-#pragma unroll
-                    for (int e = 0; e < R::EPL; ++e) acc[g][e] += p * vf[e];
+                live[i] = jj < cnt;
+                const int jc = min(jj, cnt - 1);
+                if (MODE == kDirect) {
+                    rowi[i] = jc;
+                } else {
+                    const int32_t x = kSel ? sm_row[jc] : a.tok_idx[(int64_t)bh * a.idx_stride + j0 + jc];
+                    live[i] = live[i] && x >= 0 && x < sq.n_tok_ctx;
+                    rowi[i] = min(max(x, 0), max(sq.n_tok_ctx - 1, 0));
                 }
             }
+            uint4 kraw[kIter], vraw[kIter];
 #pragma unroll
-            for (int g = 0; g < GH; ++g)
+            for (int i = 0; i < kIter; ++i) {
+                kraw[i] = *reinterpret_cast<const uint4*>(Kh + (int64_t)rowi[i] * kRowBytes + cc * 16);
+                vraw[i] = *reinterpret_cast<const uint4*>(Vh + (int64_t)rowi[i] * kRowBytes + cc * 16);
+            }
+            SKV_T(5);
+
+            // ---- 2. logits ---------------------------------------------------------------------------------
 #pragma unroll
-                for (int e = 0; e < R::EPL; ++e) acc[g][e] = sum_rows<R::RPW>(acc[g][e]);
-            if (r == 0) {
+            for (int hh = 0; hh < NH; ++hh) {
+                float qf[GH][R::EPL];
+#pragma unroll
+                for (int g = 0; g < GH; ++g) {
+                    const uint4 t = *reinterpret_cast<const uint4*>(a.q + ((qhead0 + hh * GH + g) * kHeadDim) * EB + cc * 16);
+                    R::unpack(t, qf[g]);
+                }
+#pragma unroll
+                for (int i = 0; i < kIter; ++i) {
+                    float kf[R::EPL];
+                    R::unpack(kraw[i], kf);
+#pragma unroll
+                    for (int g = 0; g < GH; ++g) {
+                        float acc = 0.f;
+#pragma unroll
+                        for (int e = 0; e < R::EPL; ++e) acc += qf[g][e] * kf[e];
+                        acc = sum_chunks<R::RPW>(acc);
+                        if (cc == 0) sm_logit[hh * GH + g][i * kRowsPerIter + w * R::RPW + r] = live[i] ? acc * scale : -INFINITY;
+                    }
+                }
+            }
+            __syncthreads();
+            SKV_T(6);
+
+            // ---- 3. softmax over the chunk, one wave per query head --------------------------------------------
+            if (w < G) {
+                const int g = w;
+                float x[kTPL];
+                float m = -INFINITY;
+#pragma unroll
+                for (int t = 0; t < kTPL; ++t) { x[t] = sm_logit[g][t * kWave + lane]; m = fmaxf(m, x[t]); }
+#pragma unroll
+                for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+                float l = 0.f;
+#pragma unroll
+                for (int t = 0; t < kTPL; ++t) {
+                    const float p = (m == -INFINITY) ? 0.f : exp2f(x[t] - m);
+                    sm_logit[g][t * kWave + lane] = p;
+                    l += p;
+                }
+#pragma unroll
+                for (int off = 32; off >= 1; off >>= 1) l += __shfl_xor(l, off);
+                if (lane == 0) {
+                    if constexpr (MODE == kStep) {
+                        unsigned long long* dst = my_part + g * kStepPartWords + kHeadDim;
+                        st_tagged(dst, m, part_tag);
+                        st_tagged(dst + 1, l, part_tag);
+                    } else {
+                        float* dst = a.ml + (((qhead0 + g) * a.max_splits) + slot) * 2;
+                        st_agent(dst, m);
+                        st_agent(dst + 1, l);
+                    }
+                }
+            }
+            __syncthreads();
+
+            // ---- 4. P.V -------------------------------------------------------------------------------------
+#pragma unroll
+            for (int hh = 0; hh < NH; ++hh) {
+                float acc[GH][R::EPL];
 #pragma unroll
                 for (int g = 0; g < GH; ++g)
 #pragma unroll
-                    for (int e = 0; e < R::EPL; e += 4)
-                        *reinterpret_cast<float4*>(&sm_red_flat[w * kRedStride + (hh * GH + g) * kHeadDim + cc * R::EPL + e]) =
-                            make_float4(acc[g][e], acc[g][e + 1], acc[g][e + 2], acc[g][e + 3]);
+                    for (int e = 0; e < R::EPL; ++e) acc[g][e] = 0.f;
+#pragma unroll
+                for (int i = 0; i < kIter; ++i) {
+                    const int jj = i * kRowsPerIter + w * R::RPW + r;
+                    float vf[R::EPL];
+                    R::unpack(vraw[i], vf);
+                    if (!live[i]) {                                      // masked rows hold a clamped (foreign) row
+#pragma unroll
+                        for (int e = 0; e < R::EPL; ++e) vf[e] = 0.f;
+                    }
+#pragma unroll
+                    for (int g = 0; g < GH; ++g) {
+                        const float p = sm_logit[hh * GH + g][jj];
+#pragma unroll
+                        for (int e = 0; e < R::EPL; ++e) acc[g][e] += p * vf[e];
+                    }
+                }
+#pragma unroll
+                for (int g = 0; g < GH; ++g)
+#pragma unroll
+                    for (int e = 0; e < R::EPL; ++e) acc[g][e] = sum_rows<R::RPW>(acc[g][e]);
+                if (r == 0) {
+#pragma unroll
+                    for (int g = 0; g < GH; ++g)
+#pragma unroll
+                        for (int e = 0; e < R::EPL; e += 4)
+                            *reinterpret_cast<float4*>(&sm_red_flat[w * kRedStride + (hh * GH + g) * kHeadDim + cc * R::EPL + e]) =
+                                make_float4(acc[g][e], acc[g][e + 1], acc[g][e + 2], acc[g][e + 3]);
+                }
             }
         }
-    }
-    __syncthreads();
-    for (int i = tid; i < kOut; i += kBlockThreads) {
-        const int g = i / kHeadDim, d = i % kHeadDim;
-        const int src = kMfma ? d * G + g : i;                     // the MFMA path leaves its sums head fastest
-        float o = sm_red_flat[src];
+        __syncthreads();
+        for (int i = tid; i < kOut; i += kBlockThreads) {
+            const int g = i / kHeadDim, d = i % kHeadDim;
+            const int src = kMfma ? d * G + g : i;                     // the MFMA path leaves its sums head fastest
+            float o = sm_red_flat[src];
 #pragma unroll
-        for (int ww = 1; ww < kRedWaves; ++ww) o += sm_red_flat[ww * kRedStride + src];
-        st_agent(a.part + (((qhead0 + g) * a.max_splits) + slot) * kHeadDim + d, o);
+            for (int ww = 1; ww < kRedWaves; ++ww) o += sm_red_flat[ww * kRedStride + src];
+            if constexpr (MODE == kStep) st_tagged(my_part + g * kStepPartWords + d, o, part_tag);
+            else st_agent(a.part + (((qhead0 + g) * a.max_splits) + slot) * kHeadDim + d, o);
+        }
+        SKV_T(7);
     }
-    SKV_T(7);
+
+    if constexpr (MODE == kStep) {
+        // ---- 5'. per-head merge without an arrival counter -------------------------------------------------------
+        // Block g < G of the pair merges query head g.  Thread (grp, col) -- a group is two whole waves, so a wave's
+        // loads of a partial row are contiguous -- reads dim `col` of the partials of the splits grp, grp + 8, ...
+        // (value and tag in one word) and their (max, normaliser) words, again and again until all carry the launch tag
+        // (bounded; no barrier, no sleep: a wave leaves as soon as its own words are there), folds them into a running
+        // (max, normaliser, output), and the eight groups meet once in LDS.  No block waits for a store
+        // acknowledgement and nothing is counted.
+        if (split >= G) return;
+        constexpr int kGroups8 = kBlockThreads / kHeadDim;               // 8 split groups of 128 threads
+        const int g = split, col = tid % kHeadDim, grp = tid / kHeadDim;
+        float M = -INFINITY, L = 0.f, o = 0.f;
+        bool ok = step_ok;
+        for (int base = 0; base < nsplit && ok; base += 4 * kGroups8) {
+            unsigned long long pv[4], mv[4], lv[4];
+            bool mine = false;
+            for (int32_t round = 0; !mine && round <= a.wait_limit; ++round) {
+                mine = true;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int sp = base + grp + u * kGroups8;             // wave-uniform
+                    if (sp < nsplit) {
+                        const unsigned long long* src = a.step_part + ((int64_t)(sp * n_pairs + bh) * G + g) * kStepPartWords;
+                        pv[u] = ld_tagged(src + col);
+                        mv[u] = ld_tagged(src + kHeadDim);
+                        lv[u] = ld_tagged(src + kHeadDim + 1);
+                        mine = mine && tag_of(pv[u]) == tag && tag_of(mv[u]) == tag && tag_of(lv[u]) == tag;
+                    }
+                }
+            }
+            ok = mine;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (base + grp + u * kGroups8 < nsplit) {
+                    const float ms = val_of(mv[u]);
+                    if (ms > -INFINITY) {
+                        const float nm = fmaxf(M, ms);
+                        const float ca = exp2f(M - nm), cb = exp2f(ms - nm);  // M == -inf gives ca == 0
+                        L = L * ca + val_of(lv[u]) * cb;
+                        o = o * ca + val_of(pv[u]) * cb;
+                        M = nm;
+                    }
+                }
+            }
+        }
+        SKV_T(10);
+        __shared__ int sm_bad;
+        if (tid == 0) sm_bad = 0;
+        __syncthreads();                                                  // also: sm_red_flat is no longer read
+        float* scratch = sm_red_flat;                                     // (o, M, L) per thread: 3 x 1024 floats
+        scratch[tid] = o; scratch[kBlockThreads + tid] = M; scratch[2 * kBlockThreads + tid] = L;
+        if (!ok) sm_bad = 1;
+        __syncthreads();
+        SKV_T(11);
+        const bool bad = sm_bad != 0;                                     // a wait of this launch ran out
+        if (tid < kHeadDim) {
+            float mg[kGroups8], lg[kGroups8], og[kGroups8];
+            float Mx = -INFINITY;
+#pragma unroll
+            for (int gg = 0; gg < kGroups8; ++gg) {
+                og[gg] = scratch[gg * kHeadDim + tid];
+                mg[gg] = scratch[kBlockThreads + gg * kHeadDim + tid];
+                lg[gg] = scratch[2 * kBlockThreads + gg * kHeadDim + tid];
+                Mx = fmaxf(Mx, mg[gg]);
+            }
+            float Ls = 0.f, os = 0.f;
+#pragma unroll
+            for (int gg = 0; gg < kGroups8; ++gg) {
+                if (mg[gg] > -INFINITY) {
+                    const float c = exp2f(mg[gg] - Mx);
+                    Ls += c * lg[gg];
+                    os += c * og[gg];
+                }
+            }
+            const bool empty = !(Ls > 0.f);                               // every retrieved position was out of range
+            float res = empty ? 0.f : os / Ls;
+            if (bad) res = __builtin_nanf("");
+            a.out[(qhead0 + g) * kHeadDim + tid] = res;
+            if (a.lse && tid == 0) a.lse[qhead0 + g] = empty ? -INFINITY : (Mx + log2f(Ls)) * kLn2;
+        }
+        if (tid == 0) {
+            // Block 0 ends the pair's launch by advancing its epoch: all its threads have seen every attending block's
+            // partial (the barrier above), and each of those blocks, and through the scores they waited for every
+            // scoring block, has read the epoch by now.
+            if (split == 0) st_agent(a.step_epoch + bh * kStepEpochStride, tag >> kStepPairBits);
+            if (bad) { st_agent(a.err_dev, 1u); if (a.err_host) st_agent(a.err_host, 1u); }
+        }
+        SKV_T(9);
+        return;
+    }
 
     // ---- 5. last arrival combines ------------------------------------------------------------------
     // Every wave waits for its own write-through partial stores, then the barrier: only after both does thread 0
@@ -1369,10 +1537,7 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
             }
         }
         const bool empty = !(L > 0.f);                       // every retrieved position was out of range
-        float inv = empty ? 0.f : 1.f / L;
-        if constexpr (MODE == kStep) {
-            if (ld_agent(a.err_dev) != 0u) inv = __builtin_nanf("");      // a block of this launch gave up waiting for scores
-        }
+        const float inv = empty ? 0.f : 1.f / L;
         reinterpret_cast<float2*>(a.out + qhead0 * kHeadDim)[tid] = make_float2(o0 * inv, o1 * inv);
         if (a.lse && (tid % (kHeadDim / 2)) == 0)
             a.lse[qhead0 + tid / (kHeadDim / 2)] = empty ? -INFINITY : (M + log2f(L)) * kLn2;
@@ -1868,20 +2033,27 @@ hipError_t launch_step(Ctx* c, const void* q_score, const void* q_attn, const vo
                        float* lse, int32_t* tok_idx_out, int32_t* n_tok_out, bool* launched) {
     *launched = false;
     const int pairs = v.B * c->d.n_kv_heads;
-    if (pairs < 1 || pairs > c->n_cu || !c->step_counter) return hipSuccess;
+    const int max_blocks = c->n_cu < kStepMaxBlocks ? c->n_cu : kStepMaxBlocks;
+    if (pairs < 1 || pairs > kStepMaxPairs || pairs > max_blocks || c->step_score_stride <= 0) return hipSuccess;
+    if (v.S_total > c->step_score_stride || (int64_t)pairs * c->step_score_stride > c->step_score_words) return hipSuccess;
     int lg = 0;
-    while ((pairs << (lg + 1)) <= c->n_cu && lg + 1 < kStepCounterSlots) ++lg;
+    while ((pairs << (lg + 1)) <= max_blocks) ++lg;
     const int parts = 1 << lg;
-    const int chunk = kAttChunkMid;
-    if ((c->d.max_budget + chunk - 1) / chunk > parts) return hipSuccess;       // the attention blocks of a pair do not fit
+    const int chunk = c->step_chunk;
+    const int att_parts = (c->d.max_budget + chunk - 1) / chunk;
+    if (att_parts > parts || c->G > parts) return hipSuccess;                    // attention blocks or mergers do not fit
     AttArgs a = att_common(c, q_attn, K_layer, V_layer, v, out, lse);
-    a.score = c->f_score; a.score_out = c->f_score; a.sent_off = sent_off; a.sent_len = sent_len;
+    a.sent_off = sent_off; a.sent_len = sent_len;
     a.tok_idx_out = tok_idx_out; a.n_tok_out = n_tok_out; a.idx_stride = c->d.max_budget;
     a.q_score = (const char*)q_score; a.semvec = (const char*)semvec_layer;
     a.sv_bytes = c->d.semvec_dtype == SKV_BF16 ? kTableBf16 : c->d.semvec_dtype == SKV_FP8_E4M3 ? kTableE4m3 : kTableF32;
-    a.lg_parts = lg; a.step_counter = c->step_counter; a.wait_limit = c->wait_limit;
+    a.lg_parts = lg; a.step_epoch = c->step_epoch; a.step_score = c->step_score; a.score_stride = c->step_score_stride;
+    a.step_part = c->step_part; a.wait_limit = c->wait_limit;
     a.err_dev = c->err_dev; a.err_host = c->err_host_dev;
     *launched = true;
+    if (chunk == kAttChunk)
+        return c->d.kv_dtype == SKV_BF16 ? launch_step_g<2, kAttChunk>(c, a, pairs * parts)
+                                         : launch_step_g<4, kAttChunk>(c, a, pairs * parts);
     return c->d.kv_dtype == SKV_BF16 ? launch_step_g<2, kAttChunkMid>(c, a, pairs * parts)
                                      : launch_step_g<4, kAttChunkMid>(c, a, pairs * parts);
 }

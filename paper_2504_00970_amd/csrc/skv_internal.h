@@ -32,8 +32,13 @@ constexpr int kMidChunkMinSentences = 1024;
 constexpr int kAttChunkWide = 256;    // tokens per split-K block when many (sequence, head) pairs fill the GPU
 constexpr int kWideChunkMinHeads = 64;   // (sequences x KV heads) from which the fp32 batch path is used
 constexpr int kComputeUnits = 256;       // MI355X; the context takes the device's own count when it can be read
-constexpr int kStepCounterSlots = 16;    // ticket counters per (sequence, head) pair of the single-launch step: one per log2(blocks per pair)
-constexpr int kStepWaitLimit = 200000;   // default bound on the polls of a block waiting for its pair's scores (a poll is about a microsecond)
+// single-launch decode step: at most kStepMaxPairs (sequence, head) pairs and kStepMaxBlocks blocks per launch
+constexpr int kStepPairBits = 6;
+constexpr int kStepMaxPairs = 1 << kStepPairBits;
+constexpr int kStepMaxBlocks = 256;
+constexpr int kStepEpochStride = 16;     // 32-bit words between the epoch counters of two pairs (one 64-byte line each)
+constexpr int kStepPartWords = kHeadDim + 2;   // 64-bit words per query head of a block's partial: D sums, max, normaliser
+constexpr int kStepWaitLimit = 200000;   // default bound on the polling rounds of a waiting block (a round is about a microsecond)
 // bf16 decode step: the fused kernel's block size (64, 128, 256 tokens) is the smallest whose blocks, (sequence, KV head)
 // pairs x ceil(max_budget / size), all fit the chip at once (one block per compute unit); if even the 256-token blocks do
 // not, the streaming kernel's 512- or 1024-token blocks
@@ -57,11 +62,16 @@ struct Ctx {
     int32_t* f_n_sel;       // [max_batch * Hkv]
     int32_t* f_n_tok;       // [max_batch * Hkv]
     int32_t* f_tok_idx;     // [max_batch * Hkv][max_budget]
-    unsigned int* step_counter;  // [max_batch * Hkv][kStepCounterSlots] ticket counters of the single-launch step; never reset
+    unsigned int* step_epoch;    // [kStepMaxPairs][kStepEpochStride] launches of the single-launch step per pair; never reset
+    unsigned long long* step_score;  // [pairs][step_score_stride] (score, tag) words
+    int32_t step_score_stride;   // words per pair (max_sentences)
+    int64_t step_score_words;    // words in step_score: a launch needs pairs * step_score_stride of them
+    unsigned long long* step_part;   // [kStepMaxBlocks][G][kStepPartWords] (value, tag) words
     unsigned int* err_dev;       // [1] set by a block of the single-launch step that gave up waiting
     unsigned int* err_host;      // the same flag in pinned host memory (host address; null: none)
     unsigned int* err_host_dev;  // device address of err_host
-    int wait_limit;              // polls before a waiting block gives up
+    int wait_limit;              // polling rounds before a waiting block gives up
+    int step_chunk;              // tokens per attention block of the single-launch step (64 or 128)
 };
 
 // Ragged-batch view handed to the decode kernels.  For single-sequence calls cu_tok / cu_sent /
