@@ -52,8 +52,10 @@ typedef struct {
     int32_t kv_dtype;       /* skv_dtype of K, V and the queries */
     int32_t max_tokens;     /* largest T (T_total for a ragged batch) any call will pass */
     int32_t max_sentences;  /* largest S (S_total for a ragged batch) any call will pass */
-    int32_t max_budget;     /* largest per-sequence token budget tau any call will pass; skv_decode_step sizes its grid and
-                               picks its block size from this value, so keep it close to the budgets in use */
+    int32_t max_budget;     /* largest per-sequence token budget tau any call will pass.  skv_decode_step sizes its grid and
+                               picks its kernel from this value, not from the budgets of a call (see there): a context
+                               made for 8192 runs a 2048-token step in larger blocks than a context made for 2048 would
+                               (measured: up to 2x slower for one sequence), so keep it close to the budgets in use */
     int32_t max_batch;      /* largest number of sequences in one skv_decode_step (>= 1, <= 4096, max_batch * Hkv <= 65535) */
     int32_t semvec_dtype;   /* skv_dtype of the semantic-vector table: SKV_F32, or SKV_BF16 / SKV_FP8_E4M3 = the fp32 mean
                                rounded once to nearest even (the mixed-precision sentence vectors of the paper's "Future
@@ -73,11 +75,12 @@ const char* skv_strerror(int status);
 /* Bytes of device workspace the context holds (0 for a NULL context). */
 int64_t skv_workspace_bytes(const skv_ctx* ctx);
 /* skv_decode_step with few (sequence, head) pairs runs as ONE launch whose blocks wait, inside the kernel, for the bucket
- * scores the other blocks of their pair compute (see skv_decode_step).  The wait is bounded: `polls` is the number of
- * times a block looks at its pair's arrival counter before it gives up (about a microsecond each; default 200000;
- * 0 makes every block that is not the last of its pair to arrive give up at once: the kernel still ends normally).
- * A give-up turns the outputs of that call into NaN and makes every later skv_decode_step on the context return
- * SKV_EHIP until this function is called again, which also clears the condition (it waits for the stream).
+ * scores and the partial attention results that the other blocks of their pair produce (see skv_decode_step).  Every
+ * such wait is bounded: `polls` is the number of times a thread reads the words it waits for before it gives up (a
+ * read takes about a microsecond; default 200000; with 0 nothing is read and every waiting block gives up at once: the
+ * kernel still ends normally).  A give-up turns the outputs of that call into NaN and makes every later skv_decode_step
+ * on the context return SKV_EHIP until this function is called again, which also clears the condition (it waits for
+ * the stream).
  * Errors: SKV_EINVAL (NULL context, polls < 0). */
 int skv_set_wait_limit(skv_ctx* ctx, int32_t polls);
 
@@ -187,8 +190,8 @@ int skv_score(skv_ctx* ctx, int32_t layer, const void* q_score, const void* semv
 int skv_select(skv_ctx* ctx, const float* score, const int32_t* sent_off, const int32_t* sent_len, int32_t S,
                int32_t budget, int32_t* sel_sent, int32_t* n_sel, int32_t* tok_idx, int32_t* n_tok);
 
-/* (4) Alg. 1 decode "load keys and values of the corresponding tokens": K_sel[h][j][:] =
- * K_pool[layer][h][tok_idx[h][j]][:] for j < n_tok[h], same for V.  Rows j >= n_tok[h] are not written.
+/* (4) Alg. 1, decoding phase, the K/V load step: K_sel[h][j][:] = K_pool[layer][h][tok_idx[h][j]][:] for
+ * j < n_tok[h], same for V.  Rows j >= n_tok[h] are not written.
  * K_pool, V_pool  [L][Hkv][T][D] kv_dtype, in HBM (pool_in_host == 0) or in pinned, device-mapped host
  *                 memory (pool_in_host == 1: the paper's CPU-offloaded store; the kernel reads it over
  *                 PCIe and the pointer passed is the host pointer).
@@ -198,8 +201,11 @@ int skv_gather(skv_ctx* ctx, int32_t layer, const void* K_pool, const void* V_po
                const int32_t* tok_idx, const int32_t* n_tok, int32_t budget, void* K_sel, void* V_sel);
 
 /* (5) Eq. 3: out[j] = softmax(q_attn[j] K_sel[h]^T / sqrt(D)) V_sel[h] over the first n_tok[h] rows,
- * h = j / G; fp32 softmax and accumulation; lse[j] = log sum_i exp(logit_i) (natural log).
- * n_tok[h] == 0 gives out = 0 and lse = -inf.
+ * h = j / G; lse[j] = log sum_i exp(logit_i) (natural log).  n_tok[h] == 0 gives out = 0 and lse = -inf.
+ * Arithmetic: logits, maxima, normalisers and all sums are fp32.  With fp32 K/V the softmax weights stay fp32.  With
+ * bf16 K/V the products run on the matrix cores: the weights exp(logit - max) are rounded to bf16 (nearest even)
+ * before P.V, and the normaliser sums those rounded weights, so out is exactly the weighted mean the rounded weights
+ * define (max-abs error against fp32 weights below 2e-2 for unit-variance values; the same holds for skv_decode_step).
  * q_attn dev [Hq][D] kv_dtype;  K_sel, V_sel dev [Hkv][budget][D];  out dev [Hq][D] fp32;
  * lse dev [Hq] fp32 or NULL. */
 int skv_attend(skv_ctx* ctx, const void* q_attn, const void* K_sel, const void* V_sel, const int32_t* n_tok,
@@ -210,9 +216,17 @@ int skv_attend(skv_ctx* ctx, const void* q_attn, const void* K_sel, const void* 
  * batch of B sequences concatenated along the token axis and the bucket axis.  The retrieved tokens
  * are read straight from the HBM pool (no K_sel/V_sel copy).  Results equal skv_score + skv_select +
  * skv_gather + skv_attend run per sequence: the selection bit for bit, out / lse up to the order of the
- * floating-point sums.  For bf16 pools that order can depend on how the hardware schedules a block's waves (the
- * streaming kernel, chosen when the 256-token blocks of the whole call, B * Hkv * ceil(max_budget / 256), outnumber
- * the compute units), so the last bits of out / lse can differ between two identical calls.
+ * floating-point sums.
+ * Launches per call (P = B * Hkv pairs of sequence and KV head, all sizes from the descriptor's max_budget):
+ *   - ONE, when P <= 64 and the 128-token attention blocks of the call, P * ceil(max_budget / 128), fit the compute
+ *     units (256) at once: P * 2^k blocks (the largest power of two that fits) first score the buckets of their pair
+ *     between them, pass the scores and later the partial attention results to each other inside the kernel, select
+ *     and attend.  The waits inside the kernel are bounded, see skv_set_wait_limit;
+ *   - TWO otherwise for bf16 pools (scores; selection + attention in 256-token blocks, or in streaming blocks of 512,
+ *     1024 or 2048 tokens when P * ceil(max_budget / 256) exceeds the compute units);
+ *   - THREE for fp32 pools with P >= 64 (scores; selection; attention through the positions).
+ * In the streaming kernel the order of the floating-point sums can depend on how the hardware schedules a block's
+ * waves, so the last bits of out / lse can differ between two identical calls; all other forms are reproducible.
  * q_score, q_attn  dev [B][Hq][D] kv_dtype (may alias)
  * K_pool, V_pool   dev [L][Hkv][T_total][D]        semvec dev [L][Hkv][S_total][D]
  * cu_tok   dev [B+1]  token offset of each sequence in the pool (cu_tok[0] == 0, cu_tok[B] == T_total)

@@ -23,7 +23,7 @@
  *   skvo_score    S(q-bar, k-bar_{s,h}) = q-bar^T k-bar_{s,h}   (Sec. 4.2 "Semantic similarity and token retrieval")
  *   skvo_select   rank buckets by score, take whole buckets in descending order until the token
  *                 budget tau is reached                        (Sec. 4.2; App. "Effect of Sentence Length")
- *   skvo_gather   K_tau, V_tau = rows of the selected tokens    (Sec. 4.2 "loaded ... back to the GPU"; Alg. 1)
+ *   skvo_gather   K_tau, V_tau = rows of the selected tokens    (Sec. 4.2 retrieval; Alg. 1, decoding phase, K/V load step)
  *   skvo_attend   O = softmax(q K_tau^T / sqrt(d)) V_tau        (Eq. 3)
  *   skvo_merge_lse  Eq. 3 over the union of two disjoint token sets from the two partial results
  *
@@ -361,7 +361,7 @@ void skvo_retain(const float* alpha, int32_t Tp, int32_t k, const int32_t* seg_i
     free(order);
 }
 
-/* Alg. 1 decode "load keys and values of the corresponding tokens": row copy.
+/* Alg. 1, decoding phase, the K/V load step: row copy.
  * pool is one layer [Hkv][T][D]; dst is [Hkv][budget_stride][D]; rows >= n_tok[h] are left untouched. */
 void skvo_gather(const void* pool, int dtype, int32_t Hkv, int32_t T, int32_t D,
                  const int32_t* tok_idx, int32_t budget_stride, const int32_t* n_tok, void* dst) {

@@ -31,7 +31,8 @@ struct Seq {
     int32_t budget;
 };
 
-// Read of an int32 array that no kernel of this library writes (the caller's cu_tok, cu_sent, budgets, n_tok), through
+// Read of an int32 array that the running launch does not write (the caller's cu_tok, cu_sent, budgets; n_tok, which an
+// earlier launch of the same call may have written), through
 // the constant address space: with a wave-uniform index it is a scalar load whatever else the kernel contains (loads of
 // a plain global pointer turn into vector loads once the compiler cannot prove that the kernel leaves the memory alone,
 // which an inline asm statement is enough to cause).
@@ -160,6 +161,13 @@ __device__ __forceinline__ float val_of(unsigned long long w) { return __uint_as
 // Barrier behind which another thread of the block publishes what this block has stored (an arrival counter).  The
 // workgroup barrier by itself does not wait for a wave's outstanding global stores (the waves of a block share their CU's
 // cache, so the compiler leaves the store counter alone at workgroup scope): each wave waits for its own first.
+// ASSUMPTION (of the kernels that publish with a counter: skv_attend, the two- and three-launch forms of
+// skv_decode_step): a device-scope relaxed atomic store that has left the store counter (vmcnt == 0) has reached the
+// level all XCDs share, so a device-scope relaxed load issued by any block after it observed the later counter
+// increment returns the stored value.  The language's memory model does not promise this for relaxed accesses to
+// different locations; it is how write-through stores and the store counter behave on this chip, and it is guarded by
+// test_repeated_launches_reproduce_their_results.  The single-launch step does not rely on it: there every word
+// carries its own validity tag (st_tagged).
 __device__ __forceinline__ void block_sync_after_stores() {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
@@ -507,7 +515,7 @@ struct SelectShared {
 // computed when COUNT is set, else 0).  Every thread of the block must call this; *n_sel_out /
 // *n_tok_out are block-uniform.
 // TAGGED: `sc` points at 64-bit (score, tag) words that other blocks of the same launch are writing; every thread reads
-// its words again and again until they carry `tag` (at most wait_limit + 1 times: *ok_out tells whether they all
+// its words again and again until they carry `tag` (at most wait_limit times: *ok_out tells whether they all
 // arrived; if not, the selection is made from whatever was read and is meaningless).
 template <int KREG, bool COUNT, bool TAGGED, typename Emit>
 __device__ __forceinline__ void select_block(const float* __restrict__ sc, const int32_t* __restrict__ len,
@@ -576,7 +584,9 @@ __device__ __forceinline__ void select_block(const float* __restrict__ sc, const
         // the keys reach their owners through LDS.
         bool mine = false;
         uint32_t kk[KREG];
-        for (int32_t round = 0; !mine && round <= wait_limit; ++round) {
+#pragma unroll
+        for (int i = 0; i < KREG; ++i) kk[i] = 0u;
+        for (int32_t round = 0; !mine && round < wait_limit; ++round) {
             mine = true;
 #pragma unroll
             for (int i = 0; i < KREG; ++i) {
@@ -1398,9 +1408,9 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
         float M = -INFINITY, L = 0.f, o = 0.f;
         bool ok = step_ok;
         for (int base = 0; base < nsplit && ok; base += 4 * kGroups8) {
-            unsigned long long pv[4], mv[4], lv[4];
+            unsigned long long pv[4] = {0, 0, 0, 0}, mv[4] = {0, 0, 0, 0}, lv[4] = {0, 0, 0, 0};
             bool mine = false;
-            for (int32_t round = 0; !mine && round <= a.wait_limit; ++round) {
+            for (int32_t round = 0; !mine && round < a.wait_limit; ++round) {
                 mine = true;
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
@@ -1417,7 +1427,7 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
             ok = mine;
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                if (base + grp + u * kGroups8 < nsplit) {
+                if (ok && base + grp + u * kGroups8 < nsplit) {
                     const float ms = val_of(mv[u]);
                     if (ms > -INFINITY) {
                         const float nm = fmaxf(M, ms);

@@ -88,3 +88,47 @@ def test_decode_entry_point_errors(env):
     assert lib.skv_attend(h, p, p, p, p, 65, p, None) == skv.SKV_ECAPACITY
     assert lib.skv_decode_step(h, 0, 3, p, p, p, p, 100, p, 10, p, p, p, p, p, p, None, None, None) == skv.SKV_ECAPACITY
     assert lib.skv_decode_step(h, 0, 1, p, p, p, p, 100, p, 10, None, p, p, p, p, p, None, None, None) == skv.SKV_EINVAL
+
+
+def test_single_launch_step_gives_up_cleanly_and_recovers():
+    """The single-launch decode step with a wait limit of zero: every block that waits for another block's words gives up
+    at once (the host forces the condition; the kernel itself ends normally), the outputs are NaN, the next step on the
+    context reports SKV_EHIP, and skv_set_wait_limit clears the condition: the same step then equals a fresh context's."""
+    import numpy as np
+    from workload import gen
+    import gpu_util as U
+    wl = gen.CFG1.scaled(n_layers=1, batch=1, t_range=(6000, 6000), budgets=(512,))
+    inp = gen.ragged_inputs(wl, seed=11, device=DEV, resident_layers=1)
+    H, Hq, D = wl.n_kv_heads, wl.n_q_heads, wl.head_dim
+    T, S = int(inp.cu_tok[-1]), int(inp.cu_sent[-1])
+    d = [U.i32(x) for x in (inp.cu_tok, inp.cu_sent, inp.sent_off, inp.sent_len, inp.budget)]
+
+    def fresh():
+        c = U.make_ctx(wl, T, S, 512)
+        sv = torch.zeros(1, H, S, D, device=DEV)
+        c.build_semvec(inp.K, U.i32(gen.offsets_of(inp.sent_len)), S, sv)
+        return c, sv
+
+    def step(c, sv, out, n_tok):
+        c.decode_step(0, 1, inp.q[0], inp.q[0], inp.K, inp.V, T, sv, S, *d, out, None, None, n_tok)
+        torch.cuda.synchronize()
+
+    ref_ctx, sv = fresh()
+    ref, ref_n = torch.zeros(1, Hq, D, device=DEV), U.empty_i32(1, H, fill=-1)
+    step(ref_ctx, sv, ref, ref_n)
+    assert bool(torch.isfinite(ref).all())
+
+    ctx, sv2 = fresh()
+    ctx.set_wait_limit(0)
+    out, n_tok = torch.zeros(1, Hq, D, device=DEV), U.empty_i32(1, H, fill=-1)
+    print("decode step with a wait limit of zero", flush=True)
+    step(ctx, sv2, out, n_tok)                               # runs to its end; every waiting block gave up
+    assert bool(torch.isnan(out).all())
+    with pytest.raises(skv.SkvError) as e:                   # the give-up is reported by the next call
+        step(ctx, sv2, out, n_tok)
+    assert e.value.status == skv.SKV_EHIP
+    ctx.set_wait_limit(200000)                               # clears the condition
+    step(ctx, sv2, out, n_tok)
+    assert torch.equal(out, ref) and torch.equal(n_tok, ref_n)
+    step(ctx, sv2, out, n_tok)
+    assert torch.equal(out, ref)
