@@ -7,8 +7,11 @@ from the HBM pool).  The prefill side (segmentation + mean key vectors) runs onc
 region and is timed separately.  Inputs are synthetic and resident in HBM before timing starts.
 
 Prints ONE JSON line:  metric / value = achieved HBM GB/s of the decode step (algorithmic bytes of
-the fused path over wall time), us_per_layer, per-kernel live timings, the roofline of the
-attention kernel, and the CPU oracle timed on a bounded sample of the same workload.
+the fused path over wall time) for cfg1 (32K context, one sequence), us_per_layer, live timings of the
+four stand-alone kernels, the roofline of the kernel the timed step runs (one launch per layer), the CPU
+oracle timed on a bounded sample of the same workload (one thread, and all cores), and under "extras" the
+same measurement for cfg2 (128K context; host-pool gather separately) and cfg4 (ragged batch), under
+"batched" for 16 and 64 sequences of cfg1's shape.
 """
 from __future__ import annotations
 
@@ -229,10 +232,17 @@ def run_single_sequence(args, wl, budget):
     b_unf = decode_bytes(wl, S, nt_chain, nt_chain / float(lengths.mean()), fused=False, sv_bytes=sv_bytes)
     kernels = {k: dict(us=round(v, 3), bytes=int(b_unf[k]), GBps=round(b_unf[k] / (v * 1e-6) / 1e9, 1))
                for k, v in kern.items()}
-    att = kernels["attend"]
-    roofline = dict(bound="hbm", kernel="attend_kernel", achieved=att["GBps"], peak=HBM_PEAK_GBPS, unit="GB/s",
-                    frac=round(att["GBps"] / HBM_PEAK_GBPS, 4), traffic=measured_traffic(wl.name, "attend_kernel"),
-                    bytes_per_launch=att["bytes"], us_per_launch=att["us"])
+    # The timed step is ONE kernel per layer (attend_kernel in its single-launch form: scores, selection and attention
+    # of the layer), so the dominant kernel's launch is the layer: its algorithmic bytes are the step's, its duration
+    # the per-layer time of the timed region (launch to launch, HIP events on the launching stream).
+    copy_peak = measured_copy_peak(dev)
+    roofline = dict(bound="hbm", kernel="attend_kernel<bf16, G, single-launch step, 128-token blocks>" if wl.dtype == "bf16"
+                    else "attend_kernel<fp32, G, single-launch step, 128-token blocks>",
+                    achieved=round(gbps, 1), peak=HBM_PEAK_GBPS, unit="GB/s", frac=round(gbps / HBM_PEAK_GBPS, 4),
+                    traffic=None if sv16 else measured_traffic(wl.name, "decode_step_kernel"),
+                    bytes_per_launch=int(bytes_layer["total"]), us_per_launch=round(us_per_layer, 3),
+                    launches_per_layer=1, measured_copy_peak_GBps=round(copy_peak, 1),
+                    frac_of_measured_copy_peak=round(gbps / copy_peak, 4))
 
     cpu = cpu_baseline(args, wl, inp, semvec, lengths, qsets, budget) if not args.no_cpu_baseline else None
     host_pool = host_pool_gather(args, wl, ctx, inp, tok_idx, n_tok, budget, K_sel) if args.host_pool_layers > 0 else None
@@ -243,7 +253,7 @@ def run_single_sequence(args, wl, budget):
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "layers": L, "layer_passes_per_step": passes, "q_heads": Hq, "kv_heads": H, "head_dim": D, "context": T,
-                   "sentences": S, "budget": budget, "batch": 1, "path": "skv_decode_step (score+select+attend from pool)",
+                   "sentences": S, "budget": budget, "batch": 1, "path": "skv_decode_step (score+select+attend from pool, one launch per layer)",
                    "kv_pool": "hbm", "launch": args.launch, "semvec_dtype": args.semvec_dtype},
         "us_per_layer": round(us_per_layer, 3),
         "us_per_layer_direct_launch": round(ms_direct * 1e3 / (L * passes), 3),
@@ -673,10 +683,44 @@ def cpu_baseline(args, wl, inp, semvec, lengths, qsets, budget):
             break
     us_layer = t_total / done * 1e6
     b = decode_bytes(wl, len(lengths), n_tok_sum / done, n_tok_sum / done / float(lengths.mean()), fused=True)
-    return {"value": round(b["total"] / (us_layer * 1e-6) / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "us_per_layer": round(us_layer, 1),
-            "sample": "%d layer-steps of the same workload (layers 0..%d, query set 0), score+select+gather+attend, "
-                      "single thread, fp32" % (done, n_layers - 1)}
+    res = {"value": round(b["total"] / (us_layer * 1e-6) / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+           "us_per_layer": round(us_layer, 1),
+           "sample": "%d layer-steps of the same workload (layers 0..%d, query set 0), score+select+gather+attend, "
+                     "single thread, fp32" % (done, n_layers - 1)}
+    # The same oracle calls on all host cores of the box's share: independent layers side by side, one call per thread
+    # (the C library runs outside the interpreter lock).  Nothing in the oracle is tuned for this.
+    from concurrent.futures import ThreadPoolExecutor
+    threads = max(1, min(16, os.cpu_count() or 1, n_layers))
+    budget_s = max(2.0, args.cpu_seconds / 2)
+
+    def one(l):
+        orc.decode_step(qh[l], qh[l], Kh[l], Vh[l], svh[l], off, lengths, budget)
+
+    done_p, t0 = 0, time.perf_counter()
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        while True:
+            list(pool.map(one, range(n_layers)))
+            done_p += n_layers
+            if time.perf_counter() - t0 > budget_s:
+                break
+    us_layer_p = (time.perf_counter() - t0) / done_p * 1e6
+    res["all_cores"] = {"value": round(b["total"] / (us_layer_p * 1e-6) / 1e9, 4), "unit": "GB/s", "cores": threads,
+                        "us_per_layer": round(us_layer_p, 1),
+                        "sample": "%d layer-steps, %d threads each running whole layers of the same workload" % (done_p, threads)}
+    return res
+
+
+def measured_copy_peak(dev="cuda:0", mib=1024, reps=5):
+    """Device-to-device copy rate of this GPU (a library copy kernel on 1 GiB: bytes read + bytes written per second),
+    the achievable yardstick beside the datasheet figure."""
+    src = torch.empty(mib << 20, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    with Timer() as t:
+        for _ in range(reps):
+            dst.copy_(src)
+    return 2.0 * reps * (mib << 20) / (t.ms * 1e-3) / 1e9
 
 
 def main():
@@ -701,6 +745,8 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--cpu-layers", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="cfg1: skip the cfg2 (128K) and cfg4 (ragged batch) measurements reported under \"extras\"")
     ap.add_argument("--phase-stamps", action="store_true",
                     help="decode workloads: load the profiling build (python -m paper_2504_00970_amd._build --stamps) and "
                          "print where the blocks of the step's last kernel spend their time instead of the benchmark line")
@@ -743,11 +789,11 @@ def main():
         res = run_ragged(args, wl)
     else:
         res = run_single_sequence(args, wl, args.budget or max(wl.budgets))
+        import copy
         sizes = [int(x) for x in args.batched_sequences.split(",") if x.strip()] if args.workload == "cfg1" else []
         for Bs in [b for b in sizes if b > 1]:
             # the same step for a batch of sequences of the same context, each with its own buckets: what the kernels reach
             # once a launch has enough work (reported extras, never `value`)
-            import copy
             a2 = copy.copy(args)
             a2.steps, a2.warmup, a2.no_cpu_baseline = min(args.steps, 10), min(args.warmup, 2), True
             wb = wl.scaled(name="%s_x%d" % (wl.name, Bs), batch=Bs, t_range=(wl.n_tokens, wl.n_tokens),
@@ -757,6 +803,32 @@ def main():
                 {"workload": wb.name, "sequences": Bs, "us_per_layer": rb["us_per_layer"], "value": rb["value"],
                  "unit": rb["unit"], "hbm_frac": rb["hbm_frac"], "bytes_per_layer": rb["bytes_per_layer"],
                  "resident_layers": args.resident_layers, "steps": a2.steps})
+            torch.cuda.empty_cache()
+        if args.workload == "cfg1" and not args.no_extras:
+            # The other configurations the target names, each measured like the headline (never `value`): the 128K
+            # context (pool in HBM; the gather from a pinned host pool separately) and the ragged 70B-shaped batch.
+            res["extras"] = []
+            a2 = copy.copy(args)
+            a2.steps, a2.warmup, a2.no_cpu_baseline, a2.host_pool_layers = min(args.steps, 10), min(args.warmup, 2), True, 2
+            torch.cuda.empty_cache()
+            r2 = run_single_sequence(a2, gen.CONFIGS["cfg2"], max(gen.CONFIGS["cfg2"].budgets))
+            res["extras"].append({"workload": r2["config"]["workload"], "context": r2["config"]["context"],
+                                  "sentences": r2["config"]["sentences"], "budget": r2["config"]["budget"], "kv_pool": "hbm",
+                                  "us_per_layer": r2["us_per_layer"], "value": r2["value"], "unit": r2["unit"],
+                                  "hbm_frac": r2["hbm_frac"], "bytes_per_layer": r2["bytes_per_layer"], "steps": a2.steps,
+                                  "frac_of_measured_copy_peak": r2["roofline"]["frac_of_measured_copy_peak"],
+                                  "host_pool_gather": r2["host_pool_gather"]})
+            del r2
+            torch.cuda.empty_cache()
+            a4 = copy.copy(a2)
+            a4.steps = min(args.steps, 5)
+            r4 = run_ragged(a4, gen.CONFIGS["cfg4"])
+            res["extras"].append({"workload": r4["config"]["workload"], "sequences": r4["config"]["batch"],
+                                  "tokens_total": r4["config"]["tokens_total"], "budget": r4["config"]["budget"],
+                                  "resident_layers": r4["config"]["resident_layers"], "us_per_layer": r4["us_per_layer"],
+                                  "value": r4["value"], "unit": r4["unit"], "hbm_frac": r4["hbm_frac"],
+                                  "bytes_per_layer": r4["bytes_per_layer"], "steps": a4.steps,
+                                  "launches_per_layer": 2})
             torch.cuda.empty_cache()
     res["host"] = {"nproc": os.cpu_count()}
     print(json.dumps(res), flush=True)
