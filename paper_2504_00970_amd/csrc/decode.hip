@@ -579,36 +579,51 @@ __device__ __forceinline__ void select_block(const float* __restrict__ sc, const
     if (TAGGED) {
         // Every thread reads its own words until all of them carry the tag (bounded), without talking to anyone; the
         // block meets at one barrier afterwards.  A thread whose wait ran out raises the block's flag.
-        // The words are read with consecutive lanes on consecutive words (thread t: words t, t + 1024, ...: whole cache
-        // lines per wave instruction; a thread's own consecutive buckets would cost kpt times the memory requests), and
-        // the keys reach their owners through LDS.
+        const bool strided = kpt <= KREG;                  // every bucket of the pair is held in registers
         bool mine = false;
-        uint32_t kk[KREG];
+        if (strided) {
+            // The words are read with consecutive lanes on consecutive words (thread t: words t, t + 1024, ...: whole
+            // cache lines per wave instruction; a thread's own consecutive buckets would cost kpt times the memory
+            // requests), and the keys reach their owners through LDS.
+            uint32_t kk[KREG];
 #pragma unroll
-        for (int i = 0; i < KREG; ++i) kk[i] = 0u;
-        for (int32_t round = 0; !mine && round < wait_limit; ++round) {
-            mine = true;
+            for (int i = 0; i < KREG; ++i) kk[i] = 0u;
+            for (int32_t round = 0; !mine && round < wait_limit; ++round) {
+                mine = true;
 #pragma unroll
-            for (int i = 0; i < KREG; ++i) {
-                if (i < kpt) {
-                    const int32_t sidx = min(i * kBlockThreads + tid, S - 1);
-                    const unsigned long long wd = ld_tagged(tw + sidx);
-                    kk[i] = (uint32_t)wd;
-                    mine = mine && tag_of(wd) == tag;
+                for (int i = 0; i < KREG; ++i) {
+                    if (i < kpt) {
+                        const int32_t sidx = min(i * kBlockThreads + tid, S - 1);
+                        const unsigned long long wd = ld_tagged(tw + sidx);
+                        kk[i] = (uint32_t)wd;
+                        mine = mine && tag_of(wd) == tag;
+                    }
                 }
             }
-            for (int i = KREG; i < kpt; ++i)               // buckets beyond the registers are re-read in every phase below
-                if (s0 + i < S) mine = mine && tag_of(ld_tagged(tw + s0 + i)) == tag;
-        }
 #pragma unroll
-        for (int i = 0; i < KREG; ++i)
-            if (i < kpt) key_lds[i * kBlockThreads + tid] = kk[i];
+            for (int i = 0; i < KREG; ++i)
+                if (i < kpt) key_lds[i * kBlockThreads + tid] = kk[i];
+        } else {
+            for (int32_t round = 0; !mine && round < wait_limit; ++round) {
+                mine = true;
+#pragma unroll
+                for (int i = 0; i < KREG; ++i) {
+                    const unsigned long long wd = ld_tagged(tw + min(s0 + i, S - 1));
+                    rkey[i] = (uint32_t)wd;
+                    mine = mine && tag_of(wd) == tag;
+                }
+                for (int i = KREG; i < kpt; ++i)           // buckets beyond the registers are re-read in every phase below
+                    if (s0 + i < S) mine = mine && tag_of(ld_tagged(tw + s0 + i)) == tag;
+            }
+        }
         if (!mine) sh.poll[0] = 1;
         __syncthreads();
         if (sh.poll[0] != 0 && ok_out) *ok_out = false;
+        if (strided) {
 #pragma unroll
-        for (int i = 0; i < KREG; ++i)
-            if (i < kpt) rkey[i] = key_lds[min(s0 + i, KREG * kBlockThreads - 1)];
+            for (int i = 0; i < KREG; ++i)
+                if (i < kpt) rkey[i] = key_lds[s0 + i];    // s0 + i < kpt * 1024 <= KREG * 1024
+        }
     }
 #pragma unroll
     for (int i = 0; i < KREG; ++i) {

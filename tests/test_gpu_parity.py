@@ -679,6 +679,8 @@ def test_fused_many_buckets_per_sequence(U, oracle32, dtype, B):
     _fused_case(U, oracle32, wl, seed=42, layers=[0])          # few, long buckets: S small, 64-token blocks; long spans
     wl = gen.CFG1.scaled(n_layers=1, batch=B, t_range=(40000, 40100), budgets=(1000,), len_dist=("uniform", 1, 30), dtype=dtype)
     _fused_case(U, oracle32, wl, seed=43, layers=[0])          # S > 2048 with buckets that span the 64-position pieces
+    wl = gen.CFG1.scaled(n_layers=1, batch=B, t_range=(16000, 16500), budgets=(600,), len_dist=("uniform", 1, 3), dtype=dtype)
+    _fused_case(U, oracle32, wl, seed=44, layers=[0])          # S > 6144: buckets beyond the six a thread keeps in registers
 
 
 # ----------------------------------------------------------------------------- seeded sweeps over shapes
