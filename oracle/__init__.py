@@ -17,7 +17,10 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "sentencekv_oracle.c")
-_BUILD = os.path.join(_HERE, "_build")
+# SKVO_SANITIZE=1 in the environment selects an AddressSanitizer + UndefinedBehaviorSanitizer build of the same source
+# (its own folder; the process must have the ASan runtime preloaded, see tests/test_oracle_sanitized.py)
+_SANITIZE = os.environ.get("SKVO_SANITIZE", "") == "1"
+_BUILD = os.path.join(_HERE, "_build_san" if _SANITIZE else "_build")
 
 F32, BF16, FP8 = 0, 1, 2
 
@@ -33,7 +36,8 @@ def build(force: bool = False) -> None:
         out = lib_path(real)
         if not force and os.path.exists(out) and os.path.getmtime(out) >= os.path.getmtime(_SRC):
             continue
-        cmd = ["gcc", "-std=c99", "-O2", "-ffp-contract=off", "-fno-fast-math", "-Wall", "-Wextra",
+        opt = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined", "-fno-sanitize-recover=all"] if _SANITIZE else ["-O2"]
+        cmd = ["gcc", "-std=c99", *opt, "-ffp-contract=off", "-fno-fast-math", "-Wall", "-Wextra",
                f"-DSKVO_REAL={ctype}", "-shared", "-fPIC", _SRC, "-o", out, "-lm"]
         subprocess.run(cmd, check=True)
 
