@@ -655,6 +655,39 @@ def run_phase_stamps(args, wl, budget):
             "note": "us since the first block start of the launch; thread 0 of every block; kernel = the last launch of skv_decode_step"}
 
 
+def run_launch_floor(args):
+    """What a dependent chain of near-empty kernels costs on this GPU: 32 "layers" of 1, 2 or 3 launches of the library's
+    smallest kernel (skv_merge_lse on one head: 64 threads, 1 KB) replayed as a HIP graph, and launched directly.  The
+    decode step of one sequence cannot be faster per layer than the chain with as many launches per layer."""
+    dev = "cuda:0"
+    ctx = skv.Context(skv.Desc(n_layers=1, n_q_heads=8, n_kv_heads=8, kv_dtype=skv.SKV_BF16, max_tokens=64, max_sentences=8,
+                               max_budget=16, max_batch=1))
+    a, b, o = (torch.zeros(8, 128, device=dev) for _ in range(3))
+    la, lb, lo = (torch.zeros(8, device=dev) for _ in range(3))
+    L, rows = 32, []
+    for per_layer in (1, 2, 3):
+        def chain():
+            for _ in range(L * per_layer):
+                ctx.merge_lse(1, a, la, b, lb, o, lo)
+        chain()
+        g = capture(ctx, chain)
+        res = {}
+        for name, fn in (("graph", g.replay), ("direct", chain)):
+            for _ in range(5):
+                fn()
+            torch.cuda.synchronize()
+            reps = max(args.steps, 20)
+            with Timer() as t:
+                for _ in range(reps):
+                    fn()
+            res[name] = t.ms * 1e3 / (reps * L)
+        rows.append({"launches_per_layer": per_layer, "us_per_layer_hip_graph": round(res["graph"], 3),
+                     "us_per_layer_direct_launch": round(res["direct"], 3),
+                     "us_per_launch_hip_graph": round(res["graph"] / per_layer, 3)})
+    return {"metric": "launch floor: dependent chain of near-empty kernels", "unit": "us/layer", "layers": L,
+            "kernel": "merge_lse_kernel (1 head, 64 threads)", "rows": rows}
+
+
 def _ctx_name(T):
     return "%dk" % (T // 1024) if T % 1024 == 0 else str(T)
 
@@ -728,7 +761,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg3-retain", "cfg4"])
+    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg3-retain", "cfg4", "floor"])
     ap.add_argument("--window", type=int, default=32, help="cfg3-retain: observation-window tokens")
     ap.add_argument("--keep", type=int, default=4096, help="cfg3-retain: tokens retained per layer (floor(r tau))")
     ap.add_argument("--resident-layers", type=int, default=4, help="cfg4: layers of the pool kept in HBM")
@@ -767,6 +800,9 @@ def main():
             print("no profiling build: run `python -m paper_2504_00970_amd._build --stamps` first", file=sys.stderr)
             sys.exit(2)
         _build.LIB = _build.LIB_STAMPS
+    if args.workload == "floor":
+        print(json.dumps(run_launch_floor(args)), flush=True)
+        return
     retain = args.workload == "cfg3-retain"
     wl = gen.CONFIGS["cfg3" if retain else args.workload]
     if args.batch > 0 and args.workload == "cfg4":
