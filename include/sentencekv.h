@@ -55,7 +55,8 @@ typedef struct {
     int32_t max_budget;     /* largest per-sequence token budget tau any call will pass.  skv_decode_step sizes its grid and
                                picks its kernel from this value, not from the budgets of a call (see there): a context
                                made for 8192 runs a 2048-token step in larger blocks than a context made for 2048 would
-                               (measured: up to 2x slower for one sequence), so keep it close to the budgets in use */
+                               (measured: up to 2x slower for one sequence), so keep it close to the budgets in use, or
+                               tell the context the budgets in use with skv_set_budget_hint */
     int32_t max_batch;      /* largest number of sequences in one skv_decode_step (>= 1, <= 4096, max_batch * Hkv <= 65535) */
     int32_t semvec_dtype;   /* skv_dtype of the semantic-vector table: SKV_F32, or SKV_BF16 / SKV_FP8_E4M3 = the fp32 mean
                                rounded once to nearest even (the mixed-precision sentence vectors of the paper's "Future
@@ -74,6 +75,13 @@ int skv_set_stream(skv_ctx* ctx, void* hip_stream);
 const char* skv_strerror(int status);
 /* Bytes of device workspace the context holds (0 for a NULL context). */
 int64_t skv_workspace_bytes(const skv_ctx* ctx);
+/* skv_decode_step plans its launches (kernel, block size, grid) for the largest budget it may meet.  That is the
+ * descriptor's max_budget unless the caller gives a tighter bound here: `budget` = the largest per-sequence budget the
+ * following skv_decode_step calls on this context will use (0 restores max_budget).  Budgets above the hint are
+ * treated as the hint.  Array shapes (tok_idx_out is [B][Hkv][max_budget]) do not change.  A context created for
+ * max_budget = 8192 and hinted 2048 runs a 2048-token step exactly as a context created for 2048 does.
+ * Errors: SKV_EINVAL (NULL context, budget < 0), SKV_ECAPACITY (budget > max_budget). */
+int skv_set_budget_hint(skv_ctx* ctx, int32_t budget);
 /* skv_decode_step with few (sequence, head) pairs runs as ONE launch whose blocks wait, inside the kernel, for the bucket
  * scores and the partial attention results that the other blocks of their pair produce (see skv_decode_step).  Every
  * such wait is bounded: `polls` is the number of times a thread reads the words it waits for before it gives up (a

@@ -40,6 +40,7 @@ _SIGNATURES = {
     "skv_strerror": (ctypes.c_char_p, [_int]),
     "skv_workspace_bytes": (_i64, [_vp]),
     "skv_set_wait_limit": (_int, [_vp, _i32]),
+    "skv_set_budget_hint": (_int, [_vp, _i32]),
     "skv_segment": (_int, [_vp, _vp, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _vp]),
     "skv_build_semvec": (_int, [_vp, _vp, _i32, _vp, _i32, _vp]),
     "skv_build_semvec_layers": (_int, [_vp, _vp, _i32, _vp, _i32, _vp]),
@@ -147,6 +148,9 @@ class Context:
 
     def workspace_bytes(self) -> int:
         return int(_lib().skv_workspace_bytes(self._h))
+
+    def set_budget_hint(self, budget: int) -> None:
+        _check(_lib().skv_set_budget_hint(self._h, budget), "skv_set_budget_hint")
 
     def set_wait_limit(self, polls: int) -> None:
         _check(_lib().skv_set_wait_limit(self._h, polls), "skv_set_wait_limit")

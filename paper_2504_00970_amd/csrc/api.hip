@@ -117,6 +117,7 @@ void fill_context(Ctx& c, const skv_desc& d, hipStream_t stream, int dev) {
     c.G = d.n_q_heads / d.n_kv_heads;
     c.max_sel = d.max_sentences < d.max_budget ? d.max_sentences : d.max_budget;
     c.max_splits = (d.max_budget + skv::kAttChunk - 1) / skv::kAttChunk;
+    c.budget_cap = d.max_budget;
     c.wait_limit = skv::kStepWaitLimit;
     c.step_chunk = skv::kAttChunkMid;
 }
@@ -230,6 +231,13 @@ int skv_set_stream(skv_ctx* ctx, void* hip_stream) {
 }
 
 int64_t skv_workspace_bytes(const skv_ctx* ctx) { return ctx ? (int64_t)ctx->c.ws_bytes : 0; }
+
+int skv_set_budget_hint(skv_ctx* ctx, int32_t budget) {
+    if (!ctx || budget < 0) return SKV_EINVAL;
+    if (budget > ctx->c.d.max_budget) return SKV_ECAPACITY;
+    ctx->c.budget_cap = budget == 0 ? ctx->c.d.max_budget : budget;
+    return SKV_OK;
+}
 
 int skv_set_wait_limit(skv_ctx* ctx, int32_t polls) {
     if (!ctx || polls < 0) return SKV_EINVAL;
@@ -361,7 +369,7 @@ int skv_select(skv_ctx* ctx, const float* score, const int32_t* sent_off, const 
     const int rc = check_ctx(ctx);
     if (rc != SKV_OK) return rc;
     const SeqView v{nullptr, nullptr, nullptr, 0, S, budget, 1};
-    return hip_status(skv::launch_select(&ctx->c, score, sent_off, sent_len, v, sel_sent, n_sel, tok_idx, budget, n_tok));
+    return hip_status(skv::launch_select(&ctx->c, score, sent_off, sent_len, v, sel_sent, n_sel, tok_idx, budget, budget, n_tok));
 }
 
 int skv_gather(skv_ctx* ctx, int32_t layer, const void* K_pool, const void* V_pool, int32_t T, int pool_in_host,
@@ -443,7 +451,7 @@ static int decode_step_launch(Ctx& c, int32_t layer, int32_t B, const void* q_sc
     hipError_t e;
     // Few (sequence, head) pairs: the whole step in one launch, when the 128-token attention blocks of the call fit the
     // chip at once (the shapes the two-launch latency path below would take in 64- or 128-token blocks).
-    if (pairs * ((c.d.max_budget + skv::kAttChunkMid - 1) / skv::kAttChunkMid) <= c.n_cu && S_total > 0) {
+    if (pairs * ((c.budget_cap + skv::kAttChunkMid - 1) / skv::kAttChunkMid) <= c.n_cu && S_total > 0) {
         bool launched = false;
         e = skv::launch_step(&c, q_score, q_attn, sv, Kl, Vl, sent_off, sent_len, v, out, lse, tok_idx_out, n_tok_out, &launched);
         if (launched || e != hipSuccess) return hip_status(e);
@@ -451,7 +459,7 @@ static int decode_step_launch(Ctx& c, int32_t layer, int32_t B, const void* q_sc
     e = skv::launch_score(&c, q_score, sv, v, c.f_score);
     if (e != hipSuccess) return hip_status(e);
     const bool can_stream = c.d.kv_dtype == SKV_BF16 && T_total < (1 << 24);
-    const int wide_blocks = pairs * ((c.d.max_budget + skv::kAttChunkWide - 1) / skv::kAttChunkWide);
+    const int wide_blocks = pairs * ((c.budget_cap + skv::kAttChunkWide - 1) / skv::kAttChunkWide);
     if (can_stream ? wide_blocks > c.n_cu : pairs >= skv::kWideChunkMinHeads) {
         if (can_stream)
             return hip_status(skv::launch_select_attend_stream(&c, q_attn, Kl, Vl, c.f_score, sent_off, sent_len, v, out, lse,
@@ -459,7 +467,7 @@ static int decode_step_launch(Ctx& c, int32_t layer, int32_t B, const void* q_sc
         // batch path: the selection runs once per (sequence, head); attention reads the pool through tok_idx
         int32_t* tok_idx = tok_idx_out ? tok_idx_out : c.f_tok_idx;
         int32_t* n_tok = n_tok_out ? n_tok_out : c.f_n_tok;
-        e = skv::launch_select(&c, c.f_score, sent_off, sent_len, v, c.f_sel_sent, c.f_n_sel, tok_idx, c.d.max_budget, n_tok);
+        e = skv::launch_select(&c, c.f_score, sent_off, sent_len, v, c.f_sel_sent, c.f_n_sel, tok_idx, c.d.max_budget, c.budget_cap, n_tok);
         if (e != hipSuccess) return hip_status(e);
         return hip_status(skv::launch_attend_indirect(&c, q_attn, Kl, Vl, tok_idx, n_tok, v, out, lse));
     }

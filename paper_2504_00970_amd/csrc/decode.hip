@@ -741,12 +741,12 @@ __global__ __launch_bounds__(kBlockThreads) void select_kernel(const float* __re
                                                                int32_t Hkv, int32_t max_sel,
                                                                int32_t* __restrict__ sel_sent, int32_t* __restrict__ n_sel,
                                                                int32_t* __restrict__ tok_idx, int32_t idx_stride,
-                                                               int32_t* __restrict__ n_tok) {
+                                                               int32_t budget_cap, int32_t* __restrict__ n_tok) {
     __shared__ SelectShared sh;
     __shared__ int4 list[kSelListCap];                        // (bucket, offset, length, first output slot)
     const int bh = blockIdx.x, b = bh / Hkv, h = bh % Hkv;
     const Seq sq = seq_of(v, b);
-    const int32_t budget = min(sq.budget, idx_stride);       // tok_idx holds at most idx_stride positions
+    const int32_t budget = min(sq.budget, min(idx_stride, budget_cap));   // tok_idx holds at most idx_stride positions
     const float* sc = score + (int64_t)h * v.S_total + sq.sent_base;
     const int32_t* len = sent_len + sq.sent_base;
     const int32_t* off = sent_off + sq.sent_base + (v.cu_sent ? b : 0);
@@ -775,9 +775,9 @@ __global__ __launch_bounds__(kBlockThreads) void select_kernel(const float* __re
 
 hipError_t launch_select(Ctx* c, const float* score, const int32_t* sent_off, const int32_t* sent_len,
                          const SeqView& v, int32_t* sel_sent, int32_t* n_sel, int32_t* tok_idx, int32_t idx_stride,
-                         int32_t* n_tok) {
+                         int32_t budget_cap, int32_t* n_tok) {
     hipLaunchKernelGGL(select_kernel, dim3(v.B * c->d.n_kv_heads), dim3(kBlockThreads), 0, c->stream, score, sent_off,
-                       sent_len, v, c->d.n_kv_heads, c->max_sel, sel_sent, n_sel, tok_idx, idx_stride, n_tok);
+                       sent_len, v, c->d.n_kv_heads, c->max_sel, sel_sent, n_sel, tok_idx, idx_stride, budget_cap, n_tok);
     return hipGetLastError();
 }
 
@@ -927,7 +927,8 @@ struct AttArgs {
     const int32_t* sent_len;  // kFused
     int32_t* tok_idx_out;     // kFused, nullable: [B*Hkv][idx_stride]
     int32_t* n_tok_out;       // kFused, nullable: [B*Hkv]
-    int32_t idx_stride;       // kFused, kIndirect: max_budget
+    int32_t idx_stride;       // kFused, kIndirect: max_budget (positions per pair in tok_idx / tok_idx_out)
+    int32_t budget_cap;       // budgets are clamped to this (the context's budget hint, at most max_budget)
     SeqView v;
     int32_t Hkv;
     int32_t max_splits;       // partial slots per query head (counted in 64-token chunks)
@@ -957,7 +958,7 @@ enum { kDirect = 0, kFused = 1, kIndirect = 2, kStep = 3 };
 // scalar-cache miss for each new 64-byte line of the argument block.
 __device__ __forceinline__ void demand_args(const AttArgs& a) {
     asm volatile("" ::"s"(a.q), "s"(a.Kb), "s"(a.Vb), "s"(a.n_tok), "s"(a.tok_idx), "s"(a.row_stride), "s"(a.score),
-                 "s"(a.sent_off), "s"(a.sent_len), "s"(a.tok_idx_out), "s"(a.n_tok_out), "s"(a.idx_stride), "s"(a.v.cu_tok),
+                 "s"(a.sent_off), "s"(a.sent_len), "s"(a.tok_idx_out), "s"(a.n_tok_out), "s"(a.idx_stride), "s"(a.budget_cap), "s"(a.v.cu_tok),
                  "s"(a.v.cu_sent), "s"(a.v.budget_arr), "s"(a.v.T_total), "s"(a.v.S_total), "s"(a.v.budget), "s"(a.v.B),
                  "s"(a.Hkv), "s"(a.max_splits), "s"(a.part), "s"(a.ml), "s"(a.counter), "s"(a.out), "s"(a.lse));
 }
@@ -1039,7 +1040,7 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
     bool step_ok = true;                                          // kStep: every wait of this block ended in time
     if constexpr (kSel) {
         __shared__ SelectShared sel_sh;
-        const int32_t budget = min(sq.budget, a.idx_stride);
+        const int32_t budget = min(sq.budget, a.budget_cap);
         if constexpr (MODE == kStep) {
             // ---- 0. scores of this block's share of the pair's buckets, published to the pair's other blocks ---------
             // Part `split` of the 2^lg_parts blocks of the pair owns the buckets [split * per, (split + 1) * per); wave
@@ -1881,7 +1882,7 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(4
     int32_t n;                    // retrieved tokens of this (sequence, head)
     {
         __shared__ SelectShared sel_sh;
-        const int32_t budget = min(sq.budget, a.idx_stride);
+        const int32_t budget = min(sq.budget, a.budget_cap);
         if (split > 0 && j0 >= budget) return;                    // n <= budget: nothing for this split
         stream_load_queries<G>(a, ss, (int64_t)b * (a.Hkv * G) + (int64_t)h * G);
         for (int p = tid; p < (CHUNK > kBlockThreads ? CHUNK : kBlockThreads); p += kBlockThreads)
@@ -1921,7 +1922,7 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(4
 
 template <int CHUNK>
 static hipError_t launch_select_attend_stream_g(Ctx* c, const AttArgs& a) {
-    int n_splits = (c->d.max_budget + CHUNK - 1) / CHUNK;
+    int n_splits = (c->budget_cap + CHUNK - 1) / CHUNK;
     if (n_splits < 1) n_splits = 1;       // block 0 still writes the empty-selection result
     const dim3 grid(n_splits, a.v.B * c->d.n_kv_heads), block(kBlockThreads);
     switch (c->G) {
@@ -1953,6 +1954,7 @@ static AttArgs att_common(Ctx* c, const void* q, const void* Kbase, const void* 
     a.q = (const char*)q; a.Kb = (const char*)Kbase; a.Vb = (const char*)Vbase;
     a.v = v; a.Hkv = c->d.n_kv_heads; a.max_splits = c->max_splits;
     a.part = c->att_part; a.ml = c->att_ml; a.counter = c->att_counter; a.out = out; a.lse = lse;
+    a.budget_cap = c->budget_cap;
     return a;
 }
 
@@ -1981,7 +1983,7 @@ hipError_t launch_attend_indirect(Ctx* c, const void* q, const void* K_layer, co
                                   const int32_t* n_tok, const SeqView& v, float* out, float* lse) {
     AttArgs a = att_common(c, q, K_layer, V_layer, v, out, lse);
     a.n_tok = n_tok; a.tok_idx = tok_idx; a.idx_stride = c->d.max_budget;
-    const int n_splits = (c->d.max_budget + kAttChunkWide - 1) / kAttChunkWide;
+    const int n_splits = (c->budget_cap + kAttChunkWide - 1) / kAttChunkWide;
     return c->d.kv_dtype == SKV_BF16 ? launch_attend_g<2, kIndirect, kAttChunkWide>(c, a, n_splits)
                                      : launch_attend_g<4, kIndirect, kAttChunkWide>(c, a, n_splits);
 }
@@ -2001,9 +2003,9 @@ hipError_t launch_select_attend_stream(Ctx* c, const void* q, const void* K_laye
     // blocks, 2048-token blocks halve the selections and, up to a budget of 2048, need no merge: a round of them takes
     // about 5/3 of a 1024-token round (32 sequences: 94.7 -> 87.0 us, 64: 180.2 -> 166.3; 48: 137.8 either way).
     const int pairs = v.B * c->d.n_kv_heads;
-    const int blocks = pairs * ((c->d.max_budget + kStreamChunk - 1) / kStreamChunk);
+    const int blocks = pairs * ((c->budget_cap + kStreamChunk - 1) / kStreamChunk);
     if (2 * blocks <= c->n_cu) return launch_select_attend_stream_g<kStreamChunk / 2>(c, a);
-    const int big_blocks = pairs * ((c->d.max_budget + kStreamMaxChunk - 1) / kStreamMaxChunk);
+    const int big_blocks = pairs * ((c->budget_cap + kStreamMaxChunk - 1) / kStreamMaxChunk);
     const int rounds = (blocks + c->n_cu - 1) / c->n_cu, big_rounds = (big_blocks + c->n_cu - 1) / c->n_cu;
     if (5 * big_rounds < 3 * rounds) return launch_select_attend_stream_g<kStreamMaxChunk>(c, a);
     return launch_select_attend_stream_g<kStreamChunk>(c, a);
@@ -2021,20 +2023,21 @@ hipError_t launch_select_attend(Ctx* c, const void* q, const void* K_layer, cons
     // smallest whose blocks all run at once; a second round of blocks costs more than the larger blocks' longer K/V phase
     // (4 sequences of 32K, 8 heads, budget 2048: 25.9 us in 128-token blocks, 17 in 256-token blocks).
     const int pairs = v.B * c->d.n_kv_heads;
-    auto blocks = [&](int chunk) { return pairs * ((c->d.max_budget + chunk - 1) / chunk); };
+    auto blocks = [&](int chunk) { return pairs * ((c->budget_cap + chunk - 1) / chunk); };
     if (c->d.kv_dtype == SKV_BF16 && blocks(kAttChunkMid) > c->n_cu) {
-        const int n_splits = (c->d.max_budget + kAttChunkWide - 1) / kAttChunkWide;
+        const int n_splits = (c->budget_cap + kAttChunkWide - 1) / kAttChunkWide;
         return launch_attend_g<2, kFused, kAttChunkWide>(c, a, n_splits);
     }
     // Every split block of a head repeats the selection; with thousands of buckets per sequence that repetition
     // (bucket loads from L2, histogram passes) outweighs the shorter K/V phase of 64-token blocks.
     if (v.S_total / (v.B > 0 ? v.B : 1) > kMidChunkMinSentences || (c->d.kv_dtype == SKV_BF16 && blocks(kAttChunk) > c->n_cu)) {
-        const int n_splits = (c->d.max_budget + kAttChunkMid - 1) / kAttChunkMid;
+        const int n_splits = (c->budget_cap + kAttChunkMid - 1) / kAttChunkMid;
         return c->d.kv_dtype == SKV_BF16 ? launch_attend_g<2, kFused, kAttChunkMid>(c, a, n_splits)
                                          : launch_attend_g<4, kFused, kAttChunkMid>(c, a, n_splits);
     }
-    return c->d.kv_dtype == SKV_BF16 ? launch_attend_g<2, kFused, kAttChunk>(c, a, c->max_splits)
-                                     : launch_attend_g<4, kFused, kAttChunk>(c, a, c->max_splits);
+    const int n_splits = (c->budget_cap + kAttChunk - 1) / kAttChunk;
+    return c->d.kv_dtype == SKV_BF16 ? launch_attend_g<2, kFused, kAttChunk>(c, a, n_splits)
+                                     : launch_attend_g<4, kFused, kAttChunk>(c, a, n_splits);
 }
 
 // Single-launch step.  Blocks per pair: the largest power of two that keeps pairs x blocks within the compute units (every
@@ -2065,7 +2068,7 @@ hipError_t launch_step(Ctx* c, const void* q_score, const void* q_attn, const vo
     while ((pairs << (lg + 1)) <= max_blocks) ++lg;
     const int parts = 1 << lg;
     const int chunk = c->step_chunk;
-    const int att_parts = (c->d.max_budget + chunk - 1) / chunk;
+    const int att_parts = (c->budget_cap + chunk - 1) / chunk;
     if (att_parts > parts || c->G > parts) return hipSuccess;                    // attention blocks or mergers do not fit
     AttArgs a = att_common(c, q_attn, K_layer, V_layer, v, out, lse);
     a.sent_off = sent_off; a.sent_len = sent_len;

@@ -51,6 +51,7 @@ struct Ctx {
     int G;
     int max_sel;            // min(max_sentences, max_budget)
     int max_splits;         // ceil(max_budget / kAttChunk)
+    int budget_cap;         // the largest budget the decode step plans for: max_budget, or the caller's hint below it
     char* ws;               // one device allocation, carved below
     size_t ws_bytes;
     unsigned long long* seg_part;  // [ceil(max_tokens / kSegTokPerBlock)] packed (count << 32 | last_end)
@@ -105,7 +106,7 @@ hipError_t launch_query_update(Ctx* c, int32_t B, const void* q_t, const int32_t
 hipError_t launch_score(Ctx* c, const void* q, const void* semvec_layer, const SeqView& v, float* score);
 hipError_t launch_select(Ctx* c, const float* score, const int32_t* sent_off, const int32_t* sent_len,
                          const SeqView& v, int32_t* sel_sent, int32_t* n_sel, int32_t* tok_idx, int32_t idx_stride,
-                         int32_t* n_tok);
+                         int32_t budget_cap, int32_t* n_tok);
 hipError_t launch_gather(Ctx* c, const void* K_layer, const void* V_layer, int32_t T, bool host_pool, const int32_t* tok_idx,
                          const int32_t* n_tok, int32_t budget, void* K_sel, void* V_sel);
 // Attention over K_sel/V_sel [B*Hkv][row_stride][D] with n_tok [B*Hkv] from memory.

@@ -572,6 +572,54 @@ def test_full_size_cfg1_batched(U, oracle32):
         torch.cuda.empty_cache()
 
 
+# ----------------------------------------------------------------------------- budget hint
+
+@pytest.mark.parametrize("B,dtype", [(1, "bf16"), (1, "f32"), (4, "bf16"), (9, "bf16"), (9, "f32")])
+def test_budget_hint_makes_a_large_context_plan_like_a_small_one(U, oracle32, B, dtype):
+    """A context created for budgets up to 8192 and told (skv_set_budget_hint) that the budgets in use are at most 700
+    runs the step exactly as a context created for 700 does: same selection, same output bits (the streaming kernel,
+    nine bf16 sequences with the unhinted capacity, is the one form whose last bits vary between calls); budgets above
+    the hint are treated as the hint; 0 restores the capacity."""
+    wl = gen.CFG4.scaled(n_layers=1, n_q_heads=32, batch=B, t_range=(1500, 4000), budgets=(700,), dtype=dtype)
+    inp = gen.ragged_inputs(wl, seed=17, device=U.DEV, resident_layers=1)
+    H, Hq, D = wl.n_kv_heads, wl.n_q_heads, wl.head_dim
+    T, S = int(inp.cu_tok[-1]), int(inp.cu_sent[-1])
+    d = [U.i32(x) for x in (inp.cu_tok, inp.cu_sent, inp.sent_off, inp.sent_len)]
+    q = inp.q[0]
+
+    def run(ctx, sv, budgets, cap):
+        out = torch.full((B, Hq, D), 3.0, device=U.DEV)
+        lse = torch.full((B, Hq), 3.0, device=U.DEV)
+        tok_idx = U.empty_i32(B, H, cap, fill=-1)
+        n_tok = U.empty_i32(B, H, fill=-1)
+        ctx.decode_step(0, B, q, q, inp.K, inp.V, T, sv, S, *d, U.i32(budgets), out, lse, tok_idx, n_tok)
+        torch.cuda.synchronize()
+        return out, lse, tok_idx[:, :, :700].clone(), n_tok
+
+    def make(cap):
+        ctx = U.make_ctx(wl, T, S, cap, batch=B)
+        sv = torch.zeros(1, H, S, D, device=U.DEV)
+        ctx.build_semvec(inp.K, U.i32(gen.offsets_of(inp.sent_len)), S, sv)
+        return ctx, sv
+
+    small, sv_s = make(700)
+    big, sv_b = make(8192)
+    ref = run(small, sv_s, [700] * B, 700)
+    big.set_budget_hint(700)
+    _say("budget hint: capacity 8192, hint 700, B", B, dtype)
+    got = run(big, sv_b, [700] * B, 8192)
+    for a, b in zip(ref, got):
+        assert torch.equal(a, b)
+    got = run(big, sv_b, [5000] * B, 8192)                  # budgets above the hint count as the hint
+    for a, b in zip(ref, got):
+        assert torch.equal(a, b)
+    big.set_budget_hint(0)                                  # back to the capacity: the larger budget now applies
+    full = run(big, sv_b, [5000] * B, 8192)
+    assert bool((full[3] >= ref[3]).all()) and int(full[3].max()) > 700
+    with pytest.raises(Exception):
+        big.set_budget_hint(9000)
+
+
 # ----------------------------------------------------------------------------- local window merge, equal chunks
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
