@@ -796,8 +796,9 @@ def main():
         sys.exit(2)
     if args.phase_stamps:
         from paper_2504_00970_amd import _build
-        if not os.path.exists(_build.LIB_STAMPS):
-            print("no profiling build: run `python -m paper_2504_00970_amd._build --stamps` first", file=sys.stderr)
+        if _build.stale(_build.LIB_STAMPS):
+            print("no profiling build of the current sources: run `python -m paper_2504_00970_amd._build --stamps` first",
+                  file=sys.stderr)
             sys.exit(2)
         _build.LIB = _build.LIB_STAMPS
     if args.workload == "floor":

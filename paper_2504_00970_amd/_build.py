@@ -24,10 +24,11 @@ HIPCC_FLAGS = [
 ]
 
 
-def stale() -> bool:
-    if not os.path.exists(LIB):
+def stale(lib: str = "") -> bool:
+    lib = lib or LIB
+    if not os.path.exists(lib):
         return True
-    t = os.path.getmtime(LIB)
+    t = os.path.getmtime(lib)
     deps = [os.path.join(CSRC, s) for s in SOURCES] + HEADERS
     return any(os.path.getmtime(d) > t for d in deps)
 
