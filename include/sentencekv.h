@@ -255,13 +255,15 @@ int skv_decode_step(skv_ctx* ctx, int32_t layer, int32_t B, const void* q_score,
  * descriptor and the stream are passed with every call, and the workspace (scores, split-K partials, arrival counters)
  * is a static array of SKV_NOALLOC_SCRATCH_BYTES of device memory inside the library, which every GPU the library runs
  * on holds until the process ends.  The call allocates and frees nothing (no hipMalloc / hipFree, no allocating library
- * routine) and never blocks the host; it queues one small clearing kernel (the arrival counters) ahead of the kernels of
- * skv_decode_step.  The address of the array is looked up once per device, at skv_create or at the first call here on
+ * routine) and never blocks the host; it queues two small clearing kernels (arrival counters, error word) ahead of the
+ * kernels of skv_decode_step; a give-up of the single-launch form shows as NaN outputs only (there is no context to report it).  The address of the array is looked up once per device, at skv_create or at the first call here on
  * that device (a symbol lookup: make that first call outside graph capture).
  * desc        host; the maxima only need to cover this call (max_tokens is not used for sizing).  The workspace a
- *             descriptor needs is about  max_batch * Hq * ceil(max_budget / 64) * 520  +  Hkv * max_sentences * 4
+ *             descriptor needs is 3.2 MB that every descriptor shares (the tagged words and epochs of the single-launch
+ *             form, never cleared) plus about  max_batch * Hq * ceil(max_budget / 64) * 520  +  Hkv * max_sentences * 4
  *             + max_batch * Hkv * (max_budget + min(max_sentences, max_budget)) * 4  bytes
- *             (0.7 MB for 32/8 heads, 2048-token budget, 1332 buckets, one sequence).
+ *             (0.7 MB for 32/8 heads, 2048-token budget, 1332 buckets, one sequence).  The single-launch form is used
+ *             when Hkv * max_batch * max_sentences <= 131072; otherwise the call takes the two-launch form.
  * Errors: as skv_decode_step, plus SKV_EINVAL for a bad descriptor and SKV_ECAPACITY when the descriptor needs more
  * than SKV_NOALLOC_SCRATCH_BYTES.
  * All calls on one GPU share the one array, on whatever stream: calls that overlap in time on the same GPU race
