@@ -226,8 +226,8 @@ int skv_attend(skv_ctx* ctx, const void* q_attn, const void* K_sel, const void* 
  * skv_gather + skv_attend run per sequence: the selection bit for bit, out / lse up to the order of the
  * floating-point sums.
  * Launches per call (P = B * Hkv pairs of sequence and KV head, all sizes from the descriptor's max_budget):
- *   - ONE, when P <= 64 and the 128-token attention blocks of the call, P * ceil(max_budget / 128), fit the compute
- *     units (256) at once: P * 2^k blocks (the largest power of two that fits) first score the buckets of their pair
+ *   - ONE, when P <= 64 and P * 2^k blocks (2^k the largest power of two with P * 2^k <= 256 compute units) cover the
+ *     budget in attention blocks of 128 or 256 tokens (2^k * 256 >= max_budget) and 2^k >= G: the blocks first score the buckets of their pair
  *     between them, pass the scores and later the partial attention results to each other inside the kernel, select
  *     and attend.  The waits inside the kernel are bounded, see skv_set_wait_limit;
  *   - TWO otherwise for bf16 pools (scores; selection + attention in 256-token blocks, or in streaming blocks of 512,

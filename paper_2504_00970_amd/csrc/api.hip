@@ -119,7 +119,6 @@ void fill_context(Ctx& c, const skv_desc& d, hipStream_t stream, int dev) {
     c.max_splits = (d.max_budget + skv::kAttChunk - 1) / skv::kAttChunk;
     c.budget_cap = d.max_budget;
     c.wait_limit = skv::kStepWaitLimit;
-    c.step_chunk = skv::kAttChunkMid;
 }
 
 // ---- static scratch of skv_decode_step_noalloc -----------------------------------------------------------------------
@@ -449,9 +448,9 @@ static int decode_step_launch(Ctx& c, int32_t layer, int32_t B, const void* q_sc
     const char* Vl = (const char*)V_pool + pool_off;
     const int pairs = B * c.d.n_kv_heads;
     hipError_t e;
-    // Few (sequence, head) pairs: the whole step in one launch, when the 128-token attention blocks of the call fit the
-    // chip at once (the shapes the two-launch latency path below would take in 64- or 128-token blocks).
-    if (pairs * ((c.budget_cap + skv::kAttChunkMid - 1) / skv::kAttChunkMid) <= c.n_cu && S_total > 0) {
+    // Few (sequence, head) pairs: the whole step in one launch, when its attention blocks (128 or 256 tokens) fit the
+    // chip at once beside each other; launch_step decides.
+    if (pairs <= skv::kStepMaxPairs && S_total > 0) {
         bool launched = false;
         e = skv::launch_step(&c, q_score, q_attn, sv, Kl, Vl, sent_off, sent_len, v, out, lse, tok_idx_out, n_tok_out, &launched);
         if (launched || e != hipSuccess) return hip_status(e);

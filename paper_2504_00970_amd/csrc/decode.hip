@@ -2067,7 +2067,9 @@ hipError_t launch_step(Ctx* c, const void* q_score, const void* q_attn, const vo
     int lg = 0;
     while ((pairs << (lg + 1)) <= max_blocks) ++lg;
     const int parts = 1 << lg;
-    const int chunk = c->step_chunk;
+    // attention blocks of 128 tokens, or of 256 when a pair has too few blocks for 128 (three or four sequences of 8 heads)
+    int chunk = kAttChunkMid;
+    if ((c->budget_cap + chunk - 1) / chunk > parts) chunk = kAttChunkWide;
     const int att_parts = (c->budget_cap + chunk - 1) / chunk;
     if (att_parts > parts || c->G > parts) return hipSuccess;                    // attention blocks or mergers do not fit
     AttArgs a = att_common(c, q_attn, K_layer, V_layer, v, out, lse);
@@ -2079,9 +2081,9 @@ hipError_t launch_step(Ctx* c, const void* q_score, const void* q_attn, const vo
     a.step_part = c->step_part; a.wait_limit = c->wait_limit;
     a.err_dev = c->err_dev; a.err_host = c->err_host_dev;
     *launched = true;
-    if (chunk == kAttChunk)
-        return c->d.kv_dtype == SKV_BF16 ? launch_step_g<2, kAttChunk>(c, a, pairs * parts)
-                                         : launch_step_g<4, kAttChunk>(c, a, pairs * parts);
+    if (chunk == kAttChunkWide)
+        return c->d.kv_dtype == SKV_BF16 ? launch_step_g<2, kAttChunkWide>(c, a, pairs * parts)
+                                         : launch_step_g<4, kAttChunkWide>(c, a, pairs * parts);
     return c->d.kv_dtype == SKV_BF16 ? launch_step_g<2, kAttChunkMid>(c, a, pairs * parts)
                                      : launch_step_g<4, kAttChunkMid>(c, a, pairs * parts);
 }

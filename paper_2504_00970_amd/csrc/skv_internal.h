@@ -72,7 +72,6 @@ struct Ctx {
     unsigned int* err_host;      // the same flag in pinned host memory (host address; null: none)
     unsigned int* err_host_dev;  // device address of err_host
     int wait_limit;              // polling rounds before a waiting block gives up
-    int step_chunk;              // tokens per attention block of the single-launch step (64 or 128)
 };
 
 // Ragged-batch view handed to the decode kernels.  For single-sequence calls cu_tok / cu_sent /

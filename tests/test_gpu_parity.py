@@ -408,6 +408,16 @@ def test_fused_batch_path_many_heads(U, oracle32, Hq, dtype, capacity):
     _fused_case(U, oracle32, wl, seed=6, layers=[0], capacity=capacity)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("budget", [100, 200, 700])
+def test_fused_two_launch_small_blocks(U, oracle32, budget, dtype):
+    """More than 64 (sequence, head) pairs with small budgets: too many pairs for the single-launch step, few enough blocks
+    for the two-launch step's fused blocks of 64 tokens (budget 100), 128 tokens (200) and 256 tokens (700) (fp32 pools of
+    64 pairs or more: selection kernel + attention through the positions)."""
+    wl = gen.CFG4.scaled(n_layers=1, n_q_heads=32, batch=9, t_range=(300, 2500), budgets=(budget,), dtype=dtype)
+    _fused_case(U, oracle32, wl, seed=51, layers=[0])
+
+
 @pytest.mark.parametrize("capacity", [0, HALF_CAPACITY, STREAM_CAPACITY])
 @pytest.mark.parametrize("budget", [512, 513, 1024, 1025, 1500, 2048])
 def test_fused_batch_path_two_blocks_per_head(U, oracle32, budget, capacity):
