@@ -998,6 +998,8 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
     __shared__ __attribute__((aligned(16))) float sm_red_flat[kRedFloats];
     __shared__ int sm_last;
     __shared__ int32_t sm_row[CHUNK];
+    // kStep: the pair's scores on their way to the owning threads; later the merging block's scratch
+    __shared__ uint32_t sm_keys[MODE == kStep ? kSelKreg * kBlockThreads : 1];
 
     // kStep: a one-dimensional grid, pair fastest, so that the hardware's round-robin of consecutive blocks over the XCDs
     // keeps the blocks of a pair together whenever the number of pairs is a multiple of the number of XCDs
@@ -1090,7 +1092,6 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
         const int32_t* off = a.sent_off + sq.sent_base + (a.v.cu_sent ? b : 0);
         if constexpr (MODE == kStep) {                            // the scores are being written by the pair's blocks
             const float* tsc = reinterpret_cast<const float*>(a.step_score + (int64_t)bh * a.score_stride);
-            __shared__ uint32_t sm_keys[kSelKreg * kBlockThreads];    // the pair's scores on their way to the owning threads
             if (sq.n_sent <= 2 * kBlockThreads)
                 select_block<2, false, true>(tsc, len, off, sq.n_sent, budget, sel_sh, mark, &nsel, &ntok, tag, a.wait_limit, &step_ok, sm_keys);
             else
@@ -1456,15 +1457,13 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
             }
         }
         SKV_T(10);
-        __shared__ int sm_bad;
-        if (tid == 0) sm_bad = 0;
-        __syncthreads();                                                  // also: sm_red_flat is no longer read
-        float* scratch = sm_red_flat;                                     // (o, M, L) per thread: 3 x 1024 floats
-        scratch[tid] = o; scratch[kBlockThreads + tid] = M; scratch[2 * kBlockThreads + tid] = L;
-        if (!ok) sm_bad = 1;
+        // (o, M, L) per thread: 3 x 1024 floats in the space the scores came through; a thread whose wait ran out leaves
+        // NaN as its maximum
+        float* scratch = reinterpret_cast<float*>(sm_keys);
+        scratch[tid] = o; scratch[kBlockThreads + tid] = ok ? M : __builtin_nanf(""); scratch[2 * kBlockThreads + tid] = L;
         __syncthreads();
         SKV_T(11);
-        const bool bad = sm_bad != 0;                                     // a wait of this launch ran out
+        bool bad = false;
         if (tid < kHeadDim) {
             float mg[kGroups8], lg[kGroups8], og[kGroups8];
             float Mx = -INFINITY;
@@ -1473,6 +1472,7 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
                 og[gg] = scratch[gg * kHeadDim + tid];
                 mg[gg] = scratch[kBlockThreads + gg * kHeadDim + tid];
                 lg[gg] = scratch[2 * kBlockThreads + gg * kHeadDim + tid];
+                bad = bad || mg[gg] != mg[gg];
                 Mx = fmaxf(Mx, mg[gg]);
             }
             float Ls = 0.f, os = 0.f;
@@ -1486,17 +1486,15 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
             }
             const bool empty = !(Ls > 0.f);                               // every retrieved position was out of range
             float res = empty ? 0.f : os / Ls;
-            if (bad) res = __builtin_nanf("");
+            if (bad) res = __builtin_nanf("");                            // a wait of this launch ran out
             a.out[(qhead0 + g) * kHeadDim + tid] = res;
             if (a.lse && tid == 0) a.lse[qhead0 + g] = empty ? -INFINITY : (Mx + log2f(Ls)) * kLn2;
-        }
-        if (tid == 0) {
-            // Block 0 ends the pair's launch by advancing its epoch: all its threads have seen every attending block's
-            // partial (the barrier above), and each of those blocks, and through the scores they waited for every
-            // scoring block, has read the epoch by now.
-            if (split == 0) st_agent(a.step_epoch + bh * kStepEpochStride, tag >> kStepPairBits);
             if (bad) { st_agent(a.err_dev, 1u); if (a.err_host) st_agent(a.err_host, 1u); }
         }
+        // Block 0 ends the pair's launch by advancing its epoch: all its threads have seen every attending block's
+        // partial (the barrier above), and each of those blocks, and through the scores they waited for every
+        // scoring block, has read the epoch by now.
+        if (tid == 0 && split == 0) st_agent(a.step_epoch + bh * kStepEpochStride, tag >> kStepPairBits);
         SKV_T(9);
         return;
     }
@@ -2043,9 +2041,36 @@ hipError_t launch_select_attend(Ctx* c, const void* q, const void* K_layer, cons
 // Single-launch step.  Blocks per pair: the largest power of two that keeps pairs x blocks within the compute units (every
 // block must be resident for the per-pair wait to end: one 1024-thread block per compute unit).  All of them score; the
 // first ceil(max_budget / CHUNK) of them attend.
+// Blocks of the single-launch kernel a compute unit can hold at once (registers, LDS), asked of the runtime once per
+// instantiation: the kernel's waits need every block of the grid resident, so the launcher refuses grids beyond
+// compute units x this number.
+template <int EB, int G, int CHUNK>
+static int step_blocks_per_cu() {
+    static int cached = -1;
+    if (cached < 0) {
+        int n = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attend_kernel<EB, G, kStep, CHUNK>, kBlockThreads, 0) != hipSuccess) {
+            (void)hipGetLastError();
+            n = 0;
+        }
+        cached = n;
+    }
+    return cached;
+}
+
 template <int EB, int CHUNK>
-static hipError_t launch_step_g(Ctx* c, const AttArgs& a, int n_blocks) {
+static hipError_t launch_step_g(Ctx* c, const AttArgs& a, int n_blocks, bool* launched) {
     const dim3 grid(n_blocks), block(kBlockThreads);
+    int per_cu = 0;
+    switch (c->G) {
+        case 1: per_cu = step_blocks_per_cu<EB, 1, CHUNK>(); break;
+        case 2: per_cu = step_blocks_per_cu<EB, 2, CHUNK>(); break;
+        case 4: per_cu = step_blocks_per_cu<EB, 4, CHUNK>(); break;
+        case 8: per_cu = step_blocks_per_cu<EB, 8, CHUNK>(); break;
+        default: return hipErrorInvalidValue;
+    }
+    if (per_cu < 1 || n_blocks > c->n_cu * per_cu) return hipSuccess;       // not every block would be resident: other forms
+    *launched = true;
     switch (c->G) {
         case 1: hipLaunchKernelGGL((attend_kernel<EB, 1, kStep, CHUNK>), grid, block, 0, c->stream, a); break;
         case 2: hipLaunchKernelGGL((attend_kernel<EB, 2, kStep, CHUNK>), grid, block, 0, c->stream, a); break;
@@ -2080,12 +2105,11 @@ hipError_t launch_step(Ctx* c, const void* q_score, const void* q_attn, const vo
     a.lg_parts = lg; a.step_epoch = c->step_epoch; a.step_score = c->step_score; a.score_stride = c->step_score_stride;
     a.step_part = c->step_part; a.wait_limit = c->wait_limit;
     a.err_dev = c->err_dev; a.err_host = c->err_host_dev;
-    *launched = true;
     if (chunk == kAttChunkWide)
-        return c->d.kv_dtype == SKV_BF16 ? launch_step_g<2, kAttChunkWide>(c, a, pairs * parts)
-                                         : launch_step_g<4, kAttChunkWide>(c, a, pairs * parts);
-    return c->d.kv_dtype == SKV_BF16 ? launch_step_g<2, kAttChunkMid>(c, a, pairs * parts)
-                                     : launch_step_g<4, kAttChunkMid>(c, a, pairs * parts);
+        return c->d.kv_dtype == SKV_BF16 ? launch_step_g<2, kAttChunkWide>(c, a, pairs * parts, launched)
+                                         : launch_step_g<4, kAttChunkWide>(c, a, pairs * parts, launched);
+    return c->d.kv_dtype == SKV_BF16 ? launch_step_g<2, kAttChunkMid>(c, a, pairs * parts, launched)
+                                     : launch_step_g<4, kAttChunkMid>(c, a, pairs * parts, launched);
 }
 
 // ------------------------------------------------------------------------------------------------
