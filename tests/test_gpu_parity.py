@@ -302,7 +302,8 @@ def test_attend_large_logits_do_not_overflow(U, oracle32):
 
 # ----------------------------------------------------------------------------- fused step
 
-# Descriptor max_budget values that steer a bf16 batch of 8 sequences x 8 KV heads: the library picks the attention kernel
+# Descriptor max_budget values that steer a bf16 batch of 8 sequences x 8 KV heads (64 pairs, 4 blocks per pair in the
+# single-launch step: budgets up to 1024 run there, in 256-token blocks); beyond that the library picks the attention kernel
 # from block counts, pairs x ceil(max_budget / 256) <= 256 compute units: 256-token fused blocks; else the streaming
 # kernel, in 512-token blocks while pairs x ceil(max_budget / 1024) <= 128, else in 1024-token blocks.
 STREAM_CAPACITY = 9000      # 1024-token streaming blocks
@@ -375,9 +376,10 @@ def _fused_case(U, oracle32, wl, seed, layers, sv_dtype="f32", seq_tokens=None, 
 
 @pytest.mark.parametrize("capacity", [0, 5000, STREAM_CAPACITY, 20000])
 def test_fused_single_sequence_matches_oracle(U, oracle32, capacity):
-    """One sequence through every bf16 block size: 128-token fused blocks, 256-token fused blocks (capacity 5000: 8 heads x
+    """One sequence through the forms of the step: single launch in 128-token blocks, in 256-token blocks (capacity 5000: 8 heads x
     40 blocks of 128 tokens no longer fit the chip at once), 512- and 1024-token streaming blocks (capacities 9000 and
-    20000: 8 x 36 > 256 blocks of 256 tokens); fp32 keeps its 64-token blocks."""
+    20000: beyond 32 blocks x 256 tokens per head, and 8 x 36 > 256 blocks of 256 tokens); fp32 runs the single launch on the
+    plain ALUs, and selection + attention through the positions for the large capacities."""
     wl = gen.CFG1.scaled(n_layers=2, batch=1, t_range=(6000, 6000), budgets=(1024,))
     _fused_case(U, oracle32, wl, seed=2, layers=[0, 1], capacity=capacity)
     wl = gen.CFG0.scaled(n_layers=1, batch=1, t_range=(4096, 4096), budgets=(512,))
@@ -386,7 +388,7 @@ def test_fused_single_sequence_matches_oracle(U, oracle32, capacity):
 
 @pytest.mark.parametrize("budget", [3000, 6000])
 def test_fused_single_sequence_large_budget(U, oracle32, budget):
-    """Budgets of thousands of tokens for one sequence: 256-token fused blocks (3000: 8 x 24 blocks of 128 tokens still
+    """Budgets of thousands of tokens for one sequence, single launch: 128-token blocks (3000: 8 x 24 blocks of 128 tokens still
     fit; 6000 does not) with every block full of retrieved tokens."""
     wl = gen.CFG1.scaled(n_layers=1, batch=1, t_range=(9000, 9000), budgets=(budget,))
     _fused_case(U, oracle32, wl, seed=5, layers=[0])
@@ -433,8 +435,8 @@ def test_fused_batch_path_two_blocks_per_head(U, oracle32, budget, capacity):
 @pytest.mark.parametrize("B", [2, 3, 8])
 def test_fused_batch_with_empty_and_tiny_sequences(U, oracle32, dtype, B, capacity):
     """Sequences without tokens, with one token and with one bucket next to ordinary ones, budgets from 0 to more than the
-    context, on the small-batch path (B = 2: 64/128-token blocks; B = 3: 256-token blocks) and on the batch paths
-    (B = 8: 256-token fused blocks, or the streaming kernel with the large capacity; fp32: selection kernel + indirect
+    context, in the single-launch step (B = 2: 128-token blocks; B = 3: 256-token blocks; B = 8 without a capacity) and on the
+    batch paths (B = 8 with a capacity: 256-token fused blocks or the streaming kernel; fp32: selection kernel + indirect
     attention)."""
     toks = [0, 1, 1500, 0, 37, 2300, 5, 0][:B]
     buds = [64, 64, 700, 0, 1000, 0, 3, 9][:B]
@@ -729,7 +731,7 @@ def test_e4m3_table_every_code_scores_like_the_oracle(U, oracle32):
 
 @pytest.mark.parametrize("dtype,B", [("bf16", 1), ("f32", 1), ("bf16", 3)])
 def test_fused_many_buckets_per_sequence(U, oracle32, dtype, B):
-    """More than 1024 buckets per sequence: the fused step runs 128-token split blocks (two 64-position pieces per block,
+    """More than 1024 buckets per sequence: the step runs 128-token split blocks (two 64-position pieces per block,
     buckets spanning both pieces) and the selection with up to 6 buckets per thread in registers."""
     wl = gen.CFG1.scaled(n_layers=1, batch=B, t_range=(5800, 6400), budgets=(700,), len_dist=("uniform", 1, 3), dtype=dtype)
     _fused_case(U, oracle32, wl, seed=41, layers=[0])
@@ -749,7 +751,7 @@ _LEN_DISTS = [("uniform", 1, 3), ("uniform", 8, 40), ("lognormal", 20, 0.7, 3, 1
 @pytest.mark.parametrize("sweep_seed", [1, 7])
 def test_fused_step_seeded_shape_sweep(U, oracle32, sweep_seed):
     """The fused step over a seeded sample of (batch, group size, pool type, table type, budget, context range, bucket
-    length distribution): every launch path (64/128-token blocks, 1024-token streaming blocks, the fp32 batch path) with
+    length distribution): every launch path (single launch, fused and streaming blocks of the two-launch step, the fp32 batch path) with
     shapes no hand-written case has."""
     rng = np.random.default_rng(sweep_seed)
     for it in range(14):
