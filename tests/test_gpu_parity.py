@@ -389,7 +389,7 @@ def test_fused_single_sequence_matches_oracle(U, oracle32, capacity):
 @pytest.mark.parametrize("budget", [3000, 6000])
 def test_fused_single_sequence_large_budget(U, oracle32, budget):
     """Budgets of thousands of tokens for one sequence, single launch: 128-token blocks (3000: 8 x 24 blocks of 128 tokens still
-    fit; 6000 does not) with every block full of retrieved tokens."""
+    fit the 32 blocks of a head; 6000 takes 256-token blocks) with every block full of retrieved tokens."""
     wl = gen.CFG1.scaled(n_layers=1, batch=1, t_range=(9000, 9000), budgets=(budget,))
     _fused_case(U, oracle32, wl, seed=5, layers=[0])
 
