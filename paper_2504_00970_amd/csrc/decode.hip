@@ -705,26 +705,39 @@ __device__ __forceinline__ void select_block(const float* __restrict__ sc, const
         }
         return false;
     };
-    uint32_t my_tok = 0, my_cnt = 0;
+    // first walk: count; the register-held buckets that are chosen are remembered in a mask, so that the second walk
+    // does not evaluate the rule again (buckets beyond the registers, re-read from memory, are evaluated in both walks)
+    uint32_t my_tok = 0, my_cnt = 0, sel_mask = 0, tie_after_regs = tie_run;
     {
         uint32_t t = tie_run;
-        for_items([&](int, int32_t, uint32_t k, int32_t ln, int32_t) {
-            if (chosen(k, ln, t)) { my_tok += (uint32_t)ln; my_cnt += 1; }
-        });
+#pragma unroll
+        for (int i = 0; i < KREG; ++i)
+            if (i < kpt && rlen[i] > 0 && chosen(rkey[i], rlen[i], t)) { my_tok += (uint32_t)rlen[i]; my_cnt += 1; sel_mask |= 1u << i; }
+        tie_after_regs = t;
+        for (int i = KREG; i < kpt; ++i)
+            if (s0 + i < S && len[s0 + i] > 0 && chosen(score_key(ldsc(s0 + i)), len[s0 + i], t)) { my_tok += (uint32_t)len[s0 + i]; my_cnt += 1; }
     }
     uint32_t tot_tok, tot_cnt = 0;
     uint32_t pos_tok = block_scan_u32(my_tok, sh.wave_tot[4], &tot_tok) - my_tok;
     uint32_t pos_cnt = 0;
     if (COUNT) pos_cnt = block_scan_u32(my_cnt, sh.wave_tot[5], &tot_cnt) - my_cnt;
     if (my_cnt != 0) {
-        uint32_t t = tie_run;
-        for_items([&](int, int32_t s, uint32_t k, int32_t ln, int32_t o) {
-            if (chosen(k, ln, t)) {
-                emit(s, o, ln, (int32_t)pos_cnt, (int32_t)pos_tok);
-                pos_tok += (uint32_t)ln;
+#pragma unroll
+        for (int i = 0; i < KREG; ++i) {
+            if ((sel_mask >> i) & 1u) {
+                emit(s0 + i, roff[i], rlen[i], (int32_t)pos_cnt, (int32_t)pos_tok);
+                pos_tok += (uint32_t)rlen[i];
                 pos_cnt += 1;
             }
-        });
+        }
+        uint32_t t = tie_after_regs;
+        for (int i = KREG; i < kpt; ++i) {
+            if (s0 + i < S && len[s0 + i] > 0 && chosen(score_key(ldsc(s0 + i)), len[s0 + i], t)) {
+                emit(s0 + i, off[s0 + i], len[s0 + i], (int32_t)pos_cnt, (int32_t)pos_tok);
+                pos_tok += (uint32_t)len[s0 + i];
+                pos_cnt += 1;
+            }
+        }
     }
     *n_sel_out = (int32_t)tot_cnt;
     *n_tok_out = (int32_t)tot_tok;
@@ -1398,7 +1411,7 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
                 }
             }
         }
-        __syncthreads();
+        if constexpr (!kMfma) __syncthreads();                    // (the matrix-core path met after its partial sums already)
         for (int i = tid; i < kOut; i += kBlockThreads) {
             const int g = i / kHeadDim, d = i % kHeadDim;
             const int src = kMfma ? d * G + g : i;                     // the MFMA path leaves its sums head fastest
