@@ -508,6 +508,7 @@ struct SelectShared {
     uint32_t wave_tot[6][kBlockWaves];                        // one slot per block scan
     int32_t res[3][4];                                        // per pass: crossing digit (-1: none), carry, count
     int32_t poll[3];                                          // tagged scores: [0] set by a thread whose wait ran out
+    __attribute__((aligned(16))) uint32_t wmax[kBlockWaves];  // largest key per wave
 };
 
 // emit(s, off_s, len_s, sel_pos, tok_pos) is called by the owner thread of every selected bucket,
@@ -569,14 +570,34 @@ __device__ __forceinline__ void select_block(const float* __restrict__ sc, const
         }
     }
     // zero the histograms while the loads are in flight
-    {
+    auto zero_hist = [&]() {
         unsigned long long* h = &sh.hist[0][0];
 #pragma unroll
         for (int i = 0; i < 3 * kBins / kBlockThreads; ++i) h[i * kBlockThreads + tid] = 0;
-        if (tid < 3) { sh.res[tid][0] = -1; sh.poll[tid] = 0; }
-    }
-    __syncthreads();
-    if (TAGGED) {
+        if (tid < 3) sh.res[tid][0] = -1;
+    };
+    zero_hist();
+    if (tid == 0) sh.poll[0] = 0;
+    // The largest key of the block (over all buckets read, with or without tokens: an upper bound of the keys that take
+    // part is all that is needed): a wave's maximum goes to LDS ahead of a barrier that is there anyway.
+    uint32_t my_max = 0;
+    auto share_max = [&]() {
+        const uint32_t wm = (uint32_t)__builtin_amdgcn_readlane((int)wave_scan_max_u32(my_max), kWave - 1);
+        if ((tid & (kWave - 1)) == 0) sh.wmax[tid >> 6] = wm;
+    };
+    if (!TAGGED) {
+#pragma unroll
+        for (int i = 0; i < KREG; ++i) {
+            rkey[i] = score_key(__uint_as_float(rkey[i]));
+            if (s0 + i >= S) rlen[i] = 0;                  // slots past the end take part in nothing
+            if (i < kpt) my_max = max(my_max, rkey[i]);
+        }
+        for (int i = KREG; i < kpt; ++i)
+            if (s0 + i < S) my_max = max(my_max, score_key(sc[s0 + i]));
+        share_max();
+        __syncthreads();
+    } else {
+        __syncthreads();                                   // the flag is clear
         // Every thread reads its own words until all of them carry the tag (bounded), without talking to anyone; the
         // block meets at one barrier afterwards.  A thread whose wait ran out raises the block's flag.
         const bool strided = kpt <= KREG;                  // every bucket of the pair is held in registers
@@ -601,8 +622,12 @@ __device__ __forceinline__ void select_block(const float* __restrict__ sc, const
                 }
             }
 #pragma unroll
-            for (int i = 0; i < KREG; ++i)
-                if (i < kpt) key_lds[i * kBlockThreads + tid] = kk[i];
+            for (int i = 0; i < KREG; ++i) {
+                if (i < kpt) {
+                    key_lds[i * kBlockThreads + tid] = kk[i];
+                    my_max = max(my_max, score_key(__uint_as_float(kk[i])));
+                }
+            }
         } else {
             for (int32_t round = 0; !mine && round < wait_limit; ++round) {
                 mine = true;
@@ -612,10 +637,18 @@ __device__ __forceinline__ void select_block(const float* __restrict__ sc, const
                     rkey[i] = (uint32_t)wd;
                     mine = mine && tag_of(wd) == tag;
                 }
-                for (int i = KREG; i < kpt; ++i)           // buckets beyond the registers are re-read in every phase below
-                    if (s0 + i < S) mine = mine && tag_of(ld_tagged(tw + s0 + i)) == tag;
+                for (int i = KREG; i < kpt; ++i) {         // buckets beyond the registers are re-read in every phase below
+                    if (s0 + i < S) {
+                        const unsigned long long wd = ld_tagged(tw + s0 + i);
+                        mine = mine && tag_of(wd) == tag;
+                        my_max = max(my_max, score_key(val_of(wd)));
+                    }
+                }
             }
+#pragma unroll
+            for (int i = 0; i < KREG; ++i) my_max = max(my_max, score_key(__uint_as_float(rkey[i])));
         }
+        share_max();
         if (!mine) sh.poll[0] = 1;
         __syncthreads();
         if (sh.poll[0] != 0 && ok_out) *ok_out = false;
@@ -624,58 +657,91 @@ __device__ __forceinline__ void select_block(const float* __restrict__ sc, const
             for (int i = 0; i < KREG; ++i)
                 if (i < kpt) rkey[i] = key_lds[s0 + i];    // s0 + i < kpt * 1024 <= KREG * 1024
         }
-    }
 #pragma unroll
-    for (int i = 0; i < KREG; ++i) {
-        rkey[i] = score_key(__uint_as_float(rkey[i]));
-        if (s0 + i >= S) rlen[i] = 0;                      // slots past the end take part in nothing
+        for (int i = 0; i < KREG; ++i) {
+            rkey[i] = score_key(__uint_as_float(rkey[i]));
+            if (s0 + i >= S) rlen[i] = 0;                  // slots past the end take part in nothing
+        }
+    }
+    uint32_t kmax = 0;
+    {
+        const uint4* wm4 = reinterpret_cast<const uint4*>(sh.wmax);
+#pragma unroll
+        for (int q4 = 0; q4 < kBlockWaves / 4; ++q4) {
+            const uint4 t = wm4[q4];
+            kmax = max(max(kmax, max(t.x, t.y)), max(t.z, t.w));
+        }
     }
     SKV_T(1);
 
     // ---- weighted radix select of the cut ----------------------------------------------------------
+    // Two attempts.  The first ranks the buckets by their distance below the best key, r = ~(kmax - key) (the same order
+    // as the key), and looks only at those within 2^24 key steps of it (two binades of score; the others cannot be told
+    // apart there and stay out of the histograms): digits of 11, 11 and 2 bits from bit 23 down, so that the first
+    // histogram already resolves 2^13 key steps and the crossing digit mostly holds a single bucket: one pass instead of
+    // two.  If those near buckets all fit the budget, the cut lies further down (or nowhere) and the second attempt runs
+    // the plain digits 11, 11, 10 of the key over all buckets.
     uint32_t prefix = 0;        // resolved high bits of the cut's key
     int shift = 32;             // number of unresolved low bits
     int32_t carry = 0;          // total length of the buckets ranked strictly above the current digit range
     int32_t cut_cnt = 0;        // number of buckets sharing the resolved prefix
     bool select_all = false;
+    bool near = true;           // first attempt: keys are distances below kmax
+    auto to_rank = [&](uint32_t k) -> uint32_t { return near ? ~(kmax - k) : k; };
 #pragma unroll
-    for (int pass = 0; pass < 3; ++pass) {
-        const int bits = pass < 2 ? 11 : 10, nbins = 1 << bits, nshift = shift - bits;
-        unsigned long long* H = sh.hist[pass];
+    for (int i = 0; i < KREG; ++i) rkey[i] = ~(kmax - rkey[i]);
+    for (int attempt = 0; attempt < 2; ++attempt) {
+        bool found_none = false;
+        prefix = near ? 0xffu : 0u;
+        shift = near ? 24 : 32;
+        carry = 0;
 #pragma unroll
-        for (int i = 0; i < KREG; ++i) {
-            if (i < kpt && rlen[i] > 0 && (pass == 0 || (rkey[i] >> shift) == prefix))
-                atomicAdd(&H[(rkey[i] >> nshift) & (nbins - 1)], (1ull << 32) | (unsigned long long)(uint32_t)rlen[i]);
-        }
-        for (int i = KREG; i < kpt; ++i) {
-            if (s0 + i < S && len[s0 + i] > 0) {               // a bucket without tokens takes part in nothing
-                const uint32_t k = score_key(ldsc(s0 + i));
-                if (pass == 0 || (k >> shift) == prefix)
-                    atomicAdd(&H[(k >> nshift) & (nbins - 1)], (1ull << 32) | (unsigned long long)(uint32_t)len[s0 + i]);
+        for (int pass = 0; pass < 3; ++pass) {
+            const int bits = pass < 2 ? 11 : (near ? 2 : 10), nbins = 1 << bits, nshift = shift - bits;
+            unsigned long long* H = sh.hist[pass];
+#pragma unroll
+            for (int i = 0; i < KREG; ++i) {
+                if (i < kpt && rlen[i] > 0 && (shift == 32 || (rkey[i] >> shift) == prefix))
+                    atomicAdd(&H[(rkey[i] >> nshift) & (nbins - 1)], (1ull << 32) | (unsigned long long)(uint32_t)rlen[i]);
             }
+            for (int i = KREG; i < kpt; ++i) {
+                if (s0 + i < S && len[s0 + i] > 0) {           // a bucket without tokens takes part in nothing
+                    const uint32_t k = to_rank(score_key(ldsc(s0 + i)));
+                    if (shift == 32 || (k >> shift) == prefix)
+                        atomicAdd(&H[(k >> nshift) & (nbins - 1)], (1ull << 32) | (unsigned long long)(uint32_t)len[s0 + i]);
+                }
+            }
+            __syncthreads();
+            // thread order == descending digit order: thread t owns digits nbins-1-2t and nbins-2-2t
+            const int d1 = nbins - 1 - 2 * tid;
+            const unsigned long long v1 = d1 >= 0 ? H[d1] : 0ull, v0 = d1 >= 1 ? H[d1 - 1] : 0ull;
+            const uint32_t l1 = (uint32_t)v1, l0 = (uint32_t)v0;
+            uint32_t total;
+            const uint32_t incl = block_scan_u32(l1 + l0, sh.wave_tot[pass], &total);
+            const uint32_t above1 = (uint32_t)carry + incl - l1 - l0, above0 = above1 + l1;
+            if (l1 > 0 && above1 <= (uint32_t)budget && above1 + l1 > (uint32_t)budget) {
+                sh.res[pass][0] = d1; sh.res[pass][1] = (int32_t)above1; sh.res[pass][2] = (int32_t)(v1 >> 32);
+            }
+            if (l0 > 0 && above0 <= (uint32_t)budget && above0 + l0 > (uint32_t)budget) {
+                sh.res[pass][0] = d1 - 1; sh.res[pass][1] = (int32_t)above0; sh.res[pass][2] = (int32_t)(v0 >> 32);
+            }
+            __syncthreads();
+            const int digit = sh.res[pass][0];
+            if (digit < 0) { found_none = true; break; }           // the buckets of this attempt all fit (only possible in pass 0)
+            prefix = (shift == 32) ? (uint32_t)digit : ((prefix << bits) | (uint32_t)digit);
+            carry = sh.res[pass][1];
+            cut_cnt = sh.res[pass][2];
+            shift = nshift;
+            if (cut_cnt == 1) break;                               // the cut is unique: it is the bucket that overflows
         }
+        if (!found_none) break;
+        if (!near) { select_all = true; break; }                   // every bucket was seen and they all fit: no cut
+        // The buckets near the best key all fit: the cut, if there is one, is among the others.
+        near = false;
+#pragma unroll
+        for (int i = 0; i < KREG; ++i) rkey[i] = kmax - ~rkey[i];  // back to the plain keys
+        zero_hist();                                               // (every thread is past its reads of the first attempt)
         __syncthreads();
-        // thread order == descending digit order: thread t owns digits nbins-1-2t and nbins-2-2t
-        const int d1 = nbins - 1 - 2 * tid;
-        const unsigned long long v1 = d1 >= 0 ? H[d1] : 0ull, v0 = d1 >= 1 ? H[d1 - 1] : 0ull;
-        const uint32_t l1 = (uint32_t)v1, l0 = (uint32_t)v0;
-        uint32_t total;
-        const uint32_t incl = block_scan_u32(l1 + l0, sh.wave_tot[pass], &total);
-        const uint32_t above1 = (uint32_t)carry + incl - l1 - l0, above0 = above1 + l1;
-        if (l1 > 0 && above1 <= (uint32_t)budget && above1 + l1 > (uint32_t)budget) {
-            sh.res[pass][0] = d1; sh.res[pass][1] = (int32_t)above1; sh.res[pass][2] = (int32_t)(v1 >> 32);
-        }
-        if (l0 > 0 && above0 <= (uint32_t)budget && above0 + l0 > (uint32_t)budget) {
-            sh.res[pass][0] = d1 - 1; sh.res[pass][1] = (int32_t)above0; sh.res[pass][2] = (int32_t)(v0 >> 32);
-        }
-        __syncthreads();
-        const int digit = sh.res[pass][0];
-        if (digit < 0) { select_all = true; break; }          // everything fits (only possible in pass 0)
-        prefix = (pass == 0) ? (uint32_t)digit : ((prefix << bits) | (uint32_t)digit);
-        carry = sh.res[pass][1];
-        cut_cnt = sh.res[pass][2];
-        shift = nshift;
-        if (cut_cnt == 1) break;                               // the cut is unique: it is the bucket that overflows
     }
     const bool ties = !select_all && cut_cnt > 1;              // then shift == 0: several buckets share the cut's score
     SKV_T(2);
@@ -687,7 +753,7 @@ __device__ __forceinline__ void select_block(const float* __restrict__ sc, const
         for (int i = 0; i < KREG; ++i)
             if (i < kpt && rlen[i] > 0) fn(i, s0 + i, rkey[i], rlen[i], roff[i]);
         for (int i = KREG; i < kpt; ++i)
-            if (s0 + i < S && len[s0 + i] > 0) fn(i, s0 + i, score_key(ldsc(s0 + i)), len[s0 + i], off[s0 + i]);
+            if (s0 + i < S && len[s0 + i] > 0) fn(i, s0 + i, to_rank(score_key(ldsc(s0 + i))), len[s0 + i], off[s0 + i]);
     };
     uint32_t tie_run = 0;          // length of tied buckets with lower ids (starts at the thread's base)
     if (ties) {
@@ -715,7 +781,7 @@ __device__ __forceinline__ void select_block(const float* __restrict__ sc, const
             if (i < kpt && rlen[i] > 0 && chosen(rkey[i], rlen[i], t)) { my_tok += (uint32_t)rlen[i]; my_cnt += 1; sel_mask |= 1u << i; }
         tie_after_regs = t;
         for (int i = KREG; i < kpt; ++i)
-            if (s0 + i < S && len[s0 + i] > 0 && chosen(score_key(ldsc(s0 + i)), len[s0 + i], t)) { my_tok += (uint32_t)len[s0 + i]; my_cnt += 1; }
+            if (s0 + i < S && len[s0 + i] > 0 && chosen(to_rank(score_key(ldsc(s0 + i))), len[s0 + i], t)) { my_tok += (uint32_t)len[s0 + i]; my_cnt += 1; }
     }
     uint32_t tot_tok, tot_cnt = 0;
     uint32_t pos_tok = block_scan_u32(my_tok, sh.wave_tot[4], &tot_tok) - my_tok;
@@ -732,7 +798,7 @@ __device__ __forceinline__ void select_block(const float* __restrict__ sc, const
         }
         uint32_t t = tie_after_regs;
         for (int i = KREG; i < kpt; ++i) {
-            if (s0 + i < S && len[s0 + i] > 0 && chosen(score_key(ldsc(s0 + i)), len[s0 + i], t)) {
+            if (s0 + i < S && len[s0 + i] > 0 && chosen(to_rank(score_key(ldsc(s0 + i))), len[s0 + i], t)) {
                 emit(s0 + i, off[s0 + i], len[s0 + i], (int32_t)pos_cnt, (int32_t)pos_tok);
                 pos_tok += (uint32_t)len[s0 + i];
                 pos_cnt += 1;
