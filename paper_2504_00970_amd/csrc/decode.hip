@@ -375,26 +375,25 @@ enum { kTableF32 = 4, kTableBf16 = 2, kTableE4m3 = 1 };       // bytes per eleme
 // of cu_sent down to eight candidates (dependent scalar loads), then eight consecutive boundaries in one scalar load,
 // which also gives the end of the first run; log2(B / 8) + 1 round trips, whatever the batch size.
 
-template <int EB, int G, int SVB, int RPWV>
-__global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_kernel(const char* __restrict__ q,
-                                                                            const char* __restrict__ semvec, SeqView v,
-                                                                            int32_t Hq, float* __restrict__ score) {
-    // every argument is demanded here, so the kernel-argument loads go out together; left alone, the compiler loads
-    // each one before its first use, a dependent round trip per branch below
-    asm volatile("" ::"s"(q), "s"(semvec), "s"(v.cu_sent), "s"(v.S_total), "s"(v.B), "s"(Hq), "s"(score));
-    const int h = blockIdx.y;
-    const int32_t r0 = (blockIdx.x * kScoreWavesPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6)) * RPWV;
-    if (r0 >= v.S_total) return;
+// The RPWV buckets [r0, r0 + RPWV) of the concatenated bucket axis, head h, by one wave.  TAGGED: `out` holds 64-bit
+// (score, tag) words, tags[pair] being the launch tag of (sequence, head) pair b * Hkv + h.
+template <int EB, int G, int SVB, int RPWV, bool TAGGED>
+__device__ __forceinline__ void score_group(const char* __restrict__ q, const char* __restrict__ semvec, const SeqView& v,
+                                            int32_t Hq, int h, int32_t r0, void* __restrict__ out,
+                                            const uint32_t* tags = nullptr) {
     const int32_t r1 = min(r0 + RPWV, v.S_total);
     auto run = [&](int b, int32_t first, int32_t n) {      // buckets [first, first + n) of the batch axis, sequence b
         const char* qg = q + ((int64_t)(b * Hq + h * G) * kHeadDim) * EB;
         const int64_t row = (int64_t)h * v.S_total + first;
+        void* dst = TAGGED ? static_cast<void*>(static_cast<unsigned long long*>(out) + row)
+                           : static_cast<void*>(static_cast<float*>(out) + row);
+        const uint32_t tag = TAGGED ? tags[b * (Hq / G) + h] : 0u;
         if (SVB == kTableF32)
-            score_wave_f32<EB, G, RPWV, false>(qg, reinterpret_cast<const float*>(semvec) + row * kHeadDim, n, 0, score + row);
+            score_wave_f32<EB, G, RPWV, TAGGED>(qg, reinterpret_cast<const float*>(semvec) + row * kHeadDim, n, 0, dst, tag);
         else if (SVB == kTableBf16)
-            score_wave_bf16<EB, G, RPWV, false>(qg, semvec + row * kHeadDim * 2, n, 0, score + row);
+            score_wave_bf16<EB, G, RPWV, TAGGED>(qg, semvec + row * kHeadDim * 2, n, 0, dst, tag);
         else
-            score_wave_e4m3<EB, G, RPWV, false>(qg, semvec + row * kHeadDim, n, 0, score + row);
+            score_wave_e4m3<EB, G, RPWV, TAGGED>(qg, semvec + row * kHeadDim, n, 0, dst, tag);
     };
     if (!v.cu_sent) {                                      // one sequence
         run(0, r0, r1 - r0);
@@ -437,6 +436,18 @@ __global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_kernel(cons
         if (cur >= r1 || ++b >= v.B) break;
         end = cu(b + 1);
     }
+}
+
+template <int EB, int G, int SVB, int RPWV>
+__global__ __launch_bounds__(kScoreWavesPerBlock * kWave) void score_kernel(const char* __restrict__ q,
+                                                                            const char* __restrict__ semvec, SeqView v,
+                                                                            int32_t Hq, float* __restrict__ score) {
+    // every argument is demanded here, so the kernel-argument loads go out together; left alone, the compiler loads
+    // each one before its first use, a dependent round trip per branch below
+    asm volatile("" ::"s"(q), "s"(semvec), "s"(v.cu_sent), "s"(v.S_total), "s"(v.B), "s"(Hq), "s"(score));
+    const int32_t r0 = (blockIdx.x * kScoreWavesPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6)) * RPWV;
+    if (r0 >= v.S_total) return;
+    score_group<EB, G, SVB, RPWV, false>(q, semvec, v, Hq, blockIdx.y, r0, score);
 }
 
 template <int EB, int G>
@@ -1197,8 +1208,41 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
     } else {
         n = min(ld_const(a.n_tok, bh), MODE == kDirect ? a.row_stride : a.idx_stride);
     }
+    // kStep: every block of the pair that ran the selection (and so used the epoch it read at its start) tells block 0 so
+    // in the first (max, tag) word of its partial: the attending blocks with their partial, the others as soon as they
+    // know that they hold no retrieved tokens.  Block 0 advances the epoch only after it has seen all of them, so that no
+    // block of this launch can read the advanced epoch.
+    auto presence = [&]() {
+        if constexpr (MODE == kStep) {
+            if (tid == 0)                                         // a block that gave up publishes nothing valid
+                st_tagged(a.step_part + (int64_t)blockIdx.x * G * kStepPartWords + kHeadDim, -INFINITY, step_ok ? tag : 0u);
+        }
+    };
+    // block 0: the words of blocks first .. (blocks of the pair that run the selection) - 1 carry the tag (bounded wait);
+    // every thread of the block calls this
+    auto others_were_here = [&](int first) -> bool {
+        if constexpr (MODE == kStep) {
+            const int n_cand = min(1 << a.lg_parts, max(G, (min(sq.budget, a.budget_cap) + CHUNK - 1) / CHUNK));
+            if (n_cand <= first) return true;                     // block-uniform: the usual case, the budget is filled
+            // the flag lives in the first word of the space the scores came through (thread 0, the only reader of that
+            // word in the merge, is past its reads when it clears it)
+            volatile uint32_t* missing = sm_keys;
+            if (tid == 0) *missing = 0u;
+            __syncthreads();
+            if (tid >= first && tid < n_cand) {
+                const unsigned long long* src = a.step_part + ((int64_t)(tid * n_pairs + bh) * G) * kStepPartWords + kHeadDim;
+                bool there = false;
+                for (int32_t round = 0; !there && round < a.wait_limit; ++round) there = tag_of(ld_tagged(src)) == tag;
+                if (!there) *missing = 1u;
+            }
+            __syncthreads();
+            return *missing == 0u;
+        }
+        return true;
+    };
     if (n <= 0) {
         if (split == 0) {
+            step_ok = others_were_here(1) && step_ok;
             for (int i = tid; i < kOut; i += kBlockThreads) a.out[qhead0 * kHeadDim + i] = step_ok ? 0.f : __builtin_nanf("");
             if (a.lse && tid < G) a.lse[qhead0 + tid] = -INFINITY;
             if constexpr (MODE == kStep) {
@@ -1207,13 +1251,18 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
                     if (!step_ok) { st_agent(a.err_dev, 1u); if (a.err_host) st_agent(a.err_host, 1u); }
                 }
             }
+        } else {
+            presence();
         }
         return;
     }
     const int nsplit = (n + CHUNK - 1) / CHUNK;
     // kStep: block g < G merges query head g of the group, whether or not it holds retrieved tokens itself
     const bool has_work = split < nsplit;
-    if (!has_work && !(MODE == kStep && split < G)) return;
+    if (!has_work) {
+        presence();
+        if (!(MODE == kStep && split < G)) return;
+    }
     unsigned long long* my_part = nullptr;
     uint32_t part_tag = 0;
     if constexpr (MODE == kStep) {
@@ -1570,10 +1619,16 @@ __global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttArgs a) {
             if (a.lse && tid == 0) a.lse[qhead0 + g] = empty ? -INFINITY : (Mx + log2f(Ls)) * kLn2;
             if (bad) { st_agent(a.err_dev, 1u); if (a.err_host) st_agent(a.err_host, 1u); }
         }
-        // Block 0 ends the pair's launch by advancing its epoch: all its threads have seen every attending block's
-        // partial (the barrier above), and each of those blocks, and through the scores they waited for every
-        // scoring block, has read the epoch by now.
-        if (tid == 0 && split == 0) st_agent(a.step_epoch + bh * kStepEpochStride, tag >> kStepPairBits);
+        // Block 0 ends the pair's launch by advancing its epoch: its threads have seen the partial of every attending
+        // block (the barrier above) and now make sure of the word of every other block that ran the selection; all of
+        // them, and through the scores they waited for every scoring block, have read the epoch by then.
+        if (split == 0) {
+            const bool all_here = others_were_here(nsplit);
+            if (tid == 0) {
+                st_agent(a.step_epoch + bh * kStepEpochStride, tag >> kStepPairBits);
+                if (!all_here) { st_agent(a.err_dev, 1u); if (a.err_host) st_agent(a.err_host, 1u); }
+            }
+        }
         SKV_T(9);
         return;
     }

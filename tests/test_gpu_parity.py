@@ -386,6 +386,18 @@ def test_fused_single_sequence_matches_oracle(U, oracle32, capacity):
     _fused_case(U, oracle32, wl, seed=3, layers=[0], capacity=capacity)
 
 
+@pytest.mark.parametrize("tokens,budget", [(700, 2048), (2500, 2048), (3000, 1)])
+@pytest.mark.parametrize("B", [1, 3])
+def test_fused_single_launch_with_idle_blocks(U, oracle32, tokens, budget, B):
+    """The single-launch step when the retrieved tokens do not fill the blocks the budget provides: a context smaller than
+    the budget (every bucket is taken: 6 of 16 blocks hold tokens), a selection that ends a block or two short of the
+    budget's last one, and a budget no bucket fits (nothing retrieved).  The blocks without tokens run the selection too,
+    and block 0 of a pair waits for their word before it ends the pair's launch."""
+    wl = gen.CFG1.scaled(n_layers=1, batch=B, t_range=(tokens, tokens), budgets=(budget,), len_dist=("uniform", 2, 300))
+    _fused_case(U, oracle32, wl, seed=61, layers=[0])
+    _fused_case(U, oracle32, wl, seed=62, layers=[0])                 # again, on a fresh context
+
+
 @pytest.mark.parametrize("budget", [3000, 6000])
 def test_fused_single_sequence_large_budget(U, oracle32, budget):
     """Budgets of thousands of tokens for one sequence, single launch: 128-token blocks (3000: 8 x 24 blocks of 128 tokens still
