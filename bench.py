@@ -759,8 +759,8 @@ def measured_copy_peak(dev="cuda:0", mib=1024, reps=5):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg3-retain", "cfg4", "floor"])
     ap.add_argument("--window", type=int, default=32, help="cfg3-retain: observation-window tokens")
     ap.add_argument("--keep", type=int, default=4096, help="cfg3-retain: tokens retained per layer (floor(r tau))")
