@@ -23,7 +23,8 @@
  *     attention head and is silent on GQA).
  *   - Decode calls are asynchronous on the context's stream and never block the host.  Calls on one
  *     context must come from one host thread at a time and execute in stream order; they share the
- *     context's workspace, so two contexts are needed for concurrent streams.
+ *     context's workspace, so two contexts are needed for concurrent streams (and skv_set_single_launch(ctx, 0)
+ *     on both when their decode steps may overlap on one GPU).
  */
 #ifndef SENTENCEKV_H
 #define SENTENCEKV_H
@@ -91,6 +92,14 @@ int skv_set_budget_hint(skv_ctx* ctx, int32_t budget);
  * the stream).
  * Errors: SKV_EINVAL (NULL context, polls < 0). */
 int skv_set_wait_limit(skv_ctx* ctx, int32_t polls);
+/* The single-launch form needs every block of its grid on the GPU at the same time: the library launches it only when
+ * the grid fits the compute units of an otherwise idle GPU.  Work that other streams, contexts or processes run on the
+ * same GPU at the same moment can keep part of the grid waiting for a compute unit while the blocks that did start
+ * wait for it: the bounded waits then run out and the step fails as described above.  A caller that overlaps steps of
+ * several contexts, or other kernels, on one GPU turns the form off (`enable` = 0): skv_decode_step then always uses
+ * the forms of two or three launches, which wait for nothing.  On by default.
+ * Errors: SKV_EINVAL (NULL context). */
+int skv_set_single_launch(skv_ctx* ctx, int32_t enable);
 
 /* ---------------------------------------------------------------------------------------------
  * (1) Prefill.  Sec. 4.1 first paragraph and Alg. 1 prefilling phase: the prompt is split into

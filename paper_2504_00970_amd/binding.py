@@ -40,6 +40,7 @@ _SIGNATURES = {
     "skv_strerror": (ctypes.c_char_p, [_int]),
     "skv_workspace_bytes": (_i64, [_vp]),
     "skv_set_wait_limit": (_int, [_vp, _i32]),
+    "skv_set_single_launch": (_int, [_vp, _i32]),
     "skv_set_budget_hint": (_int, [_vp, _i32]),
     "skv_segment": (_int, [_vp, _vp, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _vp]),
     "skv_build_semvec": (_int, [_vp, _vp, _i32, _vp, _i32, _vp]),
@@ -154,6 +155,9 @@ class Context:
 
     def set_wait_limit(self, polls: int) -> None:
         _check(_lib().skv_set_wait_limit(self._h, polls), "skv_set_wait_limit")
+
+    def set_single_launch(self, enable: bool) -> None:
+        _check(_lib().skv_set_single_launch(self._h, 1 if enable else 0), "skv_set_single_launch")
 
     # ---- (1) prefill ----------------------------------------------------------------------------
     def segment(self, tok, term_bitmap, vocab: int, seg_id, sent_off, sent_len, n_sent_dev, sync: bool = True,

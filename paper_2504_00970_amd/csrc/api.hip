@@ -119,6 +119,7 @@ void fill_context(Ctx& c, const skv_desc& d, hipStream_t stream, int dev) {
     c.max_splits = (d.max_budget + skv::kAttChunk - 1) / skv::kAttChunk;
     c.budget_cap = d.max_budget;
     c.wait_limit = skv::kStepWaitLimit;
+    c.single_launch = true;
 }
 
 // ---- static scratch of skv_decode_step_noalloc -----------------------------------------------------------------------
@@ -235,6 +236,12 @@ int skv_set_budget_hint(skv_ctx* ctx, int32_t budget) {
     if (!ctx || budget < 0) return SKV_EINVAL;
     if (budget > ctx->c.d.max_budget) return SKV_ECAPACITY;
     ctx->c.budget_cap = budget == 0 ? ctx->c.d.max_budget : budget;
+    return SKV_OK;
+}
+
+int skv_set_single_launch(skv_ctx* ctx, int32_t enable) {
+    if (!ctx) return SKV_EINVAL;
+    ctx->c.single_launch = enable != 0;
     return SKV_OK;
 }
 
@@ -450,7 +457,7 @@ static int decode_step_launch(Ctx& c, int32_t layer, int32_t B, const void* q_sc
     hipError_t e;
     // Few (sequence, head) pairs: the whole step in one launch, when its attention blocks (128 or 256 tokens) fit the
     // chip at once beside each other; launch_step decides.
-    if (pairs <= skv::kStepMaxPairs && S_total > 0) {
+    if (c.single_launch && pairs <= skv::kStepMaxPairs && S_total > 0) {
         bool launched = false;
         e = skv::launch_step(&c, q_score, q_attn, sv, Kl, Vl, sent_off, sent_len, v, out, lse, tok_idx_out, n_tok_out, &launched);
         if (launched || e != hipSuccess) return hip_status(e);

@@ -72,6 +72,7 @@ struct Ctx {
     unsigned int* err_host;      // the same flag in pinned host memory (host address; null: none)
     unsigned int* err_host_dev;  // device address of err_host
     int wait_limit;              // polling rounds before a waiting block gives up
+    bool single_launch;          // skv_decode_step may take the single-launch form
 };
 
 // Ragged-batch view handed to the decode kernels.  For single-sequence calls cu_tok / cu_sent /

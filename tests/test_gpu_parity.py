@@ -644,6 +644,41 @@ def test_budget_hint_makes_a_large_context_plan_like_a_small_one(U, oracle32, B,
         big.set_budget_hint(9000)
 
 
+@pytest.mark.parametrize("B,dtype", [(1, "bf16"), (3, "bf16"), (1, "f32")])
+def test_single_launch_can_be_turned_off(U, oracle32, B, dtype):
+    """skv_set_single_launch(ctx, 0): the step takes the two-launch form (for callers whose steps overlap with other work
+    on the GPU); the selection is the same bit for bit, the outputs agree to the attention tolerance, and turning the
+    form on again brings the single launch's own bits back."""
+    wl = gen.CFG1.scaled(n_layers=1, batch=B, t_range=(5000, 7000), budgets=(1024,), dtype=dtype)
+    inp = gen.ragged_inputs(wl, seed=23, device=U.DEV, resident_layers=1)
+    H, Hq, D = wl.n_kv_heads, wl.n_q_heads, wl.head_dim
+    T, S = int(inp.cu_tok[-1]), int(inp.cu_sent[-1])
+    d = [U.i32(x) for x in (inp.cu_tok, inp.cu_sent, inp.sent_off, inp.sent_len, inp.budget)]
+    ctx = U.make_ctx(wl, T, S, 1024, batch=B)
+    sv = torch.zeros(1, H, S, D, device=U.DEV)
+    ctx.build_semvec(inp.K, U.i32(gen.offsets_of(inp.sent_len)), S, sv)
+
+    def run():
+        out = torch.full((B, Hq, D), 3.0, device=U.DEV)
+        lse = torch.full((B, Hq), 3.0, device=U.DEV)
+        tok_idx = U.empty_i32(B, H, 1024, fill=-1)
+        n_tok = U.empty_i32(B, H, fill=-1)
+        ctx.decode_step(0, B, inp.q[0], inp.q[0], inp.K, inp.V, T, sv, S, *d, out, lse, tok_idx, n_tok)
+        torch.cuda.synchronize()
+        return out, lse, tok_idx, n_tok
+
+    one = run()
+    ctx.set_single_launch(False)
+    _say("single launch off, B", B, dtype)
+    two = run()
+    assert torch.equal(one[2], two[2]) and torch.equal(one[3], two[3])
+    assert (one[0] - two[0]).abs().max().item() <= ATT_TOL[dtype] and (one[1] - two[1]).abs().max().item() <= ATT_TOL[dtype]
+    ctx.set_single_launch(True)
+    again = run()
+    for a, b in zip(one, again):
+        assert torch.equal(a, b)
+
+
 # ----------------------------------------------------------------------------- local window merge, equal chunks
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
