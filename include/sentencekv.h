@@ -265,8 +265,10 @@ int skv_decode_step(skv_ctx* ctx, int32_t layer, int32_t B, const void* q_score,
  * is a static array of SKV_NOALLOC_SCRATCH_BYTES of device memory inside the library, which every GPU the library runs
  * on holds until the process ends.  The call allocates and frees nothing (no hipMalloc / hipFree, no allocating library
  * routine) and never blocks the host; it queues two small clearing kernels (arrival counters, error word) ahead of the
- * kernels of skv_decode_step; a give-up of the single-launch form shows as NaN outputs only (there is no context to report it).  The address of the array is looked up once per device, at skv_create or at the first call here on
- * that device (a symbol lookup: make that first call outside graph capture).
+ * kernels of skv_decode_step.  A give-up of the single-launch form (see skv_set_single_launch for what can cause one:
+ * other work on the GPU at the same moment) shows as NaN outputs only: there is no context to report it.  The address
+ * of the array is looked up once per device, at skv_create or at the first call here on that device (a symbol lookup:
+ * make that first call outside graph capture).
  * desc        host; the maxima only need to cover this call (max_tokens is not used for sizing).  The workspace a
  *             descriptor needs is 3.2 MB that every descriptor shares (the tagged words and epochs of the single-launch
  *             form, never cleared) plus about  max_batch * Hq * ceil(max_budget / 64) * 520  +  Hkv * max_sentences * 4
