@@ -633,6 +633,7 @@ def run_phase_stamps(args, wl, budget):
     read()
     rel = {k: [] for k in STAMP_LABELS}
     launches = max(args.steps, 1)
+    per_block = []                         # [launch][block][slot], us since the launch's first block start (< 0: not stamped)
     for i in range(launches):
         for j in range(3):                 # the stamped launch follows two others back to back, as in a decode step
             step(i * 3 + j)
@@ -641,6 +642,7 @@ def run_phase_stamps(args, wl, budget):
         for k in STAMP_LABELS:
             col = st[:, k]
             rel[k].append((col[col >= t0] - t0) / 100.0)
+        per_block.append((st - t0) / 100.0)
     rows = []
     for k, name in STAMP_LABELS.items():
         x = np.concatenate(rel[k]) if rel[k] else np.zeros(0)
@@ -650,7 +652,26 @@ def run_phase_stamps(args, wl, budget):
                      "median_us": round(float(np.median(x)), 2), "p10_us": round(float(np.percentile(x, 10)), 2),
                      "p90_us": round(float(np.percentile(x, 90)), 2), "max_us": round(float(x.max()), 2)})
     rows.sort(key=lambda r: r["median_us"])
-    return {"phase_stamps": rows, "workload": wl.name, "batch": B, "budget": budget, "tokens_total": T_total,
+    # The same stamps block by block (blocks are numbered x + gridDim.x * y; the hardware deals consecutive blocks to the
+    # XCDs in turn): where the "logits and value tile done" stamp (slot 6: the block's streaming is over) falls by block
+    # number modulo 8, how much one block's time varies from launch to launch, and how much the blocks' means differ.
+    pb = np.stack(per_block)
+    n_blocks = int((pb[0, :, 6] >= 0).sum())
+    spread = None
+    if n_blocks >= 8 and all(int((x[:, 6] >= 0).sum()) == n_blocks for x in pb):
+        done, issued = pb[:, :n_blocks, 6], pb[:, :n_blocks, 5]
+        mean_b = done.mean(axis=0)
+        spread = {"blocks": n_blocks, "slot": 6,
+                  "mean_done_us_by_block_mod_8": [round(float(done[:, k::8].mean()), 2) for k in range(8)],
+                  "std_over_launches_of_one_block_us": round(float(done.std(axis=0).mean()), 2),
+                  "std_over_blocks_of_their_means_us": round(float(mean_b.std()), 2),
+                  "block_means_min_max_us": [round(float(mean_b.min()), 2), round(float(mean_b.max()), 2)]}
+        if B > 1 and n_blocks % B == 0:    # blocks of a sequence are contiguous: (pairs of the sequence) x (blocks per pair)
+            per = n_blocks // B
+            spread["by_sequence"] = [{"buckets": int(inp.cu_sent[s + 1] - inp.cu_sent[s]),
+                                      "kv_issued_us": round(float(issued[:, s * per:(s + 1) * per].mean()), 2),
+                                      "done_us": round(float(done[:, s * per:(s + 1) * per].mean()), 2)} for s in range(B)]
+    return {"phase_stamps": rows, "per_block": spread, "workload": wl.name, "batch": B, "budget": budget, "tokens_total": T_total,
             "sentences_total": S_total, "launches": launches, "semvec_dtype": args.semvec_dtype,
             "note": "us since the first block start of the launch; thread 0 of every block; kernel = the last launch of skv_decode_step"}
 
